@@ -1,0 +1,143 @@
+/*
+ * bitdecode.h -- C ABI of libbitdecode.so: decode-step attention over a quantized,
+ * bit-packed KV cache on AMD MI355X (gfx950), after BitDecoding (arxiv 2503.18773).
+ *
+ * The library computes  Out = softmax(Q . D(K')^T) . D(V')  (Fig. 2 caption of the paper;
+ * D = dequantization) for one new query token per sequence, plus the online
+ * quantize-and-pack of the K/V tokens that feed the cache (Sec. III-A, Sec. IV-B).
+ *
+ * General conventions
+ *  - Every pointer named "device" is a device (HBM) address owned by the caller; the
+ *    library never allocates, frees, or synchronises.  Pointers named "host" are ordinary
+ *    host addresses read or written synchronously inside the call.
+ *  - All work is enqueued on the given hipStream_t (passed as void*; NULL = default
+ *    stream) and the call returns at once.  Buffers must stay alive until the stream has
+ *    passed the call.  Calls on one cache must be ordered on one stream.
+ *  - Lengths are host integers and are uniform across the batch (the paper's "Batches"
+ *    setting, Sec. V-A: same length, padded).
+ *  - head_dim is 128.  The residual block N_r (Eq. 1) and the quantization group are both
+ *    128 for BD_FMT_INT4 / BD_FMT_INT2; the MX group is 32 for BD_FMT_MXFP4.
+ *  - Arguments are validated before anything is launched; on error nothing is enqueued
+ *    and no state changes.  Non-finite K/V/Q values are undefined behaviour.
+ *
+ * Cache layout (all little-endian, contiguous, 16-byte aligned), B = batch, H = n_kv_heads,
+ * NBcap = capacity/128, D = 128, bits = 4 or 2, cpw = 32/bits codes per 32-bit word:
+ *
+ *  INT4 / INT2  (K channel-wise, V per token -- Sec. IV-B(1), Sec. IV-C(1))
+ *   k_codes  uint32 [B][H][NBcap][128 tokens][D/cpw]   word w of a token: channels cpw*w+n at bit bits*n
+ *   v_codes  uint32 [B][H][NBcap][D channels][128/cpw] word w of a channel: block tokens cpw*w+n at bit bits*n
+ *   k_params uint32 [B][H][NBcap][D]     half2: fp16 scale in bits 0..15, fp16 zero in bits 16..31
+ *   v_params uint32 [B][H][NBcap][128]   half2 per token of the block
+ *   k_res, v_res fp16 [B][H][128][D]     the L mod 128 newest tokens, unquantized (Sec. III-A(2))
+ *   Quantizer: zero = group minimum (-0 stored as +0); scale = fp16((max - min) / (2^bits - 1))
+ *   computed with one fp32 subtraction and one fp32 division; code = clamp(rint((x - zero) /
+ *   scale), 0, 2^bits - 1) in fp32, ties to even, 0 where scale == 0;  x_hat = code*scale + zero.
+ *
+ *  MXFP4  (Sec. IV-D(2): e2m1 elements, one e8m0 scale per 32 contiguous channels of a token;
+ *          every token is quantized on arrival, there is no residual)
+ *   k_codes  uint8 [B][H][capacity tokens][D/2]   byte j: channel 2j low nibble, 2j+1 high nibble
+ *   k_params uint8 [B][H][capacity tokens][D/32]  e8m0 (value 2^(byte-127))
+ *   v_codes  uint8 [B][H][NBcap][D channels][64]  byte j of a channel: block tokens 2j (low), 2j+1 (high)
+ *   v_params uint8 [B][H][capacity tokens][D/32]
+ *   k_res, v_res unused (may be NULL).  Inputs (K, V, Q) and the output are bf16.
+ *   Quantizer: shared exponent e = clamp(floor(log2(max|x|)) - 2, -127, 127) (byte 127 and zero
+ *   codes for an all-zero group); element = nearest e2m1 to x / 2^e, ties to the even code,
+ *   saturating at +-6, a zero magnitude stored as +0.
+ */
+#ifndef BITDECODE_H
+#define BITDECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BD_OK = 0,
+  BD_ERR_INVALID_ARG = -1,   /* NULL pointer, non-positive size, bad enum, bad length */
+  BD_ERR_UNSUPPORTED = -2,   /* a shape this build has no kernel for (head_dim != 128, g_q not in {1,2,4}) */
+  BD_ERR_ALIGNMENT = -3,     /* a device pointer is not 16-byte aligned */
+  BD_ERR_CAPACITY = -4,      /* the cache cannot hold the tokens asked for */
+  BD_ERR_HIP = -5            /* a HIP runtime call failed; see bd_last_hip_error() */
+} bd_status;
+
+typedef enum { BD_FMT_INT4 = 0, BD_FMT_INT2 = 1, BD_FMT_MXFP4 = 2 } bd_format;
+
+/* Shape and buffers of one layer's cache.  Plain data, filled by the caller, passed by
+ * const pointer; the six buffers are device pointers with the layouts given above. */
+typedef struct bd_cache {
+  int32_t batch;
+  int32_t n_q_heads;     /* multiple of n_kv_heads; g_q = n_q_heads / n_kv_heads (Sec. IV-A) */
+  int32_t n_kv_heads;
+  int32_t head_dim;      /* 128 */
+  int32_t format;        /* bd_format */
+  int32_t capacity;      /* tokens per sequence the packed buffers can hold; multiple of 128 */
+  void *k_codes, *v_codes;
+  void *k_params, *v_params;
+  void *k_res, *v_res;
+} bd_cache;
+
+/* Size in bytes of buffer `which` (0 k_codes, 1 v_codes, 2 k_params, 3 v_params, 4 k_res,
+ * 5 v_res) for the shape fields of `c` (pointers ignored).  0 on a bad argument. */
+size_t bd_cache_bytes(const bd_cache* c, int which);
+
+/* Split factor the library would pick for this shape and length (>= 1): how many
+ * workgroups share the context of one (sequence, KV head), FlashDecoding-style split
+ * over the context (the "split-partitioned" scheme named in Sec. V-A). */
+int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len);
+
+/* Bytes of device workspace bd_decode_attn needs for `num_splits`: (num_splits + 1)
+ * partial results (one extra for the residual tail), each batch*n_q_heads*(128 + 2)
+ * floats (unnormalised output row, running max in log2 units, running sum). */
+size_t bd_workspace_bytes(const bd_cache* c, int32_t num_splits);
+
+/* Prefill (Sec. IV-B(1)): quantize and pack the first L - (L mod 128) tokens of
+ * k, v (device, [B][H][L][D] contiguous, fp16; bf16 for MXFP4) and copy the remaining
+ * L mod 128 tokens into the fp16 residual.  For MXFP4 all L tokens are quantized.
+ * Writes the resulting lengths to the host integers *packed_len, *res_len
+ * (MXFP4: *packed_len = L, *res_len = 0).  L = 0 is allowed.  BD_ERR_CAPACITY if the
+ * tokens to pack exceed capacity. */
+bd_status bd_quant_pack_kv(const bd_cache* c, const void* k, const void* v, int32_t L,
+                           int32_t* packed_len, int32_t* res_len, void* stream);
+
+/* Decode-step append (Sec. IV-B(1)): store the new token k_new, v_new (device, [B][H][D])
+ * in residual slot *res_len; when that fills the 128-token block, quantize and pack the
+ * block as packed block packed_len/128 in the same call, so that on return
+ * 0 <= *res_len <= 127 and prefill(L) followed by n appends equals prefill(L + n) bit for bit.
+ * For MXFP4 the token is quantized directly.  *packed_len / *res_len are host in-out.
+ * BD_ERR_CAPACITY (state unchanged) if the flush would not fit. */
+bd_status bd_append_kv(const bd_cache* c, const void* k_new, const void* v_new,
+                       int32_t* packed_len, int32_t* res_len, void* stream);
+
+/* Decode attention (Fig. 2 caption; Sec. IV-A query transformation; Sec. IV-C fused
+ * dequantize + QK^T + online softmax (Alg. 1) + PV; split over the context):
+ * q device [B][n_q_heads][D] (fp16; bf16 for MXFP4); query head h attends KV head h / g_q
+ * over the packed_len quantized tokens and the res_len residual tokens, logits scaled by
+ * softmax_scale.  Writes num_splits + 1 partials into `workspace` (device, at least
+ * bd_workspace_bytes(c, num_splits), 16-byte aligned).  If `out` is non-NULL (device,
+ * [B][n_q_heads][D], fp16 / bf16) the merge of the partials is enqueued too, so `out`
+ * is complete when the stream passes this call; if NULL, call bd_splitk_combine.
+ * num_splits >= 1 (any value; splits beyond the number of 128-token blocks stay empty).
+ * With no tokens at all the output is zero. */
+bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, int32_t res_len,
+                         float softmax_scale, int32_t num_splits, void* workspace, void* out,
+                         void* stream);
+
+/* Merge the num_splits + 1 partials left in `workspace` by bd_decode_attn (log-sum-exp
+ * merge: m = max m_s, l = sum l_s 2^(m_s-m), O = sum O_s 2^(m_s-m) / l) into
+ * out (device, [B][n_q_heads][D], fp16 / bf16). */
+bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t num_splits,
+                            void* out, void* stream);
+
+/* Text for a status code (static storage). */
+const char* bd_strerror(bd_status s);
+
+/* hipError_t value of the last failing HIP call seen by this thread (0 if none). */
+int bd_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITDECODE_H */

@@ -1,0 +1,178 @@
+"""ctypes binding of libbitdecode.so: the same entry points as include/bitdecode.h, argument
+marshalling only.  Device memory and streams come from PyTorch; every step of the path runs
+in the library's HIP kernels.  There is no fallback: if the library has not been built,
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+BD_FMT_INT4, BD_FMT_INT2, BD_FMT_MXFP4 = 0, 1, 2
+FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4}
+BLOCK = 128
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbitdecode.so")
+_lib = None
+
+
+class bd_cache(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("format", ctypes.c_int32), ("capacity", ctypes.c_int32),
+        ("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
+        ("k_params", ctypes.c_void_p), ("v_params", ctypes.c_void_p),
+        ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
+    ]
+
+
+class BitDecodeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().bd_strerror(status).decode()
+        hip = lib().bd_last_hip_error()
+        super().__init__(f"{where}: {msg} (status {status}, hip error {hip})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2503_18773_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        P, I, V, F, S = ctypes.POINTER(bd_cache), ctypes.c_int32, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
+        IP = ctypes.POINTER(ctypes.c_int32)
+        L.bd_cache_bytes.restype, L.bd_cache_bytes.argtypes = S, [P, ctypes.c_int]
+        L.bd_choose_splits.restype, L.bd_choose_splits.argtypes = I, [P, I]
+        L.bd_workspace_bytes.restype, L.bd_workspace_bytes.argtypes = S, [P, I]
+        L.bd_quant_pack_kv.restype, L.bd_quant_pack_kv.argtypes = ctypes.c_int, [P, V, V, I, IP, IP, V]
+        L.bd_append_kv.restype, L.bd_append_kv.argtypes = ctypes.c_int, [P, V, V, IP, IP, V]
+        L.bd_decode_attn.restype, L.bd_decode_attn.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V, V]
+        L.bd_splitk_combine.restype, L.bd_splitk_combine.argtypes = ctypes.c_int, [P, V, I, V, V]
+        L.bd_strerror.restype, L.bd_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.bd_last_hip_error.restype, L.bd_last_hip_error.argtypes = ctypes.c_int, []
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
+           "bd_decode_attn", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error"]
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise BitDecodeError(status, where)
+
+
+# ---- the C-ABI, one wrapper per entry point ------------------------------------------------
+
+def bd_cache_bytes(c: bd_cache, which: int) -> int:
+    return int(lib().bd_cache_bytes(ctypes.byref(c), which))
+
+
+def bd_choose_splits(c: bd_cache, packed_len: int) -> int:
+    return int(lib().bd_choose_splits(ctypes.byref(c), packed_len))
+
+
+def bd_workspace_bytes(c: bd_cache, num_splits: int) -> int:
+    return int(lib().bd_workspace_bytes(ctypes.byref(c), num_splits))
+
+
+def bd_quant_pack_kv(c: bd_cache, k, v, L: int, stream=None):
+    """Returns (packed_len, res_len)."""
+    pl, rl = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().bd_quant_pack_kv(ctypes.byref(c), _ptr(k), _ptr(v), L, ctypes.byref(pl), ctypes.byref(rl),
+                                  _stream(stream)), "bd_quant_pack_kv")
+    return pl.value, rl.value
+
+
+def bd_append_kv(c: bd_cache, k_new, v_new, packed_len: int, res_len: int, stream=None):
+    """Returns the updated (packed_len, res_len)."""
+    pl, rl = ctypes.c_int32(packed_len), ctypes.c_int32(res_len)
+    _check(lib().bd_append_kv(ctypes.byref(c), _ptr(k_new), _ptr(v_new), ctypes.byref(pl), ctypes.byref(rl),
+                              _stream(stream)), "bd_append_kv")
+    return pl.value, rl.value
+
+
+def bd_decode_attn(c: bd_cache, q, packed_len: int, res_len: int, softmax_scale: float, num_splits: int,
+                   workspace, out=None, stream=None):
+    _check(lib().bd_decode_attn(ctypes.byref(c), _ptr(q), packed_len, res_len, softmax_scale, num_splits,
+                                _ptr(workspace), _ptr(out), _stream(stream)), "bd_decode_attn")
+
+
+def bd_splitk_combine(c: bd_cache, workspace, num_splits: int, out, stream=None):
+    _check(lib().bd_splitk_combine(ctypes.byref(c), _ptr(workspace), num_splits, _ptr(out), _stream(stream)),
+           "bd_splitk_combine")
+
+
+# ---- device-memory plumbing ------------------------------------------------------------------
+
+class KVCache:
+    """Owns the six device buffers of one layer's cache as torch tensors (zero-filled) and the
+    two host-side lengths; every operation is a call into the library."""
+
+    def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, fmt: str, capacity: int, device="cuda:0"):
+        import torch
+        self.fmt = fmt
+        self.desc = bd_cache(batch, n_q_heads, n_kv_heads, 128, FORMATS[fmt], capacity, None, None, None, None,
+                             None, None)
+        sizes = [bd_cache_bytes(self.desc, i) for i in range(6)]
+        if sizes[0] == 0:
+            raise BitDecodeError(-1, "bd_cache_bytes")
+        self.buffers = [torch.zeros(max(n, 16), dtype=torch.uint8, device=device) for n in sizes]
+        for name, buf in zip(["k_codes", "v_codes", "k_params", "v_params", "k_res", "v_res"], self.buffers):
+            setattr(self.desc, name, buf.data_ptr())
+        self.sizes = sizes
+        self.packed_len = 0
+        self.res_len = 0
+        self.device = device
+        self._ws = None
+        self._ws_splits = -1
+
+    @property
+    def length(self) -> int:
+        return self.packed_len + self.res_len
+
+    def quant_pack_kv(self, k, v, stream=None):
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        self.packed_len, self.res_len = bd_quant_pack_kv(self.desc, k, v, k.shape[2], stream)
+
+    def append_kv(self, k_new, v_new, stream=None):
+        self.packed_len, self.res_len = bd_append_kv(self.desc, k_new, v_new, self.packed_len, self.res_len, stream)
+
+    def workspace(self, num_splits: int):
+        import torch
+        if self._ws_splits != num_splits:
+            self._ws = torch.empty(bd_workspace_bytes(self.desc, num_splits), dtype=torch.uint8, device=self.device)
+            self._ws_splits = num_splits
+        return self._ws
+
+    def choose_splits(self) -> int:
+        return bd_choose_splits(self.desc, self.packed_len)
+
+    def decode_attn(self, q, softmax_scale: float, out, num_splits: int | None = None, fused: bool = True,
+                    stream=None):
+        ns = self.choose_splits() if num_splits is None else num_splits
+        ws = self.workspace(ns)
+        if fused:
+            bd_decode_attn(self.desc, q, self.packed_len, self.res_len, softmax_scale, ns, ws, out, stream)
+        else:
+            bd_decode_attn(self.desc, q, self.packed_len, self.res_len, softmax_scale, ns, ws, None, stream)
+            bd_splitk_combine(self.desc, ws, ns, out, stream)
+        return out
+
+    def host_buffer(self, i: int):
+        """Buffer i copied to host as a numpy uint8 array (for bit-exact comparisons)."""
+        return self.buffers[i][:self.sizes[i]].cpu().numpy()

@@ -1,0 +1,202 @@
+// C-ABI entry points of libbitdecode.so: argument validation and kernel sequencing only.
+#include "bd_common.h"
+
+namespace bd {
+static thread_local int g_last_hip_error = 0;
+void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+}  // namespace bd
+
+using namespace bd;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bd_status check_shape(const bd_cache* c) {
+  if (!c) return BD_ERR_INVALID_ARG;
+  if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return BD_ERR_INVALID_ARG;
+  if (c->format != BD_FMT_INT4 && c->format != BD_FMT_INT2 && c->format != BD_FMT_MXFP4) return BD_ERR_INVALID_ARG;
+  if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
+  if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;
+  const int gq = c->n_q_heads / c->n_kv_heads;
+  if (gq != 1 && gq != 2 && gq != 4) return BD_ERR_UNSUPPORTED;
+  return BD_OK;
+}
+
+bd_status check_buffers(const bd_cache* c) {
+  const bool mx = c->format == BD_FMT_MXFP4;
+  const void* need[6] = {c->k_codes, c->v_codes, c->k_params, c->v_params, mx ? (void*)16 : c->k_res,
+                         mx ? (void*)16 : c->v_res};
+  for (const void* p : need) {
+    if (!p) return BD_ERR_INVALID_ARG;
+    if (!aligned16(p)) return BD_ERR_ALIGNMENT;
+  }
+  return BD_OK;
+}
+
+bd_status hip_status(hipError_t e) {
+  if (e == hipSuccess) return BD_OK;
+  note_hip_error(e);
+  return BD_ERR_HIP;
+}
+
+int bits_of(int format) { return format == BD_FMT_INT2 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+
+size_t bd_cache_bytes(const bd_cache* c, int which) {
+  if (check_shape(c) != BD_OK || which < 0 || which > 5) return 0;
+  const size_t units = (size_t)c->batch * c->n_kv_heads, cap = (size_t)c->capacity;
+  if (c->format == BD_FMT_MXFP4) {
+    switch (which) {
+      case 0: case 1: return units * cap * (kD / 2);
+      case 2: case 3: return units * cap * (kD / kMxGroup);
+      default: return 0;
+    }
+  }
+  const size_t bits = (size_t)bits_of(c->format);
+  switch (which) {
+    case 0: case 1: return units * cap * kD * bits / 8;
+    case 2: return units * (cap / kBlock) * kD * 4;
+    case 3: return units * cap * 4;
+    default: return units * kBlock * kD * 2;
+  }
+}
+
+int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
+  if (check_shape(c) != BD_OK || packed_len <= 0) return 1;
+  // Each workgroup runs 4 waves that take 128-token blocks in turn, so the natural work
+  // quantum is 4 blocks.  Aim at ~4 workgroups per compute unit (256 CUs) over all
+  // (sequence, KV head) units, then rebalance so that every split gets the same number of quanta.
+  const int units = c->batch * c->n_kv_heads;
+  const int nb = (packed_len + kBlock - 1) / kBlock;
+  const int quanta = (nb + 3) / 4;
+  int want = (1024 + units - 1) / units;
+  if (want < 1) want = 1;
+  int splits = quanta < want ? quanta : want;
+  const int per = (quanta + splits - 1) / splits;
+  splits = (quanta + per - 1) / per;
+  return splits < 1 ? 1 : splits;
+}
+
+size_t bd_workspace_bytes(const bd_cache* c, int32_t num_splits) {
+  if (check_shape(c) != BD_OK || num_splits < 1) return 0;
+  return (size_t)(num_splits + 1) * c->batch * c->n_q_heads * (kD + 2) * sizeof(float);
+}
+
+bd_status bd_quant_pack_kv(const bd_cache* c, const void* k, const void* v, int32_t L, int32_t* packed_len,
+                           int32_t* res_len, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_buffers(c)) != BD_OK) return s;
+  if (L < 0 || !packed_len || !res_len) return BD_ERR_INVALID_ARG;
+  if (L > 0 && (!k || !v)) return BD_ERR_INVALID_ARG;
+  if (L > 0 && (!aligned16(k) || !aligned16(v))) return BD_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  const int units = c->batch * c->n_kv_heads;
+  const long stride = (long)L * kD;
+  if (c->format == BD_FMT_MXFP4) {
+    if (L > c->capacity) return BD_ERR_CAPACITY;
+    if ((s = hip_status(launch_mx_quant(k, v, stride, L, units, c, 0, st))) != BD_OK) return s;
+    *packed_len = L;
+    *res_len = 0;
+    return BD_OK;
+  }
+  const int nb = L / kBlock, r = L % kBlock;
+  if (nb * kBlock > c->capacity) return BD_ERR_CAPACITY;
+  if ((s = hip_status(launch_quant_blocks(bits_of(c->format), k, v, stride, 0, nb, units, c, 0, st))) != BD_OK)
+    return s;
+  if ((s = hip_status(launch_copy_rows(k, v, stride, nb * kBlock, c->k_res, c->v_res, (long)kBlock * kD, 0, r,
+                                       units, st))) != BD_OK)
+    return s;
+  *packed_len = nb * kBlock;
+  *res_len = r;
+  return BD_OK;
+}
+
+bd_status bd_append_kv(const bd_cache* c, const void* k_new, const void* v_new, int32_t* packed_len,
+                       int32_t* res_len, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_buffers(c)) != BD_OK) return s;
+  if (!k_new || !v_new || !packed_len || !res_len) return BD_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new)) return BD_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  const int units = c->batch * c->n_kv_heads;
+  if (c->format == BD_FMT_MXFP4) {
+    if (*packed_len < 0 || *res_len != 0) return BD_ERR_INVALID_ARG;
+    if (*packed_len + 1 > c->capacity) return BD_ERR_CAPACITY;
+    if ((s = hip_status(launch_mx_quant(k_new, v_new, (long)kD, 1, units, c, *packed_len, st))) != BD_OK) return s;
+    *packed_len += 1;
+    return BD_OK;
+  }
+  const int pl = *packed_len, r = *res_len;
+  if (pl < 0 || pl % kBlock != 0 || r < 0 || r >= kBlock || pl > c->capacity) return BD_ERR_INVALID_ARG;
+  const bool flush = r == kBlock - 1;
+  if (flush && pl + kBlock > c->capacity) return BD_ERR_CAPACITY;
+  if ((s = hip_status(launch_copy_rows(k_new, v_new, (long)kD, 0, c->k_res, c->v_res, (long)kBlock * kD, r, 1, units,
+                                       st))) != BD_OK)
+    return s;
+  if (flush) {
+    // The residual block is full: quantize and pack it as packed block pl/128 (Sec. IV-B(1)).
+    if ((s = hip_status(launch_quant_blocks(bits_of(c->format), c->k_res, c->v_res, (long)kBlock * kD, 0, 1, units, c,
+                                            pl / kBlock, st))) != BD_OK)
+      return s;
+    *packed_len = pl + kBlock;
+    *res_len = 0;
+  } else {
+    *res_len = r + 1;
+  }
+  return BD_OK;
+}
+
+bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, int32_t res_len, float softmax_scale,
+                         int32_t num_splits, void* workspace, void* out, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_buffers(c)) != BD_OK) return s;
+  if (!q || !workspace || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(workspace) || (out && !aligned16(out))) return BD_ERR_ALIGNMENT;
+  if (packed_len < 0 || packed_len > c->capacity) return BD_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  float* part_o = ws_part_o(workspace);
+  float* part_ml = ws_part_ml(c, workspace, num_splits);
+  if (c->format == BD_FMT_MXFP4) {
+    if (res_len != 0) return BD_ERR_INVALID_ARG;
+    s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, st));
+  } else {
+    if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
+    s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, st));
+  }
+  if (s != BD_OK) return s;
+  if (out) s = hip_status(launch_combine(c, part_o, part_ml, num_splits + 1, out, st));
+  return s;
+}
+
+bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t num_splits, void* out, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if (!workspace || !out || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
+  if (!aligned16(workspace) || !aligned16(out)) return BD_ERR_ALIGNMENT;
+  void* ws = const_cast<void*>(workspace);
+  return hip_status(launch_combine(c, ws_part_o(ws), ws_part_ml(c, ws, num_splits), num_splits + 1, out,
+                                   (hipStream_t)stream));
+}
+
+const char* bd_strerror(bd_status s) {
+  switch (s) {
+    case BD_OK: return "ok";
+    case BD_ERR_INVALID_ARG: return "invalid argument";
+    case BD_ERR_UNSUPPORTED: return "unsupported shape";
+    case BD_ERR_ALIGNMENT: return "device pointer not 16-byte aligned";
+    case BD_ERR_CAPACITY: return "cache capacity exceeded";
+    case BD_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int bd_last_hip_error(void) { return bd::g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Shared declarations of the HIP sources of libbitdecode.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bitdecode.h"
+
+namespace bd {
+
+constexpr int kD = 128;       // head_dim
+constexpr int kBlock = 128;   // residual block N_r (Eq. 1) == quantization group
+constexpr int kMxGroup = 32;  // elements per MX block
+
+typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u2_t __attribute__((ext_vector_type(2)));
+typedef int i8_t __attribute__((ext_vector_type(8)));
+
+// Records a failing HIP call for bd_last_hip_error().
+void note_hip_error(hipError_t e);
+
+// Kernel launchers (host side, defined next to their kernels).  All return hipError_t of
+// the launch.  `units` = batch * n_kv_heads.
+hipError_t launch_quant_blocks(int bits, const void* k, const void* v, long src_unit_stride,
+                               int src_tok0, int nblocks, int units, const bd_cache* c,
+                               int dst_blk0, hipStream_t st);
+hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0,
+                            void* kdst, void* vdst, long dst_unit_stride, int dst_tok0, int ntok,
+                            int units, hipStream_t st);
+hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, int ntok, int units,
+                           const bd_cache* c, int dst_tok0, hipStream_t st);
+
+hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,
+                             float softmax_scale, int num_splits, float* part_o, float* part_ml,
+                             hipStream_t st);
+hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale,
+                            int num_splits, float* part_o, float* part_ml, hipStream_t st);
+hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* part_ml, int nparts,
+                          void* out, hipStream_t st);
+
+static inline float* ws_part_o(void* ws) { return reinterpret_cast<float*>(ws); }
+static inline float* ws_part_ml(const bd_cache* c, void* ws, int num_splits) {
+  return reinterpret_cast<float*>(ws) + (size_t)(num_splits + 1) * c->batch * c->n_q_heads * kD;
+}
+
+}  // namespace bd

@@ -1,0 +1,350 @@
+// Online quantize-and-pack kernels: the quantize half of the paper's Residual Kernel
+// (Sec. IV-B) and the prefill quantization (Sec. IV-B(1)).
+//
+// Bit-exactness contract: every stored scale, zero and code is the result of IEEE fp32
+// subtract / divide / round-half-even in a fixed order, so contraction into FMAs is switched
+// off for this file and no fast-math substitution is allowed.
+#include "bd_common.h"
+
+#pragma clang fp contract(off)
+
+namespace bd {
+namespace {
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t b) {
+  _Float16 h;
+  __builtin_memcpy(&h, &b, 2);
+  return (float)h;
+}
+__device__ __forceinline__ uint16_t float_to_half_bits(float f) {
+  _Float16 h = (_Float16)f;  // round to nearest even, subnormals kept
+  uint16_t b;
+  __builtin_memcpy(&b, &h, 2);
+  return b;
+}
+
+// scale / zero of one group from its minimum and maximum (fp16 values held in fp32).
+__device__ __forceinline__ void group_params(float mn, float mx, int qmax, float& scale_f, float& zero_f,
+                                             uint32_t& packed) {
+  zero_f = mn + 0.0f;  // -0 -> +0
+  float s = (mx - mn) / (float)qmax;
+  uint16_t sb = float_to_half_bits(s);
+  scale_f = half_bits_to_float(sb);
+  packed = (uint32_t)sb | ((uint32_t)float_to_half_bits(zero_f) << 16);
+}
+
+__device__ __forceinline__ uint32_t quant_code(float x, float scale_f, float zero_f, int qmax) {
+  if (scale_f == 0.0f) return 0u;
+  float q = rintf((x - zero_f) / scale_f);
+  q = fminf(fmaxf(q, 0.0f), (float)qmax);
+  return (uint32_t)q;
+}
+
+// One workgroup quantizes one 128-token block of one (batch, kv_head): K channel-wise
+// (statistics over the block's tokens), V per token (statistics over the 128 channels).
+// Thread-local min/max first, then wave shuffles, then a small LDS buffer across waves:
+// the reduction ladder of Sec. IV-B(2).
+template <int BITS>
+__global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __restrict__ ksrc,
+                                                           const uint16_t* __restrict__ vsrc,
+                                                           long src_unit_stride, int src_tok0,
+                                                           uint32_t* __restrict__ k_codes,
+                                                           uint32_t* __restrict__ v_codes,
+                                                           uint32_t* __restrict__ k_params,
+                                                           uint32_t* __restrict__ v_params, int nbcap,
+                                                           int dst_blk0) {
+  constexpr int QMAX = (1 << BITS) - 1;
+  constexpr int CPT = 32 / BITS;     // channels per thread == codes per word
+  constexpr int TPR = kD / CPT;      // threads per token row == K words per token
+  constexpr int RPP = 256 / TPR;     // rows per pass
+  constexpr int NP = kBlock / RPP;   // passes
+  constexpr int WPC = kBlock / CPT;  // V words per channel
+  constexpr int PITCH = kD + 4;      // padded byte pitch of the code tile
+
+  __shared__ float red[2][4][kD];
+  __shared__ uint8_t tile[kBlock * PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tr = tid / TPR, tc = tid % TPR;
+  const int unit = blockIdx.y, blk = blockIdx.x;
+  const size_t dblk = (size_t)unit * nbcap + dst_blk0 + blk;
+  const size_t src_off = (size_t)unit * src_unit_stride + ((size_t)src_tok0 + (size_t)blk * kBlock) * kD;
+
+  // ---- K: load, per-channel min/max over the 128 tokens
+  float x[NP][CPT];
+  {
+    const uint16_t* src = ksrc + src_off;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const uint16_t* rp = src + (size_t)(p * RPP + tr) * kD + tc * CPT;
+#pragma unroll
+      for (int v = 0; v < CPT / 8; ++v) {
+        u4_t raw = *reinterpret_cast<const u4_t*>(rp + 8 * v);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          x[p][8 * v + 2 * e] = half_bits_to_float((uint16_t)(raw[e] & 0xFFFFu));
+          x[p][8 * v + 2 * e + 1] = half_bits_to_float((uint16_t)(raw[e] >> 16));
+        }
+      }
+    }
+  }
+  float mn[CPT], mx[CPT];
+#pragma unroll
+  for (int cc = 0; cc < CPT; ++cc) {
+    float a = x[0][cc], b = x[0][cc];
+#pragma unroll
+    for (int p = 1; p < NP; ++p) {
+      a = fminf(a, x[p][cc]);
+      b = fmaxf(b, x[p][cc]);
+    }
+#pragma unroll
+    for (int off = TPR; off < 64; off <<= 1) {  // lanes holding the same channels
+      a = fminf(a, __shfl_xor(a, off));
+      b = fmaxf(b, __shfl_xor(b, off));
+    }
+    mn[cc] = a;
+    mx[cc] = b;
+  }
+  if (lane < TPR) {
+#pragma unroll
+    for (int cc = 0; cc < CPT; ++cc) {
+      red[0][wave][tc * CPT + cc] = mn[cc];
+      red[1][wave][tc * CPT + cc] = mx[cc];
+    }
+  }
+  __syncthreads();
+  float ks[CPT], kz[CPT];
+#pragma unroll
+  for (int cc = 0; cc < CPT; ++cc) {
+    const int ch = tc * CPT + cc;
+    float a = fminf(fminf(red[0][0][ch], red[0][1][ch]), fminf(red[0][2][ch], red[0][3][ch]));
+    float b = fmaxf(fmaxf(red[1][0][ch], red[1][1][ch]), fmaxf(red[1][2][ch], red[1][3][ch]));
+    uint32_t packed;
+    group_params(a, b, QMAX, ks[cc], kz[cc], packed);
+    if (tr == 0) k_params[dblk * kD + ch] = packed;
+  }
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int cc = 0; cc < CPT; ++cc) w |= quant_code(x[p][cc], ks[cc], kz[cc], QMAX) << (BITS * cc);
+    k_codes[(dblk * kBlock + (size_t)(p * RPP + tr)) * TPR + tc] = w;
+  }
+
+  // ---- V: load, per-token min/max over the 128 channels
+  {
+    const uint16_t* src = vsrc + src_off;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const uint16_t* rp = src + (size_t)(p * RPP + tr) * kD + tc * CPT;
+#pragma unroll
+      for (int v = 0; v < CPT / 8; ++v) {
+        u4_t raw = *reinterpret_cast<const u4_t*>(rp + 8 * v);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          x[p][8 * v + 2 * e] = half_bits_to_float((uint16_t)(raw[e] & 0xFFFFu));
+          x[p][8 * v + 2 * e + 1] = half_bits_to_float((uint16_t)(raw[e] >> 16));
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    float a = x[p][0], b = x[p][0];
+#pragma unroll
+    for (int cc = 1; cc < CPT; ++cc) {
+      a = fminf(a, x[p][cc]);
+      b = fmaxf(b, x[p][cc]);
+    }
+#pragma unroll
+    for (int off = 1; off < TPR; off <<= 1) {  // the TPR consecutive lanes of this token row
+      a = fminf(a, __shfl_xor(a, off));
+      b = fmaxf(b, __shfl_xor(b, off));
+    }
+    float vs, vz;
+    uint32_t packed;
+    group_params(a, b, QMAX, vs, vz, packed);
+    const int row = p * RPP + tr;
+    if (tc == 0) v_params[dblk * kBlock + row] = packed;
+#pragma unroll
+    for (int cc = 0; cc < CPT; ++cc)
+      tile[row * PITCH + tc * CPT + cc] = (uint8_t)quant_code(x[p][cc], vs, vz, QMAX);
+  }
+  __syncthreads();
+  // pack along tokens: word w of channel c holds block tokens CPT*w .. CPT*w+CPT-1
+  for (int id = tid; id < kD * WPC; id += 256) {
+    const int ch = id / WPC, w = id % WPC;
+    uint32_t word = 0;
+#pragma unroll
+    for (int n = 0; n < CPT; ++n) word |= (uint32_t)tile[(CPT * w + n) * PITCH + ch] << (BITS * n);
+    v_codes[dblk * (size_t)(kD * WPC) + id] = word;
+  }
+}
+
+// Copies `ntok` token rows of K and of V between [unit][token][128] arrays of 16-bit values.
+__global__ __launch_bounds__(256) void copy_rows_kernel(const u4_t* __restrict__ ksrc,
+                                                         const u4_t* __restrict__ vsrc, long src_unit_stride,
+                                                         int src_tok0, u4_t* __restrict__ kdst,
+                                                         u4_t* __restrict__ vdst, long dst_unit_stride,
+                                                         int dst_tok0, int ntok) {
+  const int unit = blockIdx.x;
+  const size_t so = ((size_t)unit * src_unit_stride + (size_t)src_tok0 * kD) / 8;
+  const size_t dn = ((size_t)unit * dst_unit_stride + (size_t)dst_tok0 * kD) / 8;
+  const int n = ntok * (kD / 8);
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    kdst[dn + i] = ksrc[so + i];
+    vdst[dn + i] = vsrc[so + i];
+  }
+}
+
+// ---- MXFP4 -------------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Shared exponent of an MX block from its largest magnitude (> 0): floor(log2(amax)) - 2,
+// clamped to [-127, 127].  A subnormal amax has exponent field 0 and clamps to -127.
+__device__ __forceinline__ int mx_shared_exp(float amax) {
+  int ef = (int)((__float_as_uint(amax) >> 23) & 0xFFu);
+  int e = ef - 127 - 2;
+  return e < -127 ? -127 : e;
+}
+
+// Nearest e2m1 code of x / 2^e: ties to the even code, saturation at 6, no negative zero.
+__device__ __forceinline__ uint32_t e2m1_code(float x, int e) {
+  float a = fabsf(ldexpf(x, -e));
+  uint32_t idx = a <= 0.25f ? 0u : a < 0.75f ? 1u : a <= 1.25f ? 2u : a < 1.75f ? 3u
+               : a <= 2.5f ? 4u : a < 3.5f ? 5u : a <= 5.0f ? 6u : 7u;
+  return (x < 0.0f && idx != 0u) ? (idx | 8u) : idx;
+}
+
+// One workgroup quantizes up to 128 tokens (one V block) of one (batch, kv_head).
+// Thread t handles token t: 4 MX groups of K and of V.  K codes go out token-major;
+// V codes pass through an LDS tile to be written channel-major, two tokens per byte.
+// When `single` (decode append of one token) the V bytes are updated nibble-wise.
+__global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restrict__ ksrc,
+                                                        const uint16_t* __restrict__ vsrc,
+                                                        long src_unit_stride, int ntok,
+                                                        uint8_t* __restrict__ k_codes,
+                                                        uint8_t* __restrict__ k_scales,
+                                                        uint8_t* __restrict__ v_codes,
+                                                        uint8_t* __restrict__ v_scales, int capacity,
+                                                        int dst_tok0) {
+  constexpr int PITCH = kD + 4;
+  __shared__ uint8_t tile[kBlock * PITCH];
+  const int unit = blockIdx.y;
+  // this workgroup covers destination tokens [t_lo, t_hi) of block `dblk`
+  const int first_blk = dst_tok0 / kBlock;
+  const int dblk = first_blk + blockIdx.x;
+  const int t_lo = max(dblk * kBlock, dst_tok0);
+  const int t_hi = min((dblk + 1) * kBlock, dst_tok0 + ntok);
+  const int t = dblk * kBlock + threadIdx.x;  // destination token of this thread
+  const bool live = t >= t_lo && t < t_hi;
+
+  if (live) {
+    const size_t so = (size_t)unit * src_unit_stride + (size_t)(t - dst_tok0) * kD;
+    const size_t tok = (size_t)unit * capacity + t;
+#pragma unroll 1
+    for (int which = 0; which < 2; ++which) {
+      const uint16_t* src = (which == 0 ? ksrc : vsrc) + so;
+      uint32_t scale_word = 0;
+#pragma unroll 1
+      for (int g = 0; g < kD / kMxGroup; ++g) {
+        float xv[kMxGroup];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          u4_t raw = *reinterpret_cast<const u4_t*>(src + g * kMxGroup + 8 * v);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            xv[8 * v + 2 * e] = bf16_bits_to_float((uint16_t)(raw[e] & 0xFFFFu));
+            xv[8 * v + 2 * e + 1] = bf16_bits_to_float((uint16_t)(raw[e] >> 16));
+          }
+        }
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kMxGroup; ++i) amax = fmaxf(amax, fabsf(xv[i]));
+        int e = 0;
+        if (amax > 0.0f) e = mx_shared_exp(amax);
+        scale_word |= (uint32_t)(e + 127) << (8 * g);
+        if (which == 0) {
+          u4_t out;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int n = 0; n < 8; ++n)
+              word |= (amax > 0.0f ? e2m1_code(xv[8 * w + n], e) : 0u) << (4 * n);
+            out[w] = word;
+          }
+          *reinterpret_cast<u4_t*>(k_codes + tok * (kD / 2) + g * 16) = out;
+        } else {
+#pragma unroll
+          for (int i = 0; i < kMxGroup; ++i)
+            tile[threadIdx.x * PITCH + g * kMxGroup + i] =
+                (uint8_t)(amax > 0.0f ? e2m1_code(xv[i], e) : 0u);
+        }
+      }
+      *reinterpret_cast<uint32_t*>((which == 0 ? k_scales : v_scales) + tok * 4) = scale_word;
+    }
+  }
+  __syncthreads();
+  // V codes, channel-major: byte j of channel c holds block tokens 2j (low), 2j+1 (high).
+  uint8_t* vrow = v_codes + ((size_t)unit * (capacity / kBlock) + dblk) * (size_t)(kD * 64);
+  const int j_lo = (t_lo - dblk * kBlock) / 2, j_hi = (t_hi - dblk * kBlock + 1) / 2;
+  for (int id = threadIdx.x; id < kD * 64; id += 128) {
+    const int ch = id / 64, j = id % 64;
+    if (j < j_lo || j >= j_hi) continue;
+    const int ta = dblk * kBlock + 2 * j, tb = ta + 1;
+    uint8_t old = 0;
+    const bool a_new = ta >= t_lo && ta < t_hi, b_new = tb >= t_lo && tb < t_hi;
+    if (!(a_new && b_new)) old = vrow[id];       // keep the nibble of a token not in this call
+    uint8_t lo = a_new ? tile[(2 * j) * PITCH + ch] : (uint8_t)(old & 0x0F);
+    uint8_t hi = b_new ? tile[(2 * j + 1) * PITCH + ch] : (uint8_t)(old >> 4);
+    // a token beyond the current end of the cache has never been written: store 0 for it
+    if (!b_new && tb >= t_hi) hi = 0;
+    vrow[id] = (uint8_t)(lo | (hi << 4));
+  }
+}
+
+}  // namespace
+
+hipError_t launch_quant_blocks(int bits, const void* k, const void* v, long src_unit_stride, int src_tok0,
+                               int nblocks, int units, const bd_cache* c, int dst_blk0, hipStream_t st) {
+  if (nblocks <= 0) return hipSuccess;
+  dim3 grid(nblocks, units), block(256);
+  const int nbcap = c->capacity / kBlock;
+  if (bits == 4)
+    quant_block_kernel<4><<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride,
+                                                   src_tok0, (uint32_t*)c->k_codes, (uint32_t*)c->v_codes,
+                                                   (uint32_t*)c->k_params, (uint32_t*)c->v_params, nbcap,
+                                                   dst_blk0);
+  else
+    quant_block_kernel<2><<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride,
+                                                   src_tok0, (uint32_t*)c->k_codes, (uint32_t*)c->v_codes,
+                                                   (uint32_t*)c->k_params, (uint32_t*)c->v_params, nbcap,
+                                                   dst_blk0);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0, void* kdst,
+                            void* vdst, long dst_unit_stride, int dst_tok0, int ntok, int units,
+                            hipStream_t st) {
+  if (ntok <= 0) return hipSuccess;
+  const int threads = ntok * (kD / 8) >= 256 ? 256 : 64;
+  copy_rows_kernel<<<dim3(units), dim3(threads), 0, st>>>((const u4_t*)ksrc, (const u4_t*)vsrc,
+                                                          src_unit_stride, src_tok0, (u4_t*)kdst, (u4_t*)vdst,
+                                                          dst_unit_stride, dst_tok0, ntok);
+  return hipGetLastError();
+}
+
+hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, int ntok, int units,
+                           const bd_cache* c, int dst_tok0, hipStream_t st) {
+  if (ntok <= 0) return hipSuccess;
+  const int first_blk = dst_tok0 / kBlock, last_blk = (dst_tok0 + ntok - 1) / kBlock;
+  dim3 grid(last_blk - first_blk + 1, units), block(128);
+  mx_quant_kernel<<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride, ntok,
+                                          (uint8_t*)c->k_codes, (uint8_t*)c->k_params, (uint8_t*)c->v_codes,
+                                          (uint8_t*)c->v_params, c->capacity, dst_tok0);
+  return hipGetLastError();
+}
+
+}  // namespace bd

@@ -1,0 +1,100 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and
+validates arguments before touching the GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_18773_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+needs_lib = pytest.mark.skipif(not os.path.exists(B._LIB_PATH), reason="libbitdecode.so not built")
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bitdecode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bd_[a-z_0-9]+)\s*\(", text)))
+
+
+@needs_lib
+def test_every_declared_symbol_is_exported():
+    names = _declared_symbols()
+    assert sorted(B.EXPORTS) == names
+    for n in names:
+        assert hasattr(B.lib(), n), n
+
+
+def _desc(**kw):
+    d = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, format=B.BD_FMT_INT4, capacity=32768)
+    d.update(kw)
+    return B.bd_cache(d["batch"], d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["format"], d["capacity"],
+                      None, None, None, None, None, None)
+
+
+@needs_lib
+def test_cache_bytes_match_the_format():
+    c = _desc()
+    units, cap = 8, 32768
+    assert [B.bd_cache_bytes(c, i) for i in range(6)] == [
+        units * cap * 64, units * cap * 64, units * (cap // 128) * 128 * 4, units * cap * 4,
+        units * 128 * 128 * 2, units * 128 * 128 * 2]
+    c2 = _desc(format=B.BD_FMT_INT2)
+    assert B.bd_cache_bytes(c2, 0) == units * cap * 32 and B.bd_cache_bytes(c2, 3) == units * cap * 4
+    c4 = _desc(format=B.BD_FMT_MXFP4, batch=16, capacity=16384)
+    assert [B.bd_cache_bytes(c4, i) for i in range(6)] == [128 * 16384 * 64, 128 * 16384 * 64, 128 * 16384 * 4,
+                                                          128 * 16384 * 4, 0, 0]
+    # 136 / 72 / 136 bytes per token per KV head
+    for c_, per in [(c, 136), (c2, 72)]:
+        assert sum(B.bd_cache_bytes(c_, i) for i in range(4)) == per * units * cap
+    assert B.bd_cache_bytes(_desc(head_dim=64), 0) == 0
+    assert B.bd_cache_bytes(c, 6) == 0
+
+
+@needs_lib
+def test_split_heuristic_and_workspace():
+    c = _desc()
+    for L in (0, 128, 1024, 32768, 131072):
+        s = B.bd_choose_splits(c, L)
+        assert 1 <= s <= max(1, L // 128)
+    assert B.bd_workspace_bytes(c, 64) == 65 * 32 * 130 * 4
+    assert B.bd_workspace_bytes(c, 0) == 0
+
+
+@needs_lib
+def test_argument_validation_happens_before_any_launch():
+    L = B.lib()
+    c = _desc()
+    pl, rl = ctypes.c_int32(0), ctypes.c_int32(0)
+    # NULL cache buffers
+    assert L.bd_quant_pack_kv(ctypes.byref(c), None, None, 128, ctypes.byref(pl), ctypes.byref(rl), None) == -1
+    c.k_codes = c.v_codes = c.k_params = c.v_params = c.k_res = c.v_res = 4096
+    assert L.bd_quant_pack_kv(ctypes.byref(c), None, None, 128, ctypes.byref(pl), ctypes.byref(rl), None) == -1
+    assert L.bd_quant_pack_kv(ctypes.byref(c), 4096, 4096, -1, ctypes.byref(pl), ctypes.byref(rl), None) == -1
+    assert L.bd_quant_pack_kv(ctypes.byref(c), 4096, 4100, 128, ctypes.byref(pl), ctypes.byref(rl), None) == -3
+    assert L.bd_quant_pack_kv(ctypes.byref(c), 4096, 4096, 32768 + 128, ctypes.byref(pl), ctypes.byref(rl),
+                              None) == -4
+    # append that would overflow the packed buffers leaves the lengths alone
+    pl, rl = ctypes.c_int32(32768), ctypes.c_int32(127)
+    assert L.bd_append_kv(ctypes.byref(c), 4096, 4096, ctypes.byref(pl), ctypes.byref(rl), None) == -4
+    assert (pl.value, rl.value) == (32768, 127)
+    pl, rl = ctypes.c_int32(100), ctypes.c_int32(0)
+    assert L.bd_append_kv(ctypes.byref(c), 4096, 4096, ctypes.byref(pl), ctypes.byref(rl), None) == -1
+    # decode: bad split count, bad lengths, misaligned workspace
+    assert L.bd_decode_attn(ctypes.byref(c), 4096, 1024, 0, 0.1, 0, 4096, 4096, None) == -1
+    assert L.bd_decode_attn(ctypes.byref(c), 4096, 1000, 0, 0.1, 4, 4096, 4096, None) == -1
+    assert L.bd_decode_attn(ctypes.byref(c), 4096, 1024, 128, 0.1, 4, 4096, 4096, None) == -1
+    assert L.bd_decode_attn(ctypes.byref(c), 4096, 1024, 0, 0.1, 4, 4100, 4096, None) == -3
+    assert L.bd_splitk_combine(ctypes.byref(c), None, 4, 4096, None) == -1
+    # shapes this build has no kernel for
+    bad = _desc(n_q_heads=64)
+    assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
+    assert L.bd_strerror(-4) == b"cache capacity exceeded"
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "_LIB_PATH", "/nonexistent/libbitdecode.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()

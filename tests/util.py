@@ -1,0 +1,31 @@
+"""Helpers shared by the GPU parity tests: host<->device conversion and error metrics."""
+import numpy as np
+
+MAX_ABS_TOL = 2e-3     # attention output: max-abs error against the float64 oracle
+REL_L2_TOL = 1e-3      # attention output: relative L2 error against the float64 oracle
+
+
+def to_dev(x: np.ndarray, in_dtype: str):
+    """numpy fp16 array, or float32 array of bf16 values, -> torch tensor on cuda:0."""
+    import torch
+    from paper_2503_18773_amd import workloads as W
+    if in_dtype == "fp16":
+        return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    bits = W.bf16_bits(x)
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def out_to_f64(t) -> np.ndarray:
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def attn_errors(got: np.ndarray, ref: np.ndarray):
+    d = got - ref
+    return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-30))
+
+
+def assert_attn_close(got: np.ndarray, ref: np.ndarray, what=""):
+    mask = ~np.isnan(ref)
+    ma, rl = attn_errors(got[mask], ref[mask])
+    assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
+    return ma, rl
