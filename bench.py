@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-step hot path (append + attention over the packed KV cache).
+
+One "step" = one decode step of a LLaMA-3.1-8B-shaped model: 32 layers, each issuing
+bd_append_kv and bd_decode_attn (split-K + combine) on its own, independent cache, back to
+back on one stream.  Thirty-two distinct caches keep the working set (> 1 GB) far above the
+256 MB last-level cache, so every step streams its KV bytes from HBM.
+
+Prints ONE JSON line (see README for the fields).  value = effective KV GB/s:
+algorithmic bytes of the attention calls of a step / wall time of the step.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+N_LAYERS = 32
+
+
+def algorithmic_bytes(w, packed_len: int, res_len: int) -> int:
+    """Bytes one attention call must move: packed K and V codes, their parameters, the
+    residual fp16 tokens present, the query and the output."""
+    units = w.batch * w.n_kv_heads
+    per_tok = {"int4": 136, "int2": 72, "mxfp4": 136}[w.fmt]
+    qo = 2 * w.batch * w.n_q_heads * w.head_dim * 2
+    return units * (packed_len * per_tok + res_len * w.head_dim * 2 * 2) + qo
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg1", help="cfg1 (32K int4, default), cfg3 (128K int4), cfg2, cfg0")
+    ap.add_argument("--layers", type=int, default=N_LAYERS)
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+                    help="graph: the warm-up steps and the timed steps are each captured into one HIP graph "
+                         "(every step distinct) so host launch cost is out of the timed region; eager: plain calls")
+    ap.add_argument("--splits", type=int, default=0, help="override the library's split factor")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (the path shards by batch / KV head / "
+              "context, see DESIGN.md, but no multi-GPU code exists)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2503_18773_amd import binding as B
+    from paper_2503_18773_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()  # fail loudly if the HIP library is missing
+    w = W.CONFIGS[args.workload]
+    total_steps = args.warmup + args.steps
+    cap = ((w.context + total_steps + 1 + 127) // 128) * 128 + 128
+    tdt = torch.float16 if w.in_dtype == "fp16" else torch.bfloat16
+
+    def dev(x):
+        if w.in_dtype == "fp16":
+            return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        return torch.from_numpy(W.bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+    # ---- synthetic inputs, resident in HBM before anything is timed
+    t_setup = time.time()
+    K, V = W.make_kv(w)
+    Kd, Vd = dev(K), dev(V)
+    caches = []
+    for _ in range(args.layers):
+        c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, cap)
+        c.quant_pack_kv(Kd, Vd)
+        caches.append(c)
+    torch.cuda.synchronize()
+    # prefill quantize+pack time of one layer (reported, not part of the step)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); caches[0].quant_pack_kv(Kd, Vd); e1.record(); torch.cuda.synchronize()
+    prefill_ms = e0.elapsed_time(e1)
+    del Kd, Vd
+    new_kv = [tuple(dev(x) for x in W.make_new_kv(w, s)) for s in range(total_steps)]
+    qs = [dev(W.make_q(w, s)) for s in range(total_steps)]
+    outs = [torch.empty((w.batch, w.n_q_heads, 128), dtype=tdt, device="cuda:0") for _ in range(args.layers)]
+    sm_scale = W.softmax_scale(w)
+    splits = args.splits or caches[0].choose_splits()
+    for c in caches:
+        c.workspace(splits)
+    setup_s = time.time() - t_setup
+
+    step_bytes = []
+
+    def run_step(s: int):
+        kn, vn = new_kv[s]
+        nbytes = 0
+        for li, c in enumerate(caches):
+            c.append_kv(kn, vn)
+            c.decode_attn(qs[s], sm_scale, outs[li], num_splits=splits)
+            nbytes += algorithmic_bytes(w, c.packed_len, c.res_len)
+        step_bytes.append(nbytes)
+
+    stream = torch.cuda.current_stream()
+    if args.mode == "graph":
+        g_warm, g_timed = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        if args.warmup:
+            with torch.cuda.graph(g_warm):
+                for s in range(args.warmup):
+                    run_step(s)
+        with torch.cuda.graph(g_timed):
+            for s in range(args.warmup, total_steps):
+                run_step(s)
+        if args.warmup:
+            g_warm.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g_timed.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        for s in range(args.warmup):
+            run_step(s)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.warmup, total_steps):
+            run_step(s)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    elapsed = t1 - t0
+    timed_bytes = sum(step_bytes[args.warmup:])
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = timed_bytes / elapsed / 1e9
+
+    # ---- roofline of the dominant kernel (decode attention), measured live with events:
+    # one event pair around each bd_decode_attn launch (partials only, no combine), all 32
+    # layers enqueued back to back on the stream the kernels run on.
+    c0 = caches[0]
+    reps = 3
+    pairs = []
+    for _ in range(reps):
+        for li, c in enumerate(caches):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            B.bd_decode_attn(c.desc, qs[-1], c.packed_len, c.res_len, sm_scale, splits, c.workspace(splits), None)
+            b.record(stream)
+            pairs.append((a, b))
+    torch.cuda.synchronize()
+    durs = np.array([a.elapsed_time(b) * 1e3 for a, b in pairs[len(caches):]])   # us, first rep dropped
+    kernel_us = float(durs.mean())
+    launch_bytes = algorithmic_bytes(w, c0.packed_len, c0.res_len)
+    achieved = launch_bytes / (kernel_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_int_kernel" if w.fmt != "mxfp4" else "decode_mx_kernel",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(durs.min()), 3),
+                "bytes_per_launch": launch_bytes, "timing": "hip events around each launch, 32 cold caches in turn"}
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_limits
+        from oracle import bitdecode_oracle as O
+        n_units = 1 if w.context > 40000 else 2
+        with threadpool_limits(limits=1):
+            if w.fmt == "mxfp4":
+                oc = O.MxCache(1, n_units, cap)
+            else:
+                oc = O.IntCache(1, n_units, 4 if w.fmt == "int4" else 2, cap)
+            oc.quant_pack_kv(K[:1, :n_units], V[:1, :n_units])          # untimed: prefill
+            kn, vn = W.make_new_kv(w, 0)
+            q0 = W.make_q(w, 0)[:1, :n_units * w.g_q]
+            tc0 = time.perf_counter()
+            oc.append_kv(kn[:1, :n_units], vn[:1, :n_units])
+            O.decode_attn(oc, q0, sm_scale)
+            tc1 = time.perf_counter()
+        sample_bytes = n_units * (oc.packed_len * {"int4": 136, "int2": 72, "mxfp4": 136}[w.fmt]
+                                  + getattr(oc, "res_len", 0) * 512) + 2 * n_units * w.g_q * 256
+        cpu = {"value": round(sample_bytes / (tc1 - tc0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "seconds": round(tc1 - tc0, 3),
+               "sample": f"one decode step (append + attention) of {n_units} of the {w.batch * w.n_kv_heads} "
+                         f"(sequence, KV head) units of one layer at context {w.context}; numpy float64, 1 thread"}
+
+    rec = {
+        "metric": "effective KV GB/s per decode step (32-layer LLaMA-8B-shape step: append + split-K attention "
+                  "over the packed cache)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"int4": "u4->f16 mfma, f32 accumulate", "int2": "u2->f16 mfma, f32 accumulate",
+                  "mxfp4": "e2m1 mfma, f32 accumulate"}[w.fmt],
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads}/{w.n_kv_heads} heads, head_dim 128, "
+                               f"context {w.context}, {w.fmt} KV", "layers": args.layers, "mode": args.mode,
+                   "num_splits": splits},
+        "us_per_layer_call": round(ms_per_step * 1e3 / args.layers, 3),
+        "us_per_decode_step": round(ms_per_step * 1e3, 2),
+        "pct_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "prefill_quant_pack_ms_per_layer": round(prefill_ms, 4),
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(rec))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -88,9 +88,9 @@ size_t bd_cache_bytes(const bd_cache* c, int which);
  * over the context (the "split-partitioned" scheme named in Sec. V-A). */
 int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len);
 
-/* Bytes of device workspace bd_decode_attn needs for `num_splits`: (num_splits + 1)
- * partial results (one extra for the residual tail), each batch*n_q_heads*(128 + 2)
- * floats (unnormalised output row, running max in log2 units, running sum). */
+/* Bytes of device workspace bd_decode_attn needs for `num_splits`: num_splits partial
+ * results, each batch*n_q_heads*(128 + 2) floats (unnormalised output row, running max
+ * in log2 units, running sum).  The residual tokens are shared out over the splits. */
 size_t bd_workspace_bytes(const bd_cache* c, int32_t num_splits);
 
 /* Prefill (Sec. IV-B(1)): quantize and pack the first L - (L mod 128) tokens of
@@ -115,7 +115,7 @@ bd_status bd_append_kv(const bd_cache* c, const void* k_new, const void* v_new,
  * dequantize + QK^T + online softmax (Alg. 1) + PV; split over the context):
  * q device [B][n_q_heads][D] (fp16; bf16 for MXFP4); query head h attends KV head h / g_q
  * over the packed_len quantized tokens and the res_len residual tokens, logits scaled by
- * softmax_scale.  Writes num_splits + 1 partials into `workspace` (device, at least
+ * softmax_scale.  Writes num_splits partials into `workspace` (device, at least
  * bd_workspace_bytes(c, num_splits), 16-byte aligned).  If `out` is non-NULL (device,
  * [B][n_q_heads][D], fp16 / bf16) the merge of the partials is enqueued too, so `out`
  * is complete when the stream passes this call; if NULL, call bd_splitk_combine.
@@ -125,7 +125,7 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
                          float softmax_scale, int32_t num_splits, void* workspace, void* out,
                          void* stream);
 
-/* Merge the num_splits + 1 partials left in `workspace` by bd_decode_attn (log-sum-exp
+/* Merge the num_splits partials left in `workspace` by bd_decode_attn (log-sum-exp
  * merge: m = max m_s, l = sum l_s 2^(m_s-m), O = sum O_s 2^(m_s-m) / l) into
  * out (device, [B][n_q_heads][D], fp16 / bf16). */
 bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t num_splits,

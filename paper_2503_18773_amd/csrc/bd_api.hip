@@ -68,12 +68,13 @@ size_t bd_cache_bytes(const bd_cache* c, int which) {
 int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   if (check_shape(c) != BD_OK || packed_len <= 0) return 1;
   // Each workgroup runs 4 waves that take 128-token blocks in turn, so the natural work
-  // quantum is 4 blocks.  Aim at ~4 workgroups per compute unit (256 CUs) over all
-  // (sequence, KV head) units, then rebalance so that every split gets the same number of quanta.
+  // quantum is 4 blocks.  The kernel keeps 2 workgroups resident per compute unit (256 CUs):
+  // aim at one full round of 512 workgroups over all (sequence, KV head) units, then
+  // rebalance so that every split gets the same number of quanta.
   const int units = c->batch * c->n_kv_heads;
   const int nb = (packed_len + kBlock - 1) / kBlock;
   const int quanta = (nb + 3) / 4;
-  int want = (1024 + units - 1) / units;
+  int want = (512 + units - 1) / units;
   if (want < 1) want = 1;
   int splits = quanta < want ? quanta : want;
   const int per = (quanta + splits - 1) / splits;
@@ -83,7 +84,7 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
 
 size_t bd_workspace_bytes(const bd_cache* c, int32_t num_splits) {
   if (check_shape(c) != BD_OK || num_splits < 1) return 0;
-  return (size_t)(num_splits + 1) * c->batch * c->n_q_heads * (kD + 2) * sizeof(float);
+  return (size_t)num_splits * c->batch * c->n_q_heads * (kD + 2) * sizeof(float);
 }
 
 bd_status bd_quant_pack_kv(const bd_cache* c, const void* k, const void* v, int32_t L, int32_t* packed_len,
@@ -171,7 +172,7 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
     s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, st));
   }
   if (s != BD_OK) return s;
-  if (out) s = hip_status(launch_combine(c, part_o, part_ml, num_splits + 1, out, st));
+  if (out) s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st));
   return s;
 }
 
@@ -181,7 +182,7 @@ bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t nu
   if (!workspace || !out || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
   if (!aligned16(workspace) || !aligned16(out)) return BD_ERR_ALIGNMENT;
   void* ws = const_cast<void*>(workspace);
-  return hip_status(launch_combine(c, ws_part_o(ws), ws_part_ml(c, ws, num_splits), num_splits + 1, out,
+  return hip_status(launch_combine(c, ws_part_o(ws), ws_part_ml(c, ws, num_splits), num_splits, out,
                                    (hipStream_t)stream));
 }
 

@@ -43,7 +43,7 @@ hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* p
 
 static inline float* ws_part_o(void* ws) { return reinterpret_cast<float*>(ws); }
 static inline float* ws_part_ml(const bd_cache* c, void* ws, int num_splits) {
-  return reinterpret_cast<float*>(ws) + (size_t)(num_splits + 1) * c->batch * c->n_q_heads * kD;
+  return reinterpret_cast<float*>(ws) + (size_t)num_splits * c->batch * c->n_q_heads * kD;
 }
 
 }  // namespace bd

@@ -13,29 +13,48 @@
 //
 // The query group of one KV head forms the N dimension (query transformation, Sec. IV-A).
 // Because S^T comes out with 4 consecutive rows (tokens) per lane for one head, it is already
-// in the B-operand layout of the second product: probabilities go exp -> fp16 -> MFMA with no
-// cross-lane movement and no LDS round trip.  The row -> token assignment of each S^T tile
-// and the order of codes inside a word are chosen so that this holds (the analogue, for MFMA,
-// of inducing the packed layout from the consumer instruction, Sec. III-A(1)).
+// in the B-operand layout of the second product: probabilities go exp -> fp16 -> MFMA without
+// an LDS round trip.  The row -> token assignment of each S^T tile and the order of codes
+// inside a word are chosen so that this holds (the analogue, for MFMA, of inducing the packed
+// layout from the consumer instruction, Sec. III-A(1)).
 //
-// Dequantization cost is cut by linearity: K is quantized per channel, so
-//   S = sum_c (Q_c s_c) code_c + sum_c Q_c z_c ;  Q' = Q*s (rescaled once per 128-token block,
-//   kept as an fp16 hi + lo pair so that it carries ~22 bits), the zero term is one scalar per
-//   head and block.  V is quantized per token, so  O = sum_t (P_t s_t) (code_t - c) + sum_t P_t (z_t + c s_t)
-//   with c the middle code, so that what P' multiplies is centred on zero.
-// The MFMAs therefore consume raw integer codes, produced from the packed words by one
-// mask-or per two codes (fp16 bit pattern 0x6400 | code == 1024 + code, Sec. III-A(3)) and one
-// packed subtract; codes sitting at bit offsets 4..7 of a byte arrive multiplied by a power
-// of two, which is folded into Q' / P'.
+// The 16 columns carry the <= 4 heads of the group four times over (column c holds head c%4).
+// Column group c/4 then keeps only every fourth S^T tile, so the softmax arithmetic runs on
+// 8 values per lane per 128-token block instead of 32, with every lane doing useful work; the
+// packed probabilities are moved back to columns 0..3 with DPP row shifts.
+//
+// Dequantization is reduced to masking (Sec. III-A(3) uses lop3 to the same end):
+//   * a masked code sitting in the low bits of an fp16 lane IS the fp16 subnormal code * 2^-24
+//     (times a power of two when it sits at bit 4..7); gfx950's MFMA takes subnormal inputs
+//     exactly, so the MFMAs consume  word & mask  directly: 5 ALU ops per 8 int4 codes,
+//     9 per 16 int2 codes; the power-of-two factors are folded into Q' / P'.
+//   * K is quantized per channel, so  S = sum_c (Q_c s_c) code_c + sum_c Q_c z_c : the query is
+//     rescaled once per 128-token block and the zero term is one scalar per head and block.
+//     Q' = Q*s is carried as an fp16 high + low pair (two MFMAs on the same A operand), which
+//     keeps ~22 bits: a single fp16 Q' is not enough when a channel holds outliers.
+//   * V is quantized per token, so  O = sum_t (P_t s_t) code_t + sum_t P_t z_t.
+//   * Raw codes are offset by the token's zero-point, so sum_t P'_t code_t and sum_t P_t z_t are
+//     two large numbers that nearly cancel; the fp16 rounding of P' and the last bits of two
+//     separately accumulated fp32 sums would then show in the result.  Both are avoided by
+//     writing  x_hat = s_t (code - c_t) + (z_t + s_t c_t)  with the integer c_t = rint(-z_t/s_t)
+//     (the code of the value 0): a ninth A tile holds c_t for every token, so the same MFMA
+//     chain also yields sum_t P'_t c_t, which is subtracted from every channel at the end; what
+//     is left outside the MFMAs is sum_t P_t (z_t + s_t c_t), at most half a quantization step
+//     per token.
+//
+// The fp16 residual tail (Sec. IV-B) is shared out evenly over the workgroups of a
+// (sequence, KV head): each takes a slice of the <= 127 residual tokens, scores them with
+// plain dot products and folds them into its partial in the final merge, so no workgroup
+// does the tail alone.
 #include "bd_common.h"
 
 namespace bd {
 namespace {
 
 constexpr int kWaves = 4;          // waves per workgroup, all spread along the token axis (W_m = 1)
-constexpr int kQShift = 8;         // Q' is carried as Q' * 2^8 so that its low piece stays a normal fp16
-constexpr int kPShift = 8;         // P' likewise
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kTwo24 = 16777216.0f;          // codes enter the MFMAs as code * 2^-24
+constexpr float kTwoM24 = 1.0f / 16777216.0f;
 
 struct DecodeArgs {
   const uint32_t* k_codes;
@@ -66,79 +85,103 @@ __device__ __forceinline__ uint16_t f2h(float f) {
   __builtin_memcpy(&b, &h, 2);
   return b;
 }
-__device__ __forceinline__ uint32_t pack_h2(float lo, float hi) {
-  return (uint32_t)f2h(lo) | ((uint32_t)f2h(hi) << 16);
+
+// DPP lane movement inside rows of 16 lanes.
+constexpr int kRowShl4 = 0x104, kRowShl8 = 0x108, kRowRor4 = 0x124, kRowRor8 = 0x128;
+constexpr int kQuadSwap1 = 0xB1 /* [1,0,3,2] */, kQuadSwap2 = 0x4E /* [2,3,0,1] */;
+constexpr int kRowHalfMirror = 0x141, kRowMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+// sum over the 16 lanes of a row, result in every lane
+__device__ __forceinline__ float row_sum16(float x) {
+  x += dpp_f<kQuadSwap1>(x);
+  x += dpp_f<kQuadSwap2>(x);
+  x += dpp_f<kRowHalfMirror>(x);
+  x += dpp_f<kRowMirror>(x);
+  return x;
+}
+// combine over the lanes that share lane%4 (the same head): 4 column groups x 4 lane groups
+__device__ __forceinline__ float head_sum(float x) {
+  x += dpp_f<kRowRor4>(x);
+  x += dpp_f<kRowRor8>(x);
+  x += __shfl_xor(x, 16);
+  x += __shfl_xor(x, 32);
+  return x;
+}
+__device__ __forceinline__ float head_max(float x) {
+  x = fmaxf(x, dpp_f<kRowRor4>(x));
+  x = fmaxf(x, dpp_f<kRowRor8>(x));
+  x = fmaxf(x, __shfl_xor(x, 16));
+  x = fmaxf(x, __shfl_xor(x, 32));
+  return x;
 }
 
 // ---- format traits ---------------------------------------------------------------------
-// WORDS: 32-bit words one lane loads per 16-row tile (32 codes).  k-step j of the 4 k-steps
-// of a tile consumes 8 codes: `e`-th code (e = 0..7, VGPR e/2, half e%2) sits at nibble/crumb
-// n(j, e) of word wj(j) and arrives multiplied by mult(e).
+// One lane loads WORDS 32-bit words (32 codes) per 16-row tile.  k-step j (of 4) of the tile
+// consumes 8 codes as 4 VGPRs; VGPR v holds two codes that arrive multiplied by 1/un(v).
+// The B operand must present the other factor in the same order: "slot group" sg = 4*g + j
+// (g = lane/16) holds 8 entries, entry e = 2*i + run for the i-th channel of one of two runs
+// of 4 consecutive channels.
 template <int BITS>
 struct Fmt;
 
 template <>
 struct Fmt<4> {
   static constexpr int WORDS = 4;
-  // position of channel c (0..127) in the permuted Q' array read as B operand
-  __device__ static int slot(int c) {
-    const int w = c >> 3, n = c & 7;
-    return 8 * w + 2 * (n & 3) + (n >> 2);
+  static constexpr float kQmax = 15.0f;
+  // first channel of run `run` (0/1) of slot group sg: word sg, nibbles 0..3 / 4..7
+  __device__ static int run_base(int sg, int run) { return 8 * sg + 4 * run; }
+  __device__ static constexpr float un(int v) { return (v & 1) ? (1.0f / 16.0f) : 1.0f; }
+  __device__ static constexpr float inv_un(int v) { return (v & 1) ? 16.0f : 1.0f; }
+  // kPairShift brings the column group whose tile fills the high half of a P' register next to
+  // the one that fills the low half; kStepShift brings the second k-step of a pair to columns 0..3
+  static constexpr int kPairShift = kRowShl4, kStepShift = kRowShl8;
+  // position of block token t in the k-ordered P' / V operand: lane group t/32, then k-step j,
+  // register r, half -- tile T = (t%32)/4 feeds k-step T/2, half T%2
+  __device__ static int p_slot(int t) {
+    const int T = (t & 31) >> 2, r = t & 3;
+    return (t & ~31) + 8 * (T >> 1) + 2 * r + (T & 1);
   }
-  // 2^-k factor undoing the scale a code picks up from its bit position
-  __device__ static float unmult_of_slot(int slot) { return ((slot >> 1) & 1) ? (1.0f / 16.0f) : 1.0f; }
-  // S^T tiles that feed the low / high half of the P' VGPRs of PV k-step j
-  __device__ static constexpr int tile_lo(int j) { return 2 * j; }
-  __device__ static constexpr int tile_hi(int j) { return 2 * j + 1; }
-  __device__ static float unmult_of_row(int r) { return (r & 1) ? (1.0f / 16.0f) : 1.0f; }
-  // V codes enter the second product as (code - kCenter): the probabilities then multiply
-  // numbers centred on zero, which keeps fp16 rounding of P' from being amplified by the
-  // zero-point offset; the shift is returned through the per-token constant term.
-  static constexpr int kCenter = 8;
-  // 8 codes of k-step j, as fp16 integers minus `center` (times their position factor)
-  template <int CENTER>
   __device__ static h8_t dequant(const uint32_t* w, int j) {
     const uint32_t x = w[j], y = x >> 8;
     u4_t r;
-    r[0] = (x & 0x000F000Fu) | 0x64006400u;
-    r[1] = (x & 0x00F000F0u) | 0x64006400u;
-    r[2] = (y & 0x000F000Fu) | 0x64006400u;
-    r[3] = (y & 0x00F000F0u) | 0x64006400u;
-    const h8_t v = __builtin_bit_cast(h8_t, r);
-    constexpr _Float16 c0 = (_Float16)(1024.0f + CENTER), c1 = (_Float16)(1024.0f + 16.0f * CENTER);
-    const h8_t bias = {c0, c0, c1, c1, c0, c0, c1, c1};
-    return v - bias;
+    r[0] = x & 0x000F000Fu;   // nibbles 0, 4
+    r[1] = x & 0x00F000F0u;   // nibbles 1, 5 (x16)
+    r[2] = y & 0x000F000Fu;   // nibbles 2, 6
+    r[3] = y & 0x00F000F0u;   // nibbles 3, 7 (x16)
+    return __builtin_bit_cast(h8_t, r);
   }
 };
 
 template <>
 struct Fmt<2> {
   static constexpr int WORDS = 2;
-  __device__ static int slot(int c) {
-    const int W = c >> 4, n = c & 15;
-    return 8 * (2 * W + ((n & 7) >> 2)) + 2 * (n & 3) + (n >> 3);
+  static constexpr float kQmax = 3.0f;
+  // slot group sg = 2*W + jj: word W, crumbs 4*jj + 0..3 (run 0) and 8 + 4*jj + 0..3 (run 1)
+  __device__ static int run_base(int sg, int run) { return 16 * (sg >> 1) + 4 * (sg & 1) + 8 * run; }
+  __device__ static constexpr float un(int v) { return 1.0f / (float)(1 << (2 * v)); }
+  __device__ static constexpr float inv_un(int v) { return (float)(1 << (2 * v)); }
+  static constexpr int kPairShift = kRowShl8, kStepShift = kRowShl4;
+  // tile T = (t%32)/4 feeds k-step 2*(T/4) + T%2, half (T%4)/2
+  __device__ static int p_slot(int t) {
+    const int T = (t & 31) >> 2, r = t & 3;
+    return (t & ~31) + 8 * (2 * (T >> 2) + (T & 1)) + 2 * r + ((T & 3) >> 1);
   }
-  __device__ static float unmult_of_slot(int slot) {
-    const int v = (slot >> 1) & 3;
-    return 1.0f / (float)(1 << (2 * v));
-  }
-  __device__ static constexpr int tile_lo(int j) { return 4 * (j >> 1) + (j & 1); }
-  __device__ static constexpr int tile_hi(int j) { return 4 * (j >> 1) + (j & 1) + 2; }
-  __device__ static float unmult_of_row(int r) { return 1.0f / (float)(1 << (2 * r)); }
-  static constexpr int kCenter = 2;
-  template <int CENTER>
   __device__ static h8_t dequant(const uint32_t* w, int j) {
     const uint32_t x = (j & 1) ? (w[j >> 1] >> 8) : w[j >> 1];
     u4_t r;
-    r[0] = (x & 0x00030003u) | 0x64006400u;
-    r[1] = (x & 0x000C000Cu) | 0x64006400u;
-    r[2] = (x & 0x00300030u) | 0x64006400u;
-    r[3] = (x & 0x00C000C0u) | 0x64006400u;
-    const h8_t v = __builtin_bit_cast(h8_t, r);
-    constexpr _Float16 c0 = (_Float16)(1024.0f + CENTER), c1 = (_Float16)(1024.0f + 4.0f * CENTER),
-                       c2 = (_Float16)(1024.0f + 16.0f * CENTER), c3 = (_Float16)(1024.0f + 64.0f * CENTER);
-    const h8_t bias = {c0, c0, c1, c1, c2, c2, c3, c3};
-    return v - bias;
+    r[0] = x & 0x00030003u;   // crumbs 0, 8      (of the selected byte pair)
+    r[1] = x & 0x000C000Cu;   // crumbs 1, 9  (x4)
+    r[2] = x & 0x00300030u;   // crumbs 2, 10 (x16)
+    r[3] = x & 0x00C000C0u;   // crumbs 3, 11 (x64)
+    return __builtin_bit_cast(h8_t, r);
   }
 };
 
@@ -162,19 +205,19 @@ __device__ __forceinline__ RawTile<WORDS> load_raw(const uint32_t* p) {
 
 // Per-wave LDS scratch.
 struct WaveLds {
-  uint16_t qhi[4][kD];   // Q' * 2^kQShift, high fp16 piece, permuted to B-operand order
+  uint16_t qhi[4][kD];   // Q' per head, high fp16 piece, in B-operand slot order
   uint16_t qlo[4][kD];   // low piece
-  float2 vpar[kBlock];   // per V token of the block: (scale * 2^kPShift * position factor, zero + center*scale)
-  float zq[4];           // sum_c Q_c z_c * scale_log2 * 2^kQShift per head
+  float2 vpar[kBlock];   // per V token of the block: (scale * position factor, zero + scale * centre code)
+  uint16_t c16[kBlock];  // per V token: centre code * position factor, in the A-operand order of P'
+  float zq[4];           // per head: sum_c Q_c z_c * scale_log2 * 2^-24
 };
 struct MergeLds {
   float o[kWaves][4][kD];
   float m[kWaves][4], l[kWaves][4], z[kWaves][4];
 };
 
-constexpr size_t kResidualSmem = 24 * kD * sizeof(float);   // q, scores, partial outputs of the residual path
 constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
-constexpr size_t kSmemBytes = cmax(cmax(sizeof(MergeLds), kWaves * sizeof(WaveLds)), kResidualSmem);
+constexpr size_t kSmemBytes = cmax(sizeof(MergeLds), kWaves * sizeof(WaveLds));
 
 __device__ __forceinline__ void wave_sync() {
   // LDS operations of one wave execute in order; this only stops the compiler from moving
@@ -182,94 +225,6 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Residual tail (Sec. IV-B): plain fp16 tokens, at most 127 of them; written for clarity,
-// not speed -- it moves <= 64 KB.
-__device__ void residual_part(const DecodeArgs& a, int b, int hkv, float* smem) {
-  const int tid = threadIdx.x;
-  const int gq = a.gq, R = a.res_len;
-  float* sq = smem;                 // [4][128] q * scale_log2
-  float* sp = smem + 4 * kD;        // [4][128] scores, then probabilities
-  float* sred = smem + 8 * kD;      // [4][4][128] partial outputs per token quarter
-  const size_t unit = (size_t)b * a.n_kv_heads + hkv;
-  const uint16_t* kr = a.k_res + unit * kBlock * kD;
-  const uint16_t* vr = a.v_res + unit * kBlock * kD;
-  for (int i = tid; i < 4 * kD; i += 256) {
-    const int h = i / kD, c = i % kD;
-    sq[i] = h < gq ? h2f(a.q[((size_t)b * a.n_q_heads + hkv * gq + h) * kD + c]) * a.scale_log2 : 0.0f;
-  }
-  __syncthreads();
-  if (tid < kBlock) {
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    if (tid < R) {
-      for (int c8 = 0; c8 < kD / 8; ++c8) {
-        u4_t raw = *reinterpret_cast<const u4_t*>(kr + (size_t)tid * kD + 8 * c8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float kv = h2f((uint16_t)((raw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu));
-#pragma unroll
-          for (int h = 0; h < 4; ++h) s[h] += kv * sq[h * kD + 8 * c8 + e];
-        }
-      }
-    }
-#pragma unroll
-    for (int h = 0; h < 4; ++h) sp[h * kD + tid] = tid < R ? s[h] : -INFINITY;
-  }
-  __syncthreads();
-  // per-head max and sum: wave h handles head h
-  const int wave = tid >> 6, lane = tid & 63;
-  float m = fmaxf(sp[wave * kD + lane], sp[wave * kD + lane + 64]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-  float p0 = 0.f, p1 = 0.f;
-  if (R > 0) {
-    p0 = exp2f(sp[wave * kD + lane] - m);
-    p1 = exp2f(sp[wave * kD + lane + 64] - m);
-  }
-  float l = p0 + p1;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off);
-  __syncthreads();
-  sp[wave * kD + lane] = p0;
-  sp[wave * kD + lane + 64] = p1;
-  __syncthreads();
-  // O[h][c] = sum_t p[h][t] v[t][c]; thread = (token quarter, channel pair)
-  {
-    const int quarter = tid >> 6, cp = tid & 63;
-    float acc[4][2] = {};
-    for (int t = quarter * 32; t < quarter * 32 + 32 && t < R; ++t) {
-      const uint32_t raw = *reinterpret_cast<const uint32_t*>(vr + (size_t)t * kD + 2 * cp);
-      const float v0 = h2f((uint16_t)(raw & 0xFFFFu)), v1 = h2f((uint16_t)(raw >> 16));
-#pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        const float p = sp[h * kD + t];
-        acc[h][0] += p * v0;
-        acc[h][1] += p * v1;
-      }
-    }
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      sred[(quarter * 4 + h) * kD + 2 * cp] = acc[h][0];
-      sred[(quarter * 4 + h) * kD + 2 * cp + 1] = acc[h][1];
-    }
-  }
-  __syncthreads();
-  const int part = a.num_splits;  // the residual owns the last partial slot
-  const int nbh = gridDim.z * a.n_q_heads;
-  for (int i = tid; i < 4 * kD; i += 256) {
-    const int h = i / kD, c = i % kD;
-    if (h >= gq) continue;
-    const float o = sred[(0 * 4 + h) * kD + c] + sred[(1 * 4 + h) * kD + c] + sred[(2 * 4 + h) * kD + c] +
-                    sred[(3 * 4 + h) * kD + c];
-    const size_t row = (size_t)part * nbh + (size_t)b * a.n_q_heads + hkv * gq + h;
-    a.part_o[row * kD + c] = o;
-  }
-  if (lane == 0 && wave < gq) {
-    const size_t row = (size_t)part * nbh + (size_t)b * a.n_q_heads + hkv * gq + wave;
-    a.part_ml[row * 2] = R > 0 ? m : -INFINITY;
-    a.part_ml[row * 2 + 1] = R > 0 ? l : 0.0f;
-  }
 }
 
 template <int BITS>
@@ -280,40 +235,73 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   constexpr int VROW = kBlock * BITS / 32;   // V words per channel per block
 
   __shared__ __attribute__((aligned(16))) unsigned char smem_raw[kSmemBytes];
+  __shared__ float res_s[kBlock][4];         // scores of this workgroup's residual tokens, per head
 
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
-  if (split == a.num_splits) {
-    residual_part(a, b, hkv, reinterpret_cast<float*>(smem_raw));
-    return;
-  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = lane & 15, g = lane >> 4;   // MFMA column (head) and contraction group
+  const int col = lane & 15, g = lane >> 4;   // MFMA column and contraction group
+  const int head = col & 3, cg = col >> 2;    // head carried by the column; column group
   const int gq = a.gq;
   WaveLds& wl = reinterpret_cast<WaveLds*>(smem_raw)[wave];
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   const int blk0 = (int)(((long)a.nb * split) / a.num_splits);
   const int blk1 = (int)(((long)a.nb * (split + 1)) / a.num_splits);
+  // this workgroup's slice of the fp16 residual tokens
+  const int rt0 = (a.res_len * split) / a.num_splits, rt1 = (a.res_len * (split + 1)) / a.num_splits;
+  const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * gq) * kD;
 
-  // Q of this lane's prep slice: head lane/16, channels 8*(lane%16) .. +7 (zero for padding heads)
-  float qv[8];
-  {
-    const int hh = lane >> 4;
-    u4_t raw = {0u, 0u, 0u, 0u};
-    if (hh < gq)
-      raw = *reinterpret_cast<const u4_t*>(a.q + ((size_t)b * a.n_q_heads + hkv * gq + hh) * kD + 8 * (lane & 15));
+  // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
+  if (rt1 > rt0) {
+    float qr[4][2];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) qv[e] = h2f((uint16_t)((raw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu));
+    for (int h = 0; h < 4; ++h) {
+      uint32_t raw = 0;
+      if (h < gq) raw = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
+      qr[h][0] = h2f((uint16_t)(raw & 0xFFFFu)) * a.scale_log2;
+      qr[h][1] = h2f((uint16_t)(raw >> 16)) * a.scale_log2;
+    }
+    const uint16_t* kr = a.k_res + unit * kBlock * kD;
+    for (int t = rt0 + wave; t < rt1; t += kWaves) {
+      const uint32_t raw = *reinterpret_cast<const uint32_t*>(kr + (size_t)t * kD + 2 * lane);
+      const float k0 = h2f((uint16_t)(raw & 0xFFFFu)), k1 = h2f((uint16_t)(raw >> 16));
+      float sh[4];
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        float x = __builtin_fmaf(qr[h][0], k0, qr[h][1] * k1);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+        sh[h] = x;
+      }
+      if (lane < 4) res_s[t - rt0][lane] = lane == 0 ? sh[0] : lane == 1 ? sh[1] : lane == 2 ? sh[2] : sh[3];
+    }
   }
 
-  float m_run = -INFINITY;   // running max of this lane's head (log2 units), equal across g
-  float l_run = 0.0f;        // running sum over this lane's own tokens
+  // Query slice this lane rescales every block: head lane/16, slot group lane%16
+  // (two runs of 4 consecutive channels); zero for the padding heads of a small group.
+  const int prep_head = lane >> 4, prep_sg = lane & 15;
+  const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
+  float qv[2][4];
+  {
+    u2_t r0 = {0u, 0u}, r1 = {0u, 0u};
+    if (prep_head < gq) {
+      r0 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run0);
+      r1 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run1);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      qv[0][i] = h2f((uint16_t)((r0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
+      qv[1][i] = h2f((uint16_t)((r1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
+    }
+  }
+
+  float m_run = -INFINITY;   // running max of this lane's head (log2 units), equal in all lanes of the head
+  float l_run = 0.0f;        // running sum of p over this lane's own tokens
   float z_run = 0.0f;        // running sum of p * zero_t over this lane's own tokens
+  f4_t xacc = {0.f, 0.f, 0.f, 0.f};   // sum_t P'_t * centre code of token t (every row the same)
   f4_t oacc[8];
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
-
-  const float qscale = a.scale_log2 * (float)(1 << kQShift);
 
   for (int blk = blk0 + wave; blk < blk1; blk += kWaves) {
     const size_t gb = unit * a.nbcap + blk;
@@ -321,123 +309,140 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     RawTile<WORDS> kraw[8], vraw[8];
     {
       const uint32_t* kp = a.k_codes + gb * (size_t)(kBlock * KROW) + WORDS * g;
-      const int tok_base = 32 * (col >> 2) + (col & 3);   // row col of tile T holds token tok_base + 4T
+      const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
 #pragma unroll
       for (int T = 0; T < 8; ++T) kraw[T] = load_raw<WORDS>(kp + (size_t)(tok_base + 4 * T) * KROW);
       const uint32_t* vp = a.v_codes + gb * (size_t)(kD * VROW) + WORDS * g;
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
     }
-    // ---- per-block query rescale: Q' = Q * s_c (K is channel-wise), zero term sum_c Q_c z_c
+    // ---- per-block query rescale (K is channel-wise): Q' = Q * s_c, zero term sum_c Q_c z_c
     {
-      const int hh = lane >> 4, c0 = 8 * (lane & 15);
-      const uint32_t* pp = a.k_params + gb * kD + c0;
-      u4_t p0 = *reinterpret_cast<const u4_t*>(pp), p1 = *reinterpret_cast<const u4_t*>(pp + 4);
-      float zsum = 0.0f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t pr = e < 4 ? p0[e] : p1[e - 4];
-        const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
-        const int sl = F::slot(c0 + e);
-        const float t = qv[e] * s * (qscale * F::unmult_of_slot(sl));
-        const uint16_t hi = f2h(t);
-        wl.qhi[hh][sl] = hi;
-        wl.qlo[hh][sl] = f2h(t - h2f(hi));
-        zsum += qv[e] * z;
-      }
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) zsum += __shfl_xor(zsum, off);
-      if ((lane & 15) == 0) wl.zq[hh] = zsum * qscale;
-      // V parameters of the block's 128 tokens
+      const uint32_t* pp = a.k_params + gb * kD;
+      const u4_t p0 = *reinterpret_cast<const u4_t*>(pp + run0), p1 = *reinterpret_cast<const u4_t*>(pp + run1);
       const u2_t vp2 = *reinterpret_cast<const u2_t*>(a.v_params + gb * kBlock + 2 * lane);
+      float zsum = 0.0f;
+      uint16_t qh[8], ql[8];
+#pragma unroll
+      for (int run = 0; run < 2; ++run)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t pr = run ? p1[i] : p0[i];
+          const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
+          const float t = qv[run][i] * s * F::un(i);
+          const uint16_t hi = f2h(t);
+          qh[2 * i + run] = hi;
+          ql[2 * i + run] = f2h(t - h2f(hi));
+          zsum = __builtin_fmaf(qv[run][i], z, zsum);
+        }
+      zsum = row_sum16(zsum);
+      u4_t phi, plo;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
+        plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
+      }
+      *reinterpret_cast<u4_t*>(&wl.qhi[prep_head][8 * prep_sg]) = phi;
+      *reinterpret_cast<u4_t*>(&wl.qlo[prep_head][8 * prep_sg]) = plo;
+      if (prep_sg == 0) wl.zq[prep_head] = zsum * kTwoM24;
+      // V parameters of the block's 128 tokens
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const float sv = h2f((uint16_t)(vp2[u] & 0xFFFFu)), zv = h2f((uint16_t)(vp2[u] >> 16));
-        const int r = (2 * lane + u) & 3;   // row of the token inside its S^T tile
-        wl.vpar[2 * lane + u] = make_float2(sv * ((float)(1 << kPShift) * F::unmult_of_row(r)),
-                                            __builtin_fmaf((float)F::kCenter, sv, zv));
+        const int t = 2 * lane + u;
+        const int r = t & 3;                // row of the token inside its S^T tile
+        const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
+        wl.vpar[t] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+        wl.c16[F::p_slot(t)] = (uint16_t)(ct * F::inv_un(r));
       }
     }
     wave_sync();
-    h8_t bhi[4], blo[4];
+    h8_t bqh[4], bql[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      bhi[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[col & 3][8 * (4 * g + j)]);
-      blo[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[col & 3][8 * (4 * g + j)]);
+      bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
+      bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
     }
-    const float zq = wl.zq[col & 3];
+    const float zq = wl.zq[head];
 
-    // ---- S^T tiles: rows = tokens 32*(row/4) + 4T + row%4, columns = heads
-    f4_t s[8];
+    // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); column
+    //      group cg keeps tiles cg and 4+cg
+    float sc[2][4];
 #pragma unroll
-    for (int T = 0; T < 8; ++T) {
-      f4_t acc = {zq, zq, zq, zq};
+    for (int half = 0; half < 2; ++half) {
+      f4_t s[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const h8_t ak = F::template dequant<0>(kraw[T].w, j);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bhi[j], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, blo[j], acc, 0, 0, 0);
+      for (int tt = 0; tt < 4; ++tt) {
+        f4_t acc = {zq, zq, zq, zq};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const h8_t ak = F::dequant(kraw[4 * half + tt].w, j);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bqh[j], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
+        }
+        s[tt] = acc;
       }
-      s[T] = acc;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float lo = cg & 1 ? s[1][r] : s[0][r], hi = cg & 1 ? s[3][r] : s[2][r];
+        sc[half][r] = cg & 2 ? hi : lo;
+      }
     }
-    // ---- online softmax (Alg. 1), this lane: head `col`, tokens 32g + 4T + r
-    float bmax = s[0][0];
-#pragma unroll
-    for (int T = 0; T < 8; ++T)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, s[T][r]);
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
-    constexpr float kUnQ = 1.0f / (float)(1 << kQShift);
-    const float m_new = fmaxf(m_run, bmax * kUnQ);
-    const float alpha = exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
+    // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
+    float bmax = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                       fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+    bmax = head_max(bmax);
+    const float m_new = fmaxf(m_run, bmax * kTwo24);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
     l_run *= alpha;
     z_run *= alpha;
+    if (__any(alpha != 1.0f)) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
-
-    float pf[8][4];      // P' = p * scale_t (times the position factor), still fp32
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+      xacc *= alpha;
+    }
+    u4_t pb[4];   // P' as the B operand of the 4 k-steps of O^T += V^T P' (valid in columns 0..3)
 #pragma unroll
-    for (int T = 0; T < 8; ++T) {
+    for (int half = 0; half < 2; ++half) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float p = exp2f(__builtin_fmaf(s[T][r], kUnQ, -m_new));
-        const float2 par = wl.vpar[32 * g + 4 * T + r];
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[half][r], kTwo24, -m_new));
+        const float2 par = wl.vpar[32 * g + 16 * half + 4 * cg + r];
         l_run += p;
         z_run = __builtin_fmaf(p, par.y, z_run);
-        pf[T][r] = p * par.x;
+        const float pf = p * par.x;
+        const uint16_t ph = f2h(pf);
+        // gather the column groups' fp16 values into the B-operand register pairs
+        const uint32_t x = (uint32_t)ph;
+        const uint32_t pair = x | dpp_u<F::kPairShift>(x << 16);
+        pb[2 * half][r] = pair;
+        pb[2 * half + 1][r] = dpp_u<F::kStepShift>(pair);
       }
     }
     // ---- O^T += V^T P' : k-step j contracts 32 tokens (8 per lane group)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int tl = F::tile_lo(j), th = F::tile_hi(j);
-      u4_t pb;
+      const h8_t bp = __builtin_bit_cast(h8_t, pb[j]);
 #pragma unroll
-      for (int v = 0; v < 4; ++v) pb[v] = pack_h2(pf[tl][v], pf[th][v]);
-      const h8_t bp = __builtin_bit_cast(h8_t, pb);
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt) {
-        const h8_t av = F::template dequant<F::kCenter>(vraw[mt].w, j);
-        oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[mt], 0, 0, 0);
-      }
+      for (int mt = 0; mt < 8; ++mt)
+        oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[mt].w, j), bp, oacc[mt], 0, 0, 0);
+      const h8_t ac = *reinterpret_cast<const h8_t*>(&wl.c16[8 * (4 * g + j)]);
+      xacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac, bp, xacc, 0, 0, 0);
     }
     wave_sync();   // the next block's prep overwrites this wave's LDS scratch
   }
 
   // ---- merge the waves of the workgroup (cross-wave step of the cooperative softmax)
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  z_run += __shfl_xor(z_run, 16);
-  z_run += __shfl_xor(z_run, 32);
+  l_run = head_sum(l_run);
+  z_run = head_sum(z_run);
   __syncthreads();   // every wave is done with its WaveLds before the space is reused
   MergeLds& ml = *reinterpret_cast<MergeLds*>(smem_raw);
   if (col < 4) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = (oacc[mt][r] - xacc[0]) * kTwo24;
     if (g == 0) {
       ml.m[wave][col] = m_run;
       ml.l[wave][col] = l_run;
@@ -451,20 +456,30 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       float M = ml.m[0][h];
 #pragma unroll
       for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
+      const int nres = rt1 - rt0;
+      for (int t = 0; t < nres; ++t) M = fmaxf(M, res_s[t][h]);
       float L = 0.f, Z = 0.f, o0 = 0.f, o1 = 0.f;
       if (M > -INFINITY) {
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-          const float f = exp2f(ml.m[w][h] - M);
+          const float f = __builtin_amdgcn_exp2f(ml.m[w][h] - M);
           L += f * ml.l[w][h];
           Z += f * ml.z[w][h];
           o0 += f * ml.o[w][h][c0];
           o1 += f * ml.o[w][h][c0 + 1];
         }
+        // residual slice, part 2: fold the fp16 tokens in (V rows read straight from memory)
+        const uint16_t* vr = a.v_res + (unit * kBlock + rt0) * kD + c0;
+        for (int t = 0; t < nres; ++t) {
+          const float p = __builtin_amdgcn_exp2f(res_s[t][h] - M);
+          const uint32_t raw = *reinterpret_cast<const uint32_t*>(vr + (size_t)t * kD);
+          L += p;
+          o0 = __builtin_fmaf(p, h2f((uint16_t)(raw & 0xFFFFu)), o0);
+          o1 = __builtin_fmaf(p, h2f((uint16_t)(raw >> 16)), o1);
+        }
       }
-      constexpr float kUnP = 1.0f / (float)(1 << kPShift);
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * gq + h;
-      float2 o = {o0 * kUnP + Z, o1 * kUnP + Z};
+      float2 o = {o0 + Z, o1 + Z};
       *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
       if ((tid & 63) == 0) {
         a.part_ml[row * 2] = M;
@@ -475,31 +490,62 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 }
 
 // Log-sum-exp merge of the split partials into the final output row (fp16 or bf16).
+// One workgroup per output row; thread = (half of the partials, channel).
 template <bool BF16>
-__global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ part_o,
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, int nparts, int nrows,
                                                        uint16_t* __restrict__ out) {
-  const int row = blockIdx.x, c = threadIdx.x;
+  __shared__ float sw[1024];      // weight of each partial (chunks of 1024 partials)
+  __shared__ float sred[3][256];
+  const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, half = tid >> 7;
+  // pass 1: global max of the partial maxima
   float M = -INFINITY;
-  for (int p = 0; p < nparts; ++p) M = fmaxf(M, part_ml[((size_t)p * nrows + row) * 2]);
+  for (int p = tid; p < nparts; p += 256) M = fmaxf(M, part_ml[((size_t)p * nrows + row) * 2]);
+  sred[0][tid] = M;
+  __syncthreads();
+  for (int s = 128; s >= 1; s >>= 1) {
+    if (tid < s) sred[0][tid] = fmaxf(sred[0][tid], sred[0][tid + s]);
+    __syncthreads();
+  }
+  M = sred[0][0];
+  __syncthreads();
   float L = 0.f, o = 0.f;
   if (M > -INFINITY) {
-    for (int p = 0; p < nparts; ++p) {
-      const size_t r = (size_t)p * nrows + row;
-      const float ms = part_ml[r * 2];
-      if (ms == -INFINITY) continue;
-      const float f = exp2f(ms - M);
-      L += f * part_ml[r * 2 + 1];
-      o += f * part_o[r * kD + c];
+    for (int p0 = 0; p0 < nparts; p0 += 1024) {
+      const int n = min(1024, nparts - p0);
+      float lpart = 0.f;
+      for (int p = tid; p < n; p += 256) {
+        const size_t r = (size_t)(p0 + p) * nrows + row;
+        const float ms = part_ml[r * 2];
+        const float f = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+        sw[p] = f;
+        lpart += f * part_ml[r * 2 + 1];
+      }
+      L += lpart;
+      __syncthreads();
+      const int lo = half ? n / 2 : 0, hi = half ? n : n / 2;
+#pragma unroll 8
+      for (int p = lo; p < hi; ++p) o = __builtin_fmaf(sw[p], part_o[((size_t)(p0 + p) * nrows + row) * kD + c], o);
+      __syncthreads();
     }
   }
-  const float res = L > 0.f ? o / L : 0.f;
-  if (BF16) {
-    uint32_t u = __float_as_uint(res);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    out[(size_t)row * kD + c] = (uint16_t)(u >> 16);
-  } else {
-    out[(size_t)row * kD + c] = f2h(res);
+  sred[1][tid] = L;
+  sred[2][tid] = o;
+  __syncthreads();
+  for (int s = 128; s >= 1; s >>= 1) {
+    if (tid < s) sred[1][tid] += sred[1][tid + s];
+    __syncthreads();
+  }
+  if (tid < 128) {
+    const float Lt = sred[1][0];
+    const float res = Lt > 0.f ? (sred[2][tid] + sred[2][tid + 128]) / Lt : 0.f;
+    if (BF16) {
+      uint32_t u = __float_as_uint(res);
+      u += 0x7FFFu + ((u >> 16) & 1u);
+      out[(size_t)row * kD + c] = (uint16_t)(u >> 16);
+    } else {
+      out[(size_t)row * kD + c] = f2h(res);
+    }
   }
 }
 
@@ -525,7 +571,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.res_len = res_len;
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
-  dim3 grid(num_splits + 1, c->n_kv_heads, c->batch), block(256);
+  dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
   if (c->format == BD_FMT_INT4)
     decode_int_kernel<4><<<grid, block, 0, st>>>(a);
   else
@@ -537,9 +583,9 @@ hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* p
                           hipStream_t st) {
   const int nrows = c->batch * c->n_q_heads;
   if (c->format == BD_FMT_MXFP4)
-    combine_kernel<true><<<dim3(nrows), dim3(128), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
+    combine_kernel<true><<<dim3(nrows), dim3(256), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
   else
-    combine_kernel<false><<<dim3(nrows), dim3(128), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
+    combine_kernel<false><<<dim3(nrows), dim3(256), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
   return hipGetLastError();
 }
 

@@ -58,7 +58,7 @@ def test_split_heuristic_and_workspace():
     for L in (0, 128, 1024, 32768, 131072):
         s = B.bd_choose_splits(c, L)
         assert 1 <= s <= max(1, L // 128)
-    assert B.bd_workspace_bytes(c, 64) == 65 * 32 * 130 * 4
+    assert B.bd_workspace_bytes(c, 64) == 64 * 32 * 130 * 4
     assert B.bd_workspace_bytes(c, 0) == 0
 
 
