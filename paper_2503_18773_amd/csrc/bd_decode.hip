@@ -251,6 +251,45 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   const int rt0 = (a.res_len * split) / a.num_splits, rt1 = (a.res_len * (split + 1)) / a.num_splits;
   const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * gq) * kD;
 
+  float m_run = -INFINITY;   // running max of this lane's head (log2 units), equal in all lanes of the head
+  float l_run = 0.0f;        // running sum of p over this lane's own tokens
+  float z_run = 0.0f;        // running sum of p * zero_t over this lane's own tokens
+  f4_t xacc = {0.f, 0.f, 0.f, 0.f};   // sum_t P'_t * centre code of token t (every row the same)
+  f4_t oacc[8];
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+  // Software pipeline over this wave's blocks: K codes and parameters of the next block are
+  // requested right after the QK^T of the current one, its V codes right after the PV, so
+  // loads stay in flight across the softmax and the MFMAs without a second set of registers.
+  const int prep_head = lane >> 4, prep_sg = lane & 15;
+  const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
+  const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
+  RawTile<WORDS> kraw[8], vraw[8];
+  u4_t kp0, kp1;   // K parameters (half2) of this lane's two channel runs
+  u2_t vp2;        // V parameters (half2) of tokens 2*lane, 2*lane+1
+  auto issue_k = [&](int blk) {
+    const size_t gb = unit * a.nbcap + blk;
+    const uint32_t* pp = a.k_params + gb * kD;   // parameters first: the block's first consumer
+    kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
+    kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
+    const uint32_t* kp = a.k_codes + gb * (size_t)(kBlock * KROW) + WORDS * g;
+#pragma unroll
+    for (int T = 0; T < 8; ++T) kraw[T] = load_raw<WORDS>(kp + (size_t)(tok_base + 4 * T) * KROW);
+  };
+  auto issue_v = [&](int blk) {
+    const size_t gb = unit * a.nbcap + blk;
+    vp2 = *reinterpret_cast<const u2_t*>(a.v_params + gb * kBlock + 2 * lane);
+    const uint32_t* vp = a.v_codes + gb * (size_t)(kD * VROW) + WORDS * g;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
+  };
+  int blk = blk0 + wave;
+  if (blk < blk1) {
+    issue_k(blk);
+    issue_v(blk);
+  }
+
   // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
   if (rt1 > rt0) {
     float qr[4][2];
@@ -279,8 +318,6 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 
   // Query slice this lane rescales every block: head lane/16, slot group lane%16
   // (two runs of 4 consecutive channels); zero for the padding heads of a small group.
-  const int prep_head = lane >> 4, prep_sg = lane & 15;
-  const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
   float qv[2][4];
   {
     u2_t r0 = {0u, 0u}, r1 = {0u, 0u};
@@ -295,39 +332,17 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     }
   }
 
-  float m_run = -INFINITY;   // running max of this lane's head (log2 units), equal in all lanes of the head
-  float l_run = 0.0f;        // running sum of p over this lane's own tokens
-  float z_run = 0.0f;        // running sum of p * zero_t over this lane's own tokens
-  f4_t xacc = {0.f, 0.f, 0.f, 0.f};   // sum_t P'_t * centre code of token t (every row the same)
-  f4_t oacc[8];
-#pragma unroll
-  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
-
-  for (int blk = blk0 + wave; blk < blk1; blk += kWaves) {
-    const size_t gb = unit * a.nbcap + blk;
-    // ---- issue the block's loads: 8 K tiles (16 tokens each), 8 V tiles (16 channels each)
-    RawTile<WORDS> kraw[8], vraw[8];
-    {
-      const uint32_t* kp = a.k_codes + gb * (size_t)(kBlock * KROW) + WORDS * g;
-      const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
-#pragma unroll
-      for (int T = 0; T < 8; ++T) kraw[T] = load_raw<WORDS>(kp + (size_t)(tok_base + 4 * T) * KROW);
-      const uint32_t* vp = a.v_codes + gb * (size_t)(kD * VROW) + WORDS * g;
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt) vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
-    }
+  while (blk < blk1) {
+    const int nblk = blk + kWaves;
     // ---- per-block query rescale (K is channel-wise): Q' = Q * s_c, zero term sum_c Q_c z_c
     {
-      const uint32_t* pp = a.k_params + gb * kD;
-      const u4_t p0 = *reinterpret_cast<const u4_t*>(pp + run0), p1 = *reinterpret_cast<const u4_t*>(pp + run1);
-      const u2_t vp2 = *reinterpret_cast<const u2_t*>(a.v_params + gb * kBlock + 2 * lane);
       float zsum = 0.0f;
       uint16_t qh[8], ql[8];
 #pragma unroll
       for (int run = 0; run < 2; ++run)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const uint32_t pr = run ? p1[i] : p0[i];
+          const uint32_t pr = run ? kp1[i] : kp0[i];
           const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
           const float t = qv[run][i] * s * F::un(i);
           const uint16_t hi = f2h(t);
@@ -388,6 +403,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         sc[half][r] = cg & 2 ? hi : lo;
       }
     }
+    if (nblk < blk1) issue_k(nblk);
     // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
     float bmax = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                        fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
@@ -430,7 +446,9 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       const h8_t ac = *reinterpret_cast<const h8_t*>(&wl.c16[8 * (4 * g + j)]);
       xacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac, bp, xacc, 0, 0, 0);
     }
+    if (nblk < blk1) issue_v(nblk);
     wave_sync();   // the next block's prep overwrites this wave's LDS scratch
+    blk = nblk;
   }
 
   // ---- merge the waves of the workgroup (cross-wave step of the cooperative softmax)

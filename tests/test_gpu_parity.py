@@ -140,3 +140,78 @@ def test_config_decode_steps(name):
             got = _decode(gc, w, q)
             assert_attn_close(got, ref, f"{name} step {step}")
     _assert_int_cache_equal(oc, gc)
+
+
+def _sampled_units_check(w, gc, q, units, K, V, new_tokens=()):
+    """Oracle on a few (batch, kv_head) units of a full-size configuration."""
+    bits = BITS[w.fmt]
+    got = _decode(gc, w, q)
+    worst = (0.0, 0.0)
+    for (b, h) in units:
+        oc = O.IntCache(1, 1, bits, gc.desc.capacity)
+        oc.quant_pack_kv(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1])
+        for kn, vn in new_tokens:
+            oc.append_kv(kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+        # packed bytes of this unit, bit for bit
+        nb = oc.packed_len // 128
+        for i, name in enumerate(["k_codes", "v_codes", "k_params", "v_params"]):
+            ref = getattr(oc, name)[0, 0, :nb]
+            full = gc.host_buffer(i).view(np.uint32).reshape((w.batch, w.n_kv_heads) + getattr(oc, name).shape[2:])
+            assert np.array_equal(full[b, h, :nb], ref), (name, b, h)
+        g = w.g_q
+        ref = O.decode_attn(oc, q[b:b + 1, h * g:(h + 1) * g], W.softmax_scale(w))
+        ma, rl = assert_attn_close(got[b:b + 1, h * g:(h + 1) * g], ref, f"{w.name} unit {(b, h)}")
+        worst = (max(worst[0], ma), max(worst[1], rl))
+    return worst
+
+
+def test_cfg2_int2_batch8_full_size_sampled():
+    """Configuration 2 at its full size (batch 8, 32K, int2) in the launch configuration the
+    benchmark uses; the oracle checks 3 of the 64 (sequence, KV head) units, including one
+    whose K and V carry outlier channels."""
+    w = W.CONFIGS["cfg2"]
+    K, V = W.make_kv(w)
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, w.context + 128)
+    gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+    kn, vn = W.make_new_kv(w, 0)
+    gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+    hk = int(W.outlier_pairs(w, 0)[0][0]); hv = int(W.outlier_pairs(w, 1)[0][0])
+    _sampled_units_check(w, gc, W.make_q(w), [(0, hk), (5, hv), (7, 0)], K, V, [(kn, vn)])
+
+
+def test_cfg3_128k_256_steps():
+    """Configuration 3: 128K context, 256 decode steps (two residual flushes).  Lengths are
+    checked every step, packed bytes after every flush, outputs on steps around the flushes;
+    the oracle follows 2 of the 8 KV heads."""
+    w = W.CONFIGS["cfg3"]
+    K, V = W.make_kv(w)
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, w.context + 512)
+    gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+    hv = int(W.outlier_pairs(w, 1)[0][0])
+    heads = [hv, (hv + 3) % w.n_kv_heads]
+    ocs = {}
+    for h in heads:
+        oc = O.IntCache(1, 1, 4, w.context + 512); oc.quant_pack_kv(K[:, h:h + 1], V[:, h:h + 1]); ocs[h] = oc
+    check = {0, 1, 126, 127, 128, 254, 255} | set(range(15, 256, 48))
+    g = w.g_q
+    for step in range(256):
+        kn, vn = W.make_new_kv(w, step)
+        gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+        for h in heads:
+            ocs[h].append_kv(kn[:, h:h + 1], vn[:, h:h + 1])
+            assert (gc.packed_len, gc.res_len) == (ocs[h].packed_len, ocs[h].res_len)
+        if gc.res_len == 0:       # a flush happened in this step
+            full = [gc.host_buffer(i).view(np.uint32) for i in range(4)]
+            nb = gc.packed_len // 128
+            for h in heads:
+                for i, name in enumerate(["k_codes", "v_codes", "k_params", "v_params"]):
+                    ref = getattr(ocs[h], name)
+                    got = full[i].reshape((1, w.n_kv_heads) + ref.shape[2:])
+                    assert np.array_equal(got[0, h, nb - 1], ref[0, 0, nb - 1]), (name, step, h)
+        if step in check:
+            q = W.make_q(w, step)
+            got = _decode(gc, w, q)
+            for h in heads:
+                ref = O.decode_attn(ocs[h], q[:, h * g:(h + 1) * g], W.softmax_scale(w))
+                assert_attn_close(got[:, h * g:(h + 1) * g], ref, f"cfg3 step {step} head {h}")
+    assert (gc.packed_len, gc.res_len) == (131072 + 256, 0)
