@@ -36,6 +36,19 @@ def algorithmic_bytes(w, packed_len: int, res_len: int) -> int:
     return units * (packed_len * per_tok + res_len * w.head_dim * 2 * 2) + qo
 
 
+def measured_traffic(w):
+    """HBM bytes per decode-kernel launch from the committed rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", f"decode_{w.fmt}_{w.name}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,11 +56,14 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg1", help="cfg1 (32K int4, default), cfg3 (128K int4), cfg2, cfg0")
     ap.add_argument("--layers", type=int, default=N_LAYERS)
-    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+    ap.add_argument("--mode", default="eager", choices=["graph", "eager"],
                     help="graph: the warm-up steps and the timed steps are each captured into one HIP graph "
                          "(every step distinct) so host launch cost is out of the timed region; eager: plain calls")
     ap.add_argument("--splits", type=int, default=0, help="override the library's split factor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="lower bound on the oracle's timed CPU work")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (the path shards by batch / KV head / "
@@ -59,6 +75,14 @@ def main() -> int:
     from paper_2503_18773_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calib_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib_copy_bytes": 1 << 30, "launches": 5}))
+        return 0
     B.lib()  # fail loudly if the HIP library is missing
     w = W.CONFIGS[args.workload]
     total_steps = args.warmup + args.steps
@@ -136,54 +160,62 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     value = timed_bytes / elapsed / 1e9
 
-    # ---- roofline of the dominant kernel (decode attention), measured live with events:
-    # one event pair around each bd_decode_attn launch (partials only, no combine), all 32
-    # layers enqueued back to back on the stream the kernels run on.
+    # ---- roofline of the dominant kernel (decode attention), measured live with HIP events on
+    # the stream the kernels run on: one event pair around the bd_decode_attn launches (partials
+    # only, no combine) of all layers, enqueued back to back; the kernels run without gaps, so
+    # elapsed / launches is the average launch duration (cold caches: each layer has its own).
     c0 = caches[0]
-    reps = 3
-    pairs = []
-    for _ in range(reps):
-        for li, c in enumerate(caches):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
+    reps = 5
+    per_rep = []
+    for rep in range(reps + 1):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for c in caches:
             B.bd_decode_attn(c.desc, qs[-1], c.packed_len, c.res_len, sm_scale, splits, c.workspace(splits), None)
-            b.record(stream)
-            pairs.append((a, b))
-    torch.cuda.synchronize()
-    durs = np.array([a.elapsed_time(b) * 1e3 for a, b in pairs[len(caches):]])   # us, first rep dropped
-    kernel_us = float(durs.mean())
+        b.record(stream)
+        torch.cuda.synchronize()
+        if rep:
+            per_rep.append(a.elapsed_time(b) * 1e3 / len(caches))
+    kernel_us = float(np.mean(per_rep))
     launch_bytes = algorithmic_bytes(w, c0.packed_len, c0.res_len)
     achieved = launch_bytes / (kernel_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_int_kernel" if w.fmt != "mxfp4" else "decode_mx_kernel",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(durs.min()), 3),
-                "bytes_per_launch": launch_bytes, "timing": "hip events around each launch, 32 cold caches in turn"}
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(w),
+                "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(np.min(per_rep)), 3),
+                "bytes_per_launch": launch_bytes,
+                "timing": f"hip events around {len(caches)} back-to-back launches (one per cold layer cache), "
+                          f"{reps} repetitions"}
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_limits
         from oracle import bitdecode_oracle as O
-        n_units = 1 if w.context > 40000 else 2
+        n_units = min(2, w.batch * w.n_kv_heads)
+        per_tok = {"int4": 136, "int2": 72, "mxfp4": 136}[w.fmt]
         with threadpool_limits(limits=1):
             if w.fmt == "mxfp4":
                 oc = O.MxCache(1, n_units, cap)
             else:
                 oc = O.IntCache(1, n_units, 4 if w.fmt == "int4" else 2, cap)
             oc.quant_pack_kv(K[:1, :n_units], V[:1, :n_units])          # untimed: prefill
-            kn, vn = W.make_new_kv(w, 0)
-            q0 = W.make_q(w, 0)[:1, :n_units * w.g_q]
+            nsteps, sample_bytes = 0, 0
             tc0 = time.perf_counter()
-            oc.append_kv(kn[:1, :n_units], vn[:1, :n_units])
-            O.decode_attn(oc, q0, sm_scale)
+            while time.perf_counter() - tc0 < args.cpu_seconds:
+                kn, vn = W.make_new_kv(w, nsteps)
+                q0 = W.make_q(w, nsteps)[:1, :n_units * w.g_q]
+                oc.append_kv(kn[:1, :n_units], vn[:1, :n_units])
+                O.decode_attn(oc, q0, sm_scale)
+                nsteps += 1
+                plen = getattr(oc, "packed_len", getattr(oc, "length", 0))
+                sample_bytes += n_units * (plen * per_tok + getattr(oc, "res_len", 0) * 512) + 2 * n_units * w.g_q * 256
             tc1 = time.perf_counter()
-        sample_bytes = n_units * (oc.packed_len * {"int4": 136, "int2": 72, "mxfp4": 136}[w.fmt]
-                                  + getattr(oc, "res_len", 0) * 512) + 2 * n_units * w.g_q * 256
         cpu = {"value": round(sample_bytes / (tc1 - tc0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "seconds": round(tc1 - tc0, 3),
-               "sample": f"one decode step (append + attention) of {n_units} of the {w.batch * w.n_kv_heads} "
-                         f"(sequence, KV head) units of one layer at context {w.context}; numpy float64, 1 thread"}
+               "seconds": round(tc1 - tc0, 2),
+               "sample": f"{nsteps} decode steps (append + attention) of {n_units} of the "
+                         f"{w.batch * w.n_kv_heads} (sequence, KV head) units of one layer at context {w.context}; "
+                         f"numpy float64, 1 thread (includes drawing the step's inputs)"}
 
     rec = {
         "metric": "effective KV GB/s per decode step (32-layer LLaMA-8B-shape step: append + split-K attention "
