@@ -47,6 +47,7 @@
 // plain dot products and folds them into its partial in the final merge, so no workgroup
 // does the tail alone.
 #include "bd_common.h"
+#include "bd_device.h"
 
 namespace bd {
 namespace {
@@ -73,55 +74,6 @@ struct DecodeArgs {
   int num_splits;
   float scale_log2; // softmax_scale * log2(e)
 };
-
-__device__ __forceinline__ float h2f(uint16_t b) {
-  _Float16 h;
-  __builtin_memcpy(&h, &b, 2);
-  return (float)h;
-}
-__device__ __forceinline__ uint16_t f2h(float f) {
-  _Float16 h = (_Float16)f;
-  uint16_t b;
-  __builtin_memcpy(&b, &h, 2);
-  return b;
-}
-
-// DPP lane movement inside rows of 16 lanes.
-constexpr int kRowShl4 = 0x104, kRowShl8 = 0x108, kRowRor4 = 0x124, kRowRor8 = 0x128;
-constexpr int kQuadSwap1 = 0xB1 /* [1,0,3,2] */, kQuadSwap2 = 0x4E /* [2,3,0,1] */;
-constexpr int kRowHalfMirror = 0x141, kRowMirror = 0x140;
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
-}
-// sum over the 16 lanes of a row, result in every lane
-__device__ __forceinline__ float row_sum16(float x) {
-  x += dpp_f<kQuadSwap1>(x);
-  x += dpp_f<kQuadSwap2>(x);
-  x += dpp_f<kRowHalfMirror>(x);
-  x += dpp_f<kRowMirror>(x);
-  return x;
-}
-// combine over the lanes that share lane%4 (the same head): 4 column groups x 4 lane groups
-__device__ __forceinline__ float head_sum(float x) {
-  x += dpp_f<kRowRor4>(x);
-  x += dpp_f<kRowRor8>(x);
-  x += __shfl_xor(x, 16);
-  x += __shfl_xor(x, 32);
-  return x;
-}
-__device__ __forceinline__ float head_max(float x) {
-  x = fmaxf(x, dpp_f<kRowRor4>(x));
-  x = fmaxf(x, dpp_f<kRowRor8>(x));
-  x = fmaxf(x, __shfl_xor(x, 16));
-  x = fmaxf(x, __shfl_xor(x, 32));
-  return x;
-}
 
 // ---- format traits ---------------------------------------------------------------------
 // One lane loads WORDS 32-bit words (32 codes) per 16-row tile.  k-step j (of 4) of the tile
@@ -218,14 +170,6 @@ struct MergeLds {
 
 constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
 constexpr size_t kSmemBytes = cmax(sizeof(MergeLds), kWaves * sizeof(WaveLds));
-
-__device__ __forceinline__ void wave_sync() {
-  // LDS operations of one wave execute in order; this only stops the compiler from moving
-  // accesses across the exchange point.
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 template <int BITS>
 __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {

@@ -1,8 +1,303 @@
-// Decode attention over the MXFP4 cache (Sec. IV-D(2)) -- placeholder until the kernel lands.
+// Decode attention over the MXFP4 cache (Sec. IV-D(2): native low-precision matrix
+// instructions on packed 4-bit data with block scales, no dequantization for QK^T), gfx950.
+//
+//   S^T[token, head] = sum_c K[token, c] * Q[head, c]  on v_mfma_scale_f32_16x16x128_f8f6f4:
+//     A = the token's 128 e2m1 codes exactly as stored (each lane: one MX block of 32 codes,
+//     16 bytes, with its e8m0 scale applied by the instruction); B = Q.  Q stays bf16 in the
+//     interface; a bf16 (8 significant bits) is the exact sum of two e4m3 numbers (4 + 4 bits),
+//     so B is fed as a high and a low fp8 piece with their own block scales: two MFMAs per
+//     16-token tile give the exact products, accumulated in fp32.  (The paper quantizes Q to
+//     fp4, Sec. II Challenge 2; keeping it exact costs one more MFMA and no ALU work.)
+//   O^T[c, head] = sum_t V[t, c] * P'[t, head]  on v_mfma_f32_16x16x32_f16:
+//     V's MX blocks run along channels, i.e. across the M dimension of this product, where the
+//     hardware cannot apply them (it scales along the contraction).  So V codes are expanded
+//     e2m1 -> fp16 with v_cvt_scalef32_pk_f16_fp4 (scale 1) and the block scale 2^e(t, c/32) is
+//     folded into the probabilities instead: four variants of P', one per 32-channel block,
+//     each an exact exponent shift of p.  This is the re-quantization of P that the paper
+//     names as the new bottleneck of the native path (Sec. II Challenge 2); here it is 8 values
+//     per lane and block thanks to the same column-group trick as the integer kernel.
+//   V codes are stored channel-major inside each 128-token block (two tokens per byte), so the
+//   A operand of the second product is contraction-contiguous: 16-byte loads, no transposition.
 #include "bd_common.h"
+#include "bd_device.h"
 
 namespace bd {
-hipError_t launch_decode_mx(const bd_cache*, const void*, int, float, int, float*, float*, hipStream_t) {
-  return hipErrorNotSupported;
+namespace {
+
+constexpr int kWaves = 4;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kRowShl12 = 0x10C;
+
+struct MxArgs {
+  const uint8_t* k_codes;
+  const uint8_t* v_codes;
+  const uint8_t* k_scales;
+  const uint8_t* v_scales;
+  const uint16_t* q;
+  float* part_o;
+  float* part_ml;
+  int n_q_heads, n_kv_heads, gq;
+  int length;      // tokens in the cache
+  int capacity;
+  int num_splits;
+  float scale_log2;
+};
+
+struct MergeLdsMx {
+  float o[kWaves][4][kD];
+  float m[kWaves][4], l[kWaves][4];
+};
+
+__device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+__global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
+  __shared__ MergeLdsMx ml;
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, g = lane >> 4;
+  const int head = col & 3, cg = col >> 2;
+  const int gq = a.gq;
+  const size_t unit = (size_t)b * a.n_kv_heads + hkv;
+  const int nb = (a.length + kBlock - 1) / kBlock;
+  const int blk0 = (int)(((long)nb * split) / a.num_splits);
+  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  const int nbcap = a.capacity / kBlock;
+  const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
+
+  i8_t bhi, blo;          // Q[head][32g .. 32g+31] as two fp8 (e4m3) pieces
+  int sb_hi, sb_lo;       // their e8m0 block scales
+  u4_t kraw[8], vraw[8];
+  uint32_t ksc[8];
+  u4_t vsc[2];
+  auto issue = [&](int blk) {
+    const size_t tok0 = unit * a.capacity + (size_t)blk * kBlock;
+#pragma unroll
+    for (int T = 0; T < 8; ++T) {
+      const size_t t = tok0 + tok_base + 4 * T;
+      ksc[T] = *reinterpret_cast<const uint32_t*>(a.k_scales + t * 4);
+      kraw[T] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(a.k_codes + t * 64 + 16 * g));
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+      vsc[half] = *reinterpret_cast<const u4_t*>(a.v_scales + (tok0 + 32 * g + 16 * half + 4 * cg) * 4);
+    const uint8_t* vp = a.v_codes + (unit * nbcap + blk) * (size_t)(kD * 64) + 16 * g;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+      vraw[mt] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(vp + (size_t)(16 * mt + col) * 64));
+  };
+  int blk = blk0 + wave;
+  if (blk < blk1) issue(blk);
+
+  // ---- the query as the B operand: exact split of each bf16 into two e4m3 pieces.
+  // Operand layout of the 8-bit side (measured): lane (column, g) holds contraction indices
+  // 16g .. 16g+15 in bytes 0..15 and 64+16g .. 64+16g+15 in bytes 16..31, while the 4-bit
+  // side holds 32g .. 32g+31 per lane.  One block scale per head (all 128 channels) is used
+  // for B, so its value does not depend on which lane the instruction reads it from.
+  {
+    float x[32];
+    u4_t raw[4] = {};
+    if (head < gq) {
+      const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + hkv * gq + head) * kD + 16 * g;
+      raw[0] = *reinterpret_cast<const u4_t*>(qp);
+      raw[1] = *reinterpret_cast<const u4_t*>(qp + 8);
+      raw[2] = *reinterpret_cast<const u4_t*>(qp + 64);
+      raw[3] = *reinterpret_cast<const u4_t*>(qp + 72);
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      x[i] = bf2f((raw[i >> 3][(i >> 1) & 3] >> (16 * (i & 1))) & 0xFFFFu);
+      amax = fmaxf(amax, fabsf(x[i]));
+    }
+    amax = fmaxf(amax, __shfl_xor(amax, 16));
+    amax = fmaxf(amax, __shfl_xor(amax, 32));
+    int eb = 0;
+    if (amax > 0.0f) eb = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 127 - 7;   // amax * 2^-eb in [128, 256)
+    eb = min(max(eb, -123), 127);
+    sb_hi = eb + 127;
+    sb_lo = eb - 4 + 127;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+      int hi = 0, lo = 0;
+      float rem[4];
+#pragma unroll
+      for (int hw = 0; hw < 2; ++hw) {
+        const float x0 = ldexpf(x[4 * v + 2 * hw], -eb), x1 = ldexpf(x[4 * v + 2 * hw + 1], -eb);
+        hi = hw ? __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi, true) : __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi, false);
+        rem[2 * hw] = x0;
+        rem[2 * hw + 1] = x1;
+      }
+      rem[0] = (rem[0] - __builtin_amdgcn_cvt_f32_fp8(hi, 0)) * 16.0f;
+      rem[1] = (rem[1] - __builtin_amdgcn_cvt_f32_fp8(hi, 1)) * 16.0f;
+      rem[2] = (rem[2] - __builtin_amdgcn_cvt_f32_fp8(hi, 2)) * 16.0f;
+      rem[3] = (rem[3] - __builtin_amdgcn_cvt_f32_fp8(hi, 3)) * 16.0f;
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[0], rem[1], lo, false);
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[2], rem[3], lo, true);
+      bhi[v] = hi;
+      blo[v] = lo;
+    }
+  }
+
+  float m_run = -INFINITY, l_run = 0.0f;
+  f4_t oacc[8];
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+  while (blk < blk1) {
+    const int nblk = blk + kWaves;
+    // ---- S^T tiles straight from the packed codes; column group cg keeps tiles cg and 4+cg
+    float s[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      f4_t st[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const int T = 4 * half + tt;
+        const i8_t ak = {(int)kraw[T][0], (int)kraw[T][1], (int)kraw[T][2], (int)kraw[T][3], 0, 0, 0, 0};
+        const int sa = (int)((ksc[T] >> (8 * g)) & 0xFFu);
+        f4_t acc = {0.f, 0.f, 0.f, 0.f};
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, bhi, acc, 4, 0, 0, sa, 0, sb_hi);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, blo, acc, 4, 0, 0, sa, 0, sb_lo);
+        st[tt] = acc;
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float lo = cg & 1 ? st[1][r] : st[0][r], hi = cg & 1 ? st[3][r] : st[2][r];
+        const int t = blk * kBlock + 32 * g + 16 * half + 4 * cg + r;
+        s[half][r] = t < a.length ? (cg & 2 ? hi : lo) * a.scale_log2 : -INFINITY;   // tokens past the end
+      }
+    }
+    // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
+    float bmax = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                       fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    bmax = head_max(bmax);
+    const float m_new = fmaxf(m_run, bmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+    }
+    float p[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        p[half][r] = __builtin_amdgcn_exp2f(s[half][r] - m_new);
+        l_run += p[half][r];
+      }
+    // ---- O^T += V^T P'_cb for the four 32-channel blocks cb (M tiles 2cb, 2cb+1)
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+      uint32_t pk[2][2];   // [half][rows 0,1 | rows 2,3] as packed fp16
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        float pe[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          int e = (int)((vsc[half][r] >> (8 * cb)) & 0xFFu) - 127;
+          e = min(e, 15);   // keeps P' inside fp16; larger scales mean |V| > 2e5
+          pe[r] = ldexpf(p[half][r], e);
+        }
+        pk[half][0] = (uint32_t)f2h(pe[0]) | ((uint32_t)f2h(pe[1]) << 16);
+        pk[half][1] = (uint32_t)f2h(pe[2]) | ((uint32_t)f2h(pe[3]) << 16);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int half = j >> 1;
+        u4_t pb;
+        if ((j & 1) == 0) {
+          pb[0] = pk[half][0];
+          pb[1] = pk[half][1];
+          pb[2] = dpp_u<kRowShl4>(pk[half][0]);
+          pb[3] = dpp_u<kRowShl4>(pk[half][1]);
+        } else {
+          pb[0] = dpp_u<kRowShl8>(pk[half][0]);
+          pb[1] = dpp_u<kRowShl8>(pk[half][1]);
+          pb[2] = dpp_u<kRowShl12>(pk[half][0]);
+          pb[3] = dpp_u<kRowShl12>(pk[half][1]);
+        }
+        const h8_t bp = __builtin_bit_cast(h8_t, pb);
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+          const int mt = 2 * cb + mm;
+          const uint32_t w = vraw[mt][j];
+          h2_t c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0);
+          h2_t c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1);
+          h2_t c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2);
+          h2_t c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3);
+          const h8_t av = {c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
+          oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[mt], 0, 0, 0);
+        }
+      }
+    }
+    if (nblk < blk1) issue(nblk);
+    blk = nblk;
+  }
+
+  // ---- merge the waves of the workgroup
+  l_run = head_sum(l_run);
+  if (col < 4) {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
+    if (g == 0) {
+      ml.m[wave][col] = m_run;
+      ml.l[wave][col] = l_run;
+    }
+  }
+  __syncthreads();
+  {
+    const int h = tid >> 6, c0 = 2 * (tid & 63);
+    if (h < gq) {
+      float M = ml.m[0][h];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
+      float L = 0.f, o0 = 0.f, o1 = 0.f;
+      if (M > -INFINITY) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          const float f = __builtin_amdgcn_exp2f(ml.m[w][h] - M);
+          L += f * ml.l[w][h];
+          o0 += f * ml.o[w][h][c0];
+          o1 += f * ml.o[w][h][c0 + 1];
+        }
+      }
+      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * gq + h;
+      float2 o = {o0, o1};
+      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+      if ((tid & 63) == 0) {
+        a.part_ml[row * 2] = M;
+        a.part_ml[row * 2 + 1] = L;
+      }
+    }
+  }
 }
+
+}  // namespace
+
+hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale, int num_splits,
+                            float* part_o, float* part_ml, hipStream_t st) {
+  MxArgs a;
+  a.k_codes = (const uint8_t*)c->k_codes;
+  a.v_codes = (const uint8_t*)c->v_codes;
+  a.k_scales = (const uint8_t*)c->k_params;
+  a.v_scales = (const uint8_t*)c->v_params;
+  a.q = (const uint16_t*)q;
+  a.part_o = part_o;
+  a.part_ml = part_ml;
+  a.n_q_heads = c->n_q_heads;
+  a.n_kv_heads = c->n_kv_heads;
+  a.gq = c->n_q_heads / c->n_kv_heads;
+  a.length = length;
+  a.capacity = c->capacity;
+  a.num_splits = num_splits;
+  a.scale_log2 = softmax_scale * kLog2e;
+  dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
+  decode_mx_kernel<<<grid, block, 0, st>>>(a);
+  return hipGetLastError();
+}
+
 }  // namespace bd

@@ -215,3 +215,139 @@ def test_cfg3_128k_256_steps():
                 ref = O.decode_attn(ocs[h], q[:, h * g:(h + 1) * g], W.softmax_scale(w))
                 assert_attn_close(got[:, h * g:(h + 1) * g], ref, f"cfg3 step {step} head {h}")
     assert (gc.packed_len, gc.res_len) == (131072 + 256, 0)
+
+
+# ---------------------------------------------------------------------------- MXFP4
+
+def _mx_pair(w, capacity, L=None):
+    K, V = W.make_kv(w, length=L)
+    oc = O.MxCache(w.batch, w.n_kv_heads, capacity)
+    oc.quant_pack_kv(K, V)
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, "mxfp4", capacity)
+    gc.quant_pack_kv(to_dev(K, "bf16"), to_dev(V, "bf16"))
+    return K, V, oc, gc
+
+
+def _assert_mx_cache_equal(oc, gc):
+    import torch
+    torch.cuda.synchronize()
+    assert gc.packed_len == oc.length and gc.res_len == 0
+    for i, name in enumerate(["k_codes", "v_codes", "k_scales", "v_scales"]):
+        ref = getattr(oc, name)
+        got = gc.host_buffer(i).reshape(ref.shape)
+        if name == "v_codes":
+            assert np.array_equal(got, ref), name      # whole buffer: absent tokens are zero nibbles
+        else:
+            assert np.array_equal(got[:, :, :oc.length], ref[:, :, :oc.length]), name
+
+
+@pytest.mark.parametrize("L", [128 * 3 + 37, 256, 1, 0])
+def test_mx_quant_pack_bit_exact(L):
+    w = W.scaled(W.CONFIGS["cfg4"], batch=2, n_q_heads=8, n_kv_heads=2, context=L)
+    _, _, oc, gc = _mx_pair(w, 512)
+    _assert_mx_cache_equal(oc, gc)
+
+
+def test_mx_quant_adversarial_bit_exact():
+    """Zero blocks, exact ties on the e2m1 grid, saturation, negative zero, huge and tiny magnitudes."""
+    rng = np.random.default_rng(3)
+    K = W.round_to_bf16(rng.standard_normal((1, 1, 128, 128)).astype(np.float32))
+    V = W.round_to_bf16(rng.standard_normal((1, 1, 128, 128)).astype(np.float32))
+    K[0, 0, 0, :32] = 0.0
+    K[0, 0, 1, :32] = np.array([4.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0] * 4, np.float32)        # ties, amax 5 -> e 0
+    K[0, 0, 2, :32] = np.array([-4.0, -0.25, -0.75, -1.25, -1.75, -2.5, -3.5, -5.0] * 4, np.float32)
+    K[0, 0, 3, :32] = np.array([7.5, 7.0, 6.5, -7.75] + [0.1, -0.0, -0.1, 0.3] * 7, np.float32)        # saturation
+    K[0, 0, 4, :32] = W.round_to_bf16(np.full(32, 3.0e38, np.float32)); K[0, 0, 4, 1] = 1.0
+    K[0, 0, 5, :32] = W.round_to_bf16(np.full(32, 1.0e-38, np.float32)); K[0, 0, 5, 3] = -3.0e-39
+    V[0, 0, 7, 32:64] = 0.0
+    V[0, 0, 8, 32:64] = np.array([6.0, 5.0, 1.25, -1.75] * 8, np.float32)
+    K, V = W.round_to_bf16(K), W.round_to_bf16(V)
+    oc = O.MxCache(1, 1, 128); oc.quant_pack_kv(K, V)
+    gc = B.KVCache(1, 1, 1, "mxfp4", 128); gc.quant_pack_kv(to_dev(K, "bf16"), to_dev(V, "bf16"))
+    _assert_mx_cache_equal(oc, gc)
+
+
+@pytest.mark.parametrize("L,k", [(100, 60), (128, 3), (0, 130)])
+def test_mx_append_bit_exact(L, k):
+    w = W.scaled(W.CONFIGS["cfg4"], batch=2, n_q_heads=8, n_kv_heads=2, context=L)
+    _, _, oc, gc = _mx_pair(w, 384)
+    for i in range(k):
+        kn, vn = W.make_new_kv(w, i)
+        oc.append_kv(kn, vn); gc.append_kv(to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+    _assert_mx_cache_equal(oc, gc)
+
+
+def _host_combine(gc, w, ns):
+    """Log-sum-exp merge of the fp32 split partials left in the workspace, in float64 on the host."""
+    import torch
+    torch.cuda.synchronize()
+    rows = w.batch * w.n_q_heads
+    wsf = gc.workspace(ns).view(torch.float32).cpu().numpy().astype(np.float64)
+    po = wsf[:ns * rows * 128].reshape(ns, rows, 128)
+    pml = wsf[ns * rows * 128: ns * rows * 130].reshape(ns, rows, 2)
+    M = pml[:, :, 0].max(axis=0)
+    f = np.where(np.isinf(pml[:, :, 0]), 0.0, np.exp2(pml[:, :, 0] - M[None, :]))
+    L = (f * pml[:, :, 1]).sum(axis=0)
+    return ((f[:, :, None] * po).sum(axis=0) / L[:, None]).reshape(w.batch, w.n_q_heads, 128)
+
+
+def _mx_decode_check(gc, oc_ref, w, q, ns, what):
+    """bf16 output rounding alone is 2^-9 relative (about 1.1e-3 relative L2), above the bar for
+    the kernel's arithmetic.  So the bar (2e-3 max-abs, 1e-3 relative L2 against the float64
+    oracle) is applied to the fp32 result the kernel leaves in the split partials, and the bf16
+    output must then be that result rounded: within one bf16 step of it."""
+    import torch
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device="cuda:0")
+    qd = to_dev(q, "bf16")
+    B.bd_decode_attn(gc.desc, qd, gc.packed_len, gc.res_len, W.softmax_scale(w), ns, gc.workspace(ns), None)
+    exact = _host_combine(gc, w, ns)
+    ma, rl = assert_attn_close(exact, oc_ref, what + " (fp32 partials)")
+    B.bd_splitk_combine(gc.desc, gc.workspace(ns), ns, out)
+    torch.cuda.synchronize()
+    got = out_to_f64(out)
+    mask = ~np.isnan(oc_ref)
+    assert np.all(np.abs(got - exact)[mask] <= np.abs(exact[mask]) * 2.0 ** -8 + 1e-12), what + " (bf16 rounding)"
+    out2 = torch.empty_like(out)
+    B.bd_decode_attn(gc.desc, qd, gc.packed_len, gc.res_len, W.softmax_scale(w), ns, gc.workspace(ns), out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2), what + " (combine enqueued by bd_decode_attn)"
+    return ma, rl
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4)])
+@pytest.mark.parametrize("L", [128 * 9 + 37, 128 * 4, 77])
+def test_mx_decode_matches_oracle(hq, hkv, L):
+    w = W.scaled(W.CONFIGS["cfg4"], batch=2, n_q_heads=hq, n_kv_heads=hkv, context=L)
+    _, _, oc, gc = _mx_pair(w, 2048)
+    q = W.make_q(w)
+    ref = O.decode_attn(oc, q, W.softmax_scale(w))
+    nb = -(-L // 128)
+    for ns in sorted({1, 2, 3, nb, nb + 5, gc.choose_splits()}):
+        _mx_decode_check(gc, ref, w, q, ns, f"mx L={L} splits={ns}")
+
+
+def test_cfg4_mxfp4_full_size_sampled():
+    """Configuration 4 at full size (batch 16, 16K, MXFP4) plus one appended token; the oracle
+    follows 3 of the 128 (sequence, KV head) units."""
+    w = W.CONFIGS["cfg4"]
+    K, V = W.make_kv(w)
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, "mxfp4", w.context + 128)
+    gc.quant_pack_kv(to_dev(K, "bf16"), to_dev(V, "bf16"))
+    kn, vn = W.make_new_kv(w, 0)
+    gc.append_kv(to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+    q = W.make_q(w)
+    ns = gc.choose_splits()
+    ref = np.full((w.batch, w.n_q_heads, 128), np.nan)
+    g = w.g_q
+    bufs = [gc.host_buffer(i) for i in range(4)]
+    for (b, h) in [(0, 0), (7, 3), (15, 7)]:
+        oc = O.MxCache(1, 1, w.context + 128)
+        oc.quant_pack_kv(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1])
+        oc.append_kv(kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+        for i, name in enumerate(["k_codes", "v_codes", "k_scales", "v_scales"]):
+            r = getattr(oc, name)
+            full = bufs[i].reshape((w.batch, w.n_kv_heads) + r.shape[2:])
+            n = r.shape[2] if name == "v_codes" else oc.length     # tokens past the end hold no data
+            assert np.array_equal(full[b, h, :n], r[0, 0, :n]), (name, b, h)
+        ref[b, h * g:(h + 1) * g] = O.decode_attn(oc, q[b:b + 1, h * g:(h + 1) * g], W.softmax_scale(w))[0]
+    _mx_decode_check(gc, ref, w, q, ns, "cfg4")
