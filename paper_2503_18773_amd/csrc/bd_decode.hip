@@ -451,56 +451,54 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   }
 }
 
-// Log-sum-exp merge of the split partials into the final output row (fp16 or bf16).
-// One workgroup per output row; thread = (half of the partials, channel).
+// Log-sum-exp merge of the split partials into the final output rows (fp16 or bf16).
+// One workgroup per output row: 128 channels x 2 interleaved halves of the partials.  A single
+// pass with a running maximum, so that every load is independent of every other and they
+// can all be in flight at once (the kernel is pure latency: a few hundred KB in total).
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ part_o,
                                                        const float* __restrict__ part_ml, int nparts, int nrows,
                                                        uint16_t* __restrict__ out) {
-  __shared__ float sw[1024];      // weight of each partial (chunks of 1024 partials)
-  __shared__ float sred[3][256];
+  __shared__ float sm[2][128], sl[2][128], so[2][128];
   const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, half = tid >> 7;
-  // pass 1: global max of the partial maxima
-  float M = -INFINITY;
-  for (int p = tid; p < nparts; p += 256) M = fmaxf(M, part_ml[((size_t)p * nrows + row) * 2]);
-  sred[0][tid] = M;
-  __syncthreads();
-  for (int s = 128; s >= 1; s >>= 1) {
-    if (tid < s) sred[0][tid] = fmaxf(sred[0][tid], sred[0][tid + s]);
-    __syncthreads();
-  }
-  M = sred[0][0];
-  __syncthreads();
-  float L = 0.f, o = 0.f;
-  if (M > -INFINITY) {
-    for (int p0 = 0; p0 < nparts; p0 += 1024) {
-      const int n = min(1024, nparts - p0);
-      float lpart = 0.f;
-      for (int p = tid; p < n; p += 256) {
-        const size_t r = (size_t)(p0 + p) * nrows + row;
-        const float ms = part_ml[r * 2];
-        const float f = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-        sw[p] = f;
-        lpart += f * part_ml[r * 2 + 1];
-      }
-      L += lpart;
-      __syncthreads();
-      const int lo = half ? n / 2 : 0, hi = half ? n : n / 2;
-#pragma unroll 8
-      for (int p = lo; p < hi; ++p) o = __builtin_fmaf(sw[p], part_o[((size_t)(p0 + p) * nrows + row) * kD + c], o);
-      __syncthreads();
+  float M = -INFINITY, L = 0.f, o = 0.f;
+  constexpr int kBatch = 16;   // loads issued together
+  for (int p0 = half; p0 < nparts; p0 += 2 * kBatch) {
+    float2 ml[kBatch];
+    float ov[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int p = p0 + 2 * i;
+      const size_t r = (size_t)(p < nparts ? p : 0) * nrows + row;
+      ml[i] = *reinterpret_cast<const float2*>(part_ml + r * 2);
+      ov[i] = part_o[r * kD + c];
+      if (p >= nparts) ml[i].x = -INFINITY;
+    }
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const float Mn = fmaxf(M, ml[i].x);
+      const bool live = ml[i].x > -INFINITY;
+      const float fo = live ? __builtin_amdgcn_exp2f(M - Mn) : 1.0f;
+      const float fn = live ? __builtin_amdgcn_exp2f(ml[i].x - Mn) : 0.0f;
+      L = L * fo + fn * ml[i].y;
+      o = o * fo + fn * ov[i];
+      M = Mn;
     }
   }
-  sred[1][tid] = L;
-  sred[2][tid] = o;
+  sm[half][c] = M;
+  sl[half][c] = L;
+  so[half][c] = o;
   __syncthreads();
-  for (int s = 128; s >= 1; s >>= 1) {
-    if (tid < s) sred[1][tid] += sred[1][tid + s];
-    __syncthreads();
-  }
   if (tid < 128) {
-    const float Lt = sred[1][0];
-    const float res = Lt > 0.f ? (sred[2][tid] + sred[2][tid + 128]) / Lt : 0.f;
+    const float M0 = sm[0][c], M1 = sm[1][c];
+    const float Mt = fmaxf(M0, M1);
+    float res = 0.f;
+    if (Mt > -INFINITY) {
+      const float f0 = M0 > -INFINITY ? __builtin_amdgcn_exp2f(M0 - Mt) : 0.f;
+      const float f1 = M1 > -INFINITY ? __builtin_amdgcn_exp2f(M1 - Mt) : 0.f;
+      const float Lt = f0 * sl[0][c] + f1 * sl[1][c];
+      res = Lt > 0.f ? (f0 * so[0][c] + f1 * so[1][c]) / Lt : 0.f;
+    }
     if (BF16) {
       uint32_t u = __float_as_uint(res);
       u += 0x7FFFu + ((u >> 16) & 1u);

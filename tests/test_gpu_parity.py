@@ -310,7 +310,8 @@ def _mx_decode_check(gc, oc_ref, w, q, ns, what):
     out2 = torch.empty_like(out)
     B.bd_decode_attn(gc.desc, qd, gc.packed_len, gc.res_len, W.softmax_scale(w), ns, gc.workspace(ns), out2)
     torch.cuda.synchronize()
-    assert torch.equal(out, out2), what + " (combine enqueued by bd_decode_attn)"
+    got2 = out_to_f64(out2)      # merged inside the kernel: another summation order, same bar
+    assert np.all(np.abs(got2 - exact)[mask] <= np.abs(exact[mask]) * 2.0 ** -8 + 1e-12), what + " (in-kernel combine)"
     return ma, rl
 
 
