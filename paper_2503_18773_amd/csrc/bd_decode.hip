@@ -203,51 +203,70 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
 
-  // Software pipeline over this wave's blocks: K codes and parameters of the next block are
-  // requested right after the QK^T of the current one, its V codes right after the PV, so
-  // loads stay in flight across the softmax and the MFMAs without a second set of registers.
+  // Software pipeline over this wave's blocks without a second set of registers: as soon as
+  // a raw tile has been consumed, the same registers are reloaded with that tile of the wave's
+  // next block (parameters right after the query rescale), so every load has about one block
+  // period to arrive.
   const int prep_head = lane >> 4, prep_sg = lane & 15;
   const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
   RawTile<WORDS> kraw[8], vraw[8];
   u4_t kp0, kp1;   // K parameters (half2) of this lane's two channel runs
   u2_t vp2;        // V parameters (half2) of tokens 2*lane, 2*lane+1
-  auto issue_k = [&](int blk) {
-    const size_t gb = unit * a.nbcap + blk;
-    const uint32_t* pp = a.k_params + gb * kD;   // parameters first: the block's first consumer
+  auto issue_kpar = [&](int blk) {
+    const uint32_t* pp = a.k_params + (unit * a.nbcap + blk) * kD;
     kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
     kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
-    const uint32_t* kp = a.k_codes + gb * (size_t)(kBlock * KROW) + WORDS * g;
-#pragma unroll
-    for (int T = 0; T < 8; ++T) kraw[T] = load_raw<WORDS>(kp + (size_t)(tok_base + 4 * T) * KROW);
   };
-  auto issue_v = [&](int blk) {
-    const size_t gb = unit * a.nbcap + blk;
-    vp2 = *reinterpret_cast<const u2_t*>(a.v_params + gb * kBlock + 2 * lane);
-    const uint32_t* vp = a.v_codes + gb * (size_t)(kD * VROW) + WORDS * g;
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt) vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
+  auto issue_vpar = [&](int blk) {
+    vp2 = *reinterpret_cast<const u2_t*>(a.v_params + (unit * a.nbcap + blk) * kBlock + 2 * lane);
   };
+  auto issue_ktile = [&](int blk, int T) {
+    const uint32_t* kp = a.k_codes + (unit * a.nbcap + blk) * (size_t)(kBlock * KROW) + WORDS * g;
+    kraw[T] = load_raw<WORDS>(kp + (size_t)(tok_base + 4 * T) * KROW);
+  };
+  auto issue_vtile = [&](int blk, int mt) {
+    const uint32_t* vp = a.v_codes + (unit * a.nbcap + blk) * (size_t)(kD * VROW) + WORDS * g;
+    vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
+  };
+  // Loads return in order, so what is needed first is requested first: the query slices
+  // and this wave's first residual key row, then the first block.
+  u2_t qraw0 = {0u, 0u}, qraw1 = {0u, 0u};
+  if (prep_head < gq) {
+    qraw0 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run0);
+    qraw1 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run1);
+  }
+  const bool has_res = rt0 + wave < rt1;
+  const uint16_t* kres = a.k_res + unit * kBlock * kD;
+  uint32_t qres_raw[4] = {0u, 0u, 0u, 0u}, kres_raw = 0u;
+  if (has_res) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+      if (h < gq) qres_raw[h] = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
+    kres_raw = *reinterpret_cast<const uint32_t*>(kres + (size_t)(rt0 + wave) * kD + 2 * lane);
+  }
   int blk = blk0 + wave;
-  if (blk < blk1) {
-    issue_k(blk);
-    issue_v(blk);
+  if (blk < blk1) {   // parameters first: they are the block's first consumers
+    issue_kpar(blk);
+    issue_vpar(blk);
+#pragma unroll
+    for (int T = 0; T < 8; ++T) issue_ktile(blk, T);
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
   }
 
   // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
-  if (rt1 > rt0) {
+  if (has_res) {
     float qr[4][2];
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-      uint32_t raw = 0;
-      if (h < gq) raw = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
-      qr[h][0] = h2f((uint16_t)(raw & 0xFFFFu)) * a.scale_log2;
-      qr[h][1] = h2f((uint16_t)(raw >> 16)) * a.scale_log2;
+      qr[h][0] = h2f((uint16_t)(qres_raw[h] & 0xFFFFu)) * a.scale_log2;
+      qr[h][1] = h2f((uint16_t)(qres_raw[h] >> 16)) * a.scale_log2;
     }
-    const uint16_t* kr = a.k_res + unit * kBlock * kD;
+    uint32_t raw = kres_raw;
     for (int t = rt0 + wave; t < rt1; t += kWaves) {
-      const uint32_t raw = *reinterpret_cast<const uint32_t*>(kr + (size_t)t * kD + 2 * lane);
       const float k0 = h2f((uint16_t)(raw & 0xFFFFu)), k1 = h2f((uint16_t)(raw >> 16));
+      if (t + kWaves < rt1) raw = *reinterpret_cast<const uint32_t*>(kres + (size_t)(t + kWaves) * kD + 2 * lane);
       float sh[4];
 #pragma unroll
       for (int h = 0; h < 4; ++h) {
@@ -263,21 +282,27 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   // Query slice this lane rescales every block: head lane/16, slot group lane%16
   // (two runs of 4 consecutive channels); zero for the padding heads of a small group.
   float qv[2][4];
-  {
-    u2_t r0 = {0u, 0u}, r1 = {0u, 0u};
-    if (prep_head < gq) {
-      r0 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run0);
-      r1 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run1);
-    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qv[0][i] = h2f((uint16_t)((r0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
-      qv[1][i] = h2f((uint16_t)((r1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
-    }
+  for (int i = 0; i < 4; ++i) {
+    qv[0][i] = h2f((uint16_t)((qraw0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
+    qv[1][i] = h2f((uint16_t)((qraw1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
   }
 
+  // Two waves of different workgroups share each SIMD and the issue arbiter favours the older
+  // one, which then runs a block ahead, finishes early and leaves the other to drain alone with
+  // half the loads in flight.  Priority by remaining work keeps the pair in step.
+  const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
+  int done = 0;
   while (blk < blk1) {
     const int nblk = blk + kWaves;
+    {
+      const int q4 = (4 * done) / (my_blocks > 0 ? my_blocks : 1);   // quarter of the work done: 0..3
+      if (q4 == 0) __builtin_amdgcn_s_setprio(3);
+      else if (q4 == 1) __builtin_amdgcn_s_setprio(2);
+      else if (q4 == 2) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
+      ++done;
+    }
     // ---- per-block query rescale (K is channel-wise): Q' = Q * s_c, zero term sum_c Q_c z_c
     {
       float zsum = 0.0f;
@@ -323,6 +348,11 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
     }
     const float zq = wl.zq[head];
+    const bool has_next = nblk < blk1;
+    if (has_next) {
+      issue_kpar(nblk);
+      issue_vpar(nblk);
+    }
 
     // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); column
     //      group cg keeps tiles cg and 4+cg
@@ -341,13 +371,16 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         }
         s[tt] = acc;
       }
+      if (has_next) {
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) issue_ktile(nblk, 4 * half + tt);
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float lo = cg & 1 ? s[1][r] : s[0][r], hi = cg & 1 ? s[3][r] : s[2][r];
         sc[half][r] = cg & 2 ? hi : lo;
       }
     }
-    if (nblk < blk1) issue_k(nblk);
     // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
     float bmax = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                        fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
@@ -357,7 +390,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     m_run = m_new;
     l_run *= alpha;
     z_run *= alpha;
-    if (__any(alpha != 1.0f)) {
+    if (blk != blk0 + wave && __any(alpha != 1.0f)) {   // nothing to rescale on the first block
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
       xacc *= alpha;
@@ -380,17 +413,27 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         pb[2 * half + 1][r] = dpp_u<F::kStepShift>(pair);
       }
     }
-    // ---- O^T += V^T P' : k-step j contracts 32 tokens (8 per lane group)
+    // ---- O^T += V^T P' : k-step j contracts 32 tokens (8 per lane group); two M tiles at a
+    //      time, whose raw registers are then handed to the next block
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const h8_t bp = __builtin_bit_cast(h8_t, pb[j]);
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt)
-        oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[mt].w, j), bp, oacc[mt], 0, 0, 0);
       const h8_t ac = *reinterpret_cast<const h8_t*>(&wl.c16[8 * (4 * g + j)]);
-      xacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac, bp, xacc, 0, 0, 0);
+      xacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac, __builtin_bit_cast(h8_t, pb[j]), xacc, 0, 0, 0);
     }
-    if (nblk < blk1) issue_v(nblk);
+#pragma unroll
+    for (int mp = 0; mp < 4; ++mp) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const h8_t bp = __builtin_bit_cast(h8_t, pb[j]);
+        oacc[2 * mp] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[2 * mp].w, j), bp, oacc[2 * mp], 0, 0, 0);
+        oacc[2 * mp + 1] =
+            __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[2 * mp + 1].w, j), bp, oacc[2 * mp + 1], 0, 0, 0);
+      }
+      if (has_next) {
+        issue_vtile(nblk, 2 * mp);
+        issue_vtile(nblk, 2 * mp + 1);
+      }
+    }
     wave_sync();   // the next block's prep overwrites this wave's LDS scratch
     blk = nblk;
   }
