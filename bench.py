@@ -2,8 +2,8 @@
 """Benchmark of the decode-step hot path (append + attention over the packed KV cache).
 
 One "step" = one decode step of a LLaMA-3.1-8B-shaped model: 32 layers, each issuing
-bd_append_kv and bd_decode_attn (split-K + combine) on its own, independent cache, back to
-back on one stream.  Thirty-two distinct caches keep the working set (> 1 GB) far above the
+bd_decode_step (= bd_append_kv + bd_decode_attn with split-K combine) on its own,
+independent cache, back to back on one stream.  Thirty-two distinct caches keep the working set (> 1 GB) far above the
 256 MB last-level cache, so every step streams its KV bytes from HBM.
 
 Prints ONE JSON line (see README for the fields).  value = effective KV GB/s:
@@ -124,8 +124,7 @@ def main() -> int:
         kn, vn = new_kv[s]
         nbytes = 0
         for li, c in enumerate(caches):
-            c.append_kv(kn, vn)
-            c.decode_attn(qs[s], sm_scale, outs[li], num_splits=splits)
+            c.decode_step(kn, vn, qs[s], sm_scale, outs[li], num_splits=splits)
             nbytes += algorithmic_bytes(w, c.packed_len, c.res_len)
         step_bytes.append(nbytes)
 

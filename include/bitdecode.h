@@ -125,6 +125,18 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
                          float softmax_scale, int32_t num_splits, void* workspace, void* out,
                          void* stream);
 
+/* One decode step in one call: exactly bd_append_kv(k_new, v_new) followed by
+ * bd_decode_attn(q, ..., out) -- same cache contents, same lengths, same output bits -- but
+ * on steps that do not fill the residual block the new token is attended straight from
+ * k_new / v_new and filed into the residual by the attention kernel itself, which saves the
+ * separate append launch (the fusion of the paper's Residual Kernel, Sec. III-A(1) /
+ * Sec. IV-B, without its lazy flush).  All pointers as in the two calls; `out` must be
+ * non-NULL.  On error nothing is enqueued by the failing part and the lengths are those
+ * reached so far. */
+bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
+                         int32_t* packed_len, int32_t* res_len, float softmax_scale,
+                         int32_t num_splits, void* workspace, void* out, void* stream);
+
 /* Merge the num_splits partials left in `workspace` by bd_decode_attn (log-sum-exp
  * merge: m = max m_s, l = sum l_s 2^(m_s-m), O = sum O_s 2^(m_s-m) / l) into
  * out (device, [B][n_q_heads][D], fp16 / bf16). */

@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.bd_append_kv.restype, L.bd_append_kv.argtypes = ctypes.c_int, [P, V, V, IP, IP, V]
         L.bd_decode_attn.restype, L.bd_decode_attn.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V, V]
         L.bd_splitk_combine.restype, L.bd_splitk_combine.argtypes = ctypes.c_int, [P, V, I, V, V]
+        L.bd_decode_step.restype, L.bd_decode_step.argtypes = ctypes.c_int, [P, V, V, V, IP, IP, F, I, V, V, V]
         L.bd_strerror.restype, L.bd_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
         L.bd_last_hip_error.restype, L.bd_last_hip_error.argtypes = ctypes.c_int, []
         _lib = L
@@ -58,7 +59,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
-           "bd_decode_attn", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error"]
+           "bd_decode_attn", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error"]
 
 
 def _ptr(t):
@@ -110,6 +111,16 @@ def bd_decode_attn(c: bd_cache, q, packed_len: int, res_len: int, softmax_scale:
                    workspace, out=None, stream=None):
     _check(lib().bd_decode_attn(ctypes.byref(c), _ptr(q), packed_len, res_len, softmax_scale, num_splits,
                                 _ptr(workspace), _ptr(out), _stream(stream)), "bd_decode_attn")
+
+
+def bd_decode_step(c: bd_cache, k_new, v_new, q, packed_len: int, res_len: int, softmax_scale: float,
+                   num_splits: int, workspace, out, stream=None):
+    """Returns the updated (packed_len, res_len)."""
+    pl, rl = ctypes.c_int32(packed_len), ctypes.c_int32(res_len)
+    _check(lib().bd_decode_step(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), ctypes.byref(pl),
+                                ctypes.byref(rl), softmax_scale, num_splits, _ptr(workspace), _ptr(out),
+                                _stream(stream)), "bd_decode_step")
+    return pl.value, rl.value
 
 
 def bd_splitk_combine(c: bd_cache, workspace, num_splits: int, out, stream=None):
@@ -171,6 +182,12 @@ class KVCache:
         else:
             bd_decode_attn(self.desc, q, self.packed_len, self.res_len, softmax_scale, ns, ws, None, stream)
             bd_splitk_combine(self.desc, ws, ns, out, stream)
+        return out
+
+    def decode_step(self, k_new, v_new, q, softmax_scale: float, out, num_splits: int | None = None, stream=None):
+        ns = self.choose_splits() if num_splits is None else num_splits
+        self.packed_len, self.res_len = bd_decode_step(self.desc, k_new, v_new, q, self.packed_len, self.res_len,
+                                                       softmax_scale, ns, self.workspace(ns), out, stream)
         return out
 
     def host_buffer(self, i: int):

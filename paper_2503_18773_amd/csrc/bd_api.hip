@@ -169,11 +169,42 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
     s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, st));
   } else {
     if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
-    s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, st));
+    s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, nullptr,
+                                     nullptr, st));
   }
   if (s != BD_OK) return s;
   if (out) s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st));
   return s;
+}
+
+bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
+                         int32_t* packed_len, int32_t* res_len, float softmax_scale, int32_t num_splits,
+                         void* workspace, void* out, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_buffers(c)) != BD_OK) return s;
+  if (!k_new || !v_new || !q || !packed_len || !res_len || !workspace || !out) return BD_ERR_INVALID_ARG;
+  if (num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
+    return BD_ERR_ALIGNMENT;
+  const int pl = *packed_len, r = *res_len;
+  const bool fusable = c->format != BD_FMT_MXFP4 && r < kBlock - 1;
+  if (!fusable) {
+    // a step that fills the residual block (or an MXFP4 cache, whose tokens are quantized on
+    // arrival) runs as the two calls it is defined by
+    if ((s = bd_append_kv(c, k_new, v_new, packed_len, res_len, stream)) != BD_OK) return s;
+    return bd_decode_attn(c, q, *packed_len, *res_len, softmax_scale, num_splits, workspace, out, stream);
+  }
+  if (pl < 0 || pl % kBlock != 0 || r < 0 || pl > c->capacity) return BD_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  float* part_o = ws_part_o(workspace);
+  float* part_ml = ws_part_ml(c, workspace, num_splits);
+  if ((s = hip_status(launch_decode_int(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new,
+                                        st))) != BD_OK)
+    return s;
+  if ((s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
+  *res_len = r + 1;
+  return BD_OK;
 }
 
 bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t num_splits, void* out, void* stream) {

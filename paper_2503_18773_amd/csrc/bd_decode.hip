@@ -65,6 +65,9 @@ struct DecodeArgs {
   const uint16_t* k_res;
   const uint16_t* v_res;
   const uint16_t* q;
+  const uint16_t* k_new;   // fused step: the newest token, [B][Hkv][128], not yet in the residual buffers
+  const uint16_t* v_new;
+  int new_slot;            // its residual slot (res_len - 1), or -1 when the residual buffers are complete
   float* part_o;    // [nparts][B][Hq][128]
   float* part_ml;   // [nparts][B][Hq][2]   (running max in log2 units, running sum)
   int n_q_heads, n_kv_heads, gq;
@@ -238,12 +241,20 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   }
   const bool has_res = rt0 + wave < rt1;
   const uint16_t* kres = a.k_res + unit * kBlock * kD;
+  // row t of the residual keys: the newest token of a fused step is read from where the caller left it
+  auto kres_row = [&](int t) { return t == a.new_slot ? a.k_new + unit * kD : kres + (size_t)t * kD; };
   uint32_t qres_raw[4] = {0u, 0u, 0u, 0u}, kres_raw = 0u;
   if (has_res) {
 #pragma unroll
     for (int h = 0; h < 4; ++h)
       if (h < gq) qres_raw[h] = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
-    kres_raw = *reinterpret_cast<const uint32_t*>(kres + (size_t)(rt0 + wave) * kD + 2 * lane);
+    kres_raw = *reinterpret_cast<const uint32_t*>(kres_row(rt0 + wave) + 2 * lane);
+  }
+  if (a.new_slot >= 0 && split == 0 && tid < 32) {   // fused step: file the new token for later steps
+    const bool is_v = tid >= 16;
+    const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+    uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
+    *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
   int blk = blk0 + wave;
   if (blk < blk1) {   // parameters first: they are the block's first consumers
@@ -266,7 +277,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     uint32_t raw = kres_raw;
     for (int t = rt0 + wave; t < rt1; t += kWaves) {
       const float k0 = h2f((uint16_t)(raw & 0xFFFFu)), k1 = h2f((uint16_t)(raw >> 16));
-      if (t + kWaves < rt1) raw = *reinterpret_cast<const uint32_t*>(kres + (size_t)(t + kWaves) * kD + 2 * lane);
+      if (t + kWaves < rt1) raw = *reinterpret_cast<const uint32_t*>(kres_row(t + kWaves) + 2 * lane);
       float sh[4];
 #pragma unroll
       for (int h = 0; h < 4; ++h) {
@@ -477,7 +488,8 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         const uint16_t* vr = a.v_res + (unit * kBlock + rt0) * kD + c0;
         for (int t = 0; t < nres; ++t) {
           const float p = __builtin_amdgcn_exp2f(res_s[t][h] - M);
-          const uint32_t raw = *reinterpret_cast<const uint32_t*>(vr + (size_t)t * kD);
+          const uint16_t* vrow = rt0 + t == a.new_slot ? a.v_new + unit * kD + c0 : vr + (size_t)t * kD;
+          const uint32_t raw = *reinterpret_cast<const uint32_t*>(vrow);
           L += p;
           o0 = __builtin_fmaf(p, h2f((uint16_t)(raw & 0xFFFFu)), o0);
           o1 = __builtin_fmaf(p, h2f((uint16_t)(raw >> 16)), o1);
@@ -555,7 +567,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 }  // namespace
 
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
-                             int num_splits, float* part_o, float* part_ml, hipStream_t st) {
+                             int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
+                             hipStream_t st) {
   DecodeArgs a;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
@@ -564,6 +577,9 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.k_res = (const uint16_t*)c->k_res;
   a.v_res = (const uint16_t*)c->v_res;
   a.q = (const uint16_t*)q;
+  a.k_new = (const uint16_t*)k_new;
+  a.v_new = (const uint16_t*)v_new;
+  a.new_slot = k_new ? res_len - 1 : -1;
   a.part_o = part_o;
   a.part_ml = part_ml;
   a.n_q_heads = c->n_q_heads;

@@ -352,3 +352,51 @@ def test_cfg4_mxfp4_full_size_sampled():
             assert np.array_equal(full[b, h, :n], r[0, 0, :n]), (name, b, h)
         ref[b, h * g:(h + 1) * g] = O.decode_attn(oc, q[b:b + 1, h * g:(h + 1) * g], W.softmax_scale(w))[0]
     _mx_decode_check(gc, ref, w, q, ns, "cfg4")
+
+
+# ---------------------------------------------------------------------------- fused step
+
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4"])
+def test_decode_step_equals_append_then_attention(fmt):
+    """bd_decode_step is defined as bd_append_kv + bd_decode_attn: same output bits, same cache,
+    same lengths, on ordinary steps, on the step that fills the residual block and after it."""
+    import torch
+    base = W.CONFIGS["cfg4" if fmt == "mxfp4" else "cfg1"]
+    w = W.scaled(base, batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 3 + 120, fmt=fmt)
+    dt = w.in_dtype
+    K, V = W.make_kv(w)
+    a = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, 1024)
+    b = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, 1024)
+    for c in (a, b):
+        c.quant_pack_kv(to_dev(K, dt), to_dev(V, dt))
+    tdt = torch.float16 if dt == "fp16" else torch.bfloat16
+    oa = torch.empty((w.batch, w.n_q_heads, 128), dtype=tdt, device="cuda:0")
+    ob = torch.empty_like(oa)
+    ns = 3
+    for step in range(12):            # residual 120 -> 127 -> flush -> 4 (int formats)
+        kn, vn = W.make_new_kv(w, step)
+        q = to_dev(W.make_q(w, step), dt)
+        knd, vnd = to_dev(kn, dt), to_dev(vn, dt)
+        a.append_kv(knd, vnd)
+        a.decode_attn(q, W.softmax_scale(w), oa, num_splits=ns)
+        b.decode_step(knd, vnd, q, W.softmax_scale(w), ob, num_splits=ns)
+        torch.cuda.synchronize()
+        assert (a.packed_len, a.res_len) == (b.packed_len, b.res_len)
+        assert torch.equal(oa.view(torch.int16), ob.view(torch.int16)), f"{fmt} step {step}"
+    for i in range(6):
+        assert np.array_equal(a.host_buffer(i), b.host_buffer(i)), (fmt, i)
+
+
+def test_decode_step_matches_oracle_on_cfg1():
+    w = W.CONFIGS["cfg1"]
+    K, V, oc, gc = _int_cache_pair(w, w.context + 256)
+    import torch
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float16, device="cuda:0")
+    for step in range(3):
+        kn, vn = W.make_new_kv(w, step)
+        q = W.make_q(w, step)
+        oc.append_kv(kn, vn)
+        gc.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out)
+        torch.cuda.synchronize()
+        assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"cfg1 fused step {step}")
+    _assert_int_cache_equal(oc, gc)

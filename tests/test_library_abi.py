@@ -87,6 +87,12 @@ def test_argument_validation_happens_before_any_launch():
     assert L.bd_decode_attn(ctypes.byref(c), 4096, 1024, 128, 0.1, 4, 4096, 4096, None) == -1
     assert L.bd_decode_attn(ctypes.byref(c), 4096, 1024, 0, 0.1, 4, 4100, 4096, None) == -3
     assert L.bd_splitk_combine(ctypes.byref(c), None, 4, 4096, None) == -1
+    pl, rl = ctypes.c_int32(1024), ctypes.c_int32(5)
+    assert L.bd_decode_step(ctypes.byref(c), 4096, 4096, 4096, ctypes.byref(pl), ctypes.byref(rl), 0.1, 4, 4096,
+                            None, None) == -1                       # out is required
+    assert L.bd_decode_step(ctypes.byref(c), 4096, 4100, 4096, ctypes.byref(pl), ctypes.byref(rl), 0.1, 4, 4096,
+                            4096, None) == -3
+    assert (pl.value, rl.value) == (1024, 5)
     # shapes this build has no kernel for
     bad = _desc(n_q_heads=64)
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
