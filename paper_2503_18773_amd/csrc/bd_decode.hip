@@ -256,14 +256,21 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
     *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
+  // A wave with a single block (short contexts: every wave's only loads are issued at kernel
+  // start) asks for its V codes after the first half of QK^T instead, so that the memory queue
+  // first delivers everybody's keys and the QK^T work overlaps the arrival of the values.
+  const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
+  const bool defer_v = my_blocks == 1;
   int blk = blk0 + wave;
   if (blk < blk1) {   // parameters first: they are the block's first consumers
     issue_kpar(blk);
     issue_vpar(blk);
 #pragma unroll
     for (int T = 0; T < 8; ++T) issue_ktile(blk, T);
+    if (!defer_v) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
+      for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
+    }
   }
 
   // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
@@ -302,7 +309,6 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   // Two waves of different workgroups share each SIMD and the issue arbiter favours the older
   // one, which then runs a block ahead, finishes early and leaves the other to drain alone with
   // half the loads in flight.  Priority by remaining work keeps the pair in step.
-  const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
   int done = 0;
   while (blk < blk1) {
     const int nblk = blk + kWaves;
@@ -381,6 +387,10 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
         }
         s[tt] = acc;
+      }
+      if (defer_v && half == 0) {
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
       }
       if (has_next) {
 #pragma unroll
