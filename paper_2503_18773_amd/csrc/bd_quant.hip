@@ -290,9 +290,10 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
   // V codes, channel-major: byte j of channel c holds block tokens 2j (low), 2j+1 (high).
   uint8_t* vrow = v_codes + ((size_t)unit * (capacity / kBlock) + dblk) * (size_t)(kD * 64);
   const int j_lo = (t_lo - dblk * kBlock) / 2, j_hi = (t_hi - dblk * kBlock + 1) / 2;
-  for (int id = threadIdx.x; id < kD * 64; id += 128) {
-    const int ch = id / 64, j = id % 64;
-    if (j < j_lo || j >= j_hi) continue;
+  const int nj = j_hi - j_lo;
+  for (int k = threadIdx.x; k < kD * nj; k += 128) {
+    const int ch = k / nj, j = j_lo + k % nj;
+    const int id = ch * 64 + j;
     const int ta = dblk * kBlock + 2 * j, tb = ta + 1;
     uint8_t old = 0;
     const bool a_new = ta >= t_lo && ta < t_hi, b_new = tb >= t_lo && tb < t_hi;
@@ -303,6 +304,40 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
     if (!b_new && tb >= t_hi) hi = 0;
     vrow[id] = (uint8_t)(lo | (hi << 4));
   }
+}
+
+// Decode-step append for MXFP4: one token per (batch, kv_head), thread = channel.  The MX
+// group statistics are wave shuffles over 32 lanes; K bytes pair neighbouring channels, V
+// bytes are updated nibble-wise in the channel-major block layout.
+__global__ __launch_bounds__(128) void mx_append_kernel(const uint16_t* __restrict__ k_new,
+                                                         const uint16_t* __restrict__ v_new,
+                                                         uint8_t* __restrict__ k_codes,
+                                                         uint8_t* __restrict__ k_scales,
+                                                         uint8_t* __restrict__ v_codes,
+                                                         uint8_t* __restrict__ v_scales, int capacity, int t) {
+  const int unit = blockIdx.x, c = threadIdx.x;
+  const float kx = bf16_bits_to_float(k_new[(size_t)unit * kD + c]);
+  const float vx = bf16_bits_to_float(v_new[(size_t)unit * kD + c]);
+  float ka = fabsf(kx), va = fabsf(vx);
+#pragma unroll
+  for (int off = 1; off < kMxGroup; off <<= 1) {
+    ka = fmaxf(ka, __shfl_xor(ka, off));
+    va = fmaxf(va, __shfl_xor(va, off));
+  }
+  const int ke = ka > 0.0f ? mx_shared_exp(ka) : 0, ve = va > 0.0f ? mx_shared_exp(va) : 0;
+  const uint32_t kc = ka > 0.0f ? e2m1_code(kx, ke) : 0u, vc = va > 0.0f ? e2m1_code(vx, ve) : 0u;
+  const size_t tok = (size_t)unit * capacity + t;
+  if ((c & (kMxGroup - 1)) == 0) {
+    k_scales[tok * 4 + c / kMxGroup] = (uint8_t)(ke + 127);
+    v_scales[tok * 4 + c / kMxGroup] = (uint8_t)(ve + 127);
+  }
+  const uint32_t kc_hi = __shfl_down(kc, 1);
+  if ((c & 1) == 0) k_codes[tok * (kD / 2) + c / 2] = (uint8_t)(kc | (kc_hi << 4));
+  uint8_t* vb = v_codes + (((size_t)unit * (capacity / kBlock) + t / kBlock) * kD + c) * 64 + (t % kBlock) / 2;
+  if ((t & 1) == 0)
+    *vb = (uint8_t)vc;                                  // first token of the byte: the other nibble is not there yet
+  else
+    *vb = (uint8_t)((*vb & 0x0Fu) | (vc << 4));
 }
 
 }  // namespace
@@ -339,6 +374,12 @@ hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_st
 hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, int ntok, int units,
                            const bd_cache* c, int dst_tok0, hipStream_t st) {
   if (ntok <= 0) return hipSuccess;
+  if (ntok == 1 && src_unit_stride == kD) {
+    mx_append_kernel<<<dim3(units), dim3(128), 0, st>>>((const uint16_t*)k, (const uint16_t*)v, (uint8_t*)c->k_codes,
+                                                        (uint8_t*)c->k_params, (uint8_t*)c->v_codes,
+                                                        (uint8_t*)c->v_params, c->capacity, dst_tok0);
+    return hipGetLastError();
+  }
   const int first_blk = dst_tok0 / kBlock, last_blk = (dst_tok0 + ntok - 1) / kBlock;
   dim3 grid(last_blk - first_blk + 1, units), block(128);
   mx_quant_kernel<<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride, ntok,
