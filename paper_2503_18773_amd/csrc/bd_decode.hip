@@ -91,6 +91,7 @@ template <>
 struct Fmt<4> {
   static constexpr int WORDS = 4;
   static constexpr float kQmax = 15.0f;
+  static constexpr bool kValuesAtTop = false;
   // first channel of run `run` (0/1) of slot group sg: word sg, nibbles 0..3 / 4..7
   __device__ static int run_base(int sg, int run) { return 8 * sg + 4 * run; }
   __device__ static constexpr float un(int v) { return (v & 1) ? (1.0f / 16.0f) : 1.0f; }
@@ -119,6 +120,7 @@ template <>
 struct Fmt<2> {
   static constexpr int WORDS = 2;
   static constexpr float kQmax = 3.0f;
+  static constexpr bool kValuesAtTop = true;
   // slot group sg = 2*W + jj: word W, crumbs 4*jj + 0..3 (run 0) and 8 + 4*jj + 0..3 (run 1)
   __device__ static int run_base(int sg, int run) { return 16 * (sg >> 1) + 4 * (sg & 1) + 8 * run; }
   __device__ static constexpr float un(int v) { return 1.0f / (float)(1 << (2 * v)); }
@@ -206,10 +208,11 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
 
-  // Software pipeline over this wave's blocks without a second set of registers: as soon as
-  // a raw tile has been consumed, the same registers are reloaded with that tile of the wave's
-  // next block (parameters right after the query rescale), so every load has about one block
-  // period to arrive.
+  // A wave keeps little in flight: the keys of its next block are requested when the current
+  // block is done, the values of a block when its keys are about to be consumed.  The eight
+  // waves of a compute unit share one in-order memory pipeline, so whatever one wave requests
+  // early only delays what the others are waiting for: 8 KB per wave (16 MB over the chip) keeps
+  // HBM busy, and a shorter queue shortens the ramp at both ends of the kernel.
   const int prep_head = lane >> 4, prep_sg = lane & 15;
   const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
@@ -256,21 +259,16 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
     *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
-  // A wave with a single block (short contexts: every wave's only loads are issued at kernel
-  // start) asks for its V codes after the first half of QK^T instead, so that the memory queue
-  // first delivers everybody's keys and the QK^T work overlaps the arrival of the values.
+  // (Where exactly the values are requested is fixed at compile time, so that the compiler knows
+  // how many loads are in flight behind the one it waits for: half way through QK^T for int4,
+  // at the top of the block for int2, whichever measured faster.)
   const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
-  const bool defer_v = my_blocks == 1;
   int blk = blk0 + wave;
   if (blk < blk1) {   // parameters first: they are the block's first consumers
     issue_kpar(blk);
     issue_vpar(blk);
 #pragma unroll
     for (int T = 0; T < 8; ++T) issue_ktile(blk, T);
-    if (!defer_v) {
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
-    }
   }
 
   // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
@@ -366,9 +364,13 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     }
     const float zq = wl.zq[head];
     const bool has_next = nblk < blk1;
-    if (has_next) {
+    if (has_next) {   // small, and the next block's first consumers: requested a block ahead
       issue_kpar(nblk);
       issue_vpar(nblk);
+    }
+    if (F::kValuesAtTop) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
     }
 
     // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); column
@@ -388,13 +390,9 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         }
         s[tt] = acc;
       }
-      if (defer_v && half == 0) {
+      if (!F::kValuesAtTop && half == 0) {
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
-      }
-      if (has_next) {
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) issue_ktile(nblk, 4 * half + tt);
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -434,8 +432,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         pb[2 * half + 1][r] = dpp_u<F::kStepShift>(pair);
       }
     }
-    // ---- O^T += V^T P' : k-step j contracts 32 tokens (8 per lane group); two M tiles at a
-    //      time, whose raw registers are then handed to the next block
+    // ---- O^T += V^T P' : k-step j contracts 32 tokens (8 per lane group)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const h8_t ac = *reinterpret_cast<const h8_t*>(&wl.c16[8 * (4 * g + j)]);
@@ -450,10 +447,10 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         oacc[2 * mp + 1] =
             __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[2 * mp + 1].w, j), bp, oacc[2 * mp + 1], 0, 0, 0);
       }
-      if (has_next) {
-        issue_vtile(nblk, 2 * mp);
-        issue_vtile(nblk, 2 * mp + 1);
-      }
+    }
+    if (has_next) {
+#pragma unroll
+      for (int T = 0; T < 8; ++T) issue_ktile(nblk, T);
     }
     wave_sync();   // the next block's prep overwrites this wave's LDS scratch
     blk = nblk;
