@@ -176,7 +176,8 @@ struct MergeLds {
 constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
 constexpr size_t kSmemBytes = cmax(sizeof(MergeLds), kWaves * sizeof(WaveLds));
 
-template <int BITS>
+// SINGLE: no wave has more than one block (short contexts); the host picks the instance.
+template <int BITS, bool SINGLE>
 __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   using F = Fmt<BITS>;
   constexpr int WORDS = F::WORDS;            // words per lane per tile
@@ -309,8 +310,8 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   // half the loads in flight.  Priority by remaining work keeps the pair in step.
   int done = 0;
   while (blk < blk1) {
-    const int nblk = blk + kWaves;
-    {
+    const int nblk = SINGLE ? blk1 : blk + kWaves;
+    if (!SINGLE) {
       const int q4 = (4 * done) / (my_blocks > 0 ? my_blocks : 1);   // quarter of the work done: 0..3
       if (q4 == 0) __builtin_amdgcn_s_setprio(3);
       else if (q4 == 1) __builtin_amdgcn_s_setprio(2);
@@ -363,12 +364,12 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
     }
     const float zq = wl.zq[head];
-    const bool has_next = nblk < blk1;
+    const bool has_next = !SINGLE && nblk < blk1;
     if (has_next) {   // small, and the next block's first consumers: requested a block ahead
       issue_kpar(nblk);
       issue_vpar(nblk);
     }
-    if (F::kValuesAtTop) {
+    if (!SINGLE && F::kValuesAtTop) {
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
     }
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         }
         s[tt] = acc;
       }
-      if (!F::kValuesAtTop && half == 0) {
+      if ((SINGLE || !F::kValuesAtTop) && half == 0) {
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
       }
@@ -409,7 +410,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     m_run = m_new;
     l_run *= alpha;
     z_run *= alpha;
-    if (blk != blk0 + wave && __any(alpha != 1.0f)) {   // nothing to rescale on the first block
+    if (!SINGLE && blk != blk0 + wave && __any(alpha != 1.0f)) {   // nothing to rescale on the first block
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
       xacc *= alpha;
@@ -598,10 +599,14 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
   dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
-  if (c->format == BD_FMT_INT4)
-    decode_int_kernel<4><<<grid, block, 0, st>>>(a);
-  else
-    decode_int_kernel<2><<<grid, block, 0, st>>>(a);
+  const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
+  if (c->format == BD_FMT_INT4) {
+    if (single) decode_int_kernel<4, true><<<grid, block, 0, st>>>(a);
+    else decode_int_kernel<4, false><<<grid, block, 0, st>>>(a);
+  } else {
+    if (single) decode_int_kernel<2, true><<<grid, block, 0, st>>>(a);
+    else decode_int_kernel<2, false><<<grid, block, 0, st>>>(a);
+  }
   return hipGetLastError();
 }
 

@@ -69,7 +69,11 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
   u4_t kraw[8], vraw[8];
   uint32_t ksc[8];
   u4_t vsc[2];
-  auto issue = [&](int blk) {
+  // A wave keeps 8 KB in flight, not a whole block: keys (and their scales) of the next block
+  // are requested when the current block is done, the values of a block when its keys are about
+  // to be consumed.  The waves of a compute unit share one in-order memory pipeline; a shorter
+  // queue serves everybody sooner and shortens the ramp at both ends of the kernel.
+  auto issue_k = [&](int blk) {
     const size_t tok0 = unit * a.capacity + (size_t)blk * kBlock;
 #pragma unroll
     for (int T = 0; T < 8; ++T) {
@@ -77,6 +81,9 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
       ksc[T] = *reinterpret_cast<const uint32_t*>(a.k_scales + t * 4);
       kraw[T] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(a.k_codes + t * 64 + 16 * g));
     }
+  };
+  auto issue_v = [&](int blk) {
+    const size_t tok0 = unit * a.capacity + (size_t)blk * kBlock;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
       vsc[half] = *reinterpret_cast<const u4_t*>(a.v_scales + (tok0 + 32 * g + 16 * half + 4 * cg) * 4);
@@ -86,7 +93,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
       vraw[mt] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(vp + (size_t)(16 * mt + col) * 64));
   };
   int blk = blk0 + wave;
-  if (blk < blk1) issue(blk);
+  if (blk < blk1) issue_k(blk);
 
   // ---- the query as the B operand: exact split of each bf16 into two e4m3 pieces.
   // Operand layout of the 8-bit side (measured): lane (column, g) holds contraction indices
@@ -145,6 +152,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
 
   while (blk < blk1) {
     const int nblk = blk + kWaves;
+    issue_v(blk);
     // ---- S^T tiles straight from the packed codes; column group cg keeps tiles cg and 4+cg
     float s[2][4];
 #pragma unroll
@@ -232,7 +240,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
         }
       }
     }
-    if (nblk < blk1) issue(nblk);
+    if (nblk < blk1) issue_k(nblk);
     blk = nblk;
   }
 
