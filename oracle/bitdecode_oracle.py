@@ -195,6 +195,99 @@ class IntCache:
         return Kh, Vh
 
 
+class PagedIntCache:
+    """The page-managed cache of the paper's "Page" setting (Sec. V-A, Sec. V-B: kernels run on
+    both a contiguous and a paged KV cache).  The paper names the setting without describing a
+    layout; the reading used here: a page is one 128-token quantization block (so that a block's
+    channel-wise K statistics stay inside one page), the packed blocks of all sequences live
+    in one pool, block n of sequence b is page block_table[b, n], every sequence has its own
+    length, and the fp16 residual stays per sequence.
+
+      k_codes  uint32 [P, H, 128 tokens, D*bits/32]    v_codes  uint32 [P, H, D, 128*bits/32]
+      k_params uint32 [P, H, D]                        v_params uint32 [P, H, 128]
+      k_res, v_res fp16 [B, H, 128, D]
+      block_table int32 [B, max_pages]                 seq_lens int32 [B]
+
+    Paging is a pure relocation: every block holds exactly the bytes IntCache would hold.
+    """
+
+    def __init__(self, batch: int, n_kv_heads: int, bits: int, num_pages: int, max_pages: int,
+                 block_table: np.ndarray, head_dim: int = 128):
+        assert head_dim == 128 and block_table.shape == (batch, max_pages)
+        self.B, self.H, self.D, self.bits = batch, n_kv_heads, head_dim, bits
+        self.P, self.max_pages = num_pages, max_pages
+        self.k_codes = np.zeros((num_pages, n_kv_heads, BLOCK, head_dim * bits // 32), np.uint32)
+        self.v_codes = np.zeros((num_pages, n_kv_heads, head_dim, BLOCK * bits // 32), np.uint32)
+        self.k_params = np.zeros((num_pages, n_kv_heads, head_dim), np.uint32)
+        self.v_params = np.zeros((num_pages, n_kv_heads, BLOCK), np.uint32)
+        self.k_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
+        self.v_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
+        self.block_table = block_table.astype(np.int32).copy()
+        self.seq_lens = np.zeros(batch, np.int32)
+
+    def _page_of(self, b: int, n: int) -> int:
+        if n >= self.max_pages:
+            raise OverflowError("block table row is full")
+        p = int(self.block_table[b, n])
+        if not 0 <= p < self.P:
+            raise IndexError("block table entry outside the pool")
+        return p
+
+    def _store_block(self, b: int, n: int, kblk: np.ndarray, vblk: np.ndarray):
+        p = self._page_of(b, n)
+        for h in range(self.H):
+            kc, ks, kz = quantize_k_block(kblk[h], self.bits)
+            vc, vs, vz = quantize_v_block(vblk[h], self.bits)
+            self.k_codes[p, h] = pack_words(kc, self.bits)
+            self.v_codes[p, h] = pack_words(vc.T.copy(), self.bits)
+            self.k_params[p, h] = pack_half2(ks, kz)
+            self.v_params[p, h] = pack_half2(vs, vz)
+
+    def quant_pack_kv(self, b: int, K: np.ndarray, V: np.ndarray):
+        """Prefill of sequence b from K, V [H, L, D]: full blocks into its pages, the rest into
+        its residual; the sequence's previous contents are replaced."""
+        L = K.shape[1]
+        assert K.shape == V.shape == (self.H, L, self.D) and K.dtype == np.float16
+        nb, r = divmod(L, BLOCK)
+        for n in range(nb):
+            self._store_block(b, n, K[:, n * BLOCK:(n + 1) * BLOCK], V[:, n * BLOCK:(n + 1) * BLOCK])
+        self.k_res[b, :, :r] = K[:, nb * BLOCK:]
+        self.v_res[b, :, :r] = V[:, nb * BLOCK:]
+        self.seq_lens[b] = L
+
+    def append_kv(self, k_new: np.ndarray, v_new: np.ndarray):
+        """One decode step of every sequence: token b goes to slot seq_lens[b] mod 128 of
+        sequence b's residual; a residual that reaches 128 tokens is quantized into the
+        sequence's next page at once."""
+        assert k_new.shape == v_new.shape == (self.B, self.H, self.D)
+        for b in range(self.B):
+            nb, r = divmod(int(self.seq_lens[b]), BLOCK)
+            if r == BLOCK - 1:
+                self._page_of(b, nb)            # raises before anything is changed
+            self.k_res[b, :, r] = k_new[b]
+            self.v_res[b, :, r] = v_new[b]
+            if r == BLOCK - 1:
+                self._store_block(b, nb, self.k_res[b], self.v_res[b])
+            self.seq_lens[b] += 1
+
+    def dequant(self, b: int, h: int):
+        """K_hat, V_hat [seq_lens[b], D] float64 of one (sequence, kv_head)."""
+        nb, r = divmod(int(self.seq_lens[b]), BLOCK)
+        Kh = np.empty((nb * BLOCK + r, self.D), np.float64)
+        Vh = np.empty_like(Kh)
+        for n in range(nb):
+            p = self._page_of(b, n)
+            kc = unpack_words(self.k_codes[p, h], self.bits).astype(np.float64)
+            vc = unpack_words(self.v_codes[p, h], self.bits).astype(np.float64).T
+            ks, kz = unpack_half2(self.k_params[p, h])
+            vs, vz = unpack_half2(self.v_params[p, h])
+            Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[None, :] + kz.astype(np.float64)[None, :]
+            Vh[n * BLOCK:(n + 1) * BLOCK] = vc * vs.astype(np.float64)[:, None] + vz.astype(np.float64)[:, None]
+        Kh[nb * BLOCK:] = self.k_res[b, h, :r].astype(np.float64)
+        Vh[nb * BLOCK:] = self.v_res[b, h, :r].astype(np.float64)
+        return Kh, Vh
+
+
 # --------------------------------------------------------------------------- MXFP4
 
 def e2m1_decode(code: np.ndarray) -> np.ndarray:
@@ -330,6 +423,9 @@ def decode_attn(cache, q: np.ndarray, sm_scale: float, units=None) -> np.ndarray
     todo = [(b, h) for b in range(B) for h in range(cache.H)] if units is None else list(units)
     for b, h in todo:
         Kh, Vh = cache.dequant(b, h)
+        if Kh.shape[0] == 0:            # a sequence with no tokens: defined as a zero output
+            out[b, h * g:(h + 1) * g] = 0.0
+            continue
         for j in range(g):
             w = attention_weights(np.asarray(q[b, h * g + j], dtype=np.float64), Kh, sm_scale)
             out[b, h * g + j] = w @ Vh

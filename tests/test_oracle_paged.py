@@ -1,0 +1,104 @@
+"""Pins of the paged oracle.  Paging is a pure relocation of 128-token blocks, so the paged cache
+is pinned against the contiguous IntCache (itself pinned in test_oracle_quant / _attention):
+same bytes per block wherever the block lives, same attention output whatever the page order,
+ragged lengths equal to independent single-sequence caches."""
+import numpy as np
+import pytest
+
+from oracle import bitdecode_oracle as O
+from paper_2503_18773_amd import workloads as W
+
+
+def _kv(seed, H, L):
+    w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=H, n_kv_heads=H, context=max(L, 1), seed=seed)
+    K, V = W.make_kv(w)
+    return K[0, :, :L], V[0, :, :L]
+
+
+def _table(rng, B, max_pages, P):
+    """Distinct pages for every (sequence, block), scattered over the pool."""
+    perm = rng.permutation(P)[:B * max_pages]
+    return perm.reshape(B, max_pages).astype(np.int32)
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_identity_table_holds_the_contiguous_bytes(bits):
+    B, H, L = 2, 2, 3 * 128 + 17
+    c = O.IntCache(B, H, bits, 4 * 128)
+    KV = [_kv(10 + b, H, L) for b in range(B)]
+    c.quant_pack_kv(np.stack([k for k, _ in KV]), np.stack([v for _, v in KV]))
+    table = np.arange(B * 4, dtype=np.int32).reshape(B, 4)          # page = b * 4 + n
+    p = O.PagedIntCache(B, H, bits, B * 4, 4, table)
+    for b in range(B):
+        p.quant_pack_kv(b, *KV[b])
+    for name in ("k_codes", "v_codes", "k_params", "v_params"):
+        got = getattr(p, name).reshape(B, 4, H, *getattr(p, name).shape[2:]).swapaxes(1, 2)
+        assert np.array_equal(got, getattr(c, name)), name
+    assert np.array_equal(p.k_res, c.k_res) and np.array_equal(p.v_res, c.v_res)
+    assert list(p.seq_lens) == [L, L]
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_ragged_scattered_pages_equal_independent_caches(bits):
+    rng = np.random.default_rng(5)
+    B, H, Hq = 4, 2, 4
+    lens = [300, 0, 128, 517]
+    table = _table(rng, B, 6, 40)
+    p = O.PagedIntCache(B, H, bits, 40, 6, table)
+    singles = []
+    for b, L in enumerate(lens):
+        K, V = _kv(20 + b, H, L)
+        p.quant_pack_kv(b, K, V)
+        c = O.IntCache(1, H, bits, 6 * 128)
+        c.quant_pack_kv(K[None], V[None])
+        singles.append(c)
+    # three decode steps: sequence 2 (128 tokens) stays aligned, sequence 3 crosses nothing, then
+    # run sequence 0 over a flush by appending until 384
+    q = np.random.default_rng(6).standard_normal((B, Hq, 128)).astype(np.float16)
+    for step in range(90):
+        kn = rng.standard_normal((B, H, 128)).astype(np.float16)
+        vn = rng.standard_normal((B, H, 128)).astype(np.float16)
+        p.append_kv(kn, vn)
+        for b in range(B):
+            singles[b].append_kv(kn[b:b + 1], vn[b:b + 1])
+    assert [int(x) for x in p.seq_lens] == [L + 90 for L in lens]
+    out = O.decode_attn(p, q, 0.09)
+    for b in range(B):
+        ref = O.decode_attn(singles[b], q[b:b + 1], 0.09)
+        assert np.array_equal(out[b], ref[0]), b
+        # every block of the sequence holds the single cache's bytes, in its own page
+        for n in range(singles[b].packed_len // 128):
+            pg = table[b, n]
+            assert np.array_equal(p.k_codes[pg], singles[b].k_codes[0, :, n])
+            assert np.array_equal(p.v_codes[pg], singles[b].v_codes[0, :, n])
+            assert np.array_equal(p.k_params[pg], singles[b].k_params[0, :, n])
+            assert np.array_equal(p.v_params[pg], singles[b].v_params[0, :, n])
+    # pages no sequence reached stay untouched
+    used = {int(table[b, n]) for b in range(B) for n in range(int(p.seq_lens[b]) // 128)}
+    for pg in set(range(40)) - used:
+        assert not p.k_codes[pg].any() and not p.v_params[pg].any()
+
+
+def test_empty_sequence_gives_zero_and_errors_are_raised():
+    table = np.array([[0, 1], [7, 2]], np.int32)
+    p = O.PagedIntCache(2, 1, 4, 4, 2, table)
+    K, V = _kv(3, 1, 127)
+    p.quant_pack_kv(0, K, V)
+    q = np.ones((2, 2, 128), np.float16)
+    out = O.decode_attn(p, q, 0.1)
+    assert not out[1].any() and np.isfinite(out[0]).all()
+    p.quant_pack_kv(1, K, V)
+    one = np.ones((2, 1, 128), np.float16)
+    with pytest.raises(IndexError):            # sequence 1's first page (7) is outside the pool of 4
+        p.append_kv(one, one)
+    assert list(p.seq_lens) == [128, 127]      # sequence 0 had been served before the error
+    p2 = O.PagedIntCache(1, 1, 4, 4, 2, np.array([[0, 1]], np.int32))
+    K, V = _kv(4, 1, 255)
+    p2.quant_pack_kv(0, K, V)
+    p2.append_kv(one[:1], one[:1])
+    K3, V3 = _kv(4, 1, 127)
+    p2.quant_pack_kv(0, np.concatenate([K, K3[:, :1]], 1)[:, :256], np.concatenate([V, V3[:, :1]], 1)[:, :256])
+    for _ in range(127):
+        p2.append_kv(one[:1], one[:1])
+    with pytest.raises(OverflowError):         # a third block has no table entry
+        p2.append_kv(one[:1], one[:1])
