@@ -13,8 +13,9 @@
  *  - All work is enqueued on the given hipStream_t (passed as void*; NULL = default
  *    stream) and the call returns at once.  Buffers must stay alive until the stream has
  *    passed the call.  Calls on one cache must be ordered on one stream.
- *  - Lengths are host integers and are uniform across the batch (the paper's "Batches"
- *    setting, Sec. V-A: same length, padded).
+ *  - For bd_cache, lengths are host integers and are uniform across the batch (the paper's
+ *    "Batches" setting, Sec. V-A: same length, padded); bd_paged_cache (further down) keeps
+ *    per-sequence lengths on the device (the "Page" setting).
  *  - head_dim is 128.  The residual block N_r (Eq. 1) and the quantization group are both
  *    128 for BD_FMT_INT4 / BD_FMT_INT2; the MX group is 32 for BD_FMT_MXFP4.
  *  - Arguments are validated before anything is launched; on error nothing is enqueued
@@ -142,6 +143,70 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
  * out (device, [B][n_q_heads][D], fp16 / bf16). */
 bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t num_splits,
                             void* out, void* stream);
+
+/* ---- Paged cache with per-sequence lengths (the "Page" setting of Sec. V-A / V-B) ----------
+ *
+ * The paper runs its kernels on a contiguous and on a page-managed KV cache and names no
+ * layout.  Here a page is one 128-token quantization block: the packed blocks of all sequences
+ * live in one pool, block n of sequence b is page block_table[b][n], and every sequence has its
+ * own length, kept on the device.  INT4 / INT2 only.  P = num_pages:
+ *
+ *   k_codes  uint32 [P][H][128 tokens][D/cpw]      v_codes  uint32 [P][H][D channels][128/cpw]
+ *   k_params uint32 [P][H][D]                      v_params uint32 [P][H][128]
+ *   k_res, v_res fp16 [B][H][128][D]               (per sequence, as in bd_cache)
+ *   block_table int32 [B][max_pages_per_seq]       device; written by the caller, read by the library
+ *   seq_lens    int32 [B]                          device; tokens cached per sequence; written by
+ *                                                  bd_paged_quant_pack_kv / bd_paged_append_kv
+ *   status      int32 [1]                          device, may be NULL; see below
+ *
+ * Inside a page every block has exactly the bytes it has in a bd_cache.  The caller owns the
+ * page allocator: before a sequence reaches token 128*(n+1) its table entry n must name a page
+ * no other block uses.  Because lengths live on the device the host cannot validate them; the
+ * kernels do: a block whose table entry is missing (n >= max_pages_per_seq) or outside
+ * [0, num_pages) is not read or written, bit 0 (decode) or bit 1 (append / prefill) of *status
+ * is set, and an append that would have needed that block leaves the sequence's length as it
+ * was (the token is dropped).  The caller clears *status. */
+typedef struct bd_paged_cache {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;            /* 128 */
+  int32_t format;              /* BD_FMT_INT4 or BD_FMT_INT2 */
+  int32_t num_pages;
+  int32_t max_pages_per_seq;
+  void *k_codes, *v_codes;
+  void *k_params, *v_params;
+  void *k_res, *v_res;
+  int32_t* block_table;
+  int32_t* seq_lens;
+  int32_t* status;
+} bd_paged_cache;
+
+/* Size in bytes of buffer `which` (0..5 as bd_cache_bytes, 6 block_table, 7 seq_lens). */
+size_t bd_paged_cache_bytes(const bd_paged_cache* c, int which);
+
+/* Workspace size for bd_paged_decode_attn (same layout as bd_workspace_bytes). */
+size_t bd_paged_workspace_bytes(const bd_paged_cache* c, int32_t num_splits);
+
+/* Prefill of sequence `seq` (Sec. IV-B(1)) from k, v (device, [H][L][D] fp16): the first
+ * L - (L mod 128) tokens are quantized into the sequence's pages, the rest copied to its
+ * residual, seq_lens[seq] = L.  Replaces whatever the sequence held.
+ * BD_ERR_CAPACITY if L needs more than max_pages_per_seq pages. */
+bd_status bd_paged_quant_pack_kv(const bd_paged_cache* c, int32_t seq, const void* k, const void* v,
+                                 int32_t L, void* stream);
+
+/* One decode step of every sequence (Sec. IV-B): token b of k_new, v_new (device, [B][H][D]
+ * fp16) goes to residual slot seq_lens[b] mod 128 of sequence b; a residual that reaches 128
+ * tokens is quantized into page block_table[b][seq_lens[b] / 128]; seq_lens[b] += 1. */
+bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const void* v_new, void* stream);
+
+/* bd_decode_attn over the paged cache: sequence b attends its own seq_lens[b] tokens; a
+ * sequence with no tokens gets a zero output row.  Every sequence is split num_splits ways
+ * (pick it for the longest sequence, e.g. with bd_choose_splits on a bd_cache of the same
+ * shape); workspace at least bd_paged_workspace_bytes(c, num_splits); `out` (device,
+ * [B][n_q_heads][D] fp16) must be non-NULL. */
+bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float softmax_scale,
+                               int32_t num_splits, void* workspace, void* out, void* stream);
 
 /* Text for a status code (static storage). */
 const char* bd_strerror(bd_status s);

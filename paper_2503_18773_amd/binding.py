@@ -26,6 +26,18 @@ class bd_cache(ctypes.Structure):
     ]
 
 
+class bd_paged_cache(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("format", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+        ("max_pages_per_seq", ctypes.c_int32),
+        ("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
+        ("k_params", ctypes.c_void_p), ("v_params", ctypes.c_void_p),
+        ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p), ("status", ctypes.c_void_p),
+    ]
+
+
 class BitDecodeError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -52,6 +64,12 @@ def lib() -> ctypes.CDLL:
         L.bd_decode_attn.restype, L.bd_decode_attn.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V, V]
         L.bd_splitk_combine.restype, L.bd_splitk_combine.argtypes = ctypes.c_int, [P, V, I, V, V]
         L.bd_decode_step.restype, L.bd_decode_step.argtypes = ctypes.c_int, [P, V, V, V, IP, IP, F, I, V, V, V]
+        PP = ctypes.POINTER(bd_paged_cache)
+        L.bd_paged_cache_bytes.restype, L.bd_paged_cache_bytes.argtypes = S, [PP, ctypes.c_int]
+        L.bd_paged_workspace_bytes.restype, L.bd_paged_workspace_bytes.argtypes = S, [PP, I]
+        L.bd_paged_quant_pack_kv.restype, L.bd_paged_quant_pack_kv.argtypes = ctypes.c_int, [PP, I, V, V, I, V]
+        L.bd_paged_append_kv.restype, L.bd_paged_append_kv.argtypes = ctypes.c_int, [PP, V, V, V]
+        L.bd_paged_decode_attn.restype, L.bd_paged_decode_attn.argtypes = ctypes.c_int, [PP, V, F, I, V, V, V]
         L.bd_strerror.restype, L.bd_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
         L.bd_last_hip_error.restype, L.bd_last_hip_error.argtypes = ctypes.c_int, []
         _lib = L
@@ -59,7 +77,9 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
-           "bd_decode_attn", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error"]
+           "bd_decode_attn", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
+           "bd_paged_cache_bytes", "bd_paged_workspace_bytes", "bd_paged_quant_pack_kv", "bd_paged_append_kv",
+           "bd_paged_decode_attn"]
 
 
 def _ptr(t):
@@ -128,6 +148,28 @@ def bd_splitk_combine(c: bd_cache, workspace, num_splits: int, out, stream=None)
            "bd_splitk_combine")
 
 
+def bd_paged_cache_bytes(c: bd_paged_cache, which: int) -> int:
+    return int(lib().bd_paged_cache_bytes(ctypes.byref(c), which))
+
+
+def bd_paged_workspace_bytes(c: bd_paged_cache, num_splits: int) -> int:
+    return int(lib().bd_paged_workspace_bytes(ctypes.byref(c), num_splits))
+
+
+def bd_paged_quant_pack_kv(c: bd_paged_cache, seq: int, k, v, L: int, stream=None):
+    _check(lib().bd_paged_quant_pack_kv(ctypes.byref(c), seq, _ptr(k), _ptr(v), L, _stream(stream)),
+           "bd_paged_quant_pack_kv")
+
+
+def bd_paged_append_kv(c: bd_paged_cache, k_new, v_new, stream=None):
+    _check(lib().bd_paged_append_kv(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _stream(stream)), "bd_paged_append_kv")
+
+
+def bd_paged_decode_attn(c: bd_paged_cache, q, softmax_scale: float, num_splits: int, workspace, out, stream=None):
+    _check(lib().bd_paged_decode_attn(ctypes.byref(c), _ptr(q), softmax_scale, num_splits, _ptr(workspace), _ptr(out),
+                                      _stream(stream)), "bd_paged_decode_attn")
+
+
 # ---- device-memory plumbing ------------------------------------------------------------------
 
 class KVCache:
@@ -192,4 +234,55 @@ class KVCache:
 
     def host_buffer(self, i: int):
         """Buffer i copied to host as a numpy uint8 array (for bit-exact comparisons)."""
+        return self.buffers[i][:self.sizes[i]].cpu().numpy()
+
+
+class PagedKVCache:
+    """Device buffers of one layer's paged cache as torch tensors: the page pool, the per-sequence
+    residuals, the block table (given by the caller, who owns page allocation), the lengths and
+    the status word.  Every operation is a call into the library."""
+
+    def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, fmt: str, num_pages: int, block_table,
+                 device="cuda:0"):
+        import torch
+        self.fmt = fmt
+        max_pages = int(block_table.shape[1])
+        assert block_table.shape[0] == batch
+        self.desc = bd_paged_cache(batch, n_q_heads, n_kv_heads, 128, FORMATS[fmt], num_pages, max_pages)
+        self.sizes = [bd_paged_cache_bytes(self.desc, i) for i in range(8)]
+        if self.sizes[0] == 0:
+            raise BitDecodeError(-1, "bd_paged_cache_bytes")
+        self.buffers = [torch.zeros(max(n, 16), dtype=torch.uint8, device=device) for n in self.sizes[:6]]
+        self.block_table = torch.as_tensor(block_table, dtype=torch.int32).contiguous().to(device)
+        self.seq_lens = torch.zeros(batch, dtype=torch.int32, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        for name, buf in zip(["k_codes", "v_codes", "k_params", "v_params", "k_res", "v_res"], self.buffers):
+            setattr(self.desc, name, buf.data_ptr())
+        self.desc.block_table = self.block_table.data_ptr()
+        self.desc.seq_lens = self.seq_lens.data_ptr()
+        self.desc.status = self.status.data_ptr()
+        self.device = device
+        self._ws = None
+        self._ws_splits = -1
+
+    def quant_pack_kv(self, seq: int, k, v, stream=None):
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+        bd_paged_quant_pack_kv(self.desc, seq, k, v, k.shape[1], stream)
+
+    def append_kv(self, k_new, v_new, stream=None):
+        bd_paged_append_kv(self.desc, k_new, v_new, stream)
+
+    def workspace(self, num_splits: int):
+        import torch
+        if self._ws_splits != num_splits:
+            self._ws = torch.empty(bd_paged_workspace_bytes(self.desc, num_splits), dtype=torch.uint8,
+                                   device=self.device)
+            self._ws_splits = num_splits
+        return self._ws
+
+    def decode_attn(self, q, softmax_scale: float, out, num_splits: int, stream=None):
+        bd_paged_decode_attn(self.desc, q, softmax_scale, num_splits, self.workspace(num_splits), out, stream)
+        return out
+
+    def host_buffer(self, i: int):
         return self.buffers[i][:self.sizes[i]].cpu().numpy()

@@ -217,6 +217,95 @@ bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t nu
                                    (hipStream_t)stream));
 }
 
+// ---- paged cache ------------------------------------------------------------------------------
+
+static bd_cache shape_of(const bd_paged_cache* c) {
+  bd_cache s{};
+  s.batch = c->batch;
+  s.n_q_heads = c->n_q_heads;
+  s.n_kv_heads = c->n_kv_heads;
+  s.head_dim = c->head_dim;
+  s.format = c->format;
+  s.capacity = kBlock;
+  return s;
+}
+
+static bd_status check_paged_shape(const bd_paged_cache* c) {
+  if (!c) return BD_ERR_INVALID_ARG;
+  const bd_cache s = shape_of(c);
+  bd_status st = check_shape(&s);
+  if (st != BD_OK) return st;
+  if (c->format == BD_FMT_MXFP4) return BD_ERR_UNSUPPORTED;
+  if (c->num_pages <= 0 || c->max_pages_per_seq <= 0) return BD_ERR_INVALID_ARG;
+  return BD_OK;
+}
+
+static bd_status check_paged_buffers(const bd_paged_cache* c) {
+  const void* need[8] = {c->k_codes, c->v_codes, c->k_params, c->v_params, c->k_res, c->v_res, c->block_table,
+                         c->seq_lens};
+  for (int i = 0; i < 8; ++i) {
+    if (!need[i]) return BD_ERR_INVALID_ARG;
+    if (i < 6 ? !aligned16(need[i]) : (reinterpret_cast<uintptr_t>(need[i]) & 3u) != 0) return BD_ERR_ALIGNMENT;
+  }
+  if (c->status && (reinterpret_cast<uintptr_t>(c->status) & 3u) != 0) return BD_ERR_ALIGNMENT;
+  return BD_OK;
+}
+
+size_t bd_paged_cache_bytes(const bd_paged_cache* c, int which) {
+  if (check_paged_shape(c) != BD_OK || which < 0 || which > 7) return 0;
+  const size_t pool = (size_t)c->num_pages * c->n_kv_heads, bits = (size_t)bits_of(c->format);
+  switch (which) {
+    case 0: case 1: return pool * kBlock * kD * bits / 8;
+    case 2: return pool * kD * 4;
+    case 3: return pool * kBlock * 4;
+    case 4: case 5: return (size_t)c->batch * c->n_kv_heads * kBlock * kD * 2;
+    case 6: return (size_t)c->batch * c->max_pages_per_seq * 4;
+    default: return (size_t)c->batch * 4;
+  }
+}
+
+size_t bd_paged_workspace_bytes(const bd_paged_cache* c, int32_t num_splits) {
+  if (check_paged_shape(c) != BD_OK) return 0;
+  const bd_cache s = shape_of(c);
+  return bd_workspace_bytes(&s, num_splits);
+}
+
+bd_status bd_paged_quant_pack_kv(const bd_paged_cache* c, int32_t seq, const void* k, const void* v, int32_t L,
+                                 void* stream) {
+  bd_status s = check_paged_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_paged_buffers(c)) != BD_OK) return s;
+  if (seq < 0 || seq >= c->batch || L < 0) return BD_ERR_INVALID_ARG;
+  if (L > 0 && (!k || !v)) return BD_ERR_INVALID_ARG;
+  if (L > 0 && (!aligned16(k) || !aligned16(v))) return BD_ERR_ALIGNMENT;
+  if (L / kBlock > c->max_pages_per_seq) return BD_ERR_CAPACITY;
+  return hip_status(launch_paged_prefill(c, seq, k, v, L, (hipStream_t)stream));
+}
+
+bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const void* v_new, void* stream) {
+  bd_status s = check_paged_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_paged_buffers(c)) != BD_OK) return s;
+  if (!k_new || !v_new) return BD_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new)) return BD_ERR_ALIGNMENT;
+  return hip_status(launch_paged_append(c, k_new, v_new, (hipStream_t)stream));
+}
+
+bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float softmax_scale, int32_t num_splits,
+                               void* workspace, void* out, void* stream) {
+  bd_status s = check_paged_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_paged_buffers(c)) != BD_OK) return s;
+  if (!q || !workspace || !out || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(workspace) || !aligned16(out)) return BD_ERR_ALIGNMENT;
+  const bd_cache shape = shape_of(c);
+  hipStream_t st = (hipStream_t)stream;
+  float* part_o = ws_part_o(workspace);
+  float* part_ml = ws_part_ml(&shape, workspace, num_splits);
+  if ((s = hip_status(launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, st))) != BD_OK) return s;
+  return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st));
+}
+
 const char* bd_strerror(bd_status s) {
   switch (s) {
     case BD_OK: return "ok";

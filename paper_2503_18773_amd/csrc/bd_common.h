@@ -33,6 +33,12 @@ hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_st
 hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, int ntok, int units,
                            const bd_cache* c, int dst_tok0, hipStream_t st);
 
+hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k, const void* v, int L,
+                                hipStream_t st);
+hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, hipStream_t st);
+hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
+                               float* part_o, float* part_ml, hipStream_t st);
+
 // k_new / v_new non-null: fused step -- residual token res_len-1 is read from k_new / v_new
 // ([B][Hkv][128]) and also stored into the residual buffers by the kernel.
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,

@@ -76,6 +76,12 @@ struct DecodeArgs {
   int res_len;
   int num_splits;
   float scale_log2; // softmax_scale * log2(e)
+  // paged cache: block n of sequence b is page block_table[b][n], pool index page * Hkv + head;
+  // nb and res_len then come from seq_lens[b]
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  int32_t* status;
+  int max_pages, num_pages;
 };
 
 // ---- format traits ---------------------------------------------------------------------
@@ -177,7 +183,8 @@ constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
 constexpr size_t kSmemBytes = cmax(sizeof(MergeLds), kWaves * sizeof(WaveLds));
 
 // SINGLE: no wave has more than one block (short contexts); the host picks the instance.
-template <int BITS, bool SINGLE>
+// PAGED: blocks are found through the block table and every sequence has its own length.
+template <int BITS, bool SINGLE, bool PAGED>
 __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   using F = Fmt<BITS>;
   constexpr int WORDS = F::WORDS;            // words per lane per tile
@@ -195,10 +202,17 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   WaveLds& wl = reinterpret_cast<WaveLds*>(smem_raw)[wave];
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
-  const int blk0 = (int)(((long)a.nb * split) / a.num_splits);
-  const int blk1 = (int)(((long)a.nb * (split + 1)) / a.num_splits);
+  int nb = a.nb, res_len = a.res_len;
+  if (PAGED) {
+    int len = a.seq_lens[b];
+    len = len < 0 ? 0 : len;
+    nb = len / kBlock;
+    res_len = len % kBlock;
+  }
+  const int blk0 = (int)(((long)nb * split) / a.num_splits);
+  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
   // this workgroup's slice of the fp16 residual tokens
-  const int rt0 = (a.res_len * split) / a.num_splits, rt1 = (a.res_len * (split + 1)) / a.num_splits;
+  const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
   const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * gq) * kD;
 
   float m_run = -INFINITY;   // running max of this lane's head (log2 units), equal in all lanes of the head
@@ -220,20 +234,22 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   RawTile<WORDS> kraw[8], vraw[8];
   u4_t kp0, kp1;   // K parameters (half2) of this lane's two channel runs
   u2_t vp2;        // V parameters (half2) of tokens 2*lane, 2*lane+1
-  auto issue_kpar = [&](int blk) {
-    const uint32_t* pp = a.k_params + (unit * a.nbcap + blk) * kD;
+  // All four take the index `bi` of the block in the packed arrays: unit * nbcap + block for the
+  // contiguous cache, page * Hkv + head for the paged one.
+  auto issue_kpar = [&](size_t bi) {
+    const uint32_t* pp = a.k_params + bi * kD;
     kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
     kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
   };
-  auto issue_vpar = [&](int blk) {
-    vp2 = *reinterpret_cast<const u2_t*>(a.v_params + (unit * a.nbcap + blk) * kBlock + 2 * lane);
+  auto issue_vpar = [&](size_t bi) {
+    vp2 = *reinterpret_cast<const u2_t*>(a.v_params + bi * kBlock + 2 * lane);
   };
-  auto issue_ktile = [&](int blk, int T) {
-    const uint32_t* kp = a.k_codes + (unit * a.nbcap + blk) * (size_t)(kBlock * KROW) + WORDS * g;
+  auto issue_ktile = [&](size_t bi, int T) {
+    const uint32_t* kp = a.k_codes + bi * (size_t)(kBlock * KROW) + WORDS * g;
     kraw[T] = load_raw<WORDS>(kp + (size_t)(tok_base + 4 * T) * KROW);
   };
-  auto issue_vtile = [&](int blk, int mt) {
-    const uint32_t* vp = a.v_codes + (unit * a.nbcap + blk) * (size_t)(kD * VROW) + WORDS * g;
+  auto issue_vtile = [&](size_t bi, int mt) {
+    const uint32_t* vp = a.v_codes + bi * (size_t)(kD * VROW) + WORDS * g;
     vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
   };
   // Loads return in order, so what is needed first is requested first: the query slices
@@ -264,12 +280,30 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   // how many loads are in flight behind the one it waits for: half way through QK^T for int4,
   // at the top of the block for int2, whichever measured faster.)
   const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
+  // Paged: table entry of block n (-1 past the end of the row), and the first block at or after
+  // n, in this wave's stride, whose entry names a page of the pool; entries that do not are
+  // skipped and reported in *status.
+  auto table_entry = [&](int n) { return n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1; };
+  auto first_valid = [&](int n, int entry, size_t& bi) {
+    while (n < blk1) {
+      if (entry >= 0 && entry < a.num_pages) {
+        bi = (size_t)entry * a.n_kv_heads + hkv;
+        break;
+      }
+      if (a.status && lane == 0) atomicOr(a.status, 1);
+      n += kWaves;
+      entry = n < blk1 ? table_entry(n) : -1;
+    }
+    return n;
+  };
   int blk = blk0 + wave;
+  size_t bi = unit * a.nbcap + blk;
+  if (PAGED) blk = first_valid(blk, blk < blk1 ? table_entry(blk) : -1, bi);
   if (blk < blk1) {   // parameters first: they are the block's first consumers
-    issue_kpar(blk);
-    issue_vpar(blk);
+    issue_kpar(bi);
+    issue_vpar(bi);
 #pragma unroll
-    for (int T = 0; T < 8; ++T) issue_ktile(blk, T);
+    for (int T = 0; T < 8; ++T) issue_ktile(bi, T);
   }
 
   // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
@@ -309,8 +343,12 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   // one, which then runs a block ahead, finishes early and leaves the other to drain alone with
   // half the loads in flight.  Priority by remaining work keeps the pair in step.
   int done = 0;
+  bool first = true;
   while (blk < blk1) {
-    const int nblk = SINGLE ? blk1 : blk + kWaves;
+    int nblk = SINGLE ? blk1 : blk + kWaves;
+    size_t nbi = bi + kWaves;
+    int next_entry = -1;   // requested a block ahead, like the parameters
+    if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
     if (!SINGLE) {
       const int q4 = (4 * done) / (my_blocks > 0 ? my_blocks : 1);   // quarter of the work done: 0..3
       if (q4 == 0) __builtin_amdgcn_s_setprio(3);
@@ -364,14 +402,14 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
     }
     const float zq = wl.zq[head];
-    const bool has_next = !SINGLE && nblk < blk1;
-    if (has_next) {   // small, and the next block's first consumers: requested a block ahead
-      issue_kpar(nblk);
-      issue_vpar(nblk);
+    bool has_next = !SINGLE && nblk < blk1;
+    if (!PAGED && has_next) {   // small, and the next block's first consumers: requested a block ahead
+      issue_kpar(nbi);
+      issue_vpar(nbi);
     }
     if (!SINGLE && F::kValuesAtTop) {
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
+      for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
     }
 
     // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); column
@@ -393,7 +431,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       }
       if ((SINGLE || !F::kValuesAtTop) && half == 0) {
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) issue_vtile(blk, mt);
+        for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -410,7 +448,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     m_run = m_new;
     l_run *= alpha;
     z_run *= alpha;
-    if (!SINGLE && blk != blk0 + wave && __any(alpha != 1.0f)) {   // nothing to rescale on the first block
+    if (!SINGLE && !first && __any(alpha != 1.0f)) {   // nothing to rescale on the first block
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
       xacc *= alpha;
@@ -449,12 +487,22 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
             __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[2 * mp + 1].w, j), bp, oacc[2 * mp + 1], 0, 0, 0);
       }
     }
+    if (PAGED && has_next) {
+      nblk = first_valid(nblk, next_entry, nbi);
+      has_next = nblk < blk1;
+      if (has_next) {
+        issue_kpar(nbi);
+        issue_vpar(nbi);
+      }
+    }
     if (has_next) {
 #pragma unroll
-      for (int T = 0; T < 8; ++T) issue_ktile(nblk, T);
+      for (int T = 0; T < 8; ++T) issue_ktile(nbi, T);
     }
     wave_sync();   // the next block's prep overwrites this wave's LDS scratch
+    first = false;
     blk = nblk;
+    bi = nbi;
   }
 
   // ---- merge the waves of the workgroup (cross-wave step of the cooperative softmax)
@@ -598,15 +646,52 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.res_len = res_len;
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
+  a.block_table = nullptr;
+  a.seq_lens = nullptr;
+  a.status = nullptr;
+  a.max_pages = a.num_pages = 0;
   dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
   const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
   if (c->format == BD_FMT_INT4) {
-    if (single) decode_int_kernel<4, true><<<grid, block, 0, st>>>(a);
-    else decode_int_kernel<4, false><<<grid, block, 0, st>>>(a);
+    if (single) decode_int_kernel<4, true, false><<<grid, block, 0, st>>>(a);
+    else decode_int_kernel<4, false, false><<<grid, block, 0, st>>>(a);
   } else {
-    if (single) decode_int_kernel<2, true><<<grid, block, 0, st>>>(a);
-    else decode_int_kernel<2, false><<<grid, block, 0, st>>>(a);
+    if (single) decode_int_kernel<2, true, false><<<grid, block, 0, st>>>(a);
+    else decode_int_kernel<2, false, false><<<grid, block, 0, st>>>(a);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
+                               float* part_o, float* part_ml, hipStream_t st) {
+  DecodeArgs a;
+  a.k_codes = (const uint32_t*)c->k_codes;
+  a.v_codes = (const uint32_t*)c->v_codes;
+  a.k_params = (const uint32_t*)c->k_params;
+  a.v_params = (const uint32_t*)c->v_params;
+  a.k_res = (const uint16_t*)c->k_res;
+  a.v_res = (const uint16_t*)c->v_res;
+  a.q = (const uint16_t*)q;
+  a.k_new = a.v_new = nullptr;
+  a.new_slot = -1;
+  a.part_o = part_o;
+  a.part_ml = part_ml;
+  a.n_q_heads = c->n_q_heads;
+  a.n_kv_heads = c->n_kv_heads;
+  a.gq = c->n_q_heads / c->n_kv_heads;
+  a.nb = a.nbcap = a.res_len = 0;   // per sequence, from seq_lens
+  a.num_splits = num_splits;
+  a.scale_log2 = softmax_scale * kLog2e;
+  a.block_table = c->block_table;
+  a.seq_lens = c->seq_lens;
+  a.status = c->status;
+  a.max_pages = c->max_pages_per_seq;
+  a.num_pages = c->num_pages;
+  dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
+  if (c->format == BD_FMT_INT4)
+    decode_int_kernel<4, false, true><<<grid, block, 0, st>>>(a);
+  else
+    decode_int_kernel<2, false, true><<<grid, block, 0, st>>>(a);
   return hipGetLastError();
 }
 

@@ -44,15 +44,13 @@ __device__ __forceinline__ uint32_t quant_code(float x, float scale_f, float zer
 // (statistics over the block's tokens), V per token (statistics over the 128 channels).
 // Thread-local min/max first, then wave shuffles, then a small LDS buffer across waves:
 // the reduction ladder of Sec. IV-B(2).
+// quant_block: the whole workgroup (256 threads) quantizes the 128 token rows at ksrc / vsrc
+// ([128][128] fp16) into packed block `dblk` of the four destination arrays.
 template <int BITS>
-__global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __restrict__ ksrc,
-                                                           const uint16_t* __restrict__ vsrc,
-                                                           long src_unit_stride, int src_tok0,
-                                                           uint32_t* __restrict__ k_codes,
-                                                           uint32_t* __restrict__ v_codes,
-                                                           uint32_t* __restrict__ k_params,
-                                                           uint32_t* __restrict__ v_params, int nbcap,
-                                                           int dst_blk0) {
+__device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
+                                            uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes,
+                                            uint32_t* __restrict__ k_params, uint32_t* __restrict__ v_params,
+                                            size_t dblk) {
   constexpr int QMAX = (1 << BITS) - 1;
   constexpr int CPT = 32 / BITS;     // channels per thread == codes per word
   constexpr int TPR = kD / CPT;      // threads per token row == K words per token
@@ -66,14 +64,11 @@ __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __rest
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tr = tid / TPR, tc = tid % TPR;
-  const int unit = blockIdx.y, blk = blockIdx.x;
-  const size_t dblk = (size_t)unit * nbcap + dst_blk0 + blk;
-  const size_t src_off = (size_t)unit * src_unit_stride + ((size_t)src_tok0 + (size_t)blk * kBlock) * kD;
 
   // ---- K: load, per-channel min/max over the 128 tokens
   float x[NP][CPT];
   {
-    const uint16_t* src = ksrc + src_off;
+    const uint16_t* src = ksrc;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const uint16_t* rp = src + (size_t)(p * RPP + tr) * kD + tc * CPT;
@@ -133,7 +128,7 @@ __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __rest
 
   // ---- V: load, per-token min/max over the 128 channels
   {
-    const uint16_t* src = vsrc + src_off;
+    const uint16_t* src = vsrc;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       const uint16_t* rp = src + (size_t)(p * RPP + tr) * kD + tc * CPT;
@@ -179,6 +174,120 @@ __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __rest
     for (int n = 0; n < CPT; ++n) word |= (uint32_t)tile[(CPT * w + n) * PITCH + ch] << (BITS * n);
     v_codes[dblk * (size_t)(kD * WPC) + id] = word;
   }
+}
+
+// Contiguous cache: block blockIdx.x of unit blockIdx.y.
+template <int BITS>
+__global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __restrict__ ksrc,
+                                                           const uint16_t* __restrict__ vsrc,
+                                                           long src_unit_stride, int src_tok0,
+                                                           uint32_t* __restrict__ k_codes,
+                                                           uint32_t* __restrict__ v_codes,
+                                                           uint32_t* __restrict__ k_params,
+                                                           uint32_t* __restrict__ v_params, int nbcap,
+                                                           int dst_blk0) {
+  const int unit = blockIdx.y, blk = blockIdx.x;
+  const size_t dblk = (size_t)unit * nbcap + dst_blk0 + blk;
+  const size_t src_off = (size_t)unit * src_unit_stride + ((size_t)src_tok0 + (size_t)blk * kBlock) * kD;
+  quant_block<BITS>(ksrc + src_off, vsrc + src_off, k_codes, v_codes, k_params, v_params, dblk);
+}
+
+// ---- paged cache (page = one 128-token block; pool index of (page, head) = page * H + head) ---
+
+struct PagedArgs {
+  uint32_t *k_codes, *v_codes, *k_params, *v_params;
+  uint16_t *k_res, *v_res;
+  const int32_t* block_table;
+  int32_t* seq_lens;
+  int32_t* status;
+  int n_kv_heads, num_pages, max_pages;
+};
+
+// Page of block n of sequence b, or -1 (and bit `flag` of *status set) if the table has no
+// valid entry for it.
+__device__ __forceinline__ int page_of(const PagedArgs& a, int b, int n, int flag) {
+  int page = -1;
+  if (n < a.max_pages) page = a.block_table[(size_t)b * a.max_pages + n];
+  if (page < 0 || page >= a.num_pages) {
+    if (a.status && threadIdx.x == 0) atomicOr(a.status, flag);
+    return -1;
+  }
+  return page;
+}
+
+// Prefill of one sequence: block blockIdx.x of KV head blockIdx.y, source [H][L][128].
+template <int BITS>
+__global__ __launch_bounds__(256) void paged_quant_kernel(PagedArgs a, const uint16_t* __restrict__ ksrc,
+                                                           const uint16_t* __restrict__ vsrc, int seq, int L) {
+  const int blk = blockIdx.x, h = blockIdx.y;
+  const int page = page_of(a, seq, blk, 2);
+  if (page < 0) return;
+  const size_t src_off = ((size_t)h * L + (size_t)blk * kBlock) * kD;
+  quant_block<BITS>(ksrc + src_off, vsrc + src_off, a.k_codes, a.v_codes, a.k_params, a.v_params,
+                    (size_t)page * a.n_kv_heads + h);
+}
+
+// Prefill, rest: the L mod 128 newest tokens of every head go to the sequence's residual and
+// the length is recorded.  One workgroup per KV head.
+__global__ __launch_bounds__(256) void paged_tail_kernel(PagedArgs a, const u4_t* __restrict__ ksrc,
+                                                          const u4_t* __restrict__ vsrc, int seq, int L) {
+  const int h = blockIdx.x, r = L % kBlock;
+  const size_t so = ((size_t)h * L + (size_t)(L - r)) * (kD / 8);
+  const size_t dn = ((size_t)seq * a.n_kv_heads + h) * kBlock * (kD / 8);
+  u4_t* kd = reinterpret_cast<u4_t*>(a.k_res);
+  u4_t* vd = reinterpret_cast<u4_t*>(a.v_res);
+  for (int i = threadIdx.x; i < r * (kD / 8); i += blockDim.x) {
+    kd[dn + i] = ksrc[so + i];
+    vd[dn + i] = vsrc[so + i];
+  }
+  if (h == 0 && threadIdx.x == 0) a.seq_lens[seq] = L;
+}
+
+// One decode step of sequence blockIdx.y, KV head blockIdx.x: the new token row goes to residual
+// slot len mod 128; if that fills the residual it is quantized into the sequence's next page
+// (Sec. IV-B(1)).  Lengths are bumped by paged_bump_kernel afterwards, so every workgroup of
+// the sequence sees the same length here.
+template <int BITS>
+__global__ __launch_bounds__(256) void paged_append_kernel(PagedArgs a, const uint16_t* __restrict__ k_new,
+                                                            const uint16_t* __restrict__ v_new) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int len = a.seq_lens[b];
+  if (len < 0) return;
+  const int nb = len / kBlock, r = len % kBlock;
+  const size_t unit = (size_t)b * a.n_kv_heads + h;
+  int page = 0;
+  if (r == kBlock - 1) {
+    page = page_of(a, b, nb, 2);
+    if (page < 0) return;   // the token is dropped; the length stays
+  }
+  uint16_t* kr = a.k_res + unit * kBlock * kD;
+  uint16_t* vr = a.v_res + unit * kBlock * kD;
+  if (threadIdx.x < 32) {
+    const bool is_v = threadIdx.x >= 16;
+    const int c8 = 8 * (threadIdx.x & 15);
+    const u4_t val = *reinterpret_cast<const u4_t*>((is_v ? v_new : k_new) + unit * kD + c8);
+    *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (size_t)r * kD + c8) = val;
+  }
+  if (r != kBlock - 1) return;
+  // the row just written is read back below by other threads of this workgroup
+  __threadfence();
+  __syncthreads();
+  quant_block<BITS>(kr, vr, a.k_codes, a.v_codes, a.k_params, a.v_params, (size_t)page * a.n_kv_heads + h);
+}
+
+// seq_lens[b] += 1 for every sequence whose step went through (same test as the append kernel).
+__global__ void paged_bump_kernel(PagedArgs a, int batch) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= batch) return;
+  const int len = a.seq_lens[b];
+  if (len < 0) return;
+  if (len % kBlock == kBlock - 1) {
+    const int n = len / kBlock;
+    int page = -1;
+    if (n < a.max_pages) page = a.block_table[(size_t)b * a.max_pages + n];
+    if (page < 0 || page >= a.num_pages) return;
+  }
+  a.seq_lens[b] = len + 1;
 }
 
 // Copies `ntok` token rows of K and of V between [unit][token][128] arrays of 16-bit values.
@@ -357,6 +466,53 @@ hipError_t launch_quant_blocks(int bits, const void* k, const void* v, long src_
                                                    src_tok0, (uint32_t*)c->k_codes, (uint32_t*)c->v_codes,
                                                    (uint32_t*)c->k_params, (uint32_t*)c->v_params, nbcap,
                                                    dst_blk0);
+  return hipGetLastError();
+}
+
+static PagedArgs paged_args(const bd_paged_cache* c) {
+  PagedArgs a;
+  a.k_codes = (uint32_t*)c->k_codes;
+  a.v_codes = (uint32_t*)c->v_codes;
+  a.k_params = (uint32_t*)c->k_params;
+  a.v_params = (uint32_t*)c->v_params;
+  a.k_res = (uint16_t*)c->k_res;
+  a.v_res = (uint16_t*)c->v_res;
+  a.block_table = c->block_table;
+  a.seq_lens = c->seq_lens;
+  a.status = c->status;
+  a.n_kv_heads = c->n_kv_heads;
+  a.num_pages = c->num_pages;
+  a.max_pages = c->max_pages_per_seq;
+  return a;
+}
+
+hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k, const void* v, int L,
+                                hipStream_t st) {
+  const PagedArgs a = paged_args(c);
+  const int nb = L / kBlock;
+  if (nb > 0) {
+    dim3 grid(nb, c->n_kv_heads), block(256);
+    if (c->format == BD_FMT_INT4)
+      paged_quant_kernel<4><<<grid, block, 0, st>>>(a, (const uint16_t*)k, (const uint16_t*)v, seq, L);
+    else
+      paged_quant_kernel<2><<<grid, block, 0, st>>>(a, (const uint16_t*)k, (const uint16_t*)v, seq, L);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  paged_tail_kernel<<<dim3(c->n_kv_heads), dim3(256), 0, st>>>(a, (const u4_t*)k, (const u4_t*)v, seq, L);
+  return hipGetLastError();
+}
+
+hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, hipStream_t st) {
+  const PagedArgs a = paged_args(c);
+  dim3 grid(c->n_kv_heads, c->batch), block(256);
+  if (c->format == BD_FMT_INT4)
+    paged_append_kernel<4><<<grid, block, 0, st>>>(a, (const uint16_t*)k_new, (const uint16_t*)v_new);
+  else
+    paged_append_kernel<2><<<grid, block, 0, st>>>(a, (const uint16_t*)k_new, (const uint16_t*)v_new);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch);
   return hipGetLastError();
 }
 

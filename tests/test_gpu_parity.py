@@ -400,3 +400,134 @@ def test_decode_step_matches_oracle_on_cfg1():
         torch.cuda.synchronize()
         assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"cfg1 fused step {step}")
     _assert_int_cache_equal(oc, gc)
+
+
+# ---------------------------------------------------------------------------- paged cache
+
+def _paged_pair(fmt, lens, H, Hq, num_pages, max_pages, seed=31, table=None):
+    """Oracle and GPU paged caches prefilled with ragged sequences on scattered pages."""
+    bits = 4 if fmt == "int4" else 2
+    B_ = len(lens)
+    rng = np.random.default_rng(seed)
+    if table is None:
+        table = rng.permutation(num_pages)[:B_ * max_pages].reshape(B_, max_pages).astype(np.int32)
+    oc = O.PagedIntCache(B_, H, bits, num_pages, max_pages, table)
+    gc = B.PagedKVCache(B_, Hq, H, fmt, num_pages, table)
+    for b, L in enumerate(lens):
+        w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=Hq, n_kv_heads=H, context=max(L, 1), seed=seed + b)
+        K, V = W.make_kv(w)
+        K, V = np.ascontiguousarray(K[0, :, :L]), np.ascontiguousarray(V[0, :, :L])
+        oc.quant_pack_kv(b, K, V)
+        gc.quant_pack_kv(b, to_dev(K, "fp16"), to_dev(V, "fp16"))
+    return oc, gc, table
+
+
+def _assert_paged_equal(oc, gc, what):
+    import torch
+    torch.cuda.synchronize()
+    assert list(gc.seq_lens.cpu().numpy()) == list(oc.seq_lens), what
+    for i, name in enumerate(["k_codes", "v_codes", "k_params", "v_params"]):
+        ref = getattr(oc, name)
+        got = gc.host_buffer(i).view(np.uint32).reshape(ref.shape)
+        assert np.array_equal(got, ref), (what, name)          # whole pool: untouched pages stay zero
+    for i, name in [(4, "k_res"), (5, "v_res")]:
+        ref = getattr(oc, name)
+        got = gc.host_buffer(i).view(np.float16).reshape(ref.shape)
+        for b in range(oc.B):
+            r = int(oc.seq_lens[b]) % 128
+            assert np.array_equal(got[b, :, :r].view(np.uint16), ref[b, :, :r].view(np.uint16)), (what, name, b)
+
+
+@pytest.mark.parametrize("fmt", ["int4", "int2"])
+def test_paged_prefill_append_and_decode_match_oracle(fmt):
+    """Ragged batch on scattered pages: pool bytes bit-exact after prefill and after appends that
+    carry two sequences over a flush; attention within tolerance at several split factors,
+    including an empty sequence (zero output)."""
+    import torch
+    lens = [1000, 0, 126, 128 * 5, 37]
+    H, Hq = 2, 8
+    oc, gc, _ = _paged_pair(fmt, lens, H, Hq, num_pages=64, max_pages=10)
+    _assert_paged_equal(oc, gc, f"{fmt} prefill")
+    w = W.scaled(W.CONFIGS["cfg1"], batch=len(lens), n_q_heads=Hq, n_kv_heads=H, context=128, seed=77)
+    out = torch.empty((len(lens), Hq, 128), dtype=torch.float16, device="cuda:0")
+    for step in range(4):
+        kn, vn = W.make_new_kv(w, step)
+        oc.append_kv(kn, vn)
+        gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+        q = W.make_q(w, step)
+        for ns in ((1, 3, 8) if step in (0, 3) else (2,)):
+            out.zero_()
+            gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, ns)
+            torch.cuda.synchronize()
+            assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} paged step {step} ns {ns}",
+                              large_outputs=True)
+    _assert_paged_equal(oc, gc, f"{fmt} after appends")
+    assert int(gc.status.item()) == 0
+    # the sequence that started empty has 4 residual tokens now and attends only those
+    assert int(oc.seq_lens[1]) == 4
+
+
+def test_paged_bad_table_entries_are_skipped_and_reported():
+    """A block whose table entry is outside the pool is neither read nor written: decode flags bit
+    0 and attends the remaining blocks; an append that needs such a page flags bit 1 and leaves
+    the sequence's length unchanged."""
+    import torch
+    H, Hq = 1, 4
+    table = np.array([[3, 1, 9], [0, 2, -1]], np.int32)     # 9 and -1 are not pages of a pool of 4
+    oc, gc, _ = _paged_pair("int4", [255, 255], H, Hq, num_pages=4, max_pages=3, table=np.array([[3, 1, 2], [0, 2, 1]], np.int32))
+    # rebuild the GPU cache's table with the bad entries in blocks the sequences do not hold yet
+    gc.block_table.copy_(torch.from_numpy(table))
+    w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=Hq, n_kv_heads=H, context=128, seed=5)
+    kn, vn = W.make_new_kv(w, 0)
+    gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))       # fills block 1 of both: pages 1 and 2, fine
+    torch.cuda.synchronize()
+    assert list(gc.seq_lens.cpu().numpy()) == [256, 256] and int(gc.status.item()) == 0
+    for step in range(1, 128):
+        kn, vn = W.make_new_kv(w, step)
+        gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+    torch.cuda.synchronize()
+    assert list(gc.seq_lens.cpu().numpy()) == [383, 383] and int(gc.status.item()) == 0
+    kn, vn = W.make_new_kv(w, 128)
+    gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+    torch.cuda.synchronize()
+    # this append needed block 2: entries 9 and -1 -> dropped, flagged, lengths stay at 383
+    assert list(gc.seq_lens.cpu().numpy()) == [383, 383]
+    assert int(gc.status.item()) == 2
+    # decode over a table with a bad entry in a block the sequence does hold
+    gc.status.zero_()
+    bad = table.copy(); bad[0, 0] = 77
+    gc.block_table.copy_(torch.from_numpy(bad))
+    out = torch.empty((2, Hq, 128), dtype=torch.float16, device="cuda:0")
+    gc.decode_attn(to_dev(W.make_q(w), "fp16"), W.softmax_scale(w), out, 2)
+    torch.cuda.synchronize()
+    assert int(gc.status.item()) == 1
+    assert torch.isfinite(out.float()).all()
+
+
+def test_paged_long_ragged_batch_sampled_units():
+    """LLaMA-3.1-8B head geometry, lengths from 100 tokens to just over 32K, pages scattered over
+    one pool, split factor as the library picks it for the longest sequence; outputs checked on
+    sampled (sequence, KV head) units."""
+    import torch
+    lens = [32768 + 5, 8192, 100, 20000 + 127]
+    H, Hq = 8, 32
+    max_pages = 258
+    oc, gc, _ = _paged_pair("int4", lens, H, Hq, num_pages=len(lens) * max_pages + 7, max_pages=max_pages, seed=91)
+    w = W.scaled(W.CONFIGS["cfg1"], batch=len(lens), seed=92)
+    out = torch.empty((len(lens), Hq, 128), dtype=torch.float16, device="cuda:0")
+    shape = B.bd_cache(1, Hq, H, 128, B.BD_FMT_INT4, 128 * max_pages, None, None, None, None, None, None)
+    ns = B.bd_choose_splits(shape, 32768)
+    kn, vn = W.make_new_kv(w, 0)
+    oc.append_kv(kn, vn)                                         # sequence 3 flushes its residual here
+    gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+    q = W.make_q(w, 1)
+    gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, ns)
+    torch.cuda.synchronize()
+    units = [(0, 0), (0, 5), (1, 7), (2, 3), (3, 1), (3, 6)]
+    assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w), units=units), "paged long ragged",
+                      large_outputs=True)
+    assert list(gc.seq_lens.cpu().numpy()) == [L + 1 for L in lens] and int(gc.status.item()) == 0
+    # packed bytes of the flushed block of sequence 3, all heads
+    pg = int(oc.block_table[3, lens[3] // 128])
+    got = gc.host_buffer(0).view(np.uint32).reshape(oc.k_codes.shape)
+    assert np.array_equal(got[pg], oc.k_codes[pg])

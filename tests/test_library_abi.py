@@ -104,3 +104,36 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_LIB_PATH", "/nonexistent/libbitdecode.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.lib()
+
+
+def _paged(**kw):
+    d = dict(batch=4, n_q_heads=32, n_kv_heads=8, head_dim=128, format=B.BD_FMT_INT4, num_pages=100, max_pages=10)
+    d.update(kw)
+    return B.bd_paged_cache(d["batch"], d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["format"], d["num_pages"],
+                            d["max_pages"])
+
+
+@needs_lib
+def test_paged_sizes_and_argument_validation():
+    c = _paged()
+    pool = 100 * 8
+    assert [B.bd_paged_cache_bytes(c, i) for i in range(8)] == [
+        pool * 128 * 64, pool * 128 * 64, pool * 128 * 4, pool * 128 * 4, 4 * 8 * 128 * 128 * 2, 4 * 8 * 128 * 128 * 2,
+        4 * 10 * 4, 4 * 4]
+    assert B.bd_paged_cache_bytes(_paged(format=B.BD_FMT_INT2), 0) == pool * 128 * 32
+    assert B.bd_paged_cache_bytes(_paged(format=B.BD_FMT_MXFP4), 0) == 0          # not built for MXFP4
+    assert B.bd_paged_cache_bytes(_paged(num_pages=0), 0) == 0
+    assert B.bd_paged_workspace_bytes(c, 16) == 16 * 4 * 32 * 130 * 4
+    L = B.lib()
+    # NULL buffers are refused before anything is launched
+    assert L.bd_paged_append_kv(ctypes.byref(c), 16, 16, None) == -1
+    for name in ("k_codes", "v_codes", "k_params", "v_params", "k_res", "v_res", "block_table", "seq_lens"):
+        setattr(c, name, 4096)
+    assert L.bd_paged_append_kv(ctypes.byref(c), None, 16, None) == -1
+    assert L.bd_paged_append_kv(ctypes.byref(c), 8, 16, None) == -3
+    assert L.bd_paged_quant_pack_kv(ctypes.byref(c), 4, 16, 16, 10, None) == -1     # sequence out of range
+    assert L.bd_paged_quant_pack_kv(ctypes.byref(c), 0, 16, 16, 128 * 11, None) == -4   # more blocks than table columns
+    assert L.bd_paged_decode_attn(ctypes.byref(c), 16, ctypes.c_float(0.1), 0, 16, 16, None) == -1
+    assert L.bd_paged_decode_attn(ctypes.byref(c), 16, ctypes.c_float(0.1), 4, 16, None, None) == -1
+    c.seq_lens = 4098
+    assert L.bd_paged_append_kv(ctypes.byref(c), 16, 16, None) == -3

@@ -24,8 +24,16 @@ def attn_errors(got: np.ndarray, ref: np.ndarray):
     return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-30))
 
 
-def assert_attn_close(got: np.ndarray, ref: np.ndarray, what=""):
+def assert_attn_close(got: np.ndarray, ref: np.ndarray, what="", large_outputs=False):
+    """The bar of the benchmark configurations: max-abs 2e-3 and relative L2 1e-3.  With
+    `large_outputs` (sequences of a few tokens, whose outputs are single V rows: magnitudes of
+    10 and more with the x10 outlier channels, where half an fp16 step alone is 8e-3) the
+    max-abs bar is taken per element as 2e-3 + 2^-10 |ref| instead."""
     mask = ~np.isnan(ref)
     ma, rl = attn_errors(got[mask], ref[mask])
-    assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
+    if large_outputs:
+        excess = np.abs(got[mask] - ref[mask]) - (MAX_ABS_TOL + 2.0 ** -10 * np.abs(ref[mask]))
+        assert excess.max() <= 0 and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
+    else:
+        assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
     return ma, rl
