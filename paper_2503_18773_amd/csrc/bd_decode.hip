@@ -102,8 +102,13 @@ struct Fmt<4> {
   __device__ static int run_base(int sg, int run) { return 8 * sg + 4 * run; }
   __device__ static constexpr float un(int v) { return (v & 1) ? (1.0f / 16.0f) : 1.0f; }
   __device__ static constexpr float inv_un(int v) { return (v & 1) ? 16.0f : 1.0f; }
-  // kPairShift brings the column group whose tile fills the high half of a P' register next to
-  // the one that fills the low half; kStepShift brings the second k-step of a pair to columns 0..3
+  // k-step j = 2*half + jj of the second product contracts the tokens of two S^T tiles of that
+  // half: tile_lo(jj) fills the low fp16 half of the P' registers, tile_hi(jj) the high one
+  __device__ static constexpr int tile_lo(int jj) { return 2 * jj; }
+  __device__ static constexpr int tile_hi(int jj) { return 2 * jj + 1; }
+  // groups of up to 4 heads (column group c/4 keeps tiles c/4 and 4 + c/4): kPairShift brings the
+  // column group whose tile fills the high half of a P' register next to the one that fills the
+  // low half; kStepShift brings the second k-step of a pair to columns 0..3
   static constexpr int kPairShift = kRowShl4, kStepShift = kRowShl8;
   // position of block token t in the k-ordered P' / V operand: lane group t/32, then k-step j,
   // register r, half -- tile T = (t%32)/4 feeds k-step T/2, half T%2
@@ -131,6 +136,8 @@ struct Fmt<2> {
   __device__ static int run_base(int sg, int run) { return 16 * (sg >> 1) + 4 * (sg & 1) + 8 * run; }
   __device__ static constexpr float un(int v) { return 1.0f / (float)(1 << (2 * v)); }
   __device__ static constexpr float inv_un(int v) { return (float)(1 << (2 * v)); }
+  __device__ static constexpr int tile_lo(int jj) { return jj; }
+  __device__ static constexpr int tile_hi(int jj) { return jj + 2; }
   static constexpr int kPairShift = kRowShl8, kStepShift = kRowShl4;
   // tile T = (t%32)/4 feeds k-step 2*(T/4) + T%2, half (T%4)/2
   __device__ static int p_slot(int t) {
@@ -166,40 +173,58 @@ __device__ __forceinline__ RawTile<WORDS> load_raw(const uint32_t* p) {
   return t;
 }
 
-// Per-wave LDS scratch.
+// Per-wave LDS scratch.  GQP = query heads per KV head, padded to 4, 8 or 16.
+template <int GQP>
 struct WaveLds {
-  uint16_t qhi[4][kD];   // Q' per head, high fp16 piece, in B-operand slot order
-  uint16_t qlo[4][kD];   // low piece
-  float2 vpar[kBlock];   // per V token of the block: (scale * position factor, zero + scale * centre code)
-  uint16_t c16[kBlock];  // per V token: centre code * position factor, in the A-operand order of P'
-  float zq[4];           // per head: sum_c Q_c z_c * scale_log2 * 2^-24
+  uint16_t qhi[GQP][kD];   // Q' per head, high fp16 piece, in B-operand slot order
+  uint16_t qlo[GQP][kD];   // low piece
+  float2 vpar[kBlock];     // per V token of the block: (scale * position factor, zero + scale * centre code)
+  uint16_t c16[kBlock];    // per V token: centre code * position factor, in the A-operand order of P'
+  float zq[GQP];           // per head: sum_c Q_c z_c * scale_log2 * 2^-24
 };
+template <int GQP>
 struct MergeLds {
-  float o[kWaves][4][kD];
-  float m[kWaves][4], l[kWaves][4], z[kWaves][4];
+  float o[kWaves][GQP][kD];
+  float m[kWaves][GQP], l[kWaves][GQP], z[kWaves][GQP];
 };
 
 constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
-constexpr size_t kSmemBytes = cmax(sizeof(MergeLds), kWaves * sizeof(WaveLds));
 
+// GQP: the query group padded to 4, 8 or 16 heads; the 16 MFMA columns carry it 16/GQP times
+//      (column c holds head c % GQP, "column group" c / GQP) and the softmax work of a block
+//      is shared out over the column groups.
+//      GQP = 4: column group cg keeps S^T tiles cg and 4 + cg (8 values per lane) and the
+//      packed probabilities are moved to columns 0..3 with DPP row shifts, so O^T accumulates
+//      in those columns only.
+//      GQP = 8, 16: each column group owns 4 / COPIES of the block's four 32-token k-steps of
+//      the second product: it keeps the S^T tiles of those tokens, runs their softmax, and
+//      presents their P' as its part of the B operand (zero in the k-steps it does not own);
+//      no probability moves between lanes, and the column groups' partial O^T are added
+//      once, after the loop.
 // SINGLE: no wave has more than one block (short contexts); the host picks the instance.
 // PAGED: blocks are found through the block table and every sequence has its own length.
-template <int BITS, bool SINGLE, bool PAGED>
+template <int BITS, int GQP, bool SINGLE, bool PAGED>
 __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   using F = Fmt<BITS>;
+  using WL = WaveLds<GQP>;
+  using ML = MergeLds<GQP>;
   constexpr int WORDS = F::WORDS;            // words per lane per tile
   constexpr int KROW = kD * BITS / 32;       // K words per token
   constexpr int VROW = kBlock * BITS / 32;   // V words per channel per block
+  constexpr int COPIES = 16 / GQP;           // column groups
+  constexpr int OWN = 4 / COPIES;            // k-steps owned by a column group
+  constexpr int HP = GQP / 4;                // passes over the heads where 16 lanes work on one head
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem_raw[kSmemBytes];
-  __shared__ float res_s[kBlock][4];         // scores of this workgroup's residual tokens, per head
+  __shared__ __attribute__((aligned(16))) unsigned char smem_raw[cmax(sizeof(ML), kWaves * sizeof(WL))];
+  __shared__ float res_s[kBlock][GQP];       // scores of this workgroup's residual tokens, per head
+  __shared__ __attribute__((aligned(16))) float q_s[HP > 1 ? GQP : 1][kD];   // larger groups: queries * softmax_scale * log2(e); padding heads zero
 
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = lane & 15, g = lane >> 4;   // MFMA column and contraction group
-  const int head = col & 3, cg = col >> 2;    // head carried by the column; column group
+  const int col = lane & 15, g = lane >> 4;            // MFMA column and contraction group
+  const int head = col % GQP, cg = col / GQP;          // head carried by the column; column group
   const int gq = a.gq;
-  WaveLds& wl = reinterpret_cast<WaveLds*>(smem_raw)[wave];
+  WL& wl = reinterpret_cast<WL*>(smem_raw)[wave];
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int nb = a.nb, res_len = a.res_len;
@@ -228,7 +253,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   // waves of a compute unit share one in-order memory pipeline, so whatever one wave requests
   // early only delays what the others are waiting for: 8 KB per wave (16 MB over the chip) keeps
   // HBM busy, and a shorter queue shortens the ramp at both ends of the kernel.
-  const int prep_head = lane >> 4, prep_sg = lane & 15;
+  const int prep_sg = lane & 15;
   const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
   RawTile<WORDS> kraw[8], vraw[8];
@@ -252,24 +277,36 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     const uint32_t* vp = a.v_codes + bi * (size_t)(kD * VROW) + WORDS * g;
     vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
   };
-  // Loads return in order, so what is needed first is requested first: the query slices
-  // and this wave's first residual key row, then the first block.
-  u2_t qraw0 = {0u, 0u}, qraw1 = {0u, 0u};
-  if (prep_head < gq) {
-    qraw0 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run0);
-    qraw1 = *reinterpret_cast<const u2_t*>(qbase + prep_head * kD + run1);
-  }
+  // Loads return in order, so what is needed first is requested first: the queries and this
+  // wave's first residual key row, then the first block.
+  // A group of up to 4 heads: every lane keeps the query slice it rescales per block (head
+  // lane / 16, two runs of 4 channels) in registers.  Larger groups go through LDS (q_s).
   const bool has_res = rt0 + wave < rt1;
+  uint32_t qld[HP];
+  u2_t qraw0 = {0u, 0u}, qraw1 = {0u, 0u};
+  uint32_t qres_raw[4] = {0u, 0u, 0u, 0u};
+  if constexpr (HP == 1) {
+    if ((lane >> 4) < gq) {
+      qraw0 = *reinterpret_cast<const u2_t*>(qbase + (lane >> 4) * kD + run0);
+      qraw1 = *reinterpret_cast<const u2_t*>(qbase + (lane >> 4) * kD + run1);
+    }
+    if (has_res) {
+#pragma unroll
+      for (int h = 0; h < 4; ++h)
+        if (h < gq) qres_raw[h] = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int h = 4 * p + (tid >> 6);   // thread tid: head h, channels 2*(tid%64), +1
+      qld[p] = h < gq ? *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane) : 0u;
+    }
+  }
   const uint16_t* kres = a.k_res + unit * kBlock * kD;
   // row t of the residual keys: the newest token of a fused step is read from where the caller left it
   auto kres_row = [&](int t) { return t == a.new_slot ? a.k_new + unit * kD : kres + (size_t)t * kD; };
-  uint32_t qres_raw[4] = {0u, 0u, 0u, 0u}, kres_raw = 0u;
-  if (has_res) {
-#pragma unroll
-    for (int h = 0; h < 4; ++h)
-      if (h < gq) qres_raw[h] = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
-    kres_raw = *reinterpret_cast<const uint32_t*>(kres_row(rt0 + wave) + 2 * lane);
-  }
+  uint32_t kres_raw = 0u;
+  if (has_res) kres_raw = *reinterpret_cast<const uint32_t*>(kres_row(rt0 + wave) + 2 * lane);
   if (a.new_slot >= 0 && split == 0 && tid < 32) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
@@ -306,37 +343,58 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     for (int T = 0; T < 8; ++T) issue_ktile(bi, T);
   }
 
+  // ---- larger groups: the queries, scaled, for everybody in the workgroup
+  if constexpr (HP > 1) {
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int h = 4 * p + (tid >> 6);
+      float2 qq = {h2f((uint16_t)(qld[p] & 0xFFFFu)) * a.scale_log2, h2f((uint16_t)(qld[p] >> 16)) * a.scale_log2};
+      *reinterpret_cast<float2*>(&q_s[h][2 * lane]) = qq;
+    }
+    __syncthreads();
+  }
+
   // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
   if (has_res) {
-    float qr[4][2];
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      qr[h][0] = h2f((uint16_t)(qres_raw[h] & 0xFFFFu)) * a.scale_log2;
-      qr[h][1] = h2f((uint16_t)(qres_raw[h] >> 16)) * a.scale_log2;
-    }
     uint32_t raw = kres_raw;
     for (int t = rt0 + wave; t < rt1; t += kWaves) {
       const float k0 = h2f((uint16_t)(raw & 0xFFFFu)), k1 = h2f((uint16_t)(raw >> 16));
       if (t + kWaves < rt1) raw = *reinterpret_cast<const uint32_t*>(kres_row(t + kWaves) + 2 * lane);
-      float sh[4];
 #pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        float x = __builtin_fmaf(qr[h][0], k0, qr[h][1] * k1);
+      for (int h = 0; h < GQP; ++h) {
+        float2 qq;
+        if constexpr (HP == 1)
+          qq = make_float2(h2f((uint16_t)(qres_raw[h] & 0xFFFFu)) * a.scale_log2,
+                           h2f((uint16_t)(qres_raw[h] >> 16)) * a.scale_log2);
+        else
+          qq = *reinterpret_cast<const float2*>(&q_s[h][2 * lane]);
+        float x = __builtin_fmaf(qq.x, k0, qq.y * k1);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
-        sh[h] = x;
+        if (lane == 0) res_s[t - rt0][h] = x;
       }
-      if (lane < 4) res_s[t - rt0][lane] = lane == 0 ? sh[0] : lane == 1 ? sh[1] : lane == 2 ? sh[2] : sh[3];
     }
   }
 
-  // Query slice this lane rescales every block: head lane/16, slot group lane%16
-  // (two runs of 4 consecutive channels); zero for the padding heads of a small group.
+  // tokens whose softmax this lane runs: for its o-th owned k-step j = cg * OWN + o, the low
+  // (lh = 0) and high (lh = 1) fp16 halves of the P' registers come from tiles tile_lo / tile_hi
+  // of half j / 2; token = 32 g + 4 tile + row
   float qv[2][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     qv[0][i] = h2f((uint16_t)((qraw0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
     qv[1][i] = h2f((uint16_t)((qraw1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
+  }
+  int tb[OWN][2];
+#pragma unroll
+  for (int o = 0; o < OWN; ++o) {
+    const int j = cg * OWN + o;
+    tb[o][0] = 32 * g + 4 * (4 * (j >> 1) + ((j & 1) ? F::tile_lo(1) : F::tile_lo(0)));
+    tb[o][1] = 32 * g + 4 * (4 * (j >> 1) + ((j & 1) ? F::tile_hi(1) : F::tile_hi(0)));
+  }
+  if (COPIES == 4) {   // tiles cg and 4 + cg
+    tb[0][0] = 32 * g + 4 * cg;
+    tb[0][1] = 32 * g + 16 + 4 * cg;
   }
 
   // Two waves of different workgroups share each SIMD and the issue arbiter favours the older
@@ -357,8 +415,19 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       else __builtin_amdgcn_s_setprio(0);
       ++done;
     }
-    // ---- per-block query rescale (K is channel-wise): Q' = Q * s_c, zero term sum_c Q_c z_c
-    {
+    // ---- per-block query rescale (K is channel-wise): Q' = Q * s_c, zero term sum_c Q_c z_c;
+    //      16 lanes per head (slot group lane % 16: two runs of 4 consecutive channels)
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int ph = 4 * p + (lane >> 4);
+      f4_t qa, qb;
+      if constexpr (HP == 1) {
+        qa = (f4_t){qv[0][0], qv[0][1], qv[0][2], qv[0][3]};
+        qb = (f4_t){qv[1][0], qv[1][1], qv[1][2], qv[1][3]};
+      } else {
+        qa = *reinterpret_cast<const f4_t*>(&q_s[ph][run0]);
+        qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
+      }
       float zsum = 0.0f;
       uint16_t qh[8], ql[8];
 #pragma unroll
@@ -366,12 +435,13 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const uint32_t pr = run ? kp1[i] : kp0[i];
+          const float qv = run ? qb[i] : qa[i];
           const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
-          const float t = qv[run][i] * s * F::un(i);
+          const float t = qv * s * F::un(i);
           const uint16_t hi = f2h(t);
           qh[2 * i + run] = hi;
           ql[2 * i + run] = f2h(t - h2f(hi));
-          zsum = __builtin_fmaf(qv[run][i], z, zsum);
+          zsum = __builtin_fmaf(qv, z, zsum);
         }
       zsum = row_sum16(zsum);
       u4_t phi, plo;
@@ -380,19 +450,19 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
         plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
       }
-      *reinterpret_cast<u4_t*>(&wl.qhi[prep_head][8 * prep_sg]) = phi;
-      *reinterpret_cast<u4_t*>(&wl.qlo[prep_head][8 * prep_sg]) = plo;
-      if (prep_sg == 0) wl.zq[prep_head] = zsum * kTwoM24;
-      // V parameters of the block's 128 tokens
+      *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
+      *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
+      if (prep_sg == 0) wl.zq[ph] = zsum * kTwoM24;
+    }
+    // V parameters of the block's 128 tokens
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const float sv = h2f((uint16_t)(vp2[u] & 0xFFFFu)), zv = h2f((uint16_t)(vp2[u] >> 16));
-        const int t = 2 * lane + u;
-        const int r = t & 3;                // row of the token inside its S^T tile
-        const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
-        wl.vpar[t] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
-        wl.c16[F::p_slot(t)] = (uint16_t)(ct * F::inv_un(r));
-      }
+    for (int u = 0; u < 2; ++u) {
+      const float sv = h2f((uint16_t)(vp2[u] & 0xFFFFu)), zv = h2f((uint16_t)(vp2[u] >> 16));
+      const int t = 2 * lane + u;
+      const int r = t & 3;                // row of the token inside its S^T tile
+      const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
+      wl.vpar[t] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+      wl.c16[F::p_slot(t)] = (uint16_t)(ct * F::inv_un(r));
     }
     wave_sync();
     h8_t bqh[4], bql[4];
@@ -412,9 +482,9 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
     }
 
-    // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); column
-    //      group cg keeps tiles cg and 4+cg
-    float sc[2][4];
+    // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); each lane
+    //      keeps the tiles of the k-steps its column group owns: sc[o][low/high half][row]
+    float sc[OWN][2][4];
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       f4_t s[4];
@@ -433,16 +503,41 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
       }
+      // k-steps 2*half and 2*half+1 draw on this half's four tiles
+      if constexpr (COPIES == 1) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float lo = cg & 1 ? s[1][r] : s[0][r], hi = cg & 1 ? s[3][r] : s[2][r];
-        sc[half][r] = cg & 2 ? hi : lo;
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            sc[2 * half + jj][0][r] = s[F::tile_lo(jj)][r];
+            sc[2 * half + jj][1][r] = s[F::tile_hi(jj)][r];
+          }
+      } else if constexpr (COPIES == 2) {   // column group cg owns k-steps 2cg, 2cg+1: half cg
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float lo = s[F::tile_lo(jj)][r], hi = s[F::tile_hi(jj)][r];
+            sc[jj][0][r] = (half == 0 || cg == 1) ? lo : sc[jj][0][r];
+            sc[jj][1][r] = (half == 0 || cg == 1) ? hi : sc[jj][1][r];
+          }
+      } else {                              // column group cg keeps tile cg of each half
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float lo = cg & 1 ? s[1][r] : s[0][r], hi = cg & 1 ? s[3][r] : s[2][r];
+          sc[0][half][r] = cg & 2 ? hi : lo;
+        }
       }
     }
-    // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
-    float bmax = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
-                       fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-    bmax = head_max(bmax);
+    // ---- online softmax (Alg. 1) over this lane's 8 * OWN tokens of head `head`
+    float bmax = sc[0][0][0];
+#pragma unroll
+    for (int o = 0; o < OWN; ++o)
+#pragma unroll
+      for (int lh = 0; lh < 2; ++lh)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[o][lh][r]);
+    bmax = head_max<COPIES>(bmax);
     const float m_new = fmaxf(m_run, bmax * kTwo24);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
@@ -453,23 +548,46 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
       xacc *= alpha;
     }
-    u4_t pb[4];   // P' as the B operand of the 4 k-steps of O^T += V^T P' (valid in columns 0..3)
+    u4_t pb[4];   // P' as the B operand of the 4 k-steps of O^T += V^T P'
+    if constexpr (COPIES == 4) {   // valid in columns 0..3
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+      for (int half = 0; half < 2; ++half)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[half][r], kTwo24, -m_new));
-        const float2 par = wl.vpar[32 * g + 16 * half + 4 * cg + r];
-        l_run += p;
-        z_run = __builtin_fmaf(p, par.y, z_run);
-        const float pf = p * par.x;
-        const uint16_t ph = f2h(pf);
-        // gather the column groups' fp16 values into the B-operand register pairs
-        const uint32_t x = (uint32_t)ph;
-        const uint32_t pair = x | dpp_u<F::kPairShift>(x << 16);
-        pb[2 * half][r] = pair;
-        pb[2 * half + 1][r] = dpp_u<F::kStepShift>(pair);
-      }
+        for (int r = 0; r < 4; ++r) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kTwo24, -m_new));
+          const float2 par = wl.vpar[tb[0][half] + r];
+          l_run += p;
+          z_run = __builtin_fmaf(p, par.y, z_run);
+          // gather the column groups' fp16 values into the B-operand register pairs
+          const uint32_t x = (uint32_t)f2h(p * par.x);
+          const uint32_t pr = x | dpp_u<F::kPairShift>(x << 16);
+          pb[2 * half][r] = pr;
+          pb[2 * half + 1][r] = dpp_u<F::kStepShift>(pr);
+        }
+    } else {                       // zero where another column group owns the k-step
+      u4_t pair[OWN];
+#pragma unroll
+      for (int o = 0; o < OWN; ++o)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          uint32_t hv[2];
+#pragma unroll
+          for (int lh = 0; lh < 2; ++lh) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kTwo24, -m_new));
+            const float2 par = wl.vpar[tb[o][lh] + r];
+            l_run += p;
+            z_run = __builtin_fmaf(p, par.y, z_run);
+            hv[lh] = (uint32_t)f2h(p * par.x);
+          }
+          pair[o][r] = hv[0] | (hv[1] << 16);
+        }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if constexpr (COPIES == 1) pb[j][r] = pair[j][r];
+          else pb[j][r] = cg == (j >> 1) ? pair[j & 1][r] : 0u;
+        }
     }
     // ---- O^T += V^T P' : k-step j contracts 32 tokens (8 per lane group)
 #pragma unroll
@@ -505,16 +623,26 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     bi = nbi;
   }
 
-  // ---- merge the waves of the workgroup (cross-wave step of the cooperative softmax)
-  l_run = head_sum(l_run);
-  z_run = head_sum(z_run);
+  // ---- merge the column groups (groups of 8 heads), then the waves of the workgroup
+  //      (cross-wave step of the cooperative softmax)
+  l_run = head_sum<COPIES>(l_run);
+  z_run = head_sum<COPIES>(z_run);
   __syncthreads();   // every wave is done with its WaveLds before the space is reused
-  MergeLds& ml = *reinterpret_cast<MergeLds*>(smem_raw);
-  if (col < 4) {
+  ML& ml = *reinterpret_cast<ML*>(smem_raw);
+  // (all lane movement first, in passes over independent values, then one predicated run of stores)
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) oacc[mt] -= xacc[0];
+  if (COPIES == 2) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = (oacc[mt][r] - xacc[0]) * kTwo24;
+      for (int r = 0; r < 4; ++r) oacc[mt][r] += dpp_f<kRowShl8>(oacc[mt][r]);
+  }
+  if (col < GQP) {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r] * kTwo24;
     if (g == 0) {
       ml.m[wave][col] = m_run;
       ml.l[wave][col] = l_run;
@@ -522,8 +650,9 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     }
   }
   __syncthreads();
-  {
-    const int h = tid >> 6, c0 = 2 * (tid & 63);
+#pragma unroll
+  for (int p = 0; p < HP; ++p) {
+    const int h = 4 * p + (tid >> 6), c0 = 2 * (tid & 63);
     if (h < gq) {
       float M = ml.m[0][h];
 #pragma unroll
@@ -622,6 +751,31 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 
 }  // namespace
 
+namespace {
+
+template <int BITS, int GQP>
+void launch_mode(bool single, bool paged, const DecodeArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+  if (paged) decode_int_kernel<BITS, GQP, false, true><<<grid, block, 0, st>>>(a);
+  else if (single) decode_int_kernel<BITS, GQP, true, false><<<grid, block, 0, st>>>(a);
+  else decode_int_kernel<BITS, GQP, false, false><<<grid, block, 0, st>>>(a);
+}
+
+// picks the kernel instance: format, query group padded to 4 / 8 / 16 heads, loop structure
+void launch_instance(int bits, int gq, bool single, bool paged, const DecodeArgs& a, dim3 grid, dim3 block,
+                     hipStream_t st) {
+  if (bits == 4) {
+    if (gq <= 4) launch_mode<4, 4>(single, paged, a, grid, block, st);
+    else if (gq <= 8) launch_mode<4, 8>(single, paged, a, grid, block, st);
+    else launch_mode<4, 16>(single, paged, a, grid, block, st);
+  } else {
+    if (gq <= 4) launch_mode<2, 4>(single, paged, a, grid, block, st);
+    else if (gq <= 8) launch_mode<2, 8>(single, paged, a, grid, block, st);
+    else launch_mode<2, 16>(single, paged, a, grid, block, st);
+  }
+}
+
+}  // namespace
+
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
                              hipStream_t st) {
@@ -652,13 +806,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.max_pages = a.num_pages = 0;
   dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
   const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
-  if (c->format == BD_FMT_INT4) {
-    if (single) decode_int_kernel<4, true, false><<<grid, block, 0, st>>>(a);
-    else decode_int_kernel<4, false, false><<<grid, block, 0, st>>>(a);
-  } else {
-    if (single) decode_int_kernel<2, true, false><<<grid, block, 0, st>>>(a);
-    else decode_int_kernel<2, false, false><<<grid, block, 0, st>>>(a);
-  }
+  launch_instance(c->format == BD_FMT_INT4 ? 4 : 2, a.gq, single, false, a, grid, block, st);
   return hipGetLastError();
 }
 
@@ -688,10 +836,7 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.max_pages = c->max_pages_per_seq;
   a.num_pages = c->num_pages;
   dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
-  if (c->format == BD_FMT_INT4)
-    decode_int_kernel<4, false, true><<<grid, block, 0, st>>>(a);
-  else
-    decode_int_kernel<2, false, true><<<grid, block, 0, st>>>(a);
+  launch_instance(c->format == BD_FMT_INT4 ? 4 : 2, a.gq, false, true, a, grid, block, st);
   return hipGetLastError();
 }
 

@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
     // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
     float bmax = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                        fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-    bmax = head_max(bmax);
+    bmax = head_max<4>(bmax);
     const float m_new = fmaxf(m_run, bmax);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
   }
 
   // ---- merge the waves of the workgroup
-  l_run = head_sum(l_run);
+  l_run = head_sum<4>(l_run);
   if (col < 4) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)

@@ -39,17 +39,20 @@ __device__ __forceinline__ float row_sum16(float x) {
   x += dpp_f<kRowMirror>(x);
   return x;
 }
-// combine over the lanes that share lane%4 (the same head): 4 column groups x 4 lane groups
+// reductions over the lanes that carry the same head (column % (16 / COPIES)): COPIES column
+// groups x 4 lane groups
+template <int COPIES>
 __device__ __forceinline__ float head_sum(float x) {
-  x += dpp_f<kRowRor4>(x);
-  x += dpp_f<kRowRor8>(x);
+  if (COPIES == 4) x += dpp_f<kRowRor4>(x);
+  if (COPIES >= 2) x += dpp_f<kRowRor8>(x);
   x += __shfl_xor(x, 16);
   x += __shfl_xor(x, 32);
   return x;
 }
+template <int COPIES>
 __device__ __forceinline__ float head_max(float x) {
-  x = fmaxf(x, dpp_f<kRowRor4>(x));
-  x = fmaxf(x, dpp_f<kRowRor8>(x));
+  if (COPIES == 4) x = fmaxf(x, dpp_f<kRowRor4>(x));
+  if (COPIES >= 2) x = fmaxf(x, dpp_f<kRowRor8>(x));
   x = fmaxf(x, __shfl_xor(x, 16));
   x = fmaxf(x, __shfl_xor(x, 32));
   return x;

@@ -531,3 +531,44 @@ def test_paged_long_ragged_batch_sampled_units():
     pg = int(oc.block_table[3, lens[3] // 128])
     got = gc.host_buffer(0).view(np.uint32).reshape(oc.k_codes.shape)
     assert np.array_equal(got[pg], oc.k_codes[pg])
+
+
+# ---------------------------------------------------------------------------- query groups
+
+@pytest.mark.parametrize("fmt", ["int4", "int2"])
+@pytest.mark.parametrize("gq", [1, 3, 5, 8, 12, 16])
+def test_query_group_sizes(fmt, gq):
+    """Any number of query heads per KV head up to 16 (Sec. IV-A: the group forms the N dimension of
+    the matrix instructions): short context (one block per wave) and longer (several), with a
+    residual tail, several split factors, and the fused step."""
+    import torch
+    H = 2
+    for L, ns in [(128 * 3 + 70, 2), (128 * 41 + 5, 3)]:
+        w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=gq * H, n_kv_heads=H, context=L, fmt=fmt, seed=40 + gq)
+        K, V, oc, gc = _int_cache_pair(w, (L // 128 + 2) * 128)
+        out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float16, device="cuda:0")
+        q = W.make_q(w)
+        gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=ns)
+        torch.cuda.synchronize()
+        assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} gq={gq} L={L}",
+                          large_outputs=True)
+        kn, vn = W.make_new_kv(w, 0)
+        q = W.make_q(w, 1)
+        oc.append_kv(kn, vn)
+        gc.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=ns)
+        torch.cuda.synchronize()
+        assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} gq={gq} L={L} step",
+                          large_outputs=True)
+
+
+def test_paged_with_eight_query_heads_per_kv_head():
+    import torch
+    lens = [700, 129, 3000]
+    H, Hq = 2, 16
+    oc, gc, _ = _paged_pair("int4", lens, H, Hq, num_pages=80, max_pages=25, seed=55)
+    w = W.scaled(W.CONFIGS["cfg1"], batch=len(lens), n_q_heads=Hq, n_kv_heads=H, context=128, seed=56)
+    out = torch.empty((len(lens), Hq, 128), dtype=torch.float16, device="cuda:0")
+    q = W.make_q(w)
+    gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, 4)
+    torch.cuda.synchronize()
+    assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), "paged gq=8", large_outputs=True)
