@@ -74,6 +74,15 @@ def quantize_k_block(kblk: np.ndarray, bits: int):
     return quant_codes(kblk, scale[None, :], zero[None, :], bits), scale, zero
 
 
+def quantize_k_block_per_token(kblk: np.ndarray, bits: int):
+    """The KT setting (Sec. IV-C(1), Sec. V: K quantized "tensor-wise" like V instead of
+    channel-wise): K block [128 tokens, D=128] fp16 -> codes [128, D], scale [128], zero [128],
+    statistics over the 128 channels of each token."""
+    assert kblk.shape == (BLOCK, BLOCK) and kblk.dtype == np.float16
+    scale, zero = quant_params(kblk.min(axis=1), kblk.max(axis=1), bits)
+    return quant_codes(kblk, scale[:, None], zero[:, None], bits), scale, zero
+
+
 def quantize_v_block(vblk: np.ndarray, bits: int):
     """V block [128 tokens, D=128] fp16 -> codes [128, D], scale [128], zero [128]
     (per token: statistics run over the group of 128 channels, i.e. the whole head)."""
@@ -121,13 +130,16 @@ class IntCache:
       k_codes  uint32 [B, H, NBcap, 128 tokens, D*bits/32]   words run along channels
       v_codes  uint32 [B, H, NBcap, D channels, 128*bits/32] words run along the block's tokens
       k_params uint32 [B, H, NBcap, D]        half2 (scale, zero) per channel
+                                              (k_per_token: per token of the block, [.., 128])
       v_params uint32 [B, H, NBcap, 128]      half2 (scale, zero) per token
       k_res, v_res fp16 [B, H, 128, D]        residual tokens, slots [0, res_len) valid
     """
 
-    def __init__(self, batch: int, n_kv_heads: int, bits: int, capacity: int, head_dim: int = 128):
+    def __init__(self, batch: int, n_kv_heads: int, bits: int, capacity: int, head_dim: int = 128,
+                 k_per_token: bool = False):
         assert capacity % BLOCK == 0 and head_dim == 128
         self.B, self.H, self.D, self.bits, self.capacity = batch, n_kv_heads, head_dim, bits, capacity
+        self.k_per_token = k_per_token          # KT: K statistics per token instead of per channel
         nbc = capacity // BLOCK
         wpr = head_dim * bits // 32
         self.k_codes = np.zeros((batch, n_kv_heads, nbc, BLOCK, wpr), np.uint32)
@@ -143,7 +155,8 @@ class IntCache:
     def _store_block(self, nb: int, kblk: np.ndarray, vblk: np.ndarray):
         for b in range(self.B):
             for h in range(self.H):
-                kc, ks, kz = quantize_k_block(kblk[b, h], self.bits)
+                quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
+                kc, ks, kz = quant_k(kblk[b, h], self.bits)
                 vc, vs, vz = quantize_v_block(vblk[b, h], self.bits)
                 self.k_codes[b, h, nb] = pack_words(kc, self.bits)              # [token][channel words]
                 self.v_codes[b, h, nb] = pack_words(vc.T.copy(), self.bits)     # [channel][token words]
@@ -188,7 +201,10 @@ class IntCache:
             vc = unpack_words(self.v_codes[b, h, n], self.bits).astype(np.float64).T    # [c][t] -> [t][c]
             ks, kz = unpack_half2(self.k_params[b, h, n])
             vs, vz = unpack_half2(self.v_params[b, h, n])
-            Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[None, :] + kz.astype(np.float64)[None, :]
+            if self.k_per_token:
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[:, None] + kz.astype(np.float64)[:, None]
+            else:
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[None, :] + kz.astype(np.float64)[None, :]
             Vh[n * BLOCK:(n + 1) * BLOCK] = vc * vs.astype(np.float64)[:, None] + vz.astype(np.float64)[:, None]
         Kh[self.packed_len:] = self.k_res[b, h, :self.res_len].astype(np.float64)
         Vh[self.packed_len:] = self.v_res[b, h, :self.res_len].astype(np.float64)
@@ -212,9 +228,10 @@ class PagedIntCache:
     """
 
     def __init__(self, batch: int, n_kv_heads: int, bits: int, num_pages: int, max_pages: int,
-                 block_table: np.ndarray, head_dim: int = 128):
+                 block_table: np.ndarray, head_dim: int = 128, k_per_token: bool = False):
         assert head_dim == 128 and block_table.shape == (batch, max_pages)
         self.B, self.H, self.D, self.bits = batch, n_kv_heads, head_dim, bits
+        self.k_per_token = k_per_token
         self.P, self.max_pages = num_pages, max_pages
         self.k_codes = np.zeros((num_pages, n_kv_heads, BLOCK, head_dim * bits // 32), np.uint32)
         self.v_codes = np.zeros((num_pages, n_kv_heads, head_dim, BLOCK * bits // 32), np.uint32)
@@ -235,8 +252,9 @@ class PagedIntCache:
 
     def _store_block(self, b: int, n: int, kblk: np.ndarray, vblk: np.ndarray):
         p = self._page_of(b, n)
+        quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
         for h in range(self.H):
-            kc, ks, kz = quantize_k_block(kblk[h], self.bits)
+            kc, ks, kz = quant_k(kblk[h], self.bits)
             vc, vs, vz = quantize_v_block(vblk[h], self.bits)
             self.k_codes[p, h] = pack_words(kc, self.bits)
             self.v_codes[p, h] = pack_words(vc.T.copy(), self.bits)
@@ -281,7 +299,10 @@ class PagedIntCache:
             vc = unpack_words(self.v_codes[p, h], self.bits).astype(np.float64).T
             ks, kz = unpack_half2(self.k_params[p, h])
             vs, vz = unpack_half2(self.v_params[p, h])
-            Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[None, :] + kz.astype(np.float64)[None, :]
+            if self.k_per_token:
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[:, None] + kz.astype(np.float64)[:, None]
+            else:
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[None, :] + kz.astype(np.float64)[None, :]
             Vh[n * BLOCK:(n + 1) * BLOCK] = vc * vs.astype(np.float64)[:, None] + vz.astype(np.float64)[:, None]
         Kh[nb * BLOCK:] = self.k_res[b, h, :r].astype(np.float64)
         Vh[nb * BLOCK:] = self.v_res[b, h, :r].astype(np.float64)
