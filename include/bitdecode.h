@@ -24,10 +24,12 @@
  * Cache layout (all little-endian, contiguous, 16-byte aligned), B = batch, H = n_kv_heads,
  * NBcap = capacity/128, D = 128, bits = 4 or 2, cpw = 32/bits codes per 32-bit word:
  *
- *  INT4 / INT2  (K channel-wise, V per token -- Sec. IV-B(1), Sec. IV-C(1))
+ *  INT4 / INT2 and their _KT variants  (K channel-wise or per token, V per token -- Sec. IV-B(1), Sec. IV-C(1))
  *   k_codes  uint32 [B][H][NBcap][128 tokens][D/cpw]   word w of a token: channels cpw*w+n at bit bits*n
  *   v_codes  uint32 [B][H][NBcap][D channels][128/cpw] word w of a channel: block tokens cpw*w+n at bit bits*n
  *   k_params uint32 [B][H][NBcap][D]     half2: fp16 scale in bits 0..15, fp16 zero in bits 16..31
+ *                                        (BD_FMT_INT4_KT / INT2_KT: [B][H][NBcap][128], one per token
+ *                                        of the block, statistics over the token's 128 channels)
  *   v_params uint32 [B][H][NBcap][128]   half2 per token of the block
  *   k_res, v_res fp16 [B][H][128][D]     the L mod 128 newest tokens, unquantized (Sec. III-A(2))
  *   Quantizer: zero = group minimum (-0 stored as +0); scale = fp16((max - min) / (2^bits - 1))
@@ -64,7 +66,13 @@ typedef enum {
   BD_ERR_HIP = -5            /* a HIP runtime call failed; see bd_last_hip_error() */
 } bd_status;
 
-typedef enum { BD_FMT_INT4 = 0, BD_FMT_INT2 = 1, BD_FMT_MXFP4 = 2 } bd_format;
+typedef enum {
+  BD_FMT_INT4 = 0,      /* K channel-wise, V per token (the paper's KC setting, its default) */
+  BD_FMT_INT2 = 1,
+  BD_FMT_MXFP4 = 2,
+  BD_FMT_INT4_KT = 3,   /* K per token as well (the paper's KT setting, Sec. IV-C(1)) */
+  BD_FMT_INT2_KT = 4
+} bd_format;
 
 /* Shape and buffers of one layer's cache.  Plain data, filled by the caller, passed by
  * const pointer; the six buffers are device pointers with the layouts given above. */
@@ -171,7 +179,7 @@ typedef struct bd_paged_cache {
   int32_t n_q_heads;
   int32_t n_kv_heads;
   int32_t head_dim;            /* 128 */
-  int32_t format;              /* BD_FMT_INT4 or BD_FMT_INT2 */
+  int32_t format;              /* BD_FMT_INT4, BD_FMT_INT2 or their _KT variants */
   int32_t num_pages;
   int32_t max_pages_per_seq;
   void *k_codes, *v_codes;

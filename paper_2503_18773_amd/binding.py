@@ -8,8 +8,9 @@ from __future__ import annotations
 import ctypes
 import os
 
-BD_FMT_INT4, BD_FMT_INT2, BD_FMT_MXFP4 = 0, 1, 2
-FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4}
+BD_FMT_INT4, BD_FMT_INT2, BD_FMT_MXFP4, BD_FMT_INT4_KT, BD_FMT_INT2_KT = 0, 1, 2, 3, 4
+FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4, "int4_kt": BD_FMT_INT4_KT,
+           "int2_kt": BD_FMT_INT2_KT}
 BLOCK = 128
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbitdecode.so")

@@ -15,7 +15,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bd_status check_shape(const bd_cache* c) {
   if (!c) return BD_ERR_INVALID_ARG;
   if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return BD_ERR_INVALID_ARG;
-  if (c->format != BD_FMT_INT4 && c->format != BD_FMT_INT2 && c->format != BD_FMT_MXFP4) return BD_ERR_INVALID_ARG;
+  if (!fmt_is_int(c->format) && c->format != BD_FMT_MXFP4) return BD_ERR_INVALID_ARG;
   if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
   if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;
   // query heads per KV head: the int4 / int2 kernels pad the group to 4, 8 or 16 MFMA columns;
@@ -43,7 +43,7 @@ bd_status hip_status(hipError_t e) {
   return BD_ERR_HIP;
 }
 
-int bits_of(int format) { return format == BD_FMT_INT2 ? 2 : 4; }
+int bits_of(int format) { return fmt_bits(format); }
 
 }  // namespace
 
@@ -110,7 +110,7 @@ bd_status bd_quant_pack_kv(const bd_cache* c, const void* k, const void* v, int3
   }
   const int nb = L / kBlock, r = L % kBlock;
   if (nb * kBlock > c->capacity) return BD_ERR_CAPACITY;
-  if ((s = hip_status(launch_quant_blocks(bits_of(c->format), k, v, stride, 0, nb, units, c, 0, st))) != BD_OK)
+  if ((s = hip_status(launch_quant_blocks(k, v, stride, 0, nb, units, c, 0, st))) != BD_OK)
     return s;
   if ((s = hip_status(launch_copy_rows(k, v, stride, nb * kBlock, c->k_res, c->v_res, (long)kBlock * kD, 0, r,
                                        units, st))) != BD_OK)
@@ -145,7 +145,7 @@ bd_status bd_append_kv(const bd_cache* c, const void* k_new, const void* v_new, 
     return s;
   if (flush) {
     // The residual block is full: quantize and pack it as packed block pl/128 (Sec. IV-B(1)).
-    if ((s = hip_status(launch_quant_blocks(bits_of(c->format), c->k_res, c->v_res, (long)kBlock * kD, 0, 1, units, c,
+    if ((s = hip_status(launch_quant_blocks(c->k_res, c->v_res, (long)kBlock * kD, 0, 1, units, c,
                                             pl / kBlock, st))) != BD_OK)
       return s;
     *packed_len = pl + kBlock;

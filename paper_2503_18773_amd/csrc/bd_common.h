@@ -24,9 +24,15 @@ void note_hip_error(hipError_t e);
 
 // Kernel launchers (host side, defined next to their kernels).  All return hipError_t of
 // the launch.  `units` = batch * n_kv_heads.
-hipError_t launch_quant_blocks(int bits, const void* k, const void* v, long src_unit_stride,
-                               int src_tok0, int nblocks, int units, const bd_cache* c,
-                               int dst_blk0, hipStream_t st);
+hipError_t launch_quant_blocks(const void* k, const void* v, long src_unit_stride, int src_tok0,
+                               int nblocks, int units, const bd_cache* c, int dst_blk0,
+                               hipStream_t st);
+
+static inline bool fmt_is_int(int f) {
+  return f == BD_FMT_INT4 || f == BD_FMT_INT2 || f == BD_FMT_INT4_KT || f == BD_FMT_INT2_KT;
+}
+static inline int fmt_bits(int f) { return (f == BD_FMT_INT2 || f == BD_FMT_INT2_KT) ? 2 : 4; }
+static inline bool fmt_kt(int f) { return f == BD_FMT_INT4_KT || f == BD_FMT_INT2_KT; }
 hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0,
                             void* kdst, void* vdst, long dst_unit_stride, int dst_tok0, int ntok,
                             int units, hipStream_t st);

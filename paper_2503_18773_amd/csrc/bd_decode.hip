@@ -179,6 +179,7 @@ struct WaveLds {
   uint16_t qhi[GQP][kD];   // Q' per head, high fp16 piece, in B-operand slot order
   uint16_t qlo[GQP][kD];   // low piece
   float2 vpar[kBlock];     // per V token of the block: (scale * position factor, zero + scale * centre code)
+  float2 kpar[kBlock];     // per-token K only: (scale * 2^24, zero) of the block's tokens
   uint16_t c16[kBlock];    // per V token: centre code * position factor, in the A-operand order of P'
   float zq[GQP];           // per head: sum_c Q_c z_c * scale_log2 * 2^-24
 };
@@ -203,7 +204,10 @@ constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
 //      once, after the loop.
 // SINGLE: no wave has more than one block (short contexts); the host picks the instance.
 // PAGED: blocks are found through the block table and every sequence has its own length.
-template <int BITS, int GQP, bool SINGLE, bool PAGED>
+// KT: K is quantized per token (Sec. IV-C(1)):  S[t] = s_t * sum_c Q_c code_tc + z_t * sum_c Q_c,
+//     so Q' = Q is prepared once per kernel instead of once per block and the per-token scale
+//     and zero are applied to the kept S^T values.
+template <int BITS, int GQP, bool SINGLE, bool PAGED, bool KT>
 __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   using F = Fmt<BITS>;
   using WL = WaveLds<GQP>;
@@ -258,13 +262,18 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
   RawTile<WORDS> kraw[8], vraw[8];
   u4_t kp0, kp1;   // K parameters (half2) of this lane's two channel runs
+  u2_t kp2;        // per-token K: parameters of tokens 2*lane, 2*lane+1
   u2_t vp2;        // V parameters (half2) of tokens 2*lane, 2*lane+1
   // All four take the index `bi` of the block in the packed arrays: unit * nbcap + block for the
   // contiguous cache, page * Hkv + head for the paged one.
   auto issue_kpar = [&](size_t bi) {
-    const uint32_t* pp = a.k_params + bi * kD;
-    kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
-    kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
+    if constexpr (KT) {
+      kp2 = *reinterpret_cast<const u2_t*>(a.k_params + bi * kBlock + 2 * lane);
+    } else {
+      const uint32_t* pp = a.k_params + bi * kD;
+      kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
+      kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
+    }
   };
   auto issue_vpar = [&](size_t bi) {
     vp2 = *reinterpret_cast<const u2_t*>(a.v_params + bi * kBlock + 2 * lane);
@@ -397,6 +406,65 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     tb[0][1] = 32 * g + 16 + 4 * cg;
   }
 
+  // Q' = Q * s_c as an fp16 high + low pair in B-operand order, and the zero term sum_c Q_c z_c, per
+  // head: once per block for channel-wise K (with the block's parameters), once per kernel for
+  // per-token K.  16 lanes per head (slot group lane % 16: two runs of 4 consecutive channels).
+  auto prep_queries = [&]() {
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int ph = 4 * p + (lane >> 4);
+      f4_t qa, qb;
+      if constexpr (HP == 1) {
+        qa = (f4_t){qv[0][0], qv[0][1], qv[0][2], qv[0][3]};
+        qb = (f4_t){qv[1][0], qv[1][1], qv[1][2], qv[1][3]};
+      } else {
+        qa = *reinterpret_cast<const f4_t*>(&q_s[ph][run0]);
+        qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
+      }
+      float zsum = 0.0f;
+      uint16_t qh[8], ql[8];
+#pragma unroll
+      for (int run = 0; run < 2; ++run)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float qc = run ? qb[i] : qa[i];
+          float s = 1.0f, z = 1.0f;   // per-token K: Q' = Q, and the "zero term" is sum_c Q_c
+          if constexpr (!KT) {
+            const uint32_t pr = run ? kp1[i] : kp0[i];
+            s = h2f((uint16_t)(pr & 0xFFFFu));
+            z = h2f((uint16_t)(pr >> 16));
+          }
+          const float t = qc * s * F::un(i);
+          const uint16_t hi = f2h(t);
+          qh[2 * i + run] = hi;
+          ql[2 * i + run] = f2h(t - h2f(hi));
+          zsum = __builtin_fmaf(qc, z, zsum);
+        }
+      zsum = row_sum16(zsum);
+      u4_t phi, plo;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
+        plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
+      }
+      *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
+      *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
+      if (prep_sg == 0) wl.zq[ph] = KT ? zsum : zsum * kTwoM24;
+    }
+  };
+  h8_t bqh[4], bql[4];
+  float zq = 0.0f, qsum = 0.0f;
+  if constexpr (KT) {
+    prep_queries();
+    wave_sync();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
+      bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+    }
+    qsum = wl.zq[head];
+  }
+
   // Two waves of different workgroups share each SIMD and the issue arbiter favours the older
   // one, which then runs a block ahead, finishes early and leaves the other to drain alone with
   // half the loads in flight.  Priority by remaining work keeps the pair in step.
@@ -415,44 +483,13 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       else __builtin_amdgcn_s_setprio(0);
       ++done;
     }
-    // ---- per-block query rescale (K is channel-wise): Q' = Q * s_c, zero term sum_c Q_c z_c;
-    //      16 lanes per head (slot group lane % 16: two runs of 4 consecutive channels)
+    if constexpr (!KT) prep_queries();
+    if constexpr (KT) {   // K parameters of the block's 128 tokens
 #pragma unroll
-    for (int p = 0; p < HP; ++p) {
-      const int ph = 4 * p + (lane >> 4);
-      f4_t qa, qb;
-      if constexpr (HP == 1) {
-        qa = (f4_t){qv[0][0], qv[0][1], qv[0][2], qv[0][3]};
-        qb = (f4_t){qv[1][0], qv[1][1], qv[1][2], qv[1][3]};
-      } else {
-        qa = *reinterpret_cast<const f4_t*>(&q_s[ph][run0]);
-        qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
+      for (int u = 0; u < 2; ++u) {
+        const float sk = h2f((uint16_t)(kp2[u] & 0xFFFFu)), zk = h2f((uint16_t)(kp2[u] >> 16));
+        wl.kpar[2 * lane + u] = make_float2(sk * kTwo24, zk);
       }
-      float zsum = 0.0f;
-      uint16_t qh[8], ql[8];
-#pragma unroll
-      for (int run = 0; run < 2; ++run)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const uint32_t pr = run ? kp1[i] : kp0[i];
-          const float qv = run ? qb[i] : qa[i];
-          const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
-          const float t = qv * s * F::un(i);
-          const uint16_t hi = f2h(t);
-          qh[2 * i + run] = hi;
-          ql[2 * i + run] = f2h(t - h2f(hi));
-          zsum = __builtin_fmaf(qv, z, zsum);
-        }
-      zsum = row_sum16(zsum);
-      u4_t phi, plo;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
-        plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
-      }
-      *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
-      *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
-      if (prep_sg == 0) wl.zq[ph] = zsum * kTwoM24;
     }
     // V parameters of the block's 128 tokens
 #pragma unroll
@@ -465,13 +502,14 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       wl.c16[F::p_slot(t)] = (uint16_t)(ct * F::inv_un(r));
     }
     wave_sync();
-    h8_t bqh[4], bql[4];
+    if constexpr (!KT) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
-      bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+      for (int j = 0; j < 4; ++j) {
+        bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
+        bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+      }
+      zq = wl.zq[head];
     }
-    const float zq = wl.zq[head];
     bool has_next = !SINGLE && nblk < blk1;
     if (!PAGED && has_next) {   // small, and the next block's first consumers: requested a block ahead
       issue_kpar(nbi);
@@ -529,6 +567,18 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         }
       }
     }
+    if constexpr (KT) {   // per-token scale and zero of K
+#pragma unroll
+      for (int o = 0; o < OWN; ++o)
+#pragma unroll
+        for (int lh = 0; lh < 2; ++lh)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float2 kq = wl.kpar[tb[o][lh] + r];
+            sc[o][lh][r] = __builtin_fmaf(sc[o][lh][r], kq.x, kq.y * qsum);
+          }
+    }
+    constexpr float kS = KT ? 1.0f : kTwo24;   // what the kept values still have to be multiplied by
     // ---- online softmax (Alg. 1) over this lane's 8 * OWN tokens of head `head`
     float bmax = sc[0][0][0];
 #pragma unroll
@@ -538,7 +588,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[o][lh][r]);
     bmax = head_max<COPIES>(bmax);
-    const float m_new = fmaxf(m_run, bmax * kTwo24);
+    const float m_new = fmaxf(m_run, bmax * kS);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
     l_run *= alpha;
@@ -554,7 +604,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       for (int half = 0; half < 2; ++half)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kTwo24, -m_new));
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kS, -m_new));
           const float2 par = wl.vpar[tb[0][half] + r];
           l_run += p;
           z_run = __builtin_fmaf(p, par.y, z_run);
@@ -573,7 +623,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
           uint32_t hv[2];
 #pragma unroll
           for (int lh = 0; lh < 2; ++lh) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kTwo24, -m_new));
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kS, -m_new));
             const float2 par = wl.vpar[tb[o][lh] + r];
             l_run += p;
             z_run = __builtin_fmaf(p, par.y, z_run);
@@ -753,24 +803,28 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 
 namespace {
 
-template <int BITS, int GQP>
+template <int BITS, int GQP, bool KT>
 void launch_mode(bool single, bool paged, const DecodeArgs& a, dim3 grid, dim3 block, hipStream_t st) {
-  if (paged) decode_int_kernel<BITS, GQP, false, true><<<grid, block, 0, st>>>(a);
-  else if (single) decode_int_kernel<BITS, GQP, true, false><<<grid, block, 0, st>>>(a);
-  else decode_int_kernel<BITS, GQP, false, false><<<grid, block, 0, st>>>(a);
+  if (paged) decode_int_kernel<BITS, GQP, false, true, KT><<<grid, block, 0, st>>>(a);
+  else if (single) decode_int_kernel<BITS, GQP, true, false, KT><<<grid, block, 0, st>>>(a);
+  else decode_int_kernel<BITS, GQP, false, false, KT><<<grid, block, 0, st>>>(a);
+}
+
+template <int BITS, bool KT>
+void launch_group(int gq, bool single, bool paged, const DecodeArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+  if (gq <= 4) launch_mode<BITS, 4, KT>(single, paged, a, grid, block, st);
+  else if (gq <= 8) launch_mode<BITS, 8, KT>(single, paged, a, grid, block, st);
+  else launch_mode<BITS, 16, KT>(single, paged, a, grid, block, st);
 }
 
 // picks the kernel instance: format, query group padded to 4 / 8 / 16 heads, loop structure
-void launch_instance(int bits, int gq, bool single, bool paged, const DecodeArgs& a, dim3 grid, dim3 block,
+void launch_instance(int format, int gq, bool single, bool paged, const DecodeArgs& a, dim3 grid, dim3 block,
                      hipStream_t st) {
-  if (bits == 4) {
-    if (gq <= 4) launch_mode<4, 4>(single, paged, a, grid, block, st);
-    else if (gq <= 8) launch_mode<4, 8>(single, paged, a, grid, block, st);
-    else launch_mode<4, 16>(single, paged, a, grid, block, st);
-  } else {
-    if (gq <= 4) launch_mode<2, 4>(single, paged, a, grid, block, st);
-    else if (gq <= 8) launch_mode<2, 8>(single, paged, a, grid, block, st);
-    else launch_mode<2, 16>(single, paged, a, grid, block, st);
+  switch (format) {
+    case BD_FMT_INT4: launch_group<4, false>(gq, single, paged, a, grid, block, st); break;
+    case BD_FMT_INT2: launch_group<2, false>(gq, single, paged, a, grid, block, st); break;
+    case BD_FMT_INT4_KT: launch_group<4, true>(gq, single, paged, a, grid, block, st); break;
+    default: launch_group<2, true>(gq, single, paged, a, grid, block, st); break;
   }
 }
 
@@ -806,7 +860,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.max_pages = a.num_pages = 0;
   dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
   const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
-  launch_instance(c->format == BD_FMT_INT4 ? 4 : 2, a.gq, single, false, a, grid, block, st);
+  launch_instance(c->format, a.gq, single, false, a, grid, block, st);
   return hipGetLastError();
 }
 
@@ -836,7 +890,7 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.max_pages = c->max_pages_per_seq;
   a.num_pages = c->num_pages;
   dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
-  launch_instance(c->format == BD_FMT_INT4 ? 4 : 2, a.gq, false, true, a, grid, block, st);
+  launch_instance(c->format, a.gq, false, true, a, grid, block, st);
   return hipGetLastError();
 }
 

@@ -46,7 +46,8 @@ __device__ __forceinline__ uint32_t quant_code(float x, float scale_f, float zer
 // the reduction ladder of Sec. IV-B(2).
 // quant_block: the whole workgroup (256 threads) quantizes the 128 token rows at ksrc / vsrc
 // ([128][128] fp16) into packed block `dblk` of the four destination arrays.
-template <int BITS>
+// KT: K statistics per token (over its 128 channels) instead of per channel (Sec. IV-C(1)).
+template <int BITS, bool KT>
 __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                                             uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes,
                                             uint32_t* __restrict__ k_params, uint32_t* __restrict__ v_params,
@@ -83,6 +84,31 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
       }
     }
   }
+  if constexpr (KT) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      float a = x[p][0], b = x[p][0];
+#pragma unroll
+      for (int cc = 1; cc < CPT; ++cc) {
+        a = fminf(a, x[p][cc]);
+        b = fmaxf(b, x[p][cc]);
+      }
+#pragma unroll
+      for (int off = 1; off < TPR; off <<= 1) {  // the TPR consecutive lanes of this token row
+        a = fminf(a, __shfl_xor(a, off));
+        b = fmaxf(b, __shfl_xor(b, off));
+      }
+      float ks, kz;
+      uint32_t packed;
+      group_params(a, b, QMAX, ks, kz, packed);
+      const int row = p * RPP + tr;
+      if (tc == 0) k_params[dblk * kBlock + row] = packed;
+      uint32_t w = 0;
+#pragma unroll
+      for (int cc = 0; cc < CPT; ++cc) w |= quant_code(x[p][cc], ks, kz, QMAX) << (BITS * cc);
+      k_codes[(dblk * kBlock + (size_t)row) * TPR + tc] = w;
+    }
+  } else {
   float mn[CPT], mx[CPT];
 #pragma unroll
   for (int cc = 0; cc < CPT; ++cc) {
@@ -125,6 +151,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
     for (int cc = 0; cc < CPT; ++cc) w |= quant_code(x[p][cc], ks[cc], kz[cc], QMAX) << (BITS * cc);
     k_codes[(dblk * kBlock + (size_t)(p * RPP + tr)) * TPR + tc] = w;
   }
+  }  // channel-wise K
 
   // ---- V: load, per-token min/max over the 128 channels
   {
@@ -177,7 +204,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
 }
 
 // Contiguous cache: block blockIdx.x of unit blockIdx.y.
-template <int BITS>
+template <int BITS, bool KT>
 __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __restrict__ ksrc,
                                                            const uint16_t* __restrict__ vsrc,
                                                            long src_unit_stride, int src_tok0,
@@ -189,7 +216,7 @@ __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __rest
   const int unit = blockIdx.y, blk = blockIdx.x;
   const size_t dblk = (size_t)unit * nbcap + dst_blk0 + blk;
   const size_t src_off = (size_t)unit * src_unit_stride + ((size_t)src_tok0 + (size_t)blk * kBlock) * kD;
-  quant_block<BITS>(ksrc + src_off, vsrc + src_off, k_codes, v_codes, k_params, v_params, dblk);
+  quant_block<BITS, KT>(ksrc + src_off, vsrc + src_off, k_codes, v_codes, k_params, v_params, dblk);
 }
 
 // ---- paged cache (page = one 128-token block; pool index of (page, head) = page * H + head) ---
@@ -216,15 +243,15 @@ __device__ __forceinline__ int page_of(const PagedArgs& a, int b, int n, int fla
 }
 
 // Prefill of one sequence: block blockIdx.x of KV head blockIdx.y, source [H][L][128].
-template <int BITS>
+template <int BITS, bool KT>
 __global__ __launch_bounds__(256) void paged_quant_kernel(PagedArgs a, const uint16_t* __restrict__ ksrc,
                                                            const uint16_t* __restrict__ vsrc, int seq, int L) {
   const int blk = blockIdx.x, h = blockIdx.y;
   const int page = page_of(a, seq, blk, 2);
   if (page < 0) return;
   const size_t src_off = ((size_t)h * L + (size_t)blk * kBlock) * kD;
-  quant_block<BITS>(ksrc + src_off, vsrc + src_off, a.k_codes, a.v_codes, a.k_params, a.v_params,
-                    (size_t)page * a.n_kv_heads + h);
+  quant_block<BITS, KT>(ksrc + src_off, vsrc + src_off, a.k_codes, a.v_codes, a.k_params, a.v_params,
+                        (size_t)page * a.n_kv_heads + h);
 }
 
 // Prefill, rest: the L mod 128 newest tokens of every head go to the sequence's residual and
@@ -247,7 +274,7 @@ __global__ __launch_bounds__(256) void paged_tail_kernel(PagedArgs a, const u4_t
 // slot len mod 128; if that fills the residual it is quantized into the sequence's next page
 // (Sec. IV-B(1)).  Lengths are bumped by paged_bump_kernel afterwards, so every workgroup of
 // the sequence sees the same length here.
-template <int BITS>
+template <int BITS, bool KT>
 __global__ __launch_bounds__(256) void paged_append_kernel(PagedArgs a, const uint16_t* __restrict__ k_new,
                                                             const uint16_t* __restrict__ v_new) {
   const int h = blockIdx.x, b = blockIdx.y;
@@ -272,7 +299,7 @@ __global__ __launch_bounds__(256) void paged_append_kernel(PagedArgs a, const ui
   // the row just written is read back below by other threads of this workgroup
   __threadfence();
   __syncthreads();
-  quant_block<BITS>(kr, vr, a.k_codes, a.v_codes, a.k_params, a.v_params, (size_t)page * a.n_kv_heads + h);
+  quant_block<BITS, KT>(kr, vr, a.k_codes, a.v_codes, a.k_params, a.v_params, (size_t)page * a.n_kv_heads + h);
 }
 
 // seq_lens[b] += 1 for every sequence whose step went through (same test as the append kernel).
@@ -451,21 +478,28 @@ __global__ __launch_bounds__(128) void mx_append_kernel(const uint16_t* __restri
 
 }  // namespace
 
-hipError_t launch_quant_blocks(int bits, const void* k, const void* v, long src_unit_stride, int src_tok0,
-                               int nblocks, int units, const bd_cache* c, int dst_blk0, hipStream_t st) {
+hipError_t launch_quant_blocks(const void* k, const void* v, long src_unit_stride, int src_tok0, int nblocks,
+                               int units, const bd_cache* c, int dst_blk0, hipStream_t st) {
   if (nblocks <= 0) return hipSuccess;
   dim3 grid(nblocks, units), block(256);
   const int nbcap = c->capacity / kBlock;
-  if (bits == 4)
-    quant_block_kernel<4><<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride,
-                                                   src_tok0, (uint32_t*)c->k_codes, (uint32_t*)c->v_codes,
-                                                   (uint32_t*)c->k_params, (uint32_t*)c->v_params, nbcap,
-                                                   dst_blk0);
-  else
-    quant_block_kernel<2><<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride,
-                                                   src_tok0, (uint32_t*)c->k_codes, (uint32_t*)c->v_codes,
-                                                   (uint32_t*)c->k_params, (uint32_t*)c->v_params, nbcap,
-                                                   dst_blk0);
+  const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
+  uint32_t *kc = (uint32_t*)c->k_codes, *vc = (uint32_t*)c->v_codes, *kp = (uint32_t*)c->k_params,
+           *vp = (uint32_t*)c->v_params;
+  switch (c->format) {
+    case BD_FMT_INT4:
+      quant_block_kernel<4, false><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
+      break;
+    case BD_FMT_INT2:
+      quant_block_kernel<2, false><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
+      break;
+    case BD_FMT_INT4_KT:
+      quant_block_kernel<4, true><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
+      break;
+    default:
+      quant_block_kernel<2, true><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
+      break;
+  }
   return hipGetLastError();
 }
 
@@ -492,10 +526,13 @@ hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k,
   const int nb = L / kBlock;
   if (nb > 0) {
     dim3 grid(nb, c->n_kv_heads), block(256);
-    if (c->format == BD_FMT_INT4)
-      paged_quant_kernel<4><<<grid, block, 0, st>>>(a, (const uint16_t*)k, (const uint16_t*)v, seq, L);
-    else
-      paged_quant_kernel<2><<<grid, block, 0, st>>>(a, (const uint16_t*)k, (const uint16_t*)v, seq, L);
+    const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
+    switch (c->format) {
+      case BD_FMT_INT4: paged_quant_kernel<4, false><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2: paged_quant_kernel<2, false><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4_KT: paged_quant_kernel<4, true><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      default: paged_quant_kernel<2, true><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -506,10 +543,13 @@ hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k,
 hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, hipStream_t st) {
   const PagedArgs a = paged_args(c);
   dim3 grid(c->n_kv_heads, c->batch), block(256);
-  if (c->format == BD_FMT_INT4)
-    paged_append_kernel<4><<<grid, block, 0, st>>>(a, (const uint16_t*)k_new, (const uint16_t*)v_new);
-  else
-    paged_append_kernel<2><<<grid, block, 0, st>>>(a, (const uint16_t*)k_new, (const uint16_t*)v_new);
+  const uint16_t *kk = (const uint16_t*)k_new, *vv = (const uint16_t*)v_new;
+  switch (c->format) {
+    case BD_FMT_INT4: paged_append_kernel<4, false><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2: paged_append_kernel<2, false><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4_KT: paged_append_kernel<4, true><<<grid, block, 0, st>>>(a, kk, vv); break;
+    default: paged_append_kernel<2, true><<<grid, block, 0, st>>>(a, kk, vv); break;
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch);

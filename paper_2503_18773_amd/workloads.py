@@ -29,7 +29,7 @@ class Workload:
     n_q_heads: int
     n_kv_heads: int
     context: int          # tokens resident before the first decode step
-    fmt: str              # "int4" | "int2" | "mxfp4"
+    fmt: str              # "int4" | "int2" | "mxfp4" | "int4_kt" | "int2_kt" (K per token)
     steps: int            # decode steps the configuration asks for
     seed: int
     outliers: bool        # 1% of (kv_head, channel) pairs scaled by 10 in K and in V

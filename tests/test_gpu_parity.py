@@ -11,13 +11,13 @@ from tests.util import assert_attn_close, out_to_f64, to_dev
 
 pytestmark = pytest.mark.gpu
 
-BITS = {"int4": 4, "int2": 2}
+BITS = {"int4": 4, "int2": 2, "int4_kt": 4, "int2_kt": 2}
 
 
 def _int_cache_pair(w, capacity):
     """Oracle cache and GPU cache prefilled from the same K, V."""
     K, V = W.make_kv(w)
-    oc = O.IntCache(w.batch, w.n_kv_heads, BITS[w.fmt], capacity)
+    oc = O.IntCache(w.batch, w.n_kv_heads, BITS[w.fmt], capacity, k_per_token=w.fmt.endswith("_kt"))
     oc.quant_pack_kv(K, V)
     gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, capacity)
     gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
@@ -572,3 +572,88 @@ def test_paged_with_eight_query_heads_per_kv_head():
     gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, 4)
     torch.cuda.synchronize()
     assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), "paged gq=8", large_outputs=True)
+
+
+# ---------------------------------------------------------------------------- per-token K (KT)
+
+@pytest.mark.parametrize("fmt", ["int4_kt", "int2_kt"])
+@pytest.mark.parametrize("L", [128 * 5 + 37, 128 * 3, 90])
+def test_kt_quant_pack_bit_exact(fmt, L):
+    w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=8, n_kv_heads=2, context=max(L, 1), fmt=fmt, seed=61)
+    K, V, oc, gc = _int_cache_pair(w, 1024)
+    _assert_int_cache_equal(oc, gc)
+
+
+@pytest.mark.parametrize("fmt", ["int4_kt", "int2_kt"])
+@pytest.mark.parametrize("gq", [4, 8])
+def test_kt_decode_and_steps_match_oracle(fmt, gq):
+    """Per-token K: short (one block per wave) and longer contexts, residual tail, fused steps
+    over a flush (bit-exact cache afterwards), several split factors."""
+    import torch
+    H = 2
+    for L, ns in [(128 * 4 + 125, 2), (128 * 37 + 5, 3), (128 * 37 + 5, 1)]:
+        w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=gq * H, n_kv_heads=H, context=L, fmt=fmt, seed=62)
+        K, V, oc, gc = _int_cache_pair(w, (L // 128 + 2) * 128)
+        out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float16, device="cuda:0")
+        q = W.make_q(w)
+        gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=ns)
+        torch.cuda.synchronize()
+        assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} gq={gq} L={L} ns={ns}",
+                          large_outputs=True)
+        for step in range(4):
+            kn, vn = W.make_new_kv(w, step)
+            q = W.make_q(w, step + 1)
+            oc.append_kv(kn, vn)
+            gc.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out,
+                           num_splits=ns)
+            torch.cuda.synchronize()
+            assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)),
+                              f"{fmt} gq={gq} L={L} step {step}", large_outputs=True)
+        _assert_int_cache_equal(oc, gc)
+
+
+def test_kt_full_size_32k_sampled_heads():
+    """cfg1's shape with per-token K: 32K context + residual, all 8 KV heads on the GPU, 3 of them
+    through the oracle."""
+    import torch
+    w = W.scaled(W.CONFIGS["cfg1"], fmt="int4_kt", context=32768 + 77, seed=63)
+    K, V = W.make_kv(w)
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, 32768 + 256)
+    gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+    q = W.make_q(w)
+    out = torch.empty((1, 32, 128), dtype=torch.float16, device="cuda:0")
+    gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out)
+    torch.cuda.synchronize()
+    got = out_to_f64(out)
+    for h in (0, 3, 7):
+        oc = O.IntCache(1, 1, 4, 32768 + 256, k_per_token=True)
+        oc.quant_pack_kv(K[:, h:h + 1], V[:, h:h + 1])
+        ref = O.decode_attn(oc, q[:, 4 * h:4 * h + 4], W.softmax_scale(w))
+        assert_attn_close(got[:, 4 * h:4 * h + 4], ref, f"kt 32K head {h}")
+
+
+def test_paged_kt():
+    import torch
+    lens = [700, 129, 1500]
+    H, Hq = 2, 8
+    rng = np.random.default_rng(3)
+    table = rng.permutation(60)[:3 * 14].reshape(3, 14).astype(np.int32)
+    oc = O.PagedIntCache(3, H, 4, 60, 14, table, k_per_token=True)
+    gc = B.PagedKVCache(3, Hq, H, "int4_kt", 60, table)
+    for b, L in enumerate(lens):
+        w1 = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=Hq, n_kv_heads=H, context=L, seed=70 + b)
+        K, V = W.make_kv(w1)
+        K, V = np.ascontiguousarray(K[0]), np.ascontiguousarray(V[0])
+        oc.quant_pack_kv(b, K, V)
+        gc.quant_pack_kv(b, to_dev(K, "fp16"), to_dev(V, "fp16"))
+    w = W.scaled(W.CONFIGS["cfg1"], batch=3, n_q_heads=Hq, n_kv_heads=H, context=128, seed=75)
+    for step in range(130):        # every sequence crosses a flush
+        kn, vn = W.make_new_kv(w, step)
+        oc.append_kv(kn, vn)
+        gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+    _assert_paged_equal(oc, gc, "paged kt")
+    out = torch.empty((3, Hq, 128), dtype=torch.float16, device="cuda:0")
+    q = W.make_q(w)
+    gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, 3)
+    torch.cuda.synchronize()
+    assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), "paged kt", large_outputs=True)
