@@ -742,23 +742,26 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
 }
 
 // Log-sum-exp merge of the split partials into the final output rows (fp16 or bf16).
-// One workgroup per output row: 128 channels x 2 interleaved halves of the partials.  A single
-// pass with a running maximum, so that every load is independent of every other and they
-// can all be in flight at once (the kernel is pure latency: a few hundred KB in total).
+// One workgroup per output row: 128 channels x kGroups interleaved groups of partials.  The
+// kernel is pure latency (a few hundred KB in total), so every thread issues all its loads at
+// once -- up to kBatch partials per round, one round for up to kGroups * kBatch partials -- and
+// merges them with a running maximum; the groups meet in LDS.
+constexpr int kCombineGroups = 8, kCombineBatch = 8;
 template <bool BF16>
-__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ part_o,
-                                                       const float* __restrict__ part_ml, int nparts, int nrows,
-                                                       uint16_t* __restrict__ out) {
-  __shared__ float sm[2][128], sl[2][128], so[2][128];
-  const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, half = tid >> 7;
+__global__ __launch_bounds__(128 * kCombineGroups) void combine_kernel(const float* __restrict__ part_o,
+                                                                        const float* __restrict__ part_ml,
+                                                                        int nparts, int nrows,
+                                                                        uint16_t* __restrict__ out) {
+  constexpr int G = kCombineGroups, kBatch = kCombineBatch;
+  __shared__ float sm[G][128], sl[G][128], so[G][128];
+  const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, grp = tid >> 7;
   float M = -INFINITY, L = 0.f, o = 0.f;
-  constexpr int kBatch = 16;   // loads issued together
-  for (int p0 = half; p0 < nparts; p0 += 2 * kBatch) {
+  for (int p0 = grp; p0 < nparts; p0 += G * kBatch) {
     float2 ml[kBatch];
     float ov[kBatch];
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
-      const int p = p0 + 2 * i;
+      const int p = p0 + G * i;
       const size_t r = (size_t)(p < nparts ? p : 0) * nrows + row;
       ml[i] = *reinterpret_cast<const float2*>(part_ml + r * 2);
       ov[i] = part_o[r * kD + c];
@@ -775,19 +778,25 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
       M = Mn;
     }
   }
-  sm[half][c] = M;
-  sl[half][c] = L;
-  so[half][c] = o;
+  sm[grp][c] = M;
+  sl[grp][c] = L;
+  so[grp][c] = o;
   __syncthreads();
   if (tid < 128) {
-    const float M0 = sm[0][c], M1 = sm[1][c];
-    const float Mt = fmaxf(M0, M1);
+    float Mt = sm[0][c];
+#pragma unroll
+    for (int g = 1; g < G; ++g) Mt = fmaxf(Mt, sm[g][c]);
     float res = 0.f;
     if (Mt > -INFINITY) {
-      const float f0 = M0 > -INFINITY ? __builtin_amdgcn_exp2f(M0 - Mt) : 0.f;
-      const float f1 = M1 > -INFINITY ? __builtin_amdgcn_exp2f(M1 - Mt) : 0.f;
-      const float Lt = f0 * sl[0][c] + f1 * sl[1][c];
-      res = Lt > 0.f ? (f0 * so[0][c] + f1 * so[1][c]) / Lt : 0.f;
+      float Lt = 0.f, ot = 0.f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float Mg = sm[g][c];
+        const float f = Mg > -INFINITY ? __builtin_amdgcn_exp2f(Mg - Mt) : 0.f;
+        Lt += f * sl[g][c];
+        ot += f * so[g][c];
+      }
+      res = Lt > 0.f ? ot / Lt : 0.f;
     }
     if (BF16) {
       uint32_t u = __float_as_uint(res);
@@ -898,9 +907,9 @@ hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* p
                           hipStream_t st) {
   const int nrows = c->batch * c->n_q_heads;
   if (c->format == BD_FMT_MXFP4)
-    combine_kernel<true><<<dim3(nrows), dim3(256), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
+    combine_kernel<true><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
   else
-    combine_kernel<false><<<dim3(nrows), dim3(256), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
+    combine_kernel<false><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
   return hipGetLastError();
 }
 
