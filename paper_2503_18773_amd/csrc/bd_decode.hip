@@ -287,22 +287,15 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     vraw[mt] = load_raw<WORDS>(vp + (size_t)(16 * mt + col) * VROW);
   };
   // Loads return in order, so what is needed first is requested first: the queries and this
-  // wave's first residual key row, then the first block.
+  // wave's first residual key rows, then the first block.
   // A group of up to 4 heads: every lane keeps the query slice it rescales per block (head
   // lane / 16, two runs of 4 channels) in registers.  Larger groups go through LDS (q_s).
-  const bool has_res = rt0 + wave < rt1;
   uint32_t qld[HP];
   u2_t qraw0 = {0u, 0u}, qraw1 = {0u, 0u};
-  uint32_t qres_raw[4] = {0u, 0u, 0u, 0u};
   if constexpr (HP == 1) {
     if ((lane >> 4) < gq) {
       qraw0 = *reinterpret_cast<const u2_t*>(qbase + (lane >> 4) * kD + run0);
       qraw1 = *reinterpret_cast<const u2_t*>(qbase + (lane >> 4) * kD + run1);
-    }
-    if (has_res) {
-#pragma unroll
-      for (int h = 0; h < 4; ++h)
-        if (h < gq) qres_raw[h] = *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane);
     }
   } else {
 #pragma unroll
@@ -314,8 +307,26 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
   const uint16_t* kres = a.k_res + unit * kBlock * kD;
   // row t of the residual keys: the newest token of a fused step is read from where the caller left it
   auto kres_row = [&](int t) { return t == a.new_slot ? a.k_new + unit * kD : kres + (size_t)t * kD; };
-  uint32_t kres_raw = 0u;
-  if (has_res) kres_raw = *reinterpret_cast<const uint32_t*>(kres_row(rt0 + wave) + 2 * lane);
+  // The residual tokens are scored 16 at a time on the matrix unit: S[token, head] with the fp16
+  // key rows as A and the fp16 queries as B, four k-steps of 32 channels.  Wave w takes token
+  // groups w, w + 4, ...; the operands of its first group are requested here.
+  const int nres = rt1 - rt0, nres_groups = (nres + 15) >> 4;
+  const bool has_res = wave < nres_groups;
+  h8_t res_a[4], res_q[4];
+  auto load_res_keys = [&](int grp) {
+    const int t = min(rt0 + 16 * grp + col, rt1 - 1);   // rows past the slice repeat its last token
+    const uint16_t* row = kres_row(t) + 8 * g;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) res_a[j] = *reinterpret_cast<const h8_t*>(row + 32 * j);
+  };
+  if (has_res) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const h8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      res_q[j] = col < gq ? *reinterpret_cast<const h8_t*>(qbase + col * kD + 32 * j + 8 * g) : zero;
+    }
+    load_res_keys(wave);
+  }
   if (a.new_slot >= 0 && split == 0 && tid < 32) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
@@ -352,6 +363,17 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     for (int T = 0; T < 8; ++T) issue_ktile(bi, T);
   }
 
+  // The first residual value rows this workgroup folds in at the very end: requested now, so
+  // that the final merge does not wait on memory (thread tid: channels 2*(tid%64), +1).
+  constexpr int kResPre = 2;
+  auto vres_row = [&](int t) {
+    return t == a.new_slot ? a.v_new + unit * kD : a.v_res + (unit * kBlock + t) * kD;
+  };
+  uint32_t vres_pre[kResPre];
+#pragma unroll
+  for (int i = 0; i < kResPre; ++i)
+    vres_pre[i] = i < nres ? *reinterpret_cast<const uint32_t*>(vres_row(rt0 + i) + 2 * lane) : 0u;
+
   // ---- larger groups: the queries, scaled, for everybody in the workgroup
   if constexpr (HP > 1) {
 #pragma unroll
@@ -363,24 +385,17 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     __syncthreads();
   }
 
-  // ---- residual slice, part 1: scores s[t][h] = q_h . k_t (wave w takes tokens rt0+w, rt0+w+4, ..)
+  // ---- residual slice, part 1: scores s[t][h] = q_h . k_t * softmax_scale * log2(e)
   if (has_res) {
-    uint32_t raw = kres_raw;
-    for (int t = rt0 + wave; t < rt1; t += kWaves) {
-      const float k0 = h2f((uint16_t)(raw & 0xFFFFu)), k1 = h2f((uint16_t)(raw >> 16));
-      if (t + kWaves < rt1) raw = *reinterpret_cast<const uint32_t*>(kres_row(t + kWaves) + 2 * lane);
+    for (int grp = wave; grp < nres_groups; grp += kWaves) {
+      if (grp != wave) load_res_keys(grp);
+      f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int h = 0; h < GQP; ++h) {
-        float2 qq;
-        if constexpr (HP == 1)
-          qq = make_float2(h2f((uint16_t)(qres_raw[h] & 0xFFFFu)) * a.scale_log2,
-                           h2f((uint16_t)(qres_raw[h] >> 16)) * a.scale_log2);
-        else
-          qq = *reinterpret_cast<const float2*>(&q_s[h][2 * lane]);
-        float x = __builtin_fmaf(qq.x, k0, qq.y * k1);
+      for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(res_a[j], res_q[j], acc, 0, 0, 0);
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
-        if (lane == 0) res_s[t - rt0][h] = x;
+      for (int r = 0; r < 4; ++r) {
+        const int t = 16 * grp + 4 * g + r;   // row 4g + r of the tile
+        if (t < nres && col < GQP) res_s[t][col] = acc[r] * a.scale_log2;
       }
     }
   }
@@ -707,7 +722,6 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       float M = ml.m[0][h];
 #pragma unroll
       for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
-      const int nres = rt1 - rt0;
       for (int t = 0; t < nres; ++t) M = fmaxf(M, res_s[t][h]);
       float L = 0.f, Z = 0.f, o0 = 0.f, o1 = 0.f;
       if (M > -INFINITY) {
@@ -719,16 +733,18 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
           o0 += f * ml.o[w][h][c0];
           o1 += f * ml.o[w][h][c0 + 1];
         }
-        // residual slice, part 2: fold the fp16 tokens in (V rows read straight from memory)
-        const uint16_t* vr = a.v_res + (unit * kBlock + rt0) * kD + c0;
-        for (int t = 0; t < nres; ++t) {
+        // residual slice, part 2: fold the fp16 tokens in (the first rows were requested at the
+        // start of the kernel, any further ones are read here)
+        auto fold = [&](int t, uint32_t raw) {
           const float p = __builtin_amdgcn_exp2f(res_s[t][h] - M);
-          const uint16_t* vrow = rt0 + t == a.new_slot ? a.v_new + unit * kD + c0 : vr + (size_t)t * kD;
-          const uint32_t raw = *reinterpret_cast<const uint32_t*>(vrow);
           L += p;
           o0 = __builtin_fmaf(p, h2f((uint16_t)(raw & 0xFFFFu)), o0);
           o1 = __builtin_fmaf(p, h2f((uint16_t)(raw >> 16)), o1);
-        }
+        };
+#pragma unroll
+        for (int t = 0; t < kResPre; ++t)
+          if (t < nres) fold(t, vres_pre[t]);
+        for (int t = kResPre; t < nres; ++t) fold(t, *reinterpret_cast<const uint32_t*>(vres_row(rt0 + t) + c0));
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * gq + h;
       float2 o = {o0 + Z, o1 + Z};
