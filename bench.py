@@ -60,6 +60,10 @@ def main() -> int:
                     help="graph: the warm-up steps and the timed steps are each captured into one HIP graph "
                          "(every step distinct) so host launch cost is out of the timed region; eager: plain calls")
     ap.add_argument("--splits", type=int, default=0, help="override the library's split factor")
+    ap.add_argument("--per-step", default="", metavar="FILE",
+                    help="eager mode only: also time every step with its own event pair and write the list "
+                         "(step, packed_len, res_len, microseconds) to FILE; steps that fill the residual block show "
+                         "as spikes (they run the quantize kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="lower bound on the oracle's timed CPU work")
     ap.add_argument("--calib-copy", action="store_true",
@@ -149,11 +153,24 @@ def main() -> int:
         for s in range(args.warmup):
             run_step(s)
         torch.cuda.synchronize()
+        step_events = []
         t0 = time.perf_counter()
         for s in range(args.warmup, total_steps):
+            if args.per_step:
+                ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                ea.record(stream)
             run_step(s)
+            if args.per_step:
+                eb.record(stream)
+                step_events.append((s, caches[0].packed_len, caches[0].res_len, ea, eb))
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        if args.per_step:
+            with open(args.per_step, "w") as f:
+                f.write(f"# {w.name} {w.fmt}: per-step time of {args.layers} layers (bd_decode_step each), num_splits {splits}\n")
+                f.write("# step packed_len res_len(after the step) microseconds\n")
+                for s, pl, rl, ea, eb in step_events:
+                    f.write(f"{s} {pl} {rl} {ea.elapsed_time(eb) * 1e3:.1f}\n")
     elapsed = t1 - t0
     timed_bytes = sum(step_bytes[args.warmup:])
     ms_per_step = elapsed * 1e3 / args.steps
