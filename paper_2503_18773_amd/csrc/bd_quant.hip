@@ -33,11 +33,38 @@ __device__ __forceinline__ void group_params(float mn, float mx, int qmax, float
   packed = (uint32_t)sb | ((uint32_t)float_to_half_bits(zero_f) << 16);
 }
 
-__device__ __forceinline__ uint32_t quant_code(float x, float scale_f, float zero_f, int qmax) {
-  if (scale_f == 0.0f) return 0u;
-  float q = rintf((x - zero_f) / scale_f);
-  q = fminf(fmaxf(q, 0.0f), (float)qmax);
-  return (uint32_t)q;
+// codes[n] = clamp(rint((x[n] - zero) / scale)), the quotient being the IEEE fp32 one, for the N
+// values one thread holds of one row (UNIFORM: one scale / zero for all N; otherwise one per
+// value).  The division is what bounds this kernel, so the quotients are first estimated with
+// the groups' reciprocals (rcp = v_rcp_f32(scale), 1 ulp): estimate and IEEE quotient both lie
+// within 3e-6 of the exact ratio (ratio < 16), so they round to the same integer unless the
+// estimate is within that reach of a tie; only if one of the N is (a few in ten thousand are)
+// are the divisions carried out.
+template <int N, bool UNIFORM>
+__device__ __forceinline__ void quant_codes(const float* x, const float* scale, const float* rcp,
+                                            const float* zero, int qmax, uint32_t* codes) {
+  float q[N];
+  bool near_tie = false;
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    const int i = UNIFORM ? 0 : n;
+    const float est = (x[n] - zero[i]) * rcp[i];
+    q[n] = rintf(est);
+    near_tie |= fabsf(est - q[n]) >= 0.5f - 0x1p-16f;
+  }
+  if (__builtin_expect(near_tie, 0)) {
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+      const int i = UNIFORM ? 0 : n;
+      q[n] = rintf((x[n] - zero[i]) / scale[i]);
+    }
+  }
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    const int i = UNIFORM ? 0 : n;
+    const float c = scale[i] == 0.0f ? 0.0f : fminf(fmaxf(q[n], 0.0f), (float)qmax);   // degenerate group: all codes 0
+    codes[n] = (uint32_t)c;
+  }
 }
 
 // One workgroup quantizes one 128-token block of one (batch, kv_head): K channel-wise
@@ -101,11 +128,13 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
       float ks, kz;
       uint32_t packed;
       group_params(a, b, QMAX, ks, kz, packed);
+      const float kr = __builtin_amdgcn_rcpf(ks);
       const int row = p * RPP + tr;
       if (tc == 0) k_params[dblk * kBlock + row] = packed;
-      uint32_t w = 0;
+      uint32_t codes[CPT], w = 0;
+      quant_codes<CPT, true>(x[p], &ks, &kr, &kz, QMAX, codes);
 #pragma unroll
-      for (int cc = 0; cc < CPT; ++cc) w |= quant_code(x[p][cc], ks, kz, QMAX) << (BITS * cc);
+      for (int cc = 0; cc < CPT; ++cc) w |= codes[cc] << (BITS * cc);
       k_codes[(dblk * kBlock + (size_t)row) * TPR + tc] = w;
     }
   } else {
@@ -134,7 +163,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
     }
   }
   __syncthreads();
-  float ks[CPT], kz[CPT];
+  float ks[CPT], kz[CPT], kr[CPT];
 #pragma unroll
   for (int cc = 0; cc < CPT; ++cc) {
     const int ch = tc * CPT + cc;
@@ -142,13 +171,15 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
     float b = fmaxf(fmaxf(red[1][0][ch], red[1][1][ch]), fmaxf(red[1][2][ch], red[1][3][ch]));
     uint32_t packed;
     group_params(a, b, QMAX, ks[cc], kz[cc], packed);
+    kr[cc] = __builtin_amdgcn_rcpf(ks[cc]);
     if (tr == 0) k_params[dblk * kD + ch] = packed;
   }
 #pragma unroll
   for (int p = 0; p < NP; ++p) {
-    uint32_t w = 0;
+    uint32_t codes[CPT], w = 0;
+    quant_codes<CPT, false>(x[p], ks, kr, kz, QMAX, codes);
 #pragma unroll
-    for (int cc = 0; cc < CPT; ++cc) w |= quant_code(x[p][cc], ks[cc], kz[cc], QMAX) << (BITS * cc);
+    for (int cc = 0; cc < CPT; ++cc) w |= codes[cc] << (BITS * cc);
     k_codes[(dblk * kBlock + (size_t)(p * RPP + tr)) * TPR + tc] = w;
   }
   }  // channel-wise K
@@ -186,11 +217,13 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
     float vs, vz;
     uint32_t packed;
     group_params(a, b, QMAX, vs, vz, packed);
+    const float vr = __builtin_amdgcn_rcpf(vs);
     const int row = p * RPP + tr;
     if (tc == 0) v_params[dblk * kBlock + row] = packed;
+    uint32_t codes[CPT];
+    quant_codes<CPT, true>(x[p], &vs, &vr, &vz, QMAX, codes);
 #pragma unroll
-    for (int cc = 0; cc < CPT; ++cc)
-      tile[row * PITCH + tc * CPT + cc] = (uint8_t)quant_code(x[p][cc], vs, vz, QMAX);
+    for (int cc = 0; cc < CPT; ++cc) tile[row * PITCH + tc * CPT + cc] = (uint8_t)codes[cc];
   }
   __syncthreads();
   // pack along tokens: word w of channel c holds block tokens CPT*w .. CPT*w+CPT-1
