@@ -35,204 +35,243 @@ __device__ __forceinline__ void group_params(float mn, float mx, int qmax, float
 
 // codes[n] = clamp(rint((x[n] - zero) / scale)), the quotient being the IEEE fp32 one, for the N
 // values one thread holds of one row (UNIFORM: one scale / zero for all N; otherwise one per
-// value).  The division is what bounds this kernel, so the quotients are first estimated with
-// the groups' reciprocals (rcp = v_rcp_f32(scale), 1 ulp): estimate and IEEE quotient both lie
-// within 3e-6 of the exact ratio (ratio < 16), so they round to the same integer unless the
-// estimate is within that reach of a tie; only if one of the N is (a few in ten thousand are)
-// are the divisions carried out.
+// value).  Division is what would bound this kernel, so the quotients are first estimated with
+// the groups' reciprocals (rcp = v_rcp_f32(scale), 1 ulp; 0 for a degenerate group): estimate and
+// IEEE quotient both lie within 3e-6 of the exact ratio (ratio < 16 unless the scale is an fp16
+// subnormal, and then the clamp decides), so they round to the same integer unless the estimate
+// is within that reach of a tie; only if one of the N is (a few in ten thousand are) are the
+// divisions carried out.  x >= zero always (zero is the group's minimum), so only the upper
+// clamp can act.
 template <int N, bool UNIFORM>
 __device__ __forceinline__ void quant_codes(const float* x, const float* scale, const float* rcp,
                                             const float* zero, int qmax, uint32_t* codes) {
   float q[N];
-  bool near_tie = false;
+  float worst = 0.0f;   // largest distance of an estimate from its rounded value
 #pragma unroll
   for (int n = 0; n < N; ++n) {
     const int i = UNIFORM ? 0 : n;
     const float est = (x[n] - zero[i]) * rcp[i];
     q[n] = rintf(est);
-    near_tie |= fabsf(est - q[n]) >= 0.5f - 0x1p-16f;
+    worst = fmaxf(worst, fabsf(est - q[n]));
   }
-  if (__builtin_expect(near_tie, 0)) {
+  if (__builtin_expect(worst >= 0.5f - 0x1p-16f, 0)) {
 #pragma unroll
     for (int n = 0; n < N; ++n) {
       const int i = UNIFORM ? 0 : n;
-      q[n] = rintf((x[n] - zero[i]) / scale[i]);
+      q[n] = scale[i] == 0.0f ? 0.0f : rintf((x[n] - zero[i]) / scale[i]);
     }
   }
 #pragma unroll
-  for (int n = 0; n < N; ++n) {
-    const int i = UNIFORM ? 0 : n;
-    const float c = scale[i] == 0.0f ? 0.0f : fminf(fmaxf(q[n], 0.0f), (float)qmax);   // degenerate group: all codes 0
-    codes[n] = (uint32_t)c;
-  }
+  for (int n = 0; n < N; ++n) codes[n] = (uint32_t)fminf(q[n], (float)qmax);
 }
 
-// One workgroup quantizes one 128-token block of one (batch, kv_head): K channel-wise
-// (statistics over the block's tokens), V per token (statistics over the 128 channels).
-// Thread-local min/max first, then wave shuffles, then a small LDS buffer across waves:
-// the reduction ladder of Sec. IV-B(2).
+__device__ __forceinline__ float safe_rcp(float scale_f) {
+  return scale_f == 0.0f ? 0.0f : __builtin_amdgcn_rcpf(scale_f);   // degenerate group: every estimate is 0
+}
+
+__device__ __forceinline__ h2_t as_h2(uint32_t u) { return __builtin_bit_cast(h2_t, u); }
+__device__ __forceinline__ uint32_t as_u32(h2_t h) { return __builtin_bit_cast(uint32_t, h); }
+
+// (minimum, -maximum) of the fp16 pairs in raw[0..NP), as one half2, so that a single packed
+// minimum serves both reductions
+template <int NP>
+__device__ __forceinline__ h2_t min_negmax(const uint32_t* raw) {
+  h2_t lo = as_h2(raw[0]), hi = as_h2(raw[0]);
+#pragma unroll
+  for (int i = 1; i < NP; ++i) {
+    lo = __builtin_elementwise_min(lo, as_h2(raw[i]));
+    hi = __builtin_elementwise_max(hi, as_h2(raw[i]));
+  }
+  const _Float16 mn = lo[0] < lo[1] ? lo[0] : lo[1], mx = hi[0] > hi[1] ? hi[0] : hi[1];
+  return (h2_t){mn, (_Float16)(-mx)};
+}
+
+// Packed minimum over the N consecutive lanes (N = 8, 16 or 32, aligned) that hold one token
+// row; every lane ends up with the result.  DPP inside rows of 16, one shuffle across rows.
+template <int CTRL>
+__device__ __forceinline__ h2_t dpp_h2(h2_t x) {
+  return as_h2((uint32_t)__builtin_amdgcn_update_dpp(0, (int)as_u32(x), CTRL, 0xF, 0xF, true));
+}
+template <int N>
+__device__ __forceinline__ h2_t lanes_min(h2_t m) {
+  m = __builtin_elementwise_min(m, dpp_h2<0xB1>(m));    // quad_perm [1,0,3,2]
+  m = __builtin_elementwise_min(m, dpp_h2<0x4E>(m));    // quad_perm [2,3,0,1]
+  m = __builtin_elementwise_min(m, dpp_h2<0x141>(m));   // row_half_mirror: the other quad of each 8
+  if (N >= 16) m = __builtin_elementwise_min(m, dpp_h2<0x140>(m));   // row_mirror: the other half of the row
+  if (N >= 32) m = __builtin_elementwise_min(m, as_h2(__shfl_xor(as_u32(m), 16)));
+  return m;
+}
+
 // quant_block: the whole workgroup (256 threads) quantizes the 128 token rows at ksrc / vsrc
 // ([128][128] fp16) into packed block `dblk` of the four destination arrays.
 // KT: K statistics per token (over its 128 channels) instead of per channel (Sec. IV-C(1)).
+// A thread holds 64 values of each tensor: for K, 64/CPT tokens x CPT consecutive channels (one
+// K word per token); for V, CPT consecutive tokens x 64/CPT channels (one V word per channel),
+// CPT = codes per word.  Minima and maxima are taken on the fp16 pairs as loaded (packed
+// instructions), across lanes with shuffles and, for channel-wise K, across waves through LDS
+// (the reduction ladder of Sec. IV-B(2)).
 template <int BITS, bool KT>
 __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                                             uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes,
                                             uint32_t* __restrict__ k_params, uint32_t* __restrict__ v_params,
                                             size_t dblk) {
   constexpr int QMAX = (1 << BITS) - 1;
-  constexpr int CPT = 32 / BITS;     // channels per thread == codes per word
-  constexpr int TPR = kD / CPT;      // threads per token row == K words per token
-  constexpr int RPP = 256 / TPR;     // rows per pass
-  constexpr int NP = kBlock / RPP;   // passes
-  constexpr int WPC = kBlock / CPT;  // V words per channel
-  constexpr int PITCH = kD + 4;      // padded byte pitch of the code tile
-
-  __shared__ float red[2][4][kD];
-  __shared__ uint8_t tile[kBlock * PITCH];
-
+  constexpr int CPT = 32 / BITS;     // codes per word
+  __shared__ uint32_t red_lo[4][kD / 2], red_hi[4][kD / 2];   // per wave: packed fp16 minima / maxima of channel pairs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tr = tid / TPR, tc = tid % TPR;
 
-  // ---- K: load, per-channel min/max over the 128 tokens
-  float x[NP][CPT];
+  // ---- K: T token rows x C = CPT channels per thread
   {
-    const uint16_t* src = ksrc;
+    constexpr int C = CPT, T = 64 / CPT, NCG = kD / C;   // int4: 8, 8, 16;  int2: 16, 4, 8
+    const int cg = tid % NCG, tg = tid / NCG;
+    uint32_t raw[T][C / 2];
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const uint16_t* rp = src + (size_t)(p * RPP + tr) * kD + tc * CPT;
+    for (int t = 0; t < T; ++t) {
+      const uint16_t* rp = ksrc + (size_t)(T * tg + t) * kD + C * cg;
 #pragma unroll
-      for (int v = 0; v < CPT / 8; ++v) {
-        u4_t raw = *reinterpret_cast<const u4_t*>(rp + 8 * v);
+      for (int v = 0; v < C / 8; ++v) {
+        const u4_t ld = *reinterpret_cast<const u4_t*>(rp + 8 * v);
+        raw[t][4 * v] = ld[0]; raw[t][4 * v + 1] = ld[1]; raw[t][4 * v + 2] = ld[2]; raw[t][4 * v + 3] = ld[3];
+      }
+    }
+    if constexpr (KT) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          x[p][8 * v + 2 * e] = half_bits_to_float((uint16_t)(raw[e] & 0xFFFFu));
-          x[p][8 * v + 2 * e + 1] = half_bits_to_float((uint16_t)(raw[e] >> 16));
+      for (int t = 0; t < T; ++t) {
+        h2_t m = min_negmax<C / 2>(raw[t]);
+        m = lanes_min<NCG>(m);   // the NCG consecutive lanes of this token row
+        float ks, kz;
+        uint32_t packed;
+        group_params((float)m[0], -(float)m[1], QMAX, ks, kz, packed);
+        const float kr = safe_rcp(ks);
+        const int row = T * tg + t;
+        if (cg == 0) k_params[dblk * kBlock + row] = packed;
+        float x[C];
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) {
+          const h2_t h = as_h2(raw[t][i]);
+          x[2 * i] = (float)h[0];
+          x[2 * i + 1] = (float)h[1];
         }
+        uint32_t codes[C], w = 0;
+        quant_codes<C, true>(x, &ks, &kr, &kz, QMAX, codes);
+#pragma unroll
+        for (int c = 0; c < C; ++c) w |= codes[c] << (BITS * c);
+        k_codes[(dblk * kBlock + (size_t)row) * NCG + cg] = w;
+      }
+    } else {
+      h2_t lo[C / 2], hi[C / 2];
+#pragma unroll
+      for (int i = 0; i < C / 2; ++i) {
+        lo[i] = as_h2(raw[0][i]);
+        hi[i] = as_h2(raw[0][i]);
+#pragma unroll
+        for (int t = 1; t < T; ++t) {
+          lo[i] = __builtin_elementwise_min(lo[i], as_h2(raw[t][i]));
+          hi[i] = __builtin_elementwise_max(hi[i], as_h2(raw[t][i]));
+        }
+        if (NCG == 8) {   // lanes holding the same channels: the other half of the row, then the other rows
+          lo[i] = __builtin_elementwise_min(lo[i], dpp_h2<0x128>(lo[i]));   // row_ror 8
+          hi[i] = __builtin_elementwise_max(hi[i], dpp_h2<0x128>(hi[i]));
+        }
+#pragma unroll
+        for (int off = 16; off < 64; off <<= 1) {
+          lo[i] = __builtin_elementwise_min(lo[i], as_h2(__shfl_xor(as_u32(lo[i]), off)));
+          hi[i] = __builtin_elementwise_max(hi[i], as_h2(__shfl_xor(as_u32(hi[i]), off)));
+        }
+      }
+      if (lane < NCG) {
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) {
+          red_lo[wave][cg * (C / 2) + i] = as_u32(lo[i]);
+          red_hi[wave][cg * (C / 2) + i] = as_u32(hi[i]);
+        }
+      }
+      __syncthreads();
+      float ks[C], kz[C], kr[C];
+#pragma unroll
+      for (int i = 0; i < C / 2; ++i) {
+        const int pi = cg * (C / 2) + i;
+        h2_t a = as_h2(red_lo[0][pi]), b = as_h2(red_hi[0][pi]);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+          a = __builtin_elementwise_min(a, as_h2(red_lo[w][pi]));
+          b = __builtin_elementwise_max(b, as_h2(red_hi[w][pi]));
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          uint32_t packed;
+          group_params((float)a[e], (float)b[e], QMAX, ks[2 * i + e], kz[2 * i + e], packed);
+          kr[2 * i + e] = safe_rcp(ks[2 * i + e]);
+          if (tg == 0) k_params[dblk * kD + C * cg + 2 * i + e] = packed;
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        float x[C];
+#pragma unroll
+        for (int i = 0; i < C / 2; ++i) {
+          const h2_t h = as_h2(raw[t][i]);
+          x[2 * i] = (float)h[0];
+          x[2 * i + 1] = (float)h[1];
+        }
+        uint32_t codes[C], w = 0;
+        quant_codes<C, false>(x, ks, kr, kz, QMAX, codes);
+#pragma unroll
+        for (int c = 0; c < C; ++c) w |= codes[c] << (BITS * c);
+        k_codes[(dblk * kBlock + (size_t)(T * tg + t)) * NCG + cg] = w;
       }
     }
   }
-  if constexpr (KT) {
+
+  // ---- V: T = CPT consecutive tokens x C channels per thread, statistics per token
+  {
+    constexpr int T = CPT, C = 64 / CPT, NCG = kD / C, WPC = kBlock / CPT;   // int4: 8, 8, 16, 16;  int2: 16, 4, 32, 8
+    const int cg = tid % NCG, tg = tid / NCG;
+    uint32_t words[C];
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      float a = x[p][0], b = x[p][0];
+    for (int c = 0; c < C; ++c) words[c] = 0;
 #pragma unroll
-      for (int cc = 1; cc < CPT; ++cc) {
-        a = fminf(a, x[p][cc]);
-        b = fmaxf(b, x[p][cc]);
+    for (int t = 0; t < T; ++t) {
+      const int row = T * tg + t;
+      const uint16_t* rp = vsrc + (size_t)row * kD + C * cg;
+      uint32_t raw[C / 2];
+      if constexpr (C == 8) {
+        const u4_t ld = *reinterpret_cast<const u4_t*>(rp);
+        raw[0] = ld[0]; raw[1] = ld[1]; raw[2] = ld[2]; raw[3] = ld[3];
+      } else {
+        const u2_t ld = *reinterpret_cast<const u2_t*>(rp);
+        raw[0] = ld[0]; raw[1] = ld[1];
       }
-#pragma unroll
-      for (int off = 1; off < TPR; off <<= 1) {  // the TPR consecutive lanes of this token row
-        a = fminf(a, __shfl_xor(a, off));
-        b = fmaxf(b, __shfl_xor(b, off));
-      }
-      float ks, kz;
+      h2_t m = min_negmax<C / 2>(raw);
+      m = lanes_min<NCG>(m);   // the NCG consecutive lanes of this token row
+      float vs, vz;
       uint32_t packed;
-      group_params(a, b, QMAX, ks, kz, packed);
-      const float kr = __builtin_amdgcn_rcpf(ks);
-      const int row = p * RPP + tr;
-      if (tc == 0) k_params[dblk * kBlock + row] = packed;
-      uint32_t codes[CPT], w = 0;
-      quant_codes<CPT, true>(x[p], &ks, &kr, &kz, QMAX, codes);
+      group_params((float)m[0], -(float)m[1], QMAX, vs, vz, packed);
+      const float vr = safe_rcp(vs);
+      if (cg == 0) v_params[dblk * kBlock + row] = packed;
+      float x[C];
 #pragma unroll
-      for (int cc = 0; cc < CPT; ++cc) w |= codes[cc] << (BITS * cc);
-      k_codes[(dblk * kBlock + (size_t)row) * TPR + tc] = w;
-    }
-  } else {
-  float mn[CPT], mx[CPT];
-#pragma unroll
-  for (int cc = 0; cc < CPT; ++cc) {
-    float a = x[0][cc], b = x[0][cc];
-#pragma unroll
-    for (int p = 1; p < NP; ++p) {
-      a = fminf(a, x[p][cc]);
-      b = fmaxf(b, x[p][cc]);
-    }
-#pragma unroll
-    for (int off = TPR; off < 64; off <<= 1) {  // lanes holding the same channels
-      a = fminf(a, __shfl_xor(a, off));
-      b = fmaxf(b, __shfl_xor(b, off));
-    }
-    mn[cc] = a;
-    mx[cc] = b;
-  }
-  if (lane < TPR) {
-#pragma unroll
-    for (int cc = 0; cc < CPT; ++cc) {
-      red[0][wave][tc * CPT + cc] = mn[cc];
-      red[1][wave][tc * CPT + cc] = mx[cc];
-    }
-  }
-  __syncthreads();
-  float ks[CPT], kz[CPT], kr[CPT];
-#pragma unroll
-  for (int cc = 0; cc < CPT; ++cc) {
-    const int ch = tc * CPT + cc;
-    float a = fminf(fminf(red[0][0][ch], red[0][1][ch]), fminf(red[0][2][ch], red[0][3][ch]));
-    float b = fmaxf(fmaxf(red[1][0][ch], red[1][1][ch]), fmaxf(red[1][2][ch], red[1][3][ch]));
-    uint32_t packed;
-    group_params(a, b, QMAX, ks[cc], kz[cc], packed);
-    kr[cc] = __builtin_amdgcn_rcpf(ks[cc]);
-    if (tr == 0) k_params[dblk * kD + ch] = packed;
-  }
-#pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    uint32_t codes[CPT], w = 0;
-    quant_codes<CPT, false>(x[p], ks, kr, kz, QMAX, codes);
-#pragma unroll
-    for (int cc = 0; cc < CPT; ++cc) w |= codes[cc] << (BITS * cc);
-    k_codes[(dblk * kBlock + (size_t)(p * RPP + tr)) * TPR + tc] = w;
-  }
-  }  // channel-wise K
-
-  // ---- V: load, per-token min/max over the 128 channels
-  {
-    const uint16_t* src = vsrc;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const uint16_t* rp = src + (size_t)(p * RPP + tr) * kD + tc * CPT;
-#pragma unroll
-      for (int v = 0; v < CPT / 8; ++v) {
-        u4_t raw = *reinterpret_cast<const u4_t*>(rp + 8 * v);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          x[p][8 * v + 2 * e] = half_bits_to_float((uint16_t)(raw[e] & 0xFFFFu));
-          x[p][8 * v + 2 * e + 1] = half_bits_to_float((uint16_t)(raw[e] >> 16));
-        }
+      for (int i = 0; i < C / 2; ++i) {
+        const h2_t h = as_h2(raw[i]);
+        x[2 * i] = (float)h[0];
+        x[2 * i + 1] = (float)h[1];
       }
+      uint32_t codes[C];
+      quant_codes<C, true>(x, &vs, &vr, &vz, QMAX, codes);
+#pragma unroll
+      for (int c = 0; c < C; ++c) words[c] |= codes[c] << (BITS * t);
     }
-  }
+    // word tg of channel C*cg + c: block tokens CPT*tg .. CPT*tg + CPT - 1.  Through LDS, so that the
+    // block's words leave in address order (a thread's own words are WPC apart).
+    __shared__ uint32_t vw[kD][WPC + 1];
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    float a = x[p][0], b = x[p][0];
+    for (int c = 0; c < C; ++c) vw[C * cg + c][tg] = words[c];
+    __syncthreads();
 #pragma unroll
-    for (int cc = 1; cc < CPT; ++cc) {
-      a = fminf(a, x[p][cc]);
-      b = fmaxf(b, x[p][cc]);
+    for (int k = 0; k < kD * WPC / 256; ++k) {
+      const int idx = tid + 256 * k;
+      v_codes[dblk * (size_t)(kD * WPC) + idx] = vw[idx / WPC][idx % WPC];
     }
-#pragma unroll
-    for (int off = 1; off < TPR; off <<= 1) {  // the TPR consecutive lanes of this token row
-      a = fminf(a, __shfl_xor(a, off));
-      b = fmaxf(b, __shfl_xor(b, off));
-    }
-    float vs, vz;
-    uint32_t packed;
-    group_params(a, b, QMAX, vs, vz, packed);
-    const float vr = __builtin_amdgcn_rcpf(vs);
-    const int row = p * RPP + tr;
-    if (tc == 0) v_params[dblk * kBlock + row] = packed;
-    uint32_t codes[CPT];
-    quant_codes<CPT, true>(x[p], &vs, &vr, &vz, QMAX, codes);
-#pragma unroll
-    for (int cc = 0; cc < CPT; ++cc) tile[row * PITCH + tc * CPT + cc] = (uint8_t)codes[cc];
-  }
-  __syncthreads();
-  // pack along tokens: word w of channel c holds block tokens CPT*w .. CPT*w+CPT-1
-  for (int id = tid; id < kD * WPC; id += 256) {
-    const int ch = id / WPC, w = id % WPC;
-    uint32_t word = 0;
-#pragma unroll
-    for (int n = 0; n < CPT; ++n) word |= (uint32_t)tile[(CPT * w + n) * PITCH + ch] << (BITS * n);
-    v_codes[dblk * (size_t)(kD * WPC) + id] = word;
   }
 }
 
