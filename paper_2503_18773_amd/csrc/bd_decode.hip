@@ -467,15 +467,26 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       if (prep_sg == 0) wl.zq[ph] = KT ? zsum : zsum * kTwoM24;
     }
   };
+  // Groups of up to 4 heads: the high piece of Q' goes to the even column groups and the low piece to
+  // the odd ones, so one MFMA per k-step produces both partial products (added across the column
+  // groups afterwards); larger groups have no columns to spare and run two MFMAs per k-step.
+  constexpr bool kSplitCols = COPIES == 4;
   h8_t bqh[4], bql[4];
+  auto load_bq = [&](int j) {
+    if constexpr (kSplitCols) {
+      bqh[j] = *reinterpret_cast<const h8_t*>(cg & 1 ? &wl.qlo[head][8 * (4 * g + j)] : &wl.qhi[head][8 * (4 * g + j)]);
+    } else {
+      bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
+      bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+    }
+  };
   float zq = 0.0f, qsum = 0.0f;
   if constexpr (KT) {
     prep_queries();
     wave_sync();
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
-      bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+      load_bq(j);
     }
     qsum = wl.zq[head];
   }
@@ -520,8 +531,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
     if constexpr (!KT) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
-        bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+        load_bq(j);
       }
       zq = wl.zq[head];
     }
@@ -543,12 +553,13 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       f4_t s[4];
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) {
-        f4_t acc = {zq, zq, zq, zq};
+        const float z0 = kSplitCols && (cg & 1) ? 0.0f : zq;   // the zero term enters once
+        f4_t acc = {z0, z0, z0, z0};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const h8_t ak = F::dequant(kraw[4 * half + tt].w, j);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bqh[j], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
+          if constexpr (!kSplitCols) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
         }
         s[tt] = acc;
       }
@@ -574,10 +585,13 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
             sc[jj][0][r] = (half == 0 || cg == 1) ? lo : sc[jj][0][r];
             sc[jj][1][r] = (half == 0 || cg == 1) ? hi : sc[jj][1][r];
           }
-      } else {                              // column group cg keeps tile cg of each half
+      } else {                              // column group cg keeps tile cg of each half: its own partial
+                                            // product plus that of the neighbouring column group
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float lo = cg & 1 ? s[1][r] : s[0][r], hi = cg & 1 ? s[3][r] : s[2][r];
+          const float v0 = s[0][r] + dpp_f<kRowShl4>(s[0][r]), v1 = s[1][r] + dpp_f<kRowShr4>(s[1][r]);
+          const float v2 = s[2][r] + dpp_f<kRowShl4>(s[2][r]), v3 = s[3][r] + dpp_f<kRowShr4>(s[3][r]);
+          const float lo = cg & 1 ? v1 : v0, hi = cg & 1 ? v3 : v2;
           sc[0][half][r] = cg & 2 ? hi : lo;
         }
       }
