@@ -467,10 +467,10 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       if (prep_sg == 0) wl.zq[ph] = KT ? zsum : zsum * kTwoM24;
     }
   };
-  // Groups of up to 4 heads: the high piece of Q' goes to the even column groups and the low piece to
+  // Groups of up to 8 heads: the high piece of Q' goes to the even column groups and the low piece to
   // the odd ones, so one MFMA per k-step produces both partial products (added across the column
-  // groups afterwards); larger groups have no columns to spare and run two MFMAs per k-step.
-  constexpr bool kSplitCols = COPIES == 4;
+  // groups afterwards); groups of 9..16 have no columns to spare and run two MFMAs per k-step.
+  constexpr bool kSplitCols = COPIES >= 2;
   h8_t bqh[4], bql[4];
   auto load_bq = [&](int j) {
     if constexpr (kSplitCols) {
@@ -581,7 +581,10 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const float lo = s[F::tile_lo(jj)][r], hi = s[F::tile_hi(jj)][r];
+            // own partial product plus the other column group's (half 0 is kept by group 0, half 1 by group 1)
+            float lo = s[F::tile_lo(jj)][r], hi = s[F::tile_hi(jj)][r];
+            lo += half == 0 ? dpp_f<kRowShl8>(lo) : dpp_f<kRowShr8>(lo);
+            hi += half == 0 ? dpp_f<kRowShl8>(hi) : dpp_f<kRowShr8>(hi);
             sc[jj][0][r] = (half == 0 || cg == 1) ? lo : sc[jj][0][r];
             sc[jj][1][r] = (half == 0 || cg == 1) ? hi : sc[jj][1][r];
           }
