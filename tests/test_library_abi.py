@@ -99,6 +99,9 @@ def test_argument_validation_happens_before_any_launch():
     bad = _desc(n_q_heads=64, format=B.BD_FMT_MXFP4)                   # MXFP4 kernel: groups of 1, 2, 4
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
     assert B.bd_cache_bytes(_desc(n_q_heads=64), 0) > 0                # 8 per KV head is built for int4 / int2
+    bad = _desc(batch=65536)                                           # beyond the launch grid
+    assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
+    assert B.bd_cache_bytes(bad, 0) == 0
     assert L.bd_strerror(-4) == b"cache capacity exceeded"
 
 
@@ -140,3 +143,21 @@ def test_paged_sizes_and_argument_validation():
     assert L.bd_paged_decode_attn(ctypes.byref(c), 16, ctypes.c_float(0.1), 4, 16, None, None) == -1
     c.seq_lens = 4098
     assert L.bd_paged_append_kv(ctypes.byref(c), 16, 16, None) == -3
+
+
+@needs_lib
+def test_split_heuristic_properties():
+    """One resident round of workgroups: splits x units stays near 512, never exceeds the number of
+    4-block quanta, and short contexts get one block per wave at most."""
+    for batch, hkv in [(1, 8), (8, 8), (16, 8), (1, 1), (64, 2)]:
+        c = _desc(batch=batch, n_q_heads=4 * hkv, n_kv_heads=hkv, capacity=1 << 20)
+        prev = 0
+        for L in (128, 512, 4096, 32768, 131072, 1 << 20):
+            s = B.bd_choose_splits(c, L)
+            quanta = (L // 128 + 3) // 4
+            assert 1 <= s <= quanta
+            assert s * batch * hkv <= max(512 + batch * hkv, batch * hkv)
+            assert s >= prev or s * batch * hkv >= 256        # grows with the context until the chip is full
+            prev = s
+    assert B.bd_choose_splits(_desc(), 32768) == 64 and B.bd_choose_splits(_desc(), 131072) == 64
+    assert B.bd_choose_splits(_desc(batch=8), 32768) == 8
