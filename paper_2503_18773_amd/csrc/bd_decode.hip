@@ -678,14 +678,11 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       xacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac, __builtin_bit_cast(h8_t, pb[j]), xacc, 0, 0, 0);
     }
 #pragma unroll
-    for (int mp = 0; mp < 4; ++mp) {
+    for (int j = 0; j < 4; ++j) {   // k-step outermost: consecutive MFMAs go to different accumulators
+      const h8_t bp = __builtin_bit_cast(h8_t, pb[j]);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const h8_t bp = __builtin_bit_cast(h8_t, pb[j]);
-        oacc[2 * mp] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[2 * mp].w, j), bp, oacc[2 * mp], 0, 0, 0);
-        oacc[2 * mp + 1] =
-            __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[2 * mp + 1].w, j), bp, oacc[2 * mp + 1], 0, 0, 0);
-      }
+      for (int mt = 0; mt < 8; ++mt)
+        oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[mt].w, j), bp, oacc[mt], 0, 0, 0);
     }
     if (PAGED && has_next) {
       nblk = first_valid(nblk, next_entry, nbi);
