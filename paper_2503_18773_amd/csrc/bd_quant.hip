@@ -514,6 +514,125 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
   }
 }
 
+// Whole 128-token blocks of an MXFP4 cache (the bulk of a prefill).  256 threads; a thread takes
+// one MX group (32 channels) of a token at a time -- 64 contiguous bytes, neighbouring lanes
+// neighbouring groups, so every load and every K store is fully coalesced -- twice per tensor.
+// The group maximum is taken on the bf16 magnitudes as loaded (packed 16-bit maxima); codes
+// come from v_cvt_scalef32_pk_fp4_f32 (nearest e2m1, ties to the even code, saturating: measured
+// identical to the definition) except that it keeps the sign of values that round to zero,
+// which is cleared afterwards; groups with a very small maximum (shared exponent below -120,
+// where elements can be fp32 subnormals) take the explicit path.  V codes meet their
+// neighbouring token's (one byte = two tokens) by a DPP lane shift and reach their
+// channel-major place through an LDS tile.
+__global__ __launch_bounds__(256) void mx_quant_block_kernel(const uint16_t* __restrict__ ksrc,
+                                                              const uint16_t* __restrict__ vsrc,
+                                                              long src_unit_stride,
+                                                              uint8_t* __restrict__ k_codes,
+                                                              uint8_t* __restrict__ k_scales,
+                                                              uint8_t* __restrict__ v_codes,
+                                                              uint8_t* __restrict__ v_scales, int capacity,
+                                                              int dst_blk0) {
+  constexpr int PITCH = 80;   // bytes per channel row of the tile (64 used; 16-byte aligned rows)
+  __shared__ __attribute__((aligned(16))) uint8_t tile[kD * PITCH];
+  const int unit = blockIdx.y, blk = dst_blk0 + blockIdx.x, tid = threadIdx.x, g = tid & 3;
+  const size_t src_blk = (size_t)unit * src_unit_stride + (size_t)blockIdx.x * kBlock * kD;
+#pragma unroll 1
+  for (int which = 0; which < 2; ++which) {
+    const uint16_t* src = (which == 0 ? ksrc : vsrc) + src_blk;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int tl = (tid >> 2) + 64 * i;   // token inside the block
+      const size_t tok = (size_t)unit * capacity + (size_t)blk * kBlock + tl;
+      const uint16_t* sp = src + (size_t)tl * kD + kMxGroup * g;
+      uint32_t raw[16];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const u4_t ld = *reinterpret_cast<const u4_t*>(sp + 8 * v);
+        raw[4 * v] = ld[0]; raw[4 * v + 1] = ld[1]; raw[4 * v + 2] = ld[2]; raw[4 * v + 3] = ld[3];
+      }
+      typedef unsigned short us2_t __attribute__((ext_vector_type(2)));
+      us2_t m2 = {0, 0};
+#pragma unroll
+      for (int w = 0; w < 16; ++w)
+        m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2_t, raw[w] & 0x7FFF7FFFu));
+      const uint32_t mag = m2[0] > m2[1] ? m2[0] : m2[1];   // bf16 bits of the largest magnitude
+      int e = 0;
+      if (mag != 0) {
+        e = (int)(mag >> 7) - 127 - 2;   // floor(log2 amax) - 2 from the exponent field
+        e = e < -127 ? -127 : e;
+      }
+      uint32_t cw[4] = {0u, 0u, 0u, 0u};   // 32 codes: channel 8w + n of the group at nibble n of cw[w]
+      if (mag != 0) {
+        if (e >= -120) {
+          const float scale = __uint_as_float((uint32_t)(e + 127) << 23);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t c = 0;
+#define BD_CVT_PAIR(b)                                                                                        \
+  c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, __uint_as_float(raw[4 * w + b] << 16),                      \
+                                               __uint_as_float(raw[4 * w + b] & 0xFFFF0000u), scale, b)
+            BD_CVT_PAIR(0);
+            BD_CVT_PAIR(1);
+            BD_CVT_PAIR(2);
+            BD_CVT_PAIR(3);
+#undef BD_CVT_PAIR
+            // a value that rounds to zero is stored as +0: drop the sign of nibbles with no magnitude
+            const uint32_t m = c & 0x77777777u;
+            cw[w] = (((m + 0x77777777u) & c) & 0x88888888u) | m;
+          }
+        } else {
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+              const uint32_t r = raw[4 * w + (n >> 1)];
+              const float x = __uint_as_float((n & 1) ? (r & 0xFFFF0000u) : (r << 16));
+              cw[w] |= e2m1_code(x, e) << (4 * n);
+            }
+        }
+      }
+      if (which == 0) {
+        k_scales[tok * 4 + g] = (uint8_t)(e + 127);
+        u4_t out = {cw[0], cw[1], cw[2], cw[3]};
+        *reinterpret_cast<u4_t*>(k_codes + tok * (kD / 2) + g * 16) = out;
+      } else {
+        v_scales[tok * 4 + g] = (uint8_t)(e + 127);
+        // the next token's codes of the same group sit 4 lanes up
+        uint32_t pw[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) pw[w] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)cw[w], 0x104, 0xF, 0xF, true);
+        if (((tid >> 2) & 1) == 0) {   // even token: byte j = tl / 2 of 32 channel rows
+          const int col = ((tl >> 1) + 16 * g) & 63;   // rows of group g are rotated by 16 g bytes (bank spread)
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t be = (cw[w] & 0x0F0F0F0Fu) | ((pw[w] & 0x0F0F0F0Fu) << 4);          // channels 0, 2, 4, 6
+            const uint32_t bo = ((cw[w] >> 4) & 0x0F0F0F0Fu) | (pw[w] & 0xF0F0F0F0u);          // channels 1, 3, 5, 7
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const int ch = kMxGroup * g + 8 * w + 2 * k;
+              tile[ch * PITCH + col] = (uint8_t)(be >> (8 * k));
+              tile[(ch + 1) * PITCH + col] = (uint8_t)(bo >> (8 * k));
+            }
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // channel-major V codes of the block: 128 rows of 64 bytes, each thread half a row
+  {
+    const int row = tid >> 1, hf = tid & 1, gg = row >> 5;
+    uint8_t* dst = v_codes + (((size_t)unit * (capacity / kBlock) + blk) * kD + row) * 64 + 32 * hf;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int chunk = 2 * hf + c;
+      const u4_t val = *reinterpret_cast<const u4_t*>(&tile[row * PITCH + 16 * ((chunk + gg) & 3)]);
+      *reinterpret_cast<u4_t*>(dst + 16 * c) = val;
+    }
+  }
+}
+
+
 // Decode-step append for MXFP4: one token per (batch, kv_head), thread = channel.  The MX
 // group statistics are wave shuffles over 32 lanes; K bytes pair neighbouring channels, V
 // bytes are updated nibble-wise in the channel-major block layout.
@@ -648,12 +767,26 @@ hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, i
                                                         (uint8_t*)c->v_params, c->capacity, dst_tok0);
     return hipGetLastError();
   }
-  const int first_blk = dst_tok0 / kBlock, last_blk = (dst_tok0 + ntok - 1) / kBlock;
-  dim3 grid(last_blk - first_blk + 1, units), block(128);
-  mx_quant_kernel<<<grid, block, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, src_unit_stride, ntok,
-                                          (uint8_t*)c->k_codes, (uint8_t*)c->k_params, (uint8_t*)c->v_codes,
-                                          (uint8_t*)c->v_params, c->capacity, dst_tok0);
-  return hipGetLastError();
+  const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
+  uint8_t *kc = (uint8_t*)c->k_codes, *kp = (uint8_t*)c->k_params, *vc = (uint8_t*)c->v_codes, *vp = (uint8_t*)c->v_params;
+  // tokens [t0, t1) of the range that do not fill a block go through the general kernel
+  auto partial = [&](int t0, int t1) -> hipError_t {
+    if (t1 <= t0) return hipSuccess;
+    const size_t off = (size_t)(t0 - dst_tok0) * kD;
+    dim3 grid((t1 - 1) / kBlock - t0 / kBlock + 1, units), block(128);
+    mx_quant_kernel<<<grid, block, 0, st>>>(kk + off, vv + off, src_unit_stride, t1 - t0, kc, kp, vc, vp, c->capacity, t0);
+    return hipGetLastError();
+  };
+  const int end = dst_tok0 + ntok;
+  const int full0 = (dst_tok0 + kBlock - 1) / kBlock, full1 = end / kBlock;   // whole blocks [full0, full1)
+  if (full1 <= full0) return partial(dst_tok0, end);
+  hipError_t e = partial(dst_tok0, full0 * kBlock);
+  if (e != hipSuccess) return e;
+  const size_t off = (size_t)(full0 * kBlock - dst_tok0) * kD;
+  mx_quant_block_kernel<<<dim3(full1 - full0, units), dim3(256), 0, st>>>(kk + off, vv + off, src_unit_stride, kc, kp, vc,
+                                                                          vp, c->capacity, full0);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  return partial(full1 * kBlock, end);
 }
 
 }  // namespace bd

@@ -259,6 +259,12 @@ def test_mx_quant_adversarial_bit_exact():
     K[0, 0, 3, :32] = np.array([7.5, 7.0, 6.5, -7.75] + [0.1, -0.0, -0.1, 0.3] * 7, np.float32)        # saturation
     K[0, 0, 4, :32] = W.round_to_bf16(np.full(32, 3.0e38, np.float32)); K[0, 0, 4, 1] = 1.0
     K[0, 0, 5, :32] = W.round_to_bf16(np.full(32, 1.0e-38, np.float32)); K[0, 0, 5, 3] = -3.0e-39
+    # around the switch between the converting instruction and the explicit path (shared exponent -120),
+    # with fp32-subnormal elements next to a normal maximum, and negative values that round to zero
+    K[0, 0, 6, :32] = np.array([2.0 ** -118, -(2.0 ** -118), 2.0 ** -127, -(2.0 ** -130)] * 8, np.float32)
+    K[0, 0, 6, 32:64] = np.array([2.0 ** -119, -(2.0 ** -120), 2.0 ** -126, -(2.0 ** -133)] * 8, np.float32)
+    K[0, 0, 6, 64:96] = np.array([1.0, -0.124, -0.0, -0.2] * 8, np.float32)
+    V[0, 0, 6, :32] = np.array([-(2.0 ** -117), 1.5 * 2.0 ** -119, -(2.0 ** -121), 2.0 ** -128] * 8, np.float32)
     V[0, 0, 7, 32:64] = 0.0
     V[0, 0, 8, 32:64] = np.array([6.0, 5.0, 1.25, -1.75] * 8, np.float32)
     K, V = W.round_to_bf16(K), W.round_to_bf16(V)
