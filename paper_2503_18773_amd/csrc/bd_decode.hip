@@ -208,7 +208,7 @@ constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
 //     so Q' = Q is prepared once per kernel instead of once per block and the per-token scale
 //     and zero are applied to the kept S^T values.
 template <int BITS, int GQP, bool SINGLE, bool PAGED, bool KT>
-__global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   using F = Fmt<BITS>;
   using WL = WaveLds<GQP>;
   using ML = MergeLds<GQP>;
@@ -540,7 +540,9 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
       issue_kpar(nbi);
       issue_vpar(nbi);
     }
-    if (!SINGLE && F::kValuesAtTop) {
+    // groups of 9..16 heads: only once the keys' registers are free, which lets two waves fit a SIMD
+    constexpr bool kValuesAfterQK = GQP == 16;
+    if (!SINGLE && F::kValuesAtTop && !kValuesAfterQK) {
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
     }
@@ -563,7 +565,7 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
         }
         s[tt] = acc;
       }
-      if ((SINGLE || !F::kValuesAtTop) && half == 0) {
+      if ((SINGLE || !F::kValuesAtTop) && half == 0 && !kValuesAfterQK) {
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
       }
@@ -598,6 +600,10 @@ __global__ __launch_bounds__(256) void decode_int_kernel(DecodeArgs a) {
           sc[0][half][r] = cg & 2 ? hi : lo;
         }
       }
+    }
+    if (kValuesAfterQK) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
     }
     if constexpr (KT) {   // per-token scale and zero of K
 #pragma unroll
