@@ -663,3 +663,32 @@ def test_paged_kt():
     gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, 3)
     torch.cuda.synchronize()
     assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), "paged kt", large_outputs=True)
+
+
+def test_offsets_beyond_two_gigabytes():
+    """Forty sequences of 128K tokens: the packed K buffer is 2.7 GB, so byte offsets pass 2^31.  Every
+    sequence holds the same tokens (the batch is one sequence repeated on the device), so every output
+    row group must equal, bit for bit, the result of a one-sequence cache with the same split factor, and
+    so must the last sequence's packed bytes."""
+    import torch
+    w1 = W.scaled(W.CONFIGS["cfg3"], seed=81)
+    K, V = W.make_kv(w1)
+    Kd1, Vd1 = to_dev(K, "fp16"), to_dev(V, "fp16")
+    nb = 40
+    ref_c = B.KVCache(1, 32, 8, "int4", 131072 + 128)
+    ref_c.quant_pack_kv(Kd1, Vd1)
+    big = B.KVCache(nb, 32, 8, "int4", 131072 + 128)
+    assert big.sizes[0] > 2 ** 31
+    big.quant_pack_kv(Kd1.expand(nb, -1, -1, -1).contiguous(), Vd1.expand(nb, -1, -1, -1).contiguous())
+    q1 = to_dev(W.make_q(w1), "fp16")
+    ns = 2
+    o1 = torch.empty((1, 32, 128), dtype=torch.float16, device="cuda:0")
+    ob = torch.empty((nb, 32, 128), dtype=torch.float16, device="cuda:0")
+    ref_c.decode_attn(q1, W.softmax_scale(w1), o1, num_splits=ns)
+    big.decode_attn(q1.expand(nb, -1, -1).contiguous(), W.softmax_scale(w1), ob, num_splits=ns)
+    torch.cuda.synchronize()
+    assert torch.equal(ob.view(torch.int16), o1.view(torch.int16).expand(nb, -1, -1))
+    per_seq = ref_c.sizes[0]
+    assert torch.equal(big.buffers[0][(nb - 1) * per_seq: nb * per_seq], ref_c.buffers[0][:per_seq])
+    per_seq = ref_c.sizes[1]
+    assert torch.equal(big.buffers[1][(nb - 1) * per_seq: nb * per_seq], ref_c.buffers[1][:per_seq])
