@@ -6,7 +6,7 @@ bd_decode_step (= bd_append_kv + bd_decode_attn with split-K combine) on its own
 independent cache, back to back on one stream.  Thirty-two distinct caches keep the working set (> 1 GB) far above the
 256 MB last-level cache, so every step streams its KV bytes from HBM.
 
-Prints ONE JSON line (see README for the fields).  value = effective KV GB/s:
+Prints ONE JSON line.  value = effective KV GB/s:
 algorithmic bytes of the attention calls of a step / wall time of the step.
 """
 from __future__ import annotations
@@ -71,7 +71,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (the path shards by batch / KV head / "
-              "context, see DESIGN.md, but no multi-GPU code exists)", file=sys.stderr)
+              "context, but no multi-GPU code exists)", file=sys.stderr)
         return 2
 
     import torch
