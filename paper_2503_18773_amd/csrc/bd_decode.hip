@@ -97,7 +97,6 @@ template <>
 struct Fmt<4> {
   static constexpr int WORDS = 4;
   static constexpr float kQmax = 15.0f;
-  static constexpr bool kValuesAtTop = false;
   // first channel of run `run` (0/1) of slot group sg: word sg, nibbles 0..3 / 4..7
   __device__ static int run_base(int sg, int run) { return 8 * sg + 4 * run; }
   __device__ static constexpr float un(int v) { return (v & 1) ? (1.0f / 16.0f) : 1.0f; }
@@ -131,7 +130,6 @@ template <>
 struct Fmt<2> {
   static constexpr int WORDS = 2;
   static constexpr float kQmax = 3.0f;
-  static constexpr bool kValuesAtTop = true;
   // slot group sg = 2*W + jj: word W, crumbs 4*jj + 0..3 (run 0) and 8 + 4*jj + 0..3 (run 1)
   __device__ static int run_base(int sg, int run) { return 16 * (sg >> 1) + 4 * (sg & 1) + 8 * run; }
   __device__ static constexpr float un(int v) { return 1.0f / (float)(1 << (2 * v)); }
@@ -334,8 +332,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
   // (Where exactly the values are requested is fixed at compile time, so that the compiler knows
-  // how many loads are in flight behind the one it waits for: half way through QK^T for int4,
-  // at the top of the block for int2, whichever measured faster.)
+  // how many loads are in flight behind the one it waits for: half way through QK^T.)
   const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
   // Paged: table entry of block n (-1 past the end of the row), and the first block at or after
   // n, in this wave's stride, whose entry names a page of the pool; entries that do not are
@@ -542,10 +539,6 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     }
     // groups of 9..16 heads: only once the keys' registers are free, which lets two waves fit a SIMD
     constexpr bool kValuesAfterQK = GQP == 16;
-    if (!SINGLE && F::kValuesAtTop && !kValuesAfterQK) {
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
-    }
 
     // ---- S^T tiles (rows = tokens 32*(row/4) + 4T + row%4, all 16 columns valid); each lane
     //      keeps the tiles of the k-steps its column group owns: sc[o][low/high half][row]
@@ -565,7 +558,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
         }
         s[tt] = acc;
       }
-      if ((SINGLE || !F::kValuesAtTop) && half == 0 && !kValuesAfterQK) {
+      if (half == 0 && !kValuesAfterQK) {
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) issue_vtile(bi, mt);
       }
