@@ -548,8 +548,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       f4_t s[4];
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) {
-        const float z0 = kSplitCols && (cg & 1) ? 0.0f : zq;   // the zero term enters once
-        f4_t acc = {z0, z0, z0, z0};
+        f4_t acc = {0.f, 0.f, 0.f, 0.f};   // (the zero term, one number per head, joins in the softmax)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const h8_t ak = F::dequant(kraw[4 * half + tt].w, j);
@@ -619,7 +618,9 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[o][lh][r]);
     bmax = head_max<COPIES>(bmax);
-    const float m_new = fmaxf(m_run, bmax * kS);
+    // channel-wise K: every score of the head still lacks the block's zero term zq (times kS)
+    const float m_new = fmaxf(m_run, (bmax + zq) * kS);
+    const float zoff = __builtin_fmaf(zq, kS, -m_new);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
     l_run *= alpha;
@@ -635,7 +636,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       for (int half = 0; half < 2; ++half)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kS, -m_new));
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kS, zoff));
           const float2 par = wl.vpar[tb[0][half] + r];
           l_run += p;
           z_run = __builtin_fmaf(p, par.y, z_run);
@@ -654,7 +655,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
           uint32_t hv[2];
 #pragma unroll
           for (int lh = 0; lh < 2; ++lh) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kS, -m_new));
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kS, zoff));
             const float2 par = wl.vpar[tb[o][lh] + r];
             l_run += p;
             z_run = __builtin_fmaf(p, par.y, z_run);
