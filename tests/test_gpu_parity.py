@@ -692,3 +692,36 @@ def test_offsets_beyond_two_gigabytes():
     assert torch.equal(big.buffers[0][(nb - 1) * per_seq: nb * per_seq], ref_c.buffers[0][:per_seq])
     per_seq = ref_c.sizes[1]
     assert torch.equal(big.buffers[1][(nb - 1) * per_seq: nb * per_seq], ref_c.buffers[1][:per_seq])
+
+
+def test_seeded_shape_sweep():
+    """Forty seeded random shapes (format, heads per group, batch, KV heads, length, split factor,
+    fused or separate step): packed bytes bit-exact, outputs within tolerance."""
+    import torch
+    rng = np.random.default_rng(2024)
+    fmts = ["int4", "int2", "int4_kt", "int2_kt"]
+    for case in range(40):
+        fmt = fmts[int(rng.integers(4))]
+        gq = int(rng.integers(1, 17))
+        H = int(rng.integers(1, 4))
+        Bn = int(rng.integers(1, 4))
+        L = int(rng.integers(1, 128 * 24))
+        ns = int(rng.integers(1, 12))
+        w = W.scaled(W.CONFIGS["cfg1"], batch=Bn, n_q_heads=gq * H, n_kv_heads=H, context=L, fmt=fmt, seed=1000 + case)
+        K, V, oc, gc = _int_cache_pair(w, (L // 128 + 2) * 128)
+        _assert_int_cache_equal(oc, gc)
+        out = torch.empty((Bn, gq * H, 128), dtype=torch.float16, device="cuda:0")
+        what = f"case {case}: {fmt} gq={gq} H={H} B={Bn} L={L} ns={ns}"
+        for step in range(2):
+            kn, vn = W.make_new_kv(w, step)
+            q = W.make_q(w, step)
+            oc.append_kv(kn, vn)
+            if (case + step) % 2:
+                gc.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out,
+                               num_splits=ns)
+            else:
+                gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+                gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=ns, fused=bool(case % 3))
+            torch.cuda.synchronize()
+            assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), what, large_outputs=True)
+        _assert_int_cache_equal(oc, gc)
