@@ -156,8 +156,12 @@ def test_split_heuristic_properties():
             s = B.bd_choose_splits(c, L)
             quanta = (L // 128 + 3) // 4
             assert 1 <= s <= quanta
-            assert s * batch * hkv <= max(512 + batch * hkv, batch * hkv)
+            assert s * batch * hkv <= max(768, batch * hkv)
             assert s >= prev or s * batch * hkv >= 256        # grows with the context until the chip is full
             prev = s
     assert B.bd_choose_splits(_desc(), 32768) == 64 and B.bd_choose_splits(_desc(), 131072) == 64
     assert B.bd_choose_splits(_desc(batch=8), 32768) == 8
+    # one block per wave is kept up to three workgroups per compute unit (integer formats, groups <= 8)
+    assert B.bd_choose_splits(_desc(), 40960) == 80 and B.bd_choose_splits(_desc(), 49152) == 96
+    assert B.bd_choose_splits(_desc(), 57344) == 56
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_MXFP4), 49152) == 48
