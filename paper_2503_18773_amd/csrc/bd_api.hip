@@ -20,10 +20,10 @@ bd_status check_shape(const bd_cache* c) {
   if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
   if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;
   // query heads per KV head: the int4 / int2 kernels pad the group to 4, 8 or 16 MFMA columns;
-  // the MXFP4 kernel is built for groups of 1, 2 and 4
+  // the MXFP4 kernel takes them 4 at a time
   const int gq = c->n_q_heads / c->n_kv_heads;
   if (gq > 16) return BD_ERR_UNSUPPORTED;
-  if (c->format == BD_FMT_MXFP4 && gq != 1 && gq != 2 && gq != 4) return BD_ERR_UNSUPPORTED;
+  if (c->format == BD_FMT_MXFP4 && (long)c->n_kv_heads * ((gq + 3) / 4) > 65535) return BD_ERR_UNSUPPORTED;
   return BD_OK;
 }
 

@@ -52,11 +52,17 @@ __device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(
 
 __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
   __shared__ MergeLdsMx ml;
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  // Groups of more than 4 query heads run as ceil(g_q / 4) workgroups per (split, KV head), each
+  // with 4 of the heads: the same keys and values are read once per workgroup (they sit next to
+  // each other in the launch order, so the repeats mostly hit in cache), which is simple rather
+  // than fast.
+  const int ngrp = (a.gq + 3) >> 2;
+  const int split = blockIdx.x, hkv = blockIdx.y / ngrp, hg = blockIdx.y % ngrp, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;
   const int head = col & 3, cg = col >> 2;
-  const int gq = a.gq;
+  const int gq = min(4, a.gq - 4 * hg);   // heads of this workgroup's sub-group
+  const int head0 = hkv * a.gq + 4 * hg;  // its first query head
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   const int nb = (a.length + kBlock - 1) / kBlock;
   const int blk0 = (int)(((long)nb * split) / a.num_splits);
@@ -104,7 +110,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
     float x[32];
     u4_t raw[4] = {};
     if (head < gq) {
-      const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + hkv * gq + head) * kD + 16 * g;
+      const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + head0 + head) * kD + 16 * g;
       raw[0] = *reinterpret_cast<const u4_t*>(qp);
       raw[1] = *reinterpret_cast<const u4_t*>(qp + 8);
       raw[2] = *reinterpret_cast<const u4_t*>(qp + 64);
@@ -273,7 +279,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
           o1 += f * ml.o[w][h][c0 + 1];
         }
       }
-      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * gq + h;
+      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + head0 + h;
       float2 o = {o0, o1};
       *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
       if ((tid & 63) == 0) {
@@ -303,7 +309,7 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
   a.capacity = c->capacity;
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
-  dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
+  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 3) / 4), c->batch), block(256);
   decode_mx_kernel<<<grid, block, 0, st>>>(a);
   return hipGetLastError();
 }

@@ -321,7 +321,7 @@ def _mx_decode_check(gc, oc_ref, w, q, ns, what):
     return ma, rl
 
 
-@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4)])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2), (12, 1), (5, 1)])
 @pytest.mark.parametrize("L", [128 * 9 + 37, 128 * 4, 77])
 def test_mx_decode_matches_oracle(hq, hkv, L):
     w = W.scaled(W.CONFIGS["cfg4"], batch=2, n_q_heads=hq, n_kv_heads=hkv, context=L)

@@ -96,8 +96,6 @@ def test_argument_validation_happens_before_any_launch():
     # shapes this build has no kernel for
     bad = _desc(n_q_heads=8 * 17)                                      # 17 query heads per KV head
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
-    bad = _desc(n_q_heads=64, format=B.BD_FMT_MXFP4)                   # MXFP4 kernel: groups of 1, 2, 4
-    assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
     assert B.bd_cache_bytes(_desc(n_q_heads=64), 0) > 0                # 8 per KV head is built for int4 / int2
     bad = _desc(batch=65536)                                           # beyond the launch grid
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
