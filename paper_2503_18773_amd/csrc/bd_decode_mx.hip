@@ -43,26 +43,30 @@ struct MxArgs {
   float scale_log2;
 };
 
+template <int NG>
 struct MergeLdsMx {
-  float o[kWaves][4][kD];
-  float m[kWaves][4], l[kWaves][4];
+  float o[kWaves][4 * NG][kD];
+  float m[kWaves][4 * NG], l[kWaves][4 * NG];
 };
 
 __device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-__global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
-  __shared__ MergeLdsMx ml;
-  // Groups of more than 4 query heads run as ceil(g_q / 4) workgroups per (split, KV head), each
-  // with 4 of the heads: the same keys and values are read once per workgroup (they sit next to
-  // each other in the launch order, so the repeats mostly hit in cache), which is simple rather
-  // than fast.
-  const int ngrp = (a.gq + 3) >> 2;
-  const int split = blockIdx.x, hkv = blockIdx.y / ngrp, hg = blockIdx.y % ngrp, b = blockIdx.z;
+// The query group is taken four heads at a time ("sub-groups").  NG = sub-groups one workgroup runs
+// over the same loaded keys and values (1, or 2 for groups of more than 4 heads, at one wave per
+// SIMD: the second set of operands and accumulators does not fit two); groups of more than 8 heads take
+// ceil(g_q / 8) workgroups per (split, KV head), which read the cache once each.
+template <int NG>
+__global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs a) {
+  __shared__ MergeLdsMx<NG> ml;
+  const int nsub = (a.gq + 3) >> 2;              // sub-groups of the query group
+  const int nwg = (nsub + NG - 1) / NG;          // workgroups per (split, KV head)
+  const int split = blockIdx.x, hkv = blockIdx.y / nwg, sub0 = NG * (blockIdx.y % nwg), b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;
   const int head = col & 3, cg = col >> 2;
-  const int gq = min(4, a.gq - 4 * hg);   // heads of this workgroup's sub-group
-  const int head0 = hkv * a.gq + 4 * hg;  // its first query head
+  const int head0 = hkv * a.gq + 4 * sub0;       // first query head of this workgroup
+  // heads of sub-group gi of this workgroup (0 past the end of the group)
+  auto sub_heads = [&](int gi) { return max(0, min(4, a.gq - 4 * (sub0 + gi))); };
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   const int nb = (a.length + kBlock - 1) / kBlock;
   const int blk0 = (int)(((long)nb * split) / a.num_splits);
@@ -70,8 +74,8 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
   const int nbcap = a.capacity / kBlock;
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
 
-  i8_t bhi, blo;          // Q[head][32g .. 32g+31] as two fp8 (e4m3) pieces
-  int sb_hi, sb_lo;       // their e8m0 block scales
+  i8_t bhi[NG], blo[NG];      // Q[head][32g .. 32g+31] as two fp8 (e4m3) pieces, per sub-group
+  int sb_hi[NG], sb_lo[NG];   // their e8m0 block scales
   u4_t kraw[8], vraw[8];
   uint32_t ksc[8];
   u4_t vsc[2];
@@ -106,11 +110,12 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
   // 16g .. 16g+15 in bytes 0..15 and 64+16g .. 64+16g+15 in bytes 16..31, while the 4-bit
   // side holds 32g .. 32g+31 per lane.  One block scale per head (all 128 channels) is used
   // for B, so its value does not depend on which lane the instruction reads it from.
-  {
+#pragma unroll
+  for (int gi = 0; gi < NG; ++gi) {
     float x[32];
     u4_t raw[4] = {};
-    if (head < gq) {
-      const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + head0 + head) * kD + 16 * g;
+    if (head < sub_heads(gi)) {
+      const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + head0 + 4 * gi + head) * kD + 16 * g;
       raw[0] = *reinterpret_cast<const u4_t*>(qp);
       raw[1] = *reinterpret_cast<const u4_t*>(qp + 8);
       raw[2] = *reinterpret_cast<const u4_t*>(qp + 64);
@@ -127,8 +132,8 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
     int eb = 0;
     if (amax > 0.0f) eb = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 127 - 7;   // amax * 2^-eb in [128, 256)
     eb = min(max(eb, -123), 127);
-    sb_hi = eb + 127;
-    sb_lo = eb - 4 + 127;
+    sb_hi[gi] = eb + 127;
+    sb_lo[gi] = eb - 4 + 127;
 #pragma unroll
     for (int v = 0; v < 8; ++v) {
       int hi = 0, lo = 0;
@@ -146,19 +151,26 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
       rem[3] = (rem[3] - __builtin_amdgcn_cvt_f32_fp8(hi, 3)) * 16.0f;
       lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[0], rem[1], lo, false);
       lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[2], rem[3], lo, true);
-      bhi[v] = hi;
-      blo[v] = lo;
+      bhi[gi][v] = hi;
+      blo[gi][v] = lo;
     }
   }
 
-  float m_run = -INFINITY, l_run = 0.0f;
-  f4_t oacc[8];
+  float m_run[NG], l_run[NG];
+  f4_t oacc[NG][8];
 #pragma unroll
-  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+  for (int gi = 0; gi < NG; ++gi) {
+    m_run[gi] = -INFINITY;
+    l_run[gi] = 0.0f;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) oacc[gi][mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+  }
 
   while (blk < blk1) {
     const int nblk = blk + kWaves;
     issue_v(blk);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {   // the sub-groups in turn, over the same loaded block
     // ---- S^T tiles straight from the packed codes; column group cg keeps tiles cg and 4+cg
     float s[2][4];
 #pragma unroll
@@ -170,8 +182,8 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
         const i8_t ak = {(int)kraw[T][0], (int)kraw[T][1], (int)kraw[T][2], (int)kraw[T][3], 0, 0, 0, 0};
         const int sa = (int)((ksc[T] >> (8 * g)) & 0xFFu);
         f4_t acc = {0.f, 0.f, 0.f, 0.f};
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, bhi, acc, 4, 0, 0, sa, 0, sb_hi);
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, blo, acc, 4, 0, 0, sa, 0, sb_lo);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, bhi[gi], acc, 4, 0, 0, sa, 0, sb_hi[gi]);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, blo[gi], acc, 4, 0, 0, sa, 0, sb_lo[gi]);
         st[tt] = acc;
       }
 #pragma unroll
@@ -185,13 +197,13 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
     float bmax = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                        fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
     bmax = head_max<4>(bmax);
-    const float m_new = fmaxf(m_run, bmax);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    l_run *= alpha;
+    const float m_new = fmaxf(m_run[gi], bmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run[gi] - m_new);
+    m_run[gi] = m_new;
+    l_run[gi] *= alpha;
     if (__any(alpha != 1.0f)) {
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+      for (int mt = 0; mt < 8; ++mt) oacc[gi][mt] *= alpha;
     }
     float p[2][4];
 #pragma unroll
@@ -199,7 +211,7 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         p[half][r] = __builtin_amdgcn_exp2f(s[half][r] - m_new);
-        l_run += p[half][r];
+        l_run[gi] += p[half][r];
       }
     // ---- O^T += V^T P'_cb for the four 32-channel blocks cb (M tiles 2cb, 2cb+1)
 #pragma unroll
@@ -242,30 +254,35 @@ __global__ __launch_bounds__(256) void decode_mx_kernel(MxArgs a) {
           h2_t c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2);
           h2_t c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3);
           const h8_t av = {c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
-          oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[mt], 0, 0, 0);
+          oacc[gi][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[gi][mt], 0, 0, 0);
         }
       }
     }
+    }   // sub-groups
     if (nblk < blk1) issue_k(nblk);
     blk = nblk;
   }
 
   // ---- merge the waves of the workgroup
-  l_run = head_sum<4>(l_run);
-  if (col < 4) {
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
+  for (int gi = 0; gi < NG; ++gi) {
+    l_run[gi] = head_sum<4>(l_run[gi]);
+    if (col < 4) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
-    if (g == 0) {
-      ml.m[wave][col] = m_run;
-      ml.l[wave][col] = l_run;
+      for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ml.o[wave][4 * gi + col][16 * mt + 4 * g + r] = oacc[gi][mt][r];
+      if (g == 0) {
+        ml.m[wave][4 * gi + col] = m_run[gi];
+        ml.l[wave][4 * gi + col] = l_run[gi];
+      }
     }
   }
   __syncthreads();
-  {
-    const int h = tid >> 6, c0 = 2 * (tid & 63);
-    if (h < gq) {
+#pragma unroll
+  for (int gi = 0; gi < NG; ++gi) {
+    const int h = 4 * gi + (tid >> 6), c0 = 2 * (tid & 63);
+    if ((tid >> 6) < sub_heads(gi)) {
       float M = ml.m[0][h];
 #pragma unroll
       for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
@@ -309,8 +326,12 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
   a.capacity = c->capacity;
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
-  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 3) / 4), c->batch), block(256);
-  decode_mx_kernel<<<grid, block, 0, st>>>(a);
+  const int nsub = (a.gq + 3) / 4;
+  dim3 block(256);
+  if (nsub == 1)
+    decode_mx_kernel<1><<<dim3(num_splits, c->n_kv_heads, c->batch), block, 0, st>>>(a);
+  else
+    decode_mx_kernel<2><<<dim3(num_splits, c->n_kv_heads * ((nsub + 1) / 2), c->batch), block, 0, st>>>(a);
   return hipGetLastError();
 }
 
