@@ -425,6 +425,75 @@ class MxCache:
         return Kh, Vh
 
 
+class PagedMxCache:
+    """MXFP4 in the page-managed setting (same reading as PagedIntCache: a page is a 128-token
+    block, block n of sequence b is page block_table[b, n], lengths per sequence).  Inside a
+    page every array has the bytes the contiguous MxCache holds for that block:
+
+      k_codes  uint8 [P, H, 128 tokens, D/2]     k_scales uint8 [P, H, 128, D/32]
+      v_codes  uint8 [P, H, D channels, 64]      v_scales uint8 [P, H, 128, D/32]
+    """
+
+    def __init__(self, batch: int, n_kv_heads: int, num_pages: int, max_pages: int, block_table: np.ndarray,
+                 head_dim: int = 128):
+        assert head_dim == 128 and block_table.shape == (batch, max_pages)
+        self.B, self.H, self.D, self.P, self.max_pages = batch, n_kv_heads, head_dim, num_pages, max_pages
+        self.k_codes = np.zeros((num_pages, n_kv_heads, BLOCK, head_dim // 2), np.uint8)
+        self.k_scales = np.full((num_pages, n_kv_heads, BLOCK, head_dim // MX_GROUP), 127, np.uint8)
+        self.v_codes = np.zeros((num_pages, n_kv_heads, head_dim, BLOCK // 2), np.uint8)
+        self.v_scales = np.full((num_pages, n_kv_heads, BLOCK, head_dim // MX_GROUP), 127, np.uint8)
+        self.block_table = block_table.astype(np.int32).copy()
+        self.seq_lens = np.zeros(batch, np.int32)
+
+    def _page_of(self, b: int, n: int) -> int:
+        if n >= self.max_pages:
+            raise OverflowError("block table row is full")
+        p = int(self.block_table[b, n])
+        if not 0 <= p < self.P:
+            raise IndexError("block table entry outside the pool")
+        return p
+
+    def _store_token(self, b: int, t: int, k: np.ndarray, v: np.ndarray):
+        """Token t of sequence b from k, v [H, D] (bf16 values in float32)."""
+        p, i = self._page_of(b, t // BLOCK), t % BLOCK
+        kc, ks = mx_quantize(k)
+        vc, vs = mx_quantize(v)
+        self.k_codes[p, :, i] = pack_nibbles(kc)
+        self.k_scales[p, :, i] = ks
+        self.v_scales[p, :, i] = vs
+        row = self.v_codes[p, :, :, i // 2]
+        if i % 2 == 0:
+            row[...] = (row & np.uint8(0xF0)) | vc
+        else:
+            row[...] = (row & np.uint8(0x0F)) | (vc << np.uint8(4))
+
+    def quant_pack_kv(self, b: int, K: np.ndarray, V: np.ndarray):
+        """Prefill of sequence b from K, V [H, L, D]; replaces what the sequence held."""
+        L = K.shape[1]
+        assert K.shape == V.shape == (self.H, L, self.D)
+        for t in range(L):
+            self._store_token(b, t, K[:, t], V[:, t])
+        self.seq_lens[b] = L
+
+    def append_kv(self, k_new: np.ndarray, v_new: np.ndarray):
+        assert k_new.shape == v_new.shape == (self.B, self.H, self.D)
+        for b in range(self.B):
+            self._store_token(b, int(self.seq_lens[b]), k_new[b], v_new[b])
+            self.seq_lens[b] += 1
+
+    def dequant(self, b: int, h: int):
+        L = int(self.seq_lens[b])
+        Kh = np.empty((L, self.D), np.float64)
+        Vh = np.empty((L, self.D), np.float64)
+        for n in range(-(-L // BLOCK)):
+            p = self._page_of(b, n)
+            m = min(BLOCK, L - n * BLOCK)
+            Kh[n * BLOCK:n * BLOCK + m] = mx_dequantize(unpack_nibbles(self.k_codes[p, h, :m]), self.k_scales[p, h, :m])
+            vc = unpack_nibbles(self.v_codes[p, h]).T[:m]            # [c][128] -> [t][c]
+            Vh[n * BLOCK:n * BLOCK + m] = mx_dequantize(vc, self.v_scales[p, h, :m])
+        return Kh, Vh
+
+
 # --------------------------------------------------------------------------- attention
 
 def attention_weights(q: np.ndarray, Kh: np.ndarray, sm_scale: float) -> np.ndarray:

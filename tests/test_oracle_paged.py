@@ -102,3 +102,45 @@ def test_empty_sequence_gives_zero_and_errors_are_raised():
         p2.append_kv(one[:1], one[:1])
     with pytest.raises(OverflowError):         # a third block has no table entry
         p2.append_kv(one[:1], one[:1])
+
+
+def _kv_bf16(seed, H, L):
+    w = W.scaled(W.CONFIGS["cfg4"], batch=1, n_q_heads=H, n_kv_heads=H, context=max(L, 1), seed=seed)
+    K, V = W.make_kv(w)
+    return K[0, :, :L], V[0, :, :L]
+
+
+def test_paged_mx_is_a_relocation_of_the_contiguous_cache():
+    """Ragged MXFP4 sequences on scattered pages hold, block for block, the bytes of independent
+    contiguous caches, after prefill and after appends; attention is identical."""
+    rng = np.random.default_rng(9)
+    B, H, Hq = 3, 2, 4
+    lens = [300, 0, 129]
+    table = _table(rng, B, 4, 20)
+    p = O.PagedMxCache(B, H, 20, 4, table)
+    singles = []
+    for b, L in enumerate(lens):
+        K, V = _kv_bf16(30 + b, H, L)
+        p.quant_pack_kv(b, K, V)
+        c = O.MxCache(1, H, 512)
+        c.quant_pack_kv(K[None], V[None])
+        singles.append(c)
+    for step in range(5):
+        kn = W.round_to_bf16(rng.standard_normal((B, H, 128)).astype(np.float32))
+        vn = W.round_to_bf16(rng.standard_normal((B, H, 128)).astype(np.float32))
+        p.append_kv(kn, vn)
+        for b in range(B):
+            singles[b].append_kv(kn[b:b + 1], vn[b:b + 1])
+    assert [int(x) for x in p.seq_lens] == [L + 5 for L in lens]
+    q = W.round_to_bf16(np.random.default_rng(6).standard_normal((B, Hq, 128)).astype(np.float32))
+    out = O.decode_attn(p, q, 0.09)
+    for b in range(B):
+        c = singles[b]
+        assert np.array_equal(out[b], O.decode_attn(c, q[b:b + 1], 0.09)[0]), b
+        for n in range(-(-c.length // 128)):
+            pg = table[b, n]
+            m = min(128, c.length - 128 * n)
+            assert np.array_equal(p.k_codes[pg][:, :m], c.k_codes[0, :, 128 * n:128 * n + m])
+            assert np.array_equal(p.k_scales[pg][:, :m], c.k_scales[0, :, 128 * n:128 * n + m])
+            assert np.array_equal(p.v_scales[pg][:, :m], c.v_scales[0, :, 128 * n:128 * n + m])
+            assert np.array_equal(p.v_codes[pg], c.v_codes[0, :, n])
