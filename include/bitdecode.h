@@ -157,7 +157,7 @@ bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t nu
  * The paper runs its kernels on a contiguous and on a page-managed KV cache and names no
  * layout.  Here a page is one 128-token quantization block: the packed blocks of all sequences
  * live in one pool, block n of sequence b is page block_table[b][n], and every sequence has its
- * own length, kept on the device.  INT4 / INT2 only.  P = num_pages:
+ * own length, kept on the device.  P = num_pages; integer formats:
  *
  *   k_codes  uint32 [P][H][128 tokens][D/cpw]      v_codes  uint32 [P][H][D channels][128/cpw]
  *   k_params uint32 [P][H][D]                      v_params uint32 [P][H][128]
@@ -166,6 +166,13 @@ bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t nu
  *   seq_lens    int32 [B]                          device; tokens cached per sequence; written by
  *                                                  bd_paged_quant_pack_kv / bd_paged_append_kv
  *   status      int32 [1]                          device, may be NULL; see below
+ *
+ * BD_FMT_MXFP4 quantizes every token on arrival, so there is no residual (k_res, v_res unused,
+ * size 0) and the newest, partly filled block lives in a page as well: table entry n must be
+ * valid before the sequence reaches token 128*n + 1.
+ *
+ *   k_codes  uint8 [P][H][128 tokens][D/2]         v_codes  uint8 [P][H][D channels][64]
+ *   k_params uint8 [P][H][128][D/32]  (e8m0)       v_params uint8 [P][H][128][D/32]
  *
  * Inside a page every block has exactly the bytes it has in a bd_cache.  The caller owns the
  * page allocator: before a sequence reaches token 128*(n+1) its table entry n must name a page
@@ -179,7 +186,7 @@ typedef struct bd_paged_cache {
   int32_t n_q_heads;
   int32_t n_kv_heads;
   int32_t head_dim;            /* 128 */
-  int32_t format;              /* BD_FMT_INT4, BD_FMT_INT2 or their _KT variants */
+  int32_t format;              /* any bd_format */
   int32_t num_pages;
   int32_t max_pages_per_seq;
   void *k_codes, *v_codes;
@@ -196,23 +203,25 @@ size_t bd_paged_cache_bytes(const bd_paged_cache* c, int which);
 /* Workspace size for bd_paged_decode_attn (same layout as bd_workspace_bytes). */
 size_t bd_paged_workspace_bytes(const bd_paged_cache* c, int32_t num_splits);
 
-/* Prefill of sequence `seq` (Sec. IV-B(1)) from k, v (device, [H][L][D] fp16): the first
- * L - (L mod 128) tokens are quantized into the sequence's pages, the rest copied to its
- * residual, seq_lens[seq] = L.  Replaces whatever the sequence held.
- * BD_ERR_CAPACITY if L needs more than max_pages_per_seq pages. */
+/* Prefill of sequence `seq` (Sec. IV-B(1)) from k, v (device, [H][L][D] fp16; bf16 for MXFP4):
+ * the first L - (L mod 128) tokens are quantized into the sequence's pages, the rest copied to
+ * its residual (MXFP4: all L tokens are quantized into pages), seq_lens[seq] = L.  Replaces
+ * whatever the sequence held.  BD_ERR_CAPACITY if L needs more than max_pages_per_seq pages. */
 bd_status bd_paged_quant_pack_kv(const bd_paged_cache* c, int32_t seq, const void* k, const void* v,
                                  int32_t L, void* stream);
 
 /* One decode step of every sequence (Sec. IV-B): token b of k_new, v_new (device, [B][H][D]
  * fp16) goes to residual slot seq_lens[b] mod 128 of sequence b; a residual that reaches 128
- * tokens is quantized into page block_table[b][seq_lens[b] / 128]; seq_lens[b] += 1. */
+ * tokens is quantized into page block_table[b][seq_lens[b] / 128]; seq_lens[b] += 1.
+ * MXFP4 (bf16 inputs): the token is quantized straight into position seq_lens[b] mod 128 of that
+ * page. */
 bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const void* v_new, void* stream);
 
 /* bd_decode_attn over the paged cache: sequence b attends its own seq_lens[b] tokens; a
  * sequence with no tokens gets a zero output row.  Every sequence is split num_splits ways
  * (pick it for the longest sequence, e.g. with bd_choose_splits on a bd_cache of the same
  * shape); workspace at least bd_paged_workspace_bytes(c, num_splits); `out` (device,
- * [B][n_q_heads][D] fp16) must be non-NULL. */
+ * [B][n_q_heads][D] fp16; bf16 for MXFP4) must be non-NULL. */
 bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float softmax_scale,
                                int32_t num_splits, void* workspace, void* out, void* stream);
 

@@ -243,14 +243,14 @@ static bd_status check_paged_shape(const bd_paged_cache* c) {
   const bd_cache s = shape_of(c);
   bd_status st = check_shape(&s);
   if (st != BD_OK) return st;
-  if (c->format == BD_FMT_MXFP4) return BD_ERR_UNSUPPORTED;
   if (c->num_pages <= 0 || c->max_pages_per_seq <= 0) return BD_ERR_INVALID_ARG;
   return BD_OK;
 }
 
 static bd_status check_paged_buffers(const bd_paged_cache* c) {
-  const void* need[8] = {c->k_codes, c->v_codes, c->k_params, c->v_params, c->k_res, c->v_res, c->block_table,
-                         c->seq_lens};
+  const bool mx = c->format == BD_FMT_MXFP4;   // no residual: every token is quantized on arrival
+  const void* need[8] = {c->k_codes, c->v_codes, c->k_params, c->v_params, mx ? (void*)16 : c->k_res,
+                         mx ? (void*)16 : c->v_res, c->block_table, c->seq_lens};
   for (int i = 0; i < 8; ++i) {
     if (!need[i]) return BD_ERR_INVALID_ARG;
     if (i < 6 ? !aligned16(need[i]) : (reinterpret_cast<uintptr_t>(need[i]) & 3u) != 0) return BD_ERR_ALIGNMENT;
@@ -262,6 +262,14 @@ static bd_status check_paged_buffers(const bd_paged_cache* c) {
 size_t bd_paged_cache_bytes(const bd_paged_cache* c, int which) {
   if (check_paged_shape(c) != BD_OK || which < 0 || which > 7) return 0;
   const size_t pool = (size_t)c->num_pages * c->n_kv_heads, bits = (size_t)bits_of(c->format);
+  if (c->format == BD_FMT_MXFP4) {
+    switch (which) {
+      case 0: case 1: return pool * kBlock * (kD / 2);
+      case 2: case 3: return pool * kBlock * (kD / kMxGroup);
+      case 4: case 5: return 0;
+      default: break;
+    }
+  }
   switch (which) {
     case 0: case 1: return pool * kBlock * kD * bits / 8;
     case 2: return pool * kD * 4;
@@ -286,7 +294,8 @@ bd_status bd_paged_quant_pack_kv(const bd_paged_cache* c, int32_t seq, const voi
   if (seq < 0 || seq >= c->batch || L < 0) return BD_ERR_INVALID_ARG;
   if (L > 0 && (!k || !v)) return BD_ERR_INVALID_ARG;
   if (L > 0 && (!aligned16(k) || !aligned16(v))) return BD_ERR_ALIGNMENT;
-  if (L / kBlock > c->max_pages_per_seq) return BD_ERR_CAPACITY;
+  const int blocks = c->format == BD_FMT_MXFP4 ? (L + kBlock - 1) / kBlock : L / kBlock;
+  if (blocks > c->max_pages_per_seq) return BD_ERR_CAPACITY;
   return hip_status(launch_paged_prefill(c, seq, k, v, L, (hipStream_t)stream));
 }
 
@@ -310,7 +319,10 @@ bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float sof
   hipStream_t st = (hipStream_t)stream;
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(&shape, workspace, num_splits);
-  if ((s = hip_status(launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, st))) != BD_OK) return s;
+  s = hip_status(c->format == BD_FMT_MXFP4
+                     ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, st)
+                     : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, st));
+  if (s != BD_OK) return s;
   return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st));
 }
 

@@ -50,6 +50,8 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,
                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
                              const void* k_new, const void* v_new, hipStream_t st);
+hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
+                                  float* part_o, float* part_ml, hipStream_t st);
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale,
                             int num_splits, float* part_o, float* part_ml, hipStream_t st);
 hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* part_ml, int nparts,

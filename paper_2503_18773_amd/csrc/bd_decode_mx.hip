@@ -41,6 +41,11 @@ struct MxArgs {
   int capacity;
   int num_splits;
   float scale_log2;
+  // paged cache only: block n of sequence b is page block_table[b * max_pages + n]
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  int32_t* status;
+  int max_pages, num_pages;
 };
 
 template <int NG>
@@ -55,7 +60,8 @@ __device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(
 // over the same loaded keys and values (1, or 2 for groups of more than 4 heads, at one wave per
 // SIMD: the second set of operands and accumulators does not fit two); groups of more than 8 heads take
 // ceil(g_q / 8) workgroups per (split, KV head), which read the cache once each.
-template <int NG>
+// PAGED: blocks are found through the block table and every sequence has its own length.
+template <int NG, bool PAGED>
 __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs a) {
   __shared__ MergeLdsMx<NG> ml;
   const int nsub = (a.gq + 3) >> 2;              // sub-groups of the query group
@@ -68,7 +74,9 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   // heads of sub-group gi of this workgroup (0 past the end of the group)
   auto sub_heads = [&](int gi) { return max(0, min(4, a.gq - 4 * (sub0 + gi))); };
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
-  const int nb = (a.length + kBlock - 1) / kBlock;
+  int length = a.length;
+  if (PAGED) length = max(0, a.seq_lens[b]);
+  const int nb = (length + kBlock - 1) / kBlock;
   const int blk0 = (int)(((long)nb * split) / a.num_splits);
   const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
   const int nbcap = a.capacity / kBlock;
@@ -83,8 +91,9 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   // are requested when the current block is done, the values of a block when its keys are about
   // to be consumed.  The waves of a compute unit share one in-order memory pipeline; a shorter
   // queue serves everybody sooner and shortens the ramp at both ends of the kernel.
-  auto issue_k = [&](int blk) {
-    const size_t tok0 = unit * a.capacity + (size_t)blk * kBlock;
+  // bi = index of a 128-token block in the arrays: unit * nbcap + block, or page * H + KV head
+  auto issue_k = [&](size_t bi) {
+    const size_t tok0 = bi * kBlock;
 #pragma unroll
     for (int T = 0; T < 8; ++T) {
       const size_t t = tok0 + tok_base + 4 * T;
@@ -92,18 +101,36 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
       kraw[T] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(a.k_codes + t * 64 + 16 * g));
     }
   };
-  auto issue_v = [&](int blk) {
-    const size_t tok0 = unit * a.capacity + (size_t)blk * kBlock;
+  auto issue_v = [&](size_t bi) {
+    const size_t tok0 = bi * kBlock;
 #pragma unroll
     for (int half = 0; half < 2; ++half)
       vsc[half] = *reinterpret_cast<const u4_t*>(a.v_scales + (tok0 + 32 * g + 16 * half + 4 * cg) * 4);
-    const uint8_t* vp = a.v_codes + (unit * nbcap + blk) * (size_t)(kD * 64) + 16 * g;
+    const uint8_t* vp = a.v_codes + bi * (size_t)(kD * 64) + 16 * g;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
       vraw[mt] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(vp + (size_t)(16 * mt + col) * 64));
   };
+  // Paged: table entry of block n (-1 past the end of the row), and the first block at or after
+  // n, in this wave's stride, whose entry names a page of the pool; entries that do not are
+  // skipped and reported in *status.
+  auto table_entry = [&](int n) { return n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1; };
+  auto first_valid = [&](int n, int entry, size_t& bi) {
+    while (n < blk1) {
+      if (entry >= 0 && entry < a.num_pages) {
+        bi = (size_t)entry * a.n_kv_heads + hkv;
+        break;
+      }
+      if (a.status && lane == 0) atomicOr(a.status, 1);
+      n += kWaves;
+      entry = n < blk1 ? table_entry(n) : -1;
+    }
+    return n;
+  };
   int blk = blk0 + wave;
-  if (blk < blk1) issue_k(blk);
+  size_t bi = unit * nbcap + blk;
+  if (PAGED) blk = first_valid(blk, blk < blk1 ? table_entry(blk) : -1, bi);
+  if (blk < blk1) issue_k(bi);
 
   // ---- the query as the B operand: exact split of each bf16 into two e4m3 pieces.
   // Operand layout of the 8-bit side (measured): lane (column, g) holds contraction indices
@@ -167,8 +194,11 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   }
 
   while (blk < blk1) {
-    const int nblk = blk + kWaves;
-    issue_v(blk);
+    int nblk = blk + kWaves;
+    size_t nbi = bi + kWaves;
+    int next_entry = -1;   // requested a block ahead
+    if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
+    issue_v(bi);
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {   // the sub-groups in turn, over the same loaded block
     // ---- S^T tiles straight from the packed codes; column group cg keeps tiles cg and 4+cg
@@ -190,7 +220,7 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
       for (int r = 0; r < 4; ++r) {
         const float lo = cg & 1 ? st[1][r] : st[0][r], hi = cg & 1 ? st[3][r] : st[2][r];
         const int t = blk * kBlock + 32 * g + 16 * half + 4 * cg + r;
-        s[half][r] = t < a.length ? (cg & 2 ? hi : lo) * a.scale_log2 : -INFINITY;   // tokens past the end
+        s[half][r] = t < length ? (cg & 2 ? hi : lo) * a.scale_log2 : -INFINITY;   // tokens past the end
       }
     }
     // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16*half + 4cg + r
@@ -259,8 +289,10 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
       }
     }
     }   // sub-groups
-    if (nblk < blk1) issue_k(nblk);
+    if (PAGED) nblk = first_valid(nblk, next_entry, nbi);
+    if (nblk < blk1) issue_k(nbi);
     blk = nblk;
+    bi = nbi;
   }
 
   // ---- merge the waves of the workgroup
@@ -309,9 +341,20 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
 
 }  // namespace
 
+template <bool PAGED>
+static hipError_t launch_mx(const MxArgs& a, int batch, hipStream_t st) {
+  const int nsub = (a.gq + 3) / 4;
+  dim3 block(256);
+  if (nsub == 1)
+    decode_mx_kernel<1, PAGED><<<dim3(a.num_splits, a.n_kv_heads, batch), block, 0, st>>>(a);
+  else
+    decode_mx_kernel<2, PAGED><<<dim3(a.num_splits, a.n_kv_heads * ((nsub + 1) / 2), batch), block, 0, st>>>(a);
+  return hipGetLastError();
+}
+
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale, int num_splits,
                             float* part_o, float* part_ml, hipStream_t st) {
-  MxArgs a;
+  MxArgs a{};
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;
   a.k_scales = (const uint8_t*)c->k_params;
@@ -326,13 +369,31 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
   a.capacity = c->capacity;
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
-  const int nsub = (a.gq + 3) / 4;
-  dim3 block(256);
-  if (nsub == 1)
-    decode_mx_kernel<1><<<dim3(num_splits, c->n_kv_heads, c->batch), block, 0, st>>>(a);
-  else
-    decode_mx_kernel<2><<<dim3(num_splits, c->n_kv_heads * ((nsub + 1) / 2), c->batch), block, 0, st>>>(a);
-  return hipGetLastError();
+  return launch_mx<false>(a, c->batch, st);
+}
+
+hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
+                                  float* part_o, float* part_ml, hipStream_t st) {
+  MxArgs a{};
+  a.k_codes = (const uint8_t*)c->k_codes;
+  a.v_codes = (const uint8_t*)c->v_codes;
+  a.k_scales = (const uint8_t*)c->k_params;
+  a.v_scales = (const uint8_t*)c->v_params;
+  a.q = (const uint16_t*)q;
+  a.part_o = part_o;
+  a.part_ml = part_ml;
+  a.n_q_heads = c->n_q_heads;
+  a.n_kv_heads = c->n_kv_heads;
+  a.gq = c->n_q_heads / c->n_kv_heads;
+  a.capacity = kBlock;
+  a.num_splits = num_splits;
+  a.scale_log2 = softmax_scale * kLog2e;
+  a.block_table = c->block_table;
+  a.seq_lens = c->seq_lens;
+  a.status = c->status;
+  a.max_pages = c->max_pages_per_seq;
+  a.num_pages = c->num_pages;
+  return launch_mx<true>(a, c->batch, st);
 }
 
 }  // namespace bd

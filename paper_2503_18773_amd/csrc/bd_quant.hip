@@ -374,13 +374,14 @@ __global__ __launch_bounds__(256) void paged_append_kernel(PagedArgs a, const ui
   quant_block<BITS, KT>(kr, vr, a.k_codes, a.v_codes, a.k_params, a.v_params, (size_t)page * a.n_kv_heads + h);
 }
 
-// seq_lens[b] += 1 for every sequence whose step went through (same test as the append kernel).
-__global__ void paged_bump_kernel(PagedArgs a, int batch) {
+// seq_lens[b] += 1 for every sequence whose step went through (same test as the append kernel:
+// a page is needed when the step fills the residual, or, if `every_token`, by every token).
+__global__ void paged_bump_kernel(PagedArgs a, int batch, bool every_token) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= batch) return;
   const int len = a.seq_lens[b];
   if (len < 0) return;
-  if (len % kBlock == kBlock - 1) {
+  if (every_token || len % kBlock == kBlock - 1) {
     const int n = len / kBlock;
     int page = -1;
     if (n < a.max_pages) page = a.block_table[(size_t)b * a.max_pages + n];
@@ -425,20 +426,39 @@ __device__ __forceinline__ uint32_t e2m1_code(float x, int e) {
   return (x < 0.0f && idx != 0u) ? (idx | 8u) : idx;
 }
 
+// Where the 128-token blocks of an MXFP4 launch go: block `blk` of unit `u` is block
+// u * nbcap + blk of the arrays (contiguous cache), or, for one sequence of a paged cache, block
+// page * H + u with page = table_row[blk] (u = KV head).  -1 (and bit 1 of *status) if the table has
+// no valid page for it.  Inside a block: K codes [128][64], scales [128][4], V codes [128 ch][64].
+struct MxDst {
+  uint8_t *k_codes, *k_scales, *v_codes, *v_scales;
+  int nbcap;
+  const int32_t* table_row;
+  int32_t* status;
+  int n_kv_heads, num_pages, max_pages;
+};
+__device__ __forceinline__ long mx_block_index(const MxDst& d, int u, int blk) {
+  if (!d.table_row) return (long)u * d.nbcap + blk;
+  int page = -1;
+  if (blk < d.max_pages) page = d.table_row[blk];
+  if (page < 0 || page >= d.num_pages) {
+    if (d.status && threadIdx.x == 0) atomicOr(d.status, 2);
+    return -1;
+  }
+  return (long)page * d.n_kv_heads + u;
+}
+
 // One workgroup quantizes up to 128 tokens (one V block) of one (batch, kv_head).
 // Thread t handles token t: 4 MX groups of K and of V.  K codes go out token-major;
 // V codes pass through an LDS tile to be written channel-major, two tokens per byte.
 // When `single` (decode append of one token) the V bytes are updated nibble-wise.
 __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restrict__ ksrc,
                                                         const uint16_t* __restrict__ vsrc,
-                                                        long src_unit_stride, int ntok,
-                                                        uint8_t* __restrict__ k_codes,
-                                                        uint8_t* __restrict__ k_scales,
-                                                        uint8_t* __restrict__ v_codes,
-                                                        uint8_t* __restrict__ v_scales, int capacity,
+                                                        long src_unit_stride, int ntok, MxDst d,
                                                         int dst_tok0) {
   constexpr int PITCH = kD + 4;
   __shared__ uint8_t tile[kBlock * PITCH];
+  uint8_t *k_codes = d.k_codes, *k_scales = d.k_scales, *v_codes = d.v_codes, *v_scales = d.v_scales;
   const int unit = blockIdx.y;
   // this workgroup covers destination tokens [t_lo, t_hi) of block `dblk`
   const int first_blk = dst_tok0 / kBlock;
@@ -447,10 +467,12 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
   const int t_hi = min((dblk + 1) * kBlock, dst_tok0 + ntok);
   const int t = dblk * kBlock + threadIdx.x;  // destination token of this thread
   const bool live = t >= t_lo && t < t_hi;
+  const long bi = mx_block_index(d, unit, dblk);
+  if (bi < 0) return;
 
   if (live) {
     const size_t so = (size_t)unit * src_unit_stride + (size_t)(t - dst_tok0) * kD;
-    const size_t tok = (size_t)unit * capacity + t;
+    const size_t tok = (size_t)bi * kBlock + threadIdx.x;
 #pragma unroll 1
     for (int which = 0; which < 2; ++which) {
       const uint16_t* src = (which == 0 ? ksrc : vsrc) + so;
@@ -496,7 +518,7 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
   }
   __syncthreads();
   // V codes, channel-major: byte j of channel c holds block tokens 2j (low), 2j+1 (high).
-  uint8_t* vrow = v_codes + ((size_t)unit * (capacity / kBlock) + dblk) * (size_t)(kD * 64);
+  uint8_t* vrow = v_codes + (size_t)bi * (size_t)(kD * 64);
   const int j_lo = (t_lo - dblk * kBlock) / 2, j_hi = (t_hi - dblk * kBlock + 1) / 2;
   const int nj = j_hi - j_lo;
   for (int k = threadIdx.x; k < kD * nj; k += 128) {
@@ -526,15 +548,13 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
 // channel-major place through an LDS tile.
 __global__ __launch_bounds__(256) void mx_quant_block_kernel(const uint16_t* __restrict__ ksrc,
                                                               const uint16_t* __restrict__ vsrc,
-                                                              long src_unit_stride,
-                                                              uint8_t* __restrict__ k_codes,
-                                                              uint8_t* __restrict__ k_scales,
-                                                              uint8_t* __restrict__ v_codes,
-                                                              uint8_t* __restrict__ v_scales, int capacity,
-                                                              int dst_blk0) {
+                                                              long src_unit_stride, MxDst d, int dst_blk0) {
   constexpr int PITCH = 80;   // bytes per channel row of the tile (64 used; 16-byte aligned rows)
   __shared__ __attribute__((aligned(16))) uint8_t tile[kD * PITCH];
+  uint8_t *k_codes = d.k_codes, *k_scales = d.k_scales, *v_codes = d.v_codes, *v_scales = d.v_scales;
   const int unit = blockIdx.y, blk = dst_blk0 + blockIdx.x, tid = threadIdx.x, g = tid & 3;
+  const long bi = mx_block_index(d, unit, blk);
+  if (bi < 0) return;
   const size_t src_blk = (size_t)unit * src_unit_stride + (size_t)blockIdx.x * kBlock * kD;
 #pragma unroll 1
   for (int which = 0; which < 2; ++which) {
@@ -542,7 +562,7 @@ __global__ __launch_bounds__(256) void mx_quant_block_kernel(const uint16_t* __r
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int tl = (tid >> 2) + 64 * i;   // token inside the block
-      const size_t tok = (size_t)unit * capacity + (size_t)blk * kBlock + tl;
+      const size_t tok = (size_t)bi * kBlock + tl;
       const uint16_t* sp = src + (size_t)tl * kD + kMxGroup * g;
       uint32_t raw[16];
 #pragma unroll
@@ -622,7 +642,7 @@ __global__ __launch_bounds__(256) void mx_quant_block_kernel(const uint16_t* __r
   // channel-major V codes of the block: 128 rows of 64 bytes, each thread half a row
   {
     const int row = tid >> 1, hf = tid & 1, gg = row >> 5;
-    uint8_t* dst = v_codes + (((size_t)unit * (capacity / kBlock) + blk) * kD + row) * 64 + 32 * hf;
+    uint8_t* dst = v_codes + ((size_t)bi * kD + row) * 64 + 32 * hf;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int chunk = 2 * hf + c;
@@ -636,15 +656,13 @@ __global__ __launch_bounds__(256) void mx_quant_block_kernel(const uint16_t* __r
 // Decode-step append for MXFP4: one token per (batch, kv_head), thread = channel.  The MX
 // group statistics are wave shuffles over 32 lanes; K bytes pair neighbouring channels, V
 // bytes are updated nibble-wise in the channel-major block layout.
-__global__ __launch_bounds__(128) void mx_append_kernel(const uint16_t* __restrict__ k_new,
-                                                         const uint16_t* __restrict__ v_new,
-                                                         uint8_t* __restrict__ k_codes,
-                                                         uint8_t* __restrict__ k_scales,
-                                                         uint8_t* __restrict__ v_codes,
-                                                         uint8_t* __restrict__ v_scales, int capacity, int t) {
-  const int unit = blockIdx.x, c = threadIdx.x;
-  const float kx = bf16_bits_to_float(k_new[(size_t)unit * kD + c]);
-  const float vx = bf16_bits_to_float(v_new[(size_t)unit * kD + c]);
+// One token of one (sequence, KV head): thread c quantizes channel c of the new K and V rows and
+// files the codes at position i of block bi (V: one nibble of byte i/2 of its channel row).
+__device__ __forceinline__ void mx_append_token(const uint16_t* __restrict__ k_row, const uint16_t* __restrict__ v_row,
+                                                const MxDst& d, long bi, int i) {
+  const int c = threadIdx.x;
+  const float kx = bf16_bits_to_float(k_row[c]);
+  const float vx = bf16_bits_to_float(v_row[c]);
   float ka = fabsf(kx), va = fabsf(vx);
 #pragma unroll
   for (int off = 1; off < kMxGroup; off <<= 1) {
@@ -653,21 +671,73 @@ __global__ __launch_bounds__(128) void mx_append_kernel(const uint16_t* __restri
   }
   const int ke = ka > 0.0f ? mx_shared_exp(ka) : 0, ve = va > 0.0f ? mx_shared_exp(va) : 0;
   const uint32_t kc = ka > 0.0f ? e2m1_code(kx, ke) : 0u, vc = va > 0.0f ? e2m1_code(vx, ve) : 0u;
-  const size_t tok = (size_t)unit * capacity + t;
+  const size_t tok = (size_t)bi * kBlock + i;
   if ((c & (kMxGroup - 1)) == 0) {
-    k_scales[tok * 4 + c / kMxGroup] = (uint8_t)(ke + 127);
-    v_scales[tok * 4 + c / kMxGroup] = (uint8_t)(ve + 127);
+    d.k_scales[tok * 4 + c / kMxGroup] = (uint8_t)(ke + 127);
+    d.v_scales[tok * 4 + c / kMxGroup] = (uint8_t)(ve + 127);
   }
   const uint32_t kc_hi = __shfl_down(kc, 1);
-  if ((c & 1) == 0) k_codes[tok * (kD / 2) + c / 2] = (uint8_t)(kc | (kc_hi << 4));
-  uint8_t* vb = v_codes + (((size_t)unit * (capacity / kBlock) + t / kBlock) * kD + c) * 64 + (t % kBlock) / 2;
-  if ((t & 1) == 0)
+  if ((c & 1) == 0) d.k_codes[tok * (kD / 2) + c / 2] = (uint8_t)(kc | (kc_hi << 4));
+  uint8_t* vb = d.v_codes + ((size_t)bi * kD + c) * 64 + i / 2;
+  if ((i & 1) == 0)
     *vb = (uint8_t)vc;                                  // first token of the byte: the other nibble is not there yet
   else
     *vb = (uint8_t)((*vb & 0x0Fu) | (vc << 4));
 }
 
+// Contiguous cache: token t of every unit.
+__global__ __launch_bounds__(128) void mx_append_kernel(const uint16_t* __restrict__ k_new,
+                                                         const uint16_t* __restrict__ v_new, MxDst d, int t) {
+  const int unit = blockIdx.x;
+  mx_append_token(k_new + (size_t)unit * kD, v_new + (size_t)unit * kD, d, (long)unit * d.nbcap + t / kBlock,
+                  t % kBlock);
+}
+
+// Paged cache, one decode step: the token of sequence blockIdx.y, KV head blockIdx.x goes to
+// position len mod 128 of the page of block len / 128.  Without a valid page the token is dropped
+// (bit 1 of *status) and paged_bump_kernel leaves the length as it is.
+__global__ __launch_bounds__(128) void mx_paged_append_kernel(MxDst d, const int32_t* __restrict__ block_table,
+                                                               const int32_t* __restrict__ seq_lens,
+                                                               const uint16_t* __restrict__ k_new,
+                                                               const uint16_t* __restrict__ v_new) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int len = seq_lens[b];
+  if (len < 0) return;
+  d.table_row = block_table + (size_t)b * d.max_pages;
+  const long bi = mx_block_index(d, h, len / kBlock);
+  if (bi < 0) return;
+  const size_t unit = (size_t)b * d.n_kv_heads + h;
+  mx_append_token(k_new + unit * kD, v_new + unit * kD, d, bi, len % kBlock);
+}
+
+__global__ void set_len_kernel(int32_t* seq_lens, int seq, int L) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) seq_lens[seq] = L;
+}
+
 }  // namespace
+
+// Tokens [dst_tok0, dst_tok0 + ntok) of every unit: whole blocks through the block kernel, the
+// rest through the general one.
+static hipError_t launch_mx_range(const uint16_t* kk, const uint16_t* vv, long src_unit_stride, int ntok, int units,
+                           const MxDst& d, int dst_tok0, hipStream_t st) {
+  // tokens [t0, t1) of the range that do not fill a block go through the general kernel
+  auto partial = [&](int t0, int t1) -> hipError_t {
+    if (t1 <= t0) return hipSuccess;
+    const size_t off = (size_t)(t0 - dst_tok0) * kD;
+    dim3 grid((t1 - 1) / kBlock - t0 / kBlock + 1, units), block(128);
+    mx_quant_kernel<<<grid, block, 0, st>>>(kk + off, vv + off, src_unit_stride, t1 - t0, d, t0);
+    return hipGetLastError();
+  };
+  const int end = dst_tok0 + ntok;
+  const int full0 = (dst_tok0 + kBlock - 1) / kBlock, full1 = end / kBlock;   // whole blocks [full0, full1)
+  if (full1 <= full0) return partial(dst_tok0, end);
+  hipError_t e = partial(dst_tok0, full0 * kBlock);
+  if (e != hipSuccess) return e;
+  const size_t off = (size_t)(full0 * kBlock - dst_tok0) * kD;
+  mx_quant_block_kernel<<<dim3(full1 - full0, units), dim3(256), 0, st>>>(kk + off, vv + off, src_unit_stride, d, full0);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  return partial(full1 * kBlock, end);
+}
 
 hipError_t launch_quant_blocks(const void* k, const void* v, long src_unit_stride, int src_tok0, int nblocks,
                                int units, const bd_cache* c, int dst_blk0, hipStream_t st) {
@@ -711,8 +781,33 @@ static PagedArgs paged_args(const bd_paged_cache* c) {
   return a;
 }
 
+static MxDst paged_mx_dst(const bd_paged_cache* c) {
+  MxDst d{};
+  d.k_codes = (uint8_t*)c->k_codes;
+  d.k_scales = (uint8_t*)c->k_params;
+  d.v_codes = (uint8_t*)c->v_codes;
+  d.v_scales = (uint8_t*)c->v_params;
+  d.nbcap = 1;
+  d.status = c->status;
+  d.n_kv_heads = c->n_kv_heads;
+  d.num_pages = c->num_pages;
+  d.max_pages = c->max_pages_per_seq;
+  return d;
+}
+
 hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k, const void* v, int L,
                                 hipStream_t st) {
+  if (c->format == BD_FMT_MXFP4) {
+    // every token is quantized on arrival: the last, partly filled block lives in a page as well
+    MxDst d = paged_mx_dst(c);
+    d.table_row = c->block_table + (size_t)seq * c->max_pages_per_seq;
+    if (L > 0) {
+      hipError_t e = launch_mx_range((const uint16_t*)k, (const uint16_t*)v, (long)L * kD, L, c->n_kv_heads, d, 0, st);
+      if (e != hipSuccess) return e;
+    }
+    set_len_kernel<<<dim3(1), dim3(64), 0, st>>>(c->seq_lens, seq, L);
+    return hipGetLastError();
+  }
   const PagedArgs a = paged_args(c);
   const int nb = L / kBlock;
   if (nb > 0) {
@@ -735,6 +830,13 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
   const PagedArgs a = paged_args(c);
   dim3 grid(c->n_kv_heads, c->batch), block(256);
   const uint16_t *kk = (const uint16_t*)k_new, *vv = (const uint16_t*)v_new;
+  if (c->format == BD_FMT_MXFP4) {
+    mx_paged_append_kernel<<<grid, dim3(128), 0, st>>>(paged_mx_dst(c), c->block_table, c->seq_lens, kk, vv);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch, true);
+    return hipGetLastError();
+  }
   switch (c->format) {
     case BD_FMT_INT4: paged_append_kernel<4, false><<<grid, block, 0, st>>>(a, kk, vv); break;
     case BD_FMT_INT2: paged_append_kernel<2, false><<<grid, block, 0, st>>>(a, kk, vv); break;
@@ -743,7 +845,7 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch);
+  paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch, false);
   return hipGetLastError();
 }
 
@@ -761,32 +863,18 @@ hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_st
 hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, int ntok, int units,
                            const bd_cache* c, int dst_tok0, hipStream_t st) {
   if (ntok <= 0) return hipSuccess;
+  MxDst d{};
+  d.k_codes = (uint8_t*)c->k_codes;
+  d.k_scales = (uint8_t*)c->k_params;
+  d.v_codes = (uint8_t*)c->v_codes;
+  d.v_scales = (uint8_t*)c->v_params;
+  d.nbcap = c->capacity / kBlock;
+  const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
   if (ntok == 1 && src_unit_stride == kD) {
-    mx_append_kernel<<<dim3(units), dim3(128), 0, st>>>((const uint16_t*)k, (const uint16_t*)v, (uint8_t*)c->k_codes,
-                                                        (uint8_t*)c->k_params, (uint8_t*)c->v_codes,
-                                                        (uint8_t*)c->v_params, c->capacity, dst_tok0);
+    mx_append_kernel<<<dim3(units), dim3(128), 0, st>>>(kk, vv, d, dst_tok0);
     return hipGetLastError();
   }
-  const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
-  uint8_t *kc = (uint8_t*)c->k_codes, *kp = (uint8_t*)c->k_params, *vc = (uint8_t*)c->v_codes, *vp = (uint8_t*)c->v_params;
-  // tokens [t0, t1) of the range that do not fill a block go through the general kernel
-  auto partial = [&](int t0, int t1) -> hipError_t {
-    if (t1 <= t0) return hipSuccess;
-    const size_t off = (size_t)(t0 - dst_tok0) * kD;
-    dim3 grid((t1 - 1) / kBlock - t0 / kBlock + 1, units), block(128);
-    mx_quant_kernel<<<grid, block, 0, st>>>(kk + off, vv + off, src_unit_stride, t1 - t0, kc, kp, vc, vp, c->capacity, t0);
-    return hipGetLastError();
-  };
-  const int end = dst_tok0 + ntok;
-  const int full0 = (dst_tok0 + kBlock - 1) / kBlock, full1 = end / kBlock;   // whole blocks [full0, full1)
-  if (full1 <= full0) return partial(dst_tok0, end);
-  hipError_t e = partial(dst_tok0, full0 * kBlock);
-  if (e != hipSuccess) return e;
-  const size_t off = (size_t)(full0 * kBlock - dst_tok0) * kD;
-  mx_quant_block_kernel<<<dim3(full1 - full0, units), dim3(256), 0, st>>>(kk + off, vv + off, src_unit_stride, kc, kp, vc,
-                                                                          vp, c->capacity, full0);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  return partial(full1 * kBlock, end);
+  return launch_mx_range(kk, vv, src_unit_stride, ntok, units, d, dst_tok0, st);
 }
 
 }  // namespace bd

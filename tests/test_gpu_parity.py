@@ -539,6 +539,131 @@ def test_paged_long_ragged_batch_sampled_units():
     assert np.array_equal(got[pg], oc.k_codes[pg])
 
 
+def _paged_mx_pair(lens, H, Hq, num_pages, max_pages, seed=41, table=None):
+    B_ = len(lens)
+    rng = np.random.default_rng(seed)
+    if table is None:
+        table = rng.permutation(num_pages)[:B_ * max_pages].reshape(B_, max_pages).astype(np.int32)
+    oc = O.PagedMxCache(B_, H, num_pages, max_pages, table)
+    gc = B.PagedKVCache(B_, Hq, H, "mxfp4", num_pages, table)
+    for b, L in enumerate(lens):
+        w = W.scaled(W.CONFIGS["cfg4"], batch=1, n_q_heads=Hq, n_kv_heads=H, context=max(L, 1), seed=seed + b)
+        K, V = W.make_kv(w)
+        K, V = np.ascontiguousarray(K[0, :, :L]), np.ascontiguousarray(V[0, :, :L])
+        oc.quant_pack_kv(b, K, V)
+        gc.quant_pack_kv(b, to_dev(K, "bf16"), to_dev(V, "bf16"))
+    return oc, gc, table
+
+
+def _assert_paged_mx_equal(oc, gc, what):
+    """Lengths, and the bytes of every block a sequence holds (token rows up to its length; the
+    channel-major V block whole: absent tokens are zero nibbles)."""
+    import torch
+    torch.cuda.synchronize()
+    assert list(gc.seq_lens.cpu().numpy()) == list(oc.seq_lens), what
+    got = {name: gc.host_buffer(i).reshape(getattr(oc, name).shape)
+           for i, name in enumerate(["k_codes", "v_codes", "k_scales", "v_scales"])}
+    for b in range(oc.B):
+        L = int(oc.seq_lens[b])
+        for n in range(-(-L // 128)):
+            p, m = int(oc.block_table[b, n]), min(128, L - n * 128)
+            for name in ("k_codes", "k_scales", "v_scales"):
+                assert np.array_equal(got[name][p, :, :m], getattr(oc, name)[p, :, :m]), (what, name, b, n)
+            assert np.array_equal(got["v_codes"][p], oc.v_codes[p]), (what, "v_codes", b, n)
+
+
+def _paged_mx_decode_check(gc, oc, w, q, ns, what):
+    """Same bar as the contiguous MXFP4 cache: the fp32 partials against the oracle, the bf16
+    output within one bf16 step of them."""
+    import torch
+    out = torch.full((w.batch, w.n_q_heads, 128), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    gc.decode_attn(to_dev(q, "bf16"), W.softmax_scale(w), out, ns)
+    with np.errstate(invalid="ignore", divide="ignore"):
+        exact = _host_combine(gc, w, ns)
+    ref = O.decode_attn(oc, q, W.softmax_scale(w))
+    empty = np.repeat(np.asarray(oc.seq_lens) == 0, w.n_q_heads * 128).reshape(ref.shape)
+    exact[empty] = 0.0
+    assert_attn_close(exact, ref, what + " (fp32 partials)", large_outputs=True)
+    got = out_to_f64(out)
+    assert np.all(np.abs(got - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-12), what + " (bf16 rounding)"
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (12, 1)])
+def test_paged_mx_prefill_append_and_decode_match_oracle(hq, hkv):
+    """MXFP4 in pages: ragged batch (an empty sequence, one that ends on a block boundary, partial
+    last blocks), bytes bit-exact after prefill and after appends that open new pages, attention
+    within tolerance at several split factors."""
+    lens = [1000, 0, 127, 128 * 5, 37]
+    oc, gc, _ = _paged_mx_pair(lens, hkv, hq, num_pages=64, max_pages=10)
+    _assert_paged_mx_equal(oc, gc, "mx paged prefill")
+    w = W.scaled(W.CONFIGS["cfg4"], batch=len(lens), n_q_heads=hq, n_kv_heads=hkv, context=128, seed=78)
+    for ns in (1, 3, 8):
+        _paged_mx_decode_check(gc, oc, w, W.make_q(w, 9), ns, f"mx paged prefill ns {ns}")
+    for step in range(4):
+        kn, vn = W.make_new_kv(w, step)
+        oc.append_kv(kn, vn)
+        gc.append_kv(to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+        for ns in ((1, 3, 8) if step in (0, 3) else (2,)):
+            _paged_mx_decode_check(gc, oc, w, W.make_q(w, step), ns, f"mx paged step {step} ns {ns}")
+    _assert_paged_mx_equal(oc, gc, "mx paged after appends")
+    assert int(gc.status.item()) == 0
+
+
+def test_paged_mx_bad_table_entries_are_skipped_and_reported():
+    """MXFP4 needs a page for every token: an append into a block whose entry is outside the pool is
+    dropped and flagged (bit 1), the length stays; decode skips such a block and flags bit 0."""
+    import torch
+    H, Hq = 1, 4
+    good = np.array([[3, 1, 2], [0, 2, 1]], np.int32)
+    oc, gc, _ = _paged_mx_pair([255, 200], H, Hq, num_pages=4, max_pages=3, table=good)
+    gc.block_table.copy_(torch.from_numpy(np.array([[3, 1, 9], [0, 2, -1]], np.int32)))
+    w = W.scaled(W.CONFIGS["cfg4"], batch=2, n_q_heads=Hq, n_kv_heads=H, context=128, seed=5)
+    for step in range(3):
+        kn, vn = W.make_new_kv(w, step)
+        gc.append_kv(to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+    torch.cuda.synchronize()
+    # sequence 0: token 255 fits block 1, tokens 256 and 257 need block 2 (entry 9): dropped
+    assert list(gc.seq_lens.cpu().numpy()) == [256, 203] and int(gc.status.item()) == 2
+    gc.status.zero_()
+    gc.block_table.copy_(torch.from_numpy(np.array([[77, 1, 2], [0, 2, 1]], np.int32)))
+    out = torch.empty((2, Hq, 128), dtype=torch.bfloat16, device="cuda:0")
+    gc.decode_attn(to_dev(W.make_q(w), "bf16"), W.softmax_scale(w), out, 2)
+    torch.cuda.synchronize()
+    assert int(gc.status.item()) == 1 and torch.isfinite(out.float()).all()
+    # sequence 1 has only good entries: its output is the oracle's after the same three appends
+    for step in range(3):
+        kn, vn = W.make_new_kv(w, step)
+        oc._store_token(1, int(oc.seq_lens[1]), kn[1], vn[1]); oc.seq_lens[1] += 1
+    ref = O.decode_attn(oc, W.make_q(w), W.softmax_scale(w), units=[(1, 0)])
+    got = out_to_f64(out)
+    mask = ~np.isnan(ref)
+    assert np.all(np.abs(got - ref)[mask] <= np.abs(ref[mask]) * 2.0 ** -7 + 2e-3)
+
+
+def test_paged_mx_long_batch_sampled_units():
+    """cfg4 head geometry (g_q = 4), lengths to just over 16K on scattered pages, split factor as
+    the library picks it; sampled units against the oracle."""
+    lens = [16384 + 5, 4096, 100]
+    H, Hq = 8, 32
+    max_pages = 130
+    oc, gc, _ = _paged_mx_pair(lens, H, Hq, num_pages=len(lens) * max_pages + 3, max_pages=max_pages, seed=93)
+    w = W.scaled(W.CONFIGS["cfg4"], batch=len(lens), seed=94)
+    kn, vn = W.make_new_kv(w, 0)
+    oc.append_kv(kn, vn)
+    gc.append_kv(to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+    shape = B.bd_cache(len(lens), Hq, H, 128, B.BD_FMT_MXFP4, 128 * max_pages, None, None, None, None, None, None)
+    ns = B.bd_choose_splits(shape, 16384)
+    import torch
+    out = torch.empty((len(lens), Hq, 128), dtype=torch.bfloat16, device="cuda:0")
+    q = W.make_q(w, 1)
+    gc.decode_attn(to_dev(q, "bf16"), W.softmax_scale(w), out, ns)
+    with np.errstate(invalid="ignore", divide="ignore"):
+        exact = _host_combine(gc, w, ns)
+    units = [(0, 0), (0, 6), (1, 3), (2, 7)]
+    assert_attn_close(exact, O.decode_attn(oc, q, W.softmax_scale(w), units=units), "mx paged long", large_outputs=True)
+    assert list(gc.seq_lens.cpu().numpy()) == [L + 1 for L in lens] and int(gc.status.item()) == 0
+
+
 # ---------------------------------------------------------------------------- query groups
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])

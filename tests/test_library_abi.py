@@ -125,7 +125,9 @@ def test_paged_sizes_and_argument_validation():
         pool * 128 * 64, pool * 128 * 64, pool * 128 * 4, pool * 128 * 4, 4 * 8 * 128 * 128 * 2, 4 * 8 * 128 * 128 * 2,
         4 * 10 * 4, 4 * 4]
     assert B.bd_paged_cache_bytes(_paged(format=B.BD_FMT_INT2), 0) == pool * 128 * 32
-    assert B.bd_paged_cache_bytes(_paged(format=B.BD_FMT_MXFP4), 0) == 0          # not built for MXFP4
+    mx = _paged(format=B.BD_FMT_MXFP4)                    # no residual: every token is quantized on arrival
+    assert [B.bd_paged_cache_bytes(mx, i) for i in range(8)] == [
+        pool * 128 * 64, pool * 128 * 64, pool * 128 * 4, pool * 128 * 4, 0, 0, 4 * 10 * 4, 4 * 4]
     assert B.bd_paged_cache_bytes(_paged(num_pages=0), 0) == 0
     assert B.bd_paged_workspace_bytes(c, 16) == 16 * 4 * 32 * 130 * 4
     L = B.lib()
@@ -141,6 +143,11 @@ def test_paged_sizes_and_argument_validation():
     assert L.bd_paged_decode_attn(ctypes.byref(c), 16, ctypes.c_float(0.1), 4, 16, None, None) == -1
     c.seq_lens = 4098
     assert L.bd_paged_append_kv(ctypes.byref(c), 16, 16, None) == -3
+    for name in ("k_codes", "v_codes", "k_params", "v_params", "block_table", "seq_lens"):
+        setattr(mx, name, 4096)
+    # MXFP4 keeps partly filled blocks in pages: 128 * 10 + 1 tokens need an eleventh table column
+    assert L.bd_paged_quant_pack_kv(ctypes.byref(mx), 0, 16, 16, 128 * 10 + 1, None) == -4
+    assert L.bd_paged_quant_pack_kv(ctypes.byref(mx), 0, 16, 20, 128, None) == -3
 
 
 @needs_lib
