@@ -12,6 +12,13 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// workgroups per split and sequence: KV heads x pieces of the query group
+long group_workgroups(const bd_cache* c) {
+  const int gq = c->n_q_heads / c->n_kv_heads;
+  const int pieces = c->format == BD_FMT_MXFP4 ? ((gq + 3) / 4 + 1) / 2 : (gq + 15) / 16;
+  return (long)c->n_kv_heads * pieces;
+}
+
 bd_status check_shape(const bd_cache* c) {
   if (!c) return BD_ERR_INVALID_ARG;
   if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return BD_ERR_INVALID_ARG;
@@ -19,11 +26,10 @@ bd_status check_shape(const bd_cache* c) {
   if (!fmt_is_int(c->format) && c->format != BD_FMT_MXFP4) return BD_ERR_INVALID_ARG;
   if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
   if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;
-  // query heads per KV head: the int4 / int2 kernels pad the group to 4, 8 or 16 MFMA columns;
-  // the MXFP4 kernel takes them 4 at a time
-  const int gq = c->n_q_heads / c->n_kv_heads;
-  if (gq > 16) return BD_ERR_UNSUPPORTED;
-  if (c->format == BD_FMT_MXFP4 && (long)c->n_kv_heads * ((gq + 3) / 4) > 65535) return BD_ERR_UNSUPPORTED;
+  // query heads per KV head: the int4 / int2 kernels pad the group to 4, 8 or 16 MFMA columns and
+  // take larger groups 16 heads per workgroup; the MXFP4 kernel takes them 4 at a time, 8 per
+  // workgroup.  The workgroups of one split must fit grid dimension y.
+  if (group_workgroups(c) > 65535) return BD_ERR_UNSUPPORTED;
   return BD_OK;
 }
 
@@ -75,14 +81,14 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   // quantum is 4 blocks.  The kernel keeps 2 workgroups resident per compute unit (256 CUs):
   // aim at one full round of 512 workgroups over all (sequence, KV head) units, then
   // rebalance so that every split gets the same number of quanta.
-  const int units = c->batch * c->n_kv_heads;
+  const long units = (long)c->batch * group_workgroups(c);
   const int nb = (packed_len + kBlock - 1) / kBlock;
   const int quanta = (nb + 3) / 4;
   // Up to three workgroups per compute unit fit when no wave has more than one block (that kernel
   // instance needs half the registers; groups of up to 8 heads, integer formats): then one block
   // per wave beats two blocks for some waves and one for others.  Measured at 40K and 48K tokens.
   if (c->format != BD_FMT_MXFP4 && c->n_q_heads / c->n_kv_heads <= 8 && (long)quanta * units <= 768) return quanta;
-  int want = (512 + units - 1) / units;
+  int want = (int)((512 + units - 1) / units);
   if (want < 1) want = 1;
   int splits = quanta < want ? quanta : want;
   const int per = (quanta + splits - 1) / splits;

@@ -221,11 +221,19 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   __shared__ float res_s[kBlock][GQP];       // scores of this workgroup's residual tokens, per head
   __shared__ __attribute__((aligned(16))) float q_s[HP > 1 ? GQP : 1][kD];   // larger groups: queries * softmax_scale * log2(e); padding heads zero
 
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int split = blockIdx.x, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;            // MFMA column and contraction group
   const int head = col % GQP, cg = col / GQP;          // head carried by the column; column group
-  const int gq = a.gq;
+  // Query groups of more than 16 heads are taken 16 at a time by ceil(g_q / 16) workgroups per
+  // (split, KV head), each of which reads the cache once.
+  int hkv = blockIdx.y, head0 = 0;
+  if (GQP == 16 && a.gq > 16) {
+    const int nchunk = (a.gq + 15) >> 4;
+    hkv = blockIdx.y / nchunk;
+    head0 = 16 * (blockIdx.y % nchunk);
+  }
+  const int gq = min(a.gq - head0, 16);                // heads of this workgroup
   WL& wl = reinterpret_cast<WL*>(smem_raw)[wave];
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
@@ -240,7 +248,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
   // this workgroup's slice of the fp16 residual tokens
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
-  const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * gq) * kD;
+  const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * a.gq + head0) * kD;
 
   float m_run = -INFINITY;   // running max of this lane's head (log2 units), equal in all lanes of the head
   float l_run = 0.0f;        // running sum of p over this lane's own tokens
@@ -325,7 +333,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     }
     load_res_keys(wave);
   }
-  if (a.new_slot >= 0 && split == 0 && tid < 32) {   // fused step: file the new token for later steps
+  if (a.new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
     uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
@@ -760,7 +768,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
           if (t < nres) fold(t, vres_pre[t]);
         for (int t = kResPre; t < nres; ++t) fold(t, *reinterpret_cast<const uint32_t*>(vres_row(rt0 + t) + c0));
       }
-      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * gq + h;
+      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * a.gq + head0 + h;
       float2 o = {o0 + Z, o1 + Z};
       *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
       if ((tid & 63) == 0) {
@@ -897,7 +905,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.seq_lens = nullptr;
   a.status = nullptr;
   a.max_pages = a.num_pages = 0;
-  dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
+  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
   const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
   launch_instance(c->format, a.gq, single, false, a, grid, block, st);
   return hipGetLastError();
@@ -928,7 +936,7 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.status = c->status;
   a.max_pages = c->max_pages_per_seq;
   a.num_pages = c->num_pages;
-  dim3 grid(num_splits, c->n_kv_heads, c->batch), block(256);
+  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
   launch_instance(c->format, a.gq, false, true, a, grid, block, st);
   return hipGetLastError();
 }

@@ -321,7 +321,7 @@ def _mx_decode_check(gc, oc_ref, w, q, ns, what):
     return ma, rl
 
 
-@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2), (12, 1), (5, 1)])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2), (12, 1), (5, 1), (21, 1), (64, 2)])
 @pytest.mark.parametrize("L", [128 * 9 + 37, 128 * 4, 77])
 def test_mx_decode_matches_oracle(hq, hkv, L):
     w = W.scaled(W.CONFIGS["cfg4"], batch=2, n_q_heads=hq, n_kv_heads=hkv, context=L)
@@ -667,10 +667,10 @@ def test_paged_mx_long_batch_sampled_units():
 # ---------------------------------------------------------------------------- query groups
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])
-@pytest.mark.parametrize("gq", [1, 3, 5, 8, 12, 16])
+@pytest.mark.parametrize("gq", [1, 3, 5, 8, 12, 16, 20, 32, 40])
 def test_query_group_sizes(fmt, gq):
-    """Any number of query heads per KV head up to 16 (Sec. IV-A: the group forms the N dimension of
-    the matrix instructions): short context (one block per wave) and longer (several), with a
+    """Any number of query heads per KV head (Sec. IV-A: the group forms the N dimension of the
+    matrix instructions; beyond 16 heads the group is taken 16 at a time): short context (one block per wave) and longer (several), with a
     residual tail, several split factors, and the fused step."""
     import torch
     H = 2
@@ -692,17 +692,18 @@ def test_query_group_sizes(fmt, gq):
                           large_outputs=True)
 
 
-def test_paged_with_eight_query_heads_per_kv_head():
+@pytest.mark.parametrize("Hq", [16, 48])
+def test_paged_with_larger_query_groups(Hq):
     import torch
     lens = [700, 129, 3000]
-    H, Hq = 2, 16
+    H = 2
     oc, gc, _ = _paged_pair("int4", lens, H, Hq, num_pages=80, max_pages=25, seed=55)
     w = W.scaled(W.CONFIGS["cfg1"], batch=len(lens), n_q_heads=Hq, n_kv_heads=H, context=128, seed=56)
     out = torch.empty((len(lens), Hq, 128), dtype=torch.float16, device="cuda:0")
     q = W.make_q(w)
     gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, 4)
     torch.cuda.synchronize()
-    assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), "paged gq=8", large_outputs=True)
+    assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"paged gq={Hq // 2}", large_outputs=True)
 
 
 # ---------------------------------------------------------------------------- per-token K (KT)

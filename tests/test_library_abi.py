@@ -94,9 +94,10 @@ def test_argument_validation_happens_before_any_launch():
                             4096, None) == -3
     assert (pl.value, rl.value) == (1024, 5)
     # shapes this build has no kernel for
-    bad = _desc(n_q_heads=8 * 17)                                      # 17 query heads per KV head
+    assert B.bd_cache_bytes(_desc(n_q_heads=64), 0) > 0                # 8 per KV head
+    assert B.bd_cache_bytes(_desc(n_q_heads=8 * 40), 0) > 0            # 40 per KV head: 16 at a time
+    bad = _desc(n_kv_heads=40000, n_q_heads=40000 * 17)                # 2 x 40000 workgroups per split
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
-    assert B.bd_cache_bytes(_desc(n_q_heads=64), 0) > 0                # 8 per KV head is built for int4 / int2
     bad = _desc(batch=65536)                                           # beyond the launch grid
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
     assert B.bd_cache_bytes(bad, 0) == 0
