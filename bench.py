@@ -25,20 +25,31 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 N_LAYERS = 32
+# packed K + packed V + their parameters, per token and KV head
+PER_TOKEN_BYTES = {"int4": 136, "int2": 72, "mxfp4": 136, "int4_kt": 136, "int2_kt": 72}
+VARIANTS = {
+    "": "the configuration as listed",
+    "paged": "the same tokens in a paged cache (128-token pages scattered over a pool, lengths on the device): "
+             "bd_paged_decode_step per layer",
+    "kt": "K quantized per token instead of per channel (formats int4_kt / int2_kt)",
+    "gq8": "8 query heads per KV head (64/8 heads)",
+    "gq16": "16 query heads per KV head (128/8 heads)",
+}
 
 
 def algorithmic_bytes(w, packed_len: int, res_len: int) -> int:
     """Bytes one attention call must move: packed K and V codes, their parameters, the
     residual fp16 tokens present, the query and the output."""
     units = w.batch * w.n_kv_heads
-    per_tok = {"int4": 136, "int2": 72, "mxfp4": 136}[w.fmt]
     qo = 2 * w.batch * w.n_q_heads * w.head_dim * 2
-    return units * (packed_len * per_tok + res_len * w.head_dim * 2 * 2) + qo
+    return units * (packed_len * PER_TOKEN_BYTES[w.fmt] + res_len * w.head_dim * 2 * 2) + qo
 
 
-def measured_traffic(w):
+def measured_traffic(w, variant: str):
     """HBM bytes per decode-kernel launch from the committed rocprofv3 --pmc summary of this
     workload (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy), or None."""
+    if variant:
+        return None
     path = os.path.join(ROOT, "profiles", f"decode_{w.fmt}_{w.name}_pmc.txt")
     try:
         for line in open(path):
@@ -55,6 +66,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg1", help="cfg1 (32K int4, default), cfg3 (128K int4), cfg2, cfg0")
+    ap.add_argument("--variant", default="", choices=sorted(VARIANTS),
+                    help="a variation of the workload: " + "; ".join(f"{k or '(none)'}: {v}" for k, v in VARIANTS.items()))
     ap.add_argument("--layers", type=int, default=N_LAYERS)
     ap.add_argument("--mode", default="eager", choices=["graph", "eager"],
                     help="graph: the warm-up steps and the timed steps are each captured into one HIP graph "
@@ -89,6 +102,11 @@ def main() -> int:
         return 0
     B.lib()  # fail loudly if the HIP library is missing
     w = W.CONFIGS[args.workload]
+    if args.variant == "kt":
+        w = W.scaled(w, fmt=w.fmt + "_kt")
+    elif args.variant in ("gq8", "gq16"):
+        w = W.scaled(w, n_q_heads=int(args.variant[2:]) * w.n_kv_heads)
+    paged = args.variant == "paged"
     total_steps = args.warmup + args.steps
     cap = ((w.context + total_steps + 1 + 127) // 128) * 128 + 128
     tdt = torch.float16 if w.in_dtype == "fp16" else torch.bfloat16
@@ -103,33 +121,60 @@ def main() -> int:
     K, V = W.make_kv(w)
     Kd, Vd = dev(K), dev(V)
     caches = []
-    for _ in range(args.layers):
-        c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, cap)
-        c.quant_pack_kv(Kd, Vd)
+    max_pages = cap // 128
+    for li in range(args.layers):
+        if paged:
+            # every layer its own pool; the pages of a sequence are scattered over it
+            num_pages = w.batch * max_pages + 16
+            table = np.random.default_rng(1000 + li).permutation(num_pages)[:w.batch * max_pages]
+            c = B.PagedKVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, num_pages,
+                               table.reshape(w.batch, max_pages).astype(np.int32))
+            for b in range(w.batch):
+                c.quant_pack_kv(b, Kd[b], Vd[b])
+        else:
+            c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, cap)
+            c.quant_pack_kv(Kd, Vd)
         caches.append(c)
     torch.cuda.synchronize()
     # prefill quantize+pack time of one layer (reported, not part of the step)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(); caches[0].quant_pack_kv(Kd, Vd); e1.record(); torch.cuda.synchronize()
+    e0.record()
+    if paged:
+        for b in range(w.batch):
+            caches[0].quant_pack_kv(b, Kd[b], Vd[b])
+    else:
+        caches[0].quant_pack_kv(Kd, Vd)
+    e1.record(); torch.cuda.synchronize()
     prefill_ms = e0.elapsed_time(e1)
     del Kd, Vd
     new_kv = [tuple(dev(x) for x in W.make_new_kv(w, s)) for s in range(total_steps)]
     qs = [dev(W.make_q(w, s)) for s in range(total_steps)]
     outs = [torch.empty((w.batch, w.n_q_heads, 128), dtype=tdt, device="cuda:0") for _ in range(args.layers)]
     sm_scale = W.softmax_scale(w)
-    splits = args.splits or caches[0].choose_splits()
+    shape = B.bd_cache(w.batch, w.n_q_heads, w.n_kv_heads, 128, B.FORMATS[w.fmt], cap, None, None, None, None, None,
+                       None)
+    splits = args.splits or B.bd_choose_splits(shape, w.context)
     for c in caches:
         c.workspace(splits)
     setup_s = time.time() - t_setup
 
     step_bytes = []
+    mx = w.fmt == "mxfp4"
+
+    def lengths(n_tokens: int):
+        """(packed, residual) token counts of a sequence of n_tokens."""
+        return (n_tokens, 0) if mx else (n_tokens - n_tokens % 128, n_tokens % 128)
 
     def run_step(s: int):
         kn, vn = new_kv[s]
         nbytes = 0
         for li, c in enumerate(caches):
-            c.decode_step(kn, vn, qs[s], sm_scale, outs[li], num_splits=splits)
-            nbytes += algorithmic_bytes(w, c.packed_len, c.res_len)
+            if paged:   # the lengths live on the device; the host knows them by counting
+                c.decode_step(kn, vn, qs[s], sm_scale, outs[li], splits)
+                nbytes += algorithmic_bytes(w, *lengths(w.context + s + 1))
+            else:
+                c.decode_step(kn, vn, qs[s], sm_scale, outs[li], num_splits=splits)
+                nbytes += algorithmic_bytes(w, c.packed_len, c.res_len)
         step_bytes.append(nbytes)
 
     stream = torch.cuda.current_stream()
@@ -162,7 +207,7 @@ def main() -> int:
             run_step(s)
             if args.per_step:
                 eb.record(stream)
-                step_events.append((s, caches[0].packed_len, caches[0].res_len, ea, eb))
+                step_events.append((s, *(lengths(w.context + s + 1) if paged else (caches[0].packed_len, caches[0].res_len)), ea, eb))
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         if args.per_step:
@@ -186,22 +231,25 @@ def main() -> int:
     for rep in range(reps + 1):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream)
-        for c in caches:
-            B.bd_decode_attn(c.desc, qs[-1], c.packed_len, c.res_len, sm_scale, splits, c.workspace(splits), None)
+        for li, c in enumerate(caches):
+            if paged:   # this entry point always merges: the figure includes the combine kernel
+                c.decode_attn(qs[-1], sm_scale, outs[li], splits)
+            else:
+                B.bd_decode_attn(c.desc, qs[-1], c.packed_len, c.res_len, sm_scale, splits, c.workspace(splits), None)
         b.record(stream)
         torch.cuda.synchronize()
         if rep:
             per_rep.append(a.elapsed_time(b) * 1e3 / len(caches))
     kernel_us = float(np.mean(per_rep))
-    launch_bytes = algorithmic_bytes(w, c0.packed_len, c0.res_len)
+    launch_bytes = algorithmic_bytes(w, *(lengths(w.context + total_steps) if paged else (c0.packed_len, c0.res_len)))
     achieved = launch_bytes / (kernel_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_int_kernel" if w.fmt != "mxfp4" else "decode_mx_kernel",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(w),
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(w, args.variant),
                 "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(np.min(per_rep)), 3),
                 "bytes_per_launch": launch_bytes,
                 "timing": f"hip events around {len(caches)} back-to-back launches (one per cold layer cache), "
-                          f"{reps} repetitions"}
+                          f"{reps} repetitions" + (" (paged entry point: decode + combine kernels)" if paged else "")}
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
@@ -209,12 +257,12 @@ def main() -> int:
         from threadpoolctl import threadpool_limits
         from oracle import bitdecode_oracle as O
         n_units = min(2, w.batch * w.n_kv_heads)
-        per_tok = {"int4": 136, "int2": 72, "mxfp4": 136}[w.fmt]
+        per_tok = PER_TOKEN_BYTES[w.fmt]
         with threadpool_limits(limits=1):
             if w.fmt == "mxfp4":
                 oc = O.MxCache(1, n_units, cap)
             else:
-                oc = O.IntCache(1, n_units, 4 if w.fmt == "int4" else 2, cap)
+                oc = O.IntCache(1, n_units, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token=w.fmt.endswith("_kt"))
             oc.quant_pack_kv(K[:1, :n_units], V[:1, :n_units])          # untimed: prefill
             nsteps, sample_bytes = 0, 0
             tc0 = time.perf_counter()
@@ -239,11 +287,11 @@ def main() -> int:
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"int4": "u4->f16 mfma, f32 accumulate", "int2": "u2->f16 mfma, f32 accumulate",
-                  "mxfp4": "e2m1 mfma, f32 accumulate"}[w.fmt],
+                  "mxfp4": "e2m1 mfma, f32 accumulate"}[w.fmt.replace("_kt", "")],
         "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads}/{w.n_kv_heads} heads, head_dim 128, "
-                               f"context {w.context}, {w.fmt} KV", "layers": args.layers, "mode": args.mode,
-                   "num_splits": splits},
+                               f"context {w.context}, {w.fmt} KV" + (f", variant {args.variant}" if args.variant else ""),
+                   "layers": args.layers, "mode": args.mode, "num_splits": splits},
         "us_per_layer_call": round(ms_per_step * 1e3 / args.layers, 3),
         "us_per_decode_step": round(ms_per_step * 1e3, 2),
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),

@@ -225,6 +225,15 @@ bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const v
 bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float softmax_scale,
                                int32_t num_splits, void* workspace, void* out, void* stream);
 
+/* One decode step of every sequence (Sec. III-A(1), IV-B: the step's append and its attention
+ * in one call): the same results, bit for bit, as bd_paged_append_kv followed by
+ * bd_paged_decode_attn, in three kernel launches instead of four (the lengths are raised by
+ * the merge, the last kernel, instead of by a launch of their own).  A sequence whose token
+ * is dropped for want of a valid page (bit 1 of *status) attends the tokens it had. */
+bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const void* v_new,
+                               const void* q, float softmax_scale, int32_t num_splits,
+                               void* workspace, void* out, void* stream);
+
 /* Text for a status code (static storage). */
 const char* bd_strerror(bd_status s);
 

@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.bd_paged_quant_pack_kv.restype, L.bd_paged_quant_pack_kv.argtypes = ctypes.c_int, [PP, I, V, V, I, V]
         L.bd_paged_append_kv.restype, L.bd_paged_append_kv.argtypes = ctypes.c_int, [PP, V, V, V]
         L.bd_paged_decode_attn.restype, L.bd_paged_decode_attn.argtypes = ctypes.c_int, [PP, V, F, I, V, V, V]
+        L.bd_paged_decode_step.restype, L.bd_paged_decode_step.argtypes = ctypes.c_int, [PP, V, V, V, F, I, V, V, V]
         L.bd_strerror.restype, L.bd_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
         L.bd_last_hip_error.restype, L.bd_last_hip_error.argtypes = ctypes.c_int, []
         _lib = L
@@ -80,7 +81,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
            "bd_decode_attn", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
            "bd_paged_cache_bytes", "bd_paged_workspace_bytes", "bd_paged_quant_pack_kv", "bd_paged_append_kv",
-           "bd_paged_decode_attn"]
+           "bd_paged_decode_attn", "bd_paged_decode_step"]
 
 
 def _ptr(t):
@@ -169,6 +170,12 @@ def bd_paged_append_kv(c: bd_paged_cache, k_new, v_new, stream=None):
 def bd_paged_decode_attn(c: bd_paged_cache, q, softmax_scale: float, num_splits: int, workspace, out, stream=None):
     _check(lib().bd_paged_decode_attn(ctypes.byref(c), _ptr(q), softmax_scale, num_splits, _ptr(workspace), _ptr(out),
                                       _stream(stream)), "bd_paged_decode_attn")
+
+
+def bd_paged_decode_step(c: bd_paged_cache, k_new, v_new, q, softmax_scale: float, num_splits: int, workspace, out,
+                         stream=None):
+    _check(lib().bd_paged_decode_step(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), softmax_scale, num_splits,
+                                      _ptr(workspace), _ptr(out), _stream(stream)), "bd_paged_decode_step")
 
 
 # ---- device-memory plumbing ------------------------------------------------------------------
@@ -283,6 +290,11 @@ class PagedKVCache:
 
     def decode_attn(self, q, softmax_scale: float, out, num_splits: int, stream=None):
         bd_paged_decode_attn(self.desc, q, softmax_scale, num_splits, self.workspace(num_splits), out, stream)
+        return out
+
+    def decode_step(self, k_new, v_new, q, softmax_scale: float, out, num_splits: int, stream=None):
+        bd_paged_decode_step(self.desc, k_new, v_new, q, softmax_scale, num_splits, self.workspace(num_splits), out,
+                             stream)
         return out
 
     def host_buffer(self, i: int):

@@ -311,7 +311,21 @@ bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const v
   if ((s = check_paged_buffers(c)) != BD_OK) return s;
   if (!k_new || !v_new) return BD_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(v_new)) return BD_ERR_ALIGNMENT;
-  return hip_status(launch_paged_append(c, k_new, v_new, (hipStream_t)stream));
+  return hip_status(launch_paged_append(c, k_new, v_new, true, (hipStream_t)stream));
+}
+
+// attention over the paged cache; `step`: the lengths still lack the token a preceding
+// launch_paged_append(bump = false) filed, and the merge raises them
+static bd_status paged_attention(const bd_paged_cache* c, const void* q, float softmax_scale, int32_t num_splits,
+                                 void* workspace, void* out, bool step, hipStream_t st) {
+  const bd_cache shape = shape_of(c);
+  float* part_o = ws_part_o(workspace);
+  float* part_ml = ws_part_ml(&shape, workspace, num_splits);
+  bd_status s = hip_status(c->format == BD_FMT_MXFP4
+                               ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st)
+                               : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st));
+  if (s != BD_OK) return s;
+  return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st, step ? c : nullptr));
 }
 
 bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float softmax_scale, int32_t num_splits,
@@ -321,15 +335,22 @@ bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float sof
   if ((s = check_paged_buffers(c)) != BD_OK) return s;
   if (!q || !workspace || !out || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(workspace) || !aligned16(out)) return BD_ERR_ALIGNMENT;
-  const bd_cache shape = shape_of(c);
-  hipStream_t st = (hipStream_t)stream;
-  float* part_o = ws_part_o(workspace);
-  float* part_ml = ws_part_ml(&shape, workspace, num_splits);
-  s = hip_status(c->format == BD_FMT_MXFP4
-                     ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, st)
-                     : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, st));
+  return paged_attention(c, q, softmax_scale, num_splits, workspace, out, false, (hipStream_t)stream);
+}
+
+bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const void* v_new, const void* q,
+                               float softmax_scale, int32_t num_splits, void* workspace, void* out, void* stream) {
+  bd_status s = check_paged_shape(c);
   if (s != BD_OK) return s;
-  return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st));
+  if ((s = check_paged_buffers(c)) != BD_OK) return s;
+  if (!k_new || !v_new || !q || !workspace || !out || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
+    return BD_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  // three launches instead of four: the append leaves the lengths alone, the attention kernel
+  // counts the new token in, and the merge, last in line, raises the lengths
+  if ((s = hip_status(launch_paged_append(c, k_new, v_new, false, st))) != BD_OK) return s;
+  return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, st);
 }
 
 const char* bd_strerror(bd_status s) {

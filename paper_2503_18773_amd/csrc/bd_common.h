@@ -41,9 +41,10 @@ hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, i
 
 hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k, const void* v, int L,
                                 hipStream_t st);
-hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, hipStream_t st);
+hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, bool bump,
+                               hipStream_t st);
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                               float* part_o, float* part_ml, hipStream_t st);
+                               float* part_o, float* part_ml, bool step, hipStream_t st);
 
 // k_new / v_new non-null: fused step -- residual token res_len-1 is read from k_new / v_new
 // ([B][Hkv][128]) and also stored into the residual buffers by the kernel.
@@ -51,11 +52,12 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
                              const void* k_new, const void* v_new, hipStream_t st);
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                  float* part_o, float* part_ml, hipStream_t st);
+                                  float* part_o, float* part_ml, bool step, hipStream_t st);
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale,
                             int num_splits, float* part_o, float* part_ml, hipStream_t st);
+// step_of: the paged cache whose fused step this merge ends (it then raises the lengths), or nullptr
 hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* part_ml, int nparts,
-                          void* out, hipStream_t st);
+                          void* out, hipStream_t st, const bd_paged_cache* step_of = nullptr);
 
 static inline float* ws_part_o(void* ws) { return reinterpret_cast<float*>(ws); }
 static inline float* ws_part_ml(const bd_cache* c, void* ws, int num_splits) {

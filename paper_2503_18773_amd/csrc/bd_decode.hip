@@ -82,6 +82,7 @@ struct DecodeArgs {
   const int32_t* seq_lens;
   int32_t* status;
   int max_pages, num_pages;
+  int step;            // paged: 1 when this launch is the attention of a fused step (see the kernel)
 };
 
 // ---- format traits ---------------------------------------------------------------------
@@ -240,6 +241,17 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   int nb = a.nb, res_len = a.res_len;
   if (PAGED) {
     int len = a.seq_lens[b];
+    if (a.step && len >= 0) {
+      // fused step: the preceding kernel has appended this step's token (unless it needed a page
+      // the table does not name) and the length is raised only after this kernel
+      bool ok = true;
+      if (len % kBlock == kBlock - 1) {
+        const int n = len / kBlock;
+        const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
+        ok = e >= 0 && e < a.num_pages;
+      }
+      len += ok ? 1 : 0;
+    }
     len = len < 0 ? 0 : len;
     nb = len / kBlock;
     res_len = len % kBlock;
@@ -785,14 +797,36 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 // once -- up to kBatch partials per round, one round for up to kGroups * kBatch partials -- and
 // merges them with a running maximum; the groups meet in LDS.
 constexpr int kCombineGroups = 8, kCombineBatch = 8;
+// Fused step of a paged cache: the merge is the last kernel of the step, so it also raises the
+// length of every sequence whose token was appended (same test as the append kernel).
+struct StepBump {
+  int32_t* seq_lens;            // nullptr: nothing to raise
+  const int32_t* block_table;
+  int n_q_heads, max_pages, num_pages;
+  int every_token;              // a page is needed by every token (MXFP4), not only by the 128th
+};
+
 template <bool BF16>
 __global__ __launch_bounds__(128 * kCombineGroups) void combine_kernel(const float* __restrict__ part_o,
                                                                         const float* __restrict__ part_ml,
                                                                         int nparts, int nrows,
-                                                                        uint16_t* __restrict__ out) {
+                                                                        uint16_t* __restrict__ out, StepBump bump) {
   constexpr int G = kCombineGroups, kBatch = kCombineBatch;
   __shared__ float sm[G][128], sl[G][128], so[G][128];
   const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, grp = tid >> 7;
+  if (bump.seq_lens && tid == 128 * G - 1 && row % bump.n_q_heads == 0) {   // one thread per sequence
+    const int b = row / bump.n_q_heads;
+    const int len = bump.seq_lens[b];
+    if (len >= 0) {
+      bool ok = true;
+      if (bump.every_token || len % kBlock == kBlock - 1) {
+        const int n = len / kBlock;
+        const int e = n < bump.max_pages ? bump.block_table[(size_t)b * bump.max_pages + n] : -1;
+        ok = e >= 0 && e < bump.num_pages;
+      }
+      if (ok) bump.seq_lens[b] = len + 1;
+    }
+  }
   float M = -INFINITY, L = 0.f, o = 0.f;
   for (int p0 = grp; p0 < nparts; p0 += G * kBatch) {
     float2 ml[kBatch];
@@ -905,6 +939,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.seq_lens = nullptr;
   a.status = nullptr;
   a.max_pages = a.num_pages = 0;
+  a.step = 0;
   dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
   const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
   launch_instance(c->format, a.gq, single, false, a, grid, block, st);
@@ -912,8 +947,9 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
 }
 
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                               float* part_o, float* part_ml, hipStream_t st) {
+                               float* part_o, float* part_ml, bool step, hipStream_t st) {
   DecodeArgs a;
+  a.step = step ? 1 : 0;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;
@@ -942,12 +978,21 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
 }
 
 hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* part_ml, int nparts, void* out,
-                          hipStream_t st) {
+                          hipStream_t st, const bd_paged_cache* step_of) {
   const int nrows = c->batch * c->n_q_heads;
+  StepBump bump{};
+  if (step_of) {
+    bump.seq_lens = step_of->seq_lens;
+    bump.block_table = step_of->block_table;
+    bump.n_q_heads = step_of->n_q_heads;
+    bump.max_pages = step_of->max_pages_per_seq;
+    bump.num_pages = step_of->num_pages;
+    bump.every_token = step_of->format == BD_FMT_MXFP4;
+  }
   if (c->format == BD_FMT_MXFP4)
-    combine_kernel<true><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
+    combine_kernel<true><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out, bump);
   else
-    combine_kernel<false><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out);
+    combine_kernel<false><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out, bump);
   return hipGetLastError();
 }
 

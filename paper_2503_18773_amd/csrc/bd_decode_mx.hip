@@ -46,6 +46,7 @@ struct MxArgs {
   const int32_t* seq_lens;
   int32_t* status;
   int max_pages, num_pages;
+  int step;   // paged: 1 when this launch is the attention of a fused step
 };
 
 template <int NG>
@@ -75,7 +76,17 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   auto sub_heads = [&](int gi) { return max(0, min(4, a.gq - 4 * (sub0 + gi))); };
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int length = a.length;
-  if (PAGED) length = max(0, a.seq_lens[b]);
+  if (PAGED) {
+    length = a.seq_lens[b];
+    if (a.step && length >= 0) {
+      // fused step: the preceding kernel has appended this step's token if the table names a
+      // page for it; the length is raised only after this kernel
+      const int n = length / kBlock;
+      const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
+      length += (e >= 0 && e < a.num_pages) ? 1 : 0;
+    }
+    length = max(0, length);
+  }
   const int nb = (length + kBlock - 1) / kBlock;
   const int blk0 = (int)(((long)nb * split) / a.num_splits);
   const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
@@ -373,8 +384,9 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
 }
 
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                  float* part_o, float* part_ml, hipStream_t st) {
+                                  float* part_o, float* part_ml, bool step, hipStream_t st) {
   MxArgs a{};
+  a.step = step ? 1 : 0;
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;
   a.k_scales = (const uint8_t*)c->k_params;

@@ -826,14 +826,15 @@ hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k,
   return hipGetLastError();
 }
 
-hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, hipStream_t st) {
+hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, bool bump,
+                               hipStream_t st) {
   const PagedArgs a = paged_args(c);
   dim3 grid(c->n_kv_heads, c->batch), block(256);
   const uint16_t *kk = (const uint16_t*)k_new, *vv = (const uint16_t*)v_new;
   if (c->format == BD_FMT_MXFP4) {
     mx_paged_append_kernel<<<grid, dim3(128), 0, st>>>(paged_mx_dst(c), c->block_table, c->seq_lens, kk, vv);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !bump) return e;
     paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch, true);
     return hipGetLastError();
   }
@@ -844,7 +845,7 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
     default: paged_append_kernel<2, true><<<grid, block, 0, st>>>(a, kk, vv); break;
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !bump) return e;
   paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(a, c->batch, false);
   return hipGetLastError();
 }

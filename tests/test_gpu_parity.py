@@ -664,6 +664,63 @@ def test_paged_mx_long_batch_sampled_units():
     assert list(gc.seq_lens.cpu().numpy()) == [L + 1 for L in lens] and int(gc.status.item()) == 0
 
 
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4"])
+def test_paged_fused_step_equals_append_then_attention(fmt):
+    """bd_paged_decode_step against bd_paged_append_kv + bd_paged_decode_attn on a twin cache:
+    outputs, pool bytes and lengths identical bit for bit over steps that cross block
+    boundaries, including a sequence whose next page is missing (its token is dropped, it
+    attends what it had, bit 1 of the status word); and against the oracle."""
+    import torch
+    mx = fmt == "mxfp4"
+    dt, tdt = ("bf16", torch.bfloat16) if mx else ("fp16", torch.float16)
+    H, Hq = 2, 8
+    lens = [126, 0, 300, 255]
+    table = np.random.default_rng(8).permutation(40)[:4 * 6].reshape(4, 6).astype(np.int32)
+    twins = []
+    for _ in range(2):
+        if mx:
+            oc, gc, _ = _paged_mx_pair(lens, H, Hq, num_pages=40, max_pages=6, table=table)
+        else:
+            oc, gc, _ = _paged_pair(fmt, lens, H, Hq, num_pages=40, max_pages=6, table=table)
+        twins.append(gc)
+    bad = table.copy(); bad[3, 2] = -5          # sequence 3 (255 tokens) has no page for its third block
+    for gc in twins:
+        gc.block_table.copy_(torch.from_numpy(bad))
+    a, b = twins
+    w = W.scaled(W.CONFIGS["cfg4" if mx else "cfg1"], batch=4, n_q_heads=Hq, n_kv_heads=H, context=128, seed=61)
+    outs = [torch.empty((4, Hq, 128), dtype=tdt, device="cuda:0") for _ in range(2)]
+    for step in range(5):
+        kn, vn, q = (to_dev(x, dt) for x in (*W.make_new_kv(w, step), W.make_q(w, step)))
+        ns = (1, 3, 2, 5, 4)[step]
+        a.decode_step(kn, vn, q, W.softmax_scale(w), outs[0], ns)
+        b.append_kv(kn, vn)
+        b.decode_attn(q, W.softmax_scale(w), outs[1], ns)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16)), step
+        assert torch.equal(a.seq_lens, b.seq_lens), step
+    # int formats drop sequence 3's token only when it would fill the residual (token 384 never arrives);
+    # MXFP4 needs the page from token 257 on
+    assert list(a.seq_lens.cpu().numpy()) == ([131, 5, 305, 256] if mx else [131, 5, 305, 260])
+    assert int(a.status.item()) == int(b.status.item()) == (2 if mx else 0)
+    for i in range(4 if mx else 6):
+        assert torch.equal(a.buffers[i], b.buffers[i]), i
+    # against the oracle (sequences 0..2, whose tables are intact)
+    for step in range(5):
+        kn, vn = W.make_new_kv(w, step)
+        for s_ in range(3):
+            if mx:
+                oc._store_token(s_, int(oc.seq_lens[s_]), kn[s_], vn[s_]); oc.seq_lens[s_] += 1
+        if not mx:
+            oc.append_kv(kn, vn)
+    ref = O.decode_attn(oc, W.make_q(w, 4), W.softmax_scale(w), units=[(s_, h) for s_ in range(3) for h in range(H)])
+    got = out_to_f64(outs[0])
+    if mx:
+        mask = ~np.isnan(ref)
+        assert np.all(np.abs(got - ref)[mask] <= np.abs(ref[mask]) * 2.0 ** -7 + 2e-3)
+    else:
+        assert_attn_close(got, ref, f"{fmt} paged fused step", large_outputs=True)
+
+
 # ---------------------------------------------------------------------------- query groups
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])
