@@ -91,6 +91,38 @@ def quantize_v_block(vblk: np.ndarray, bits: int):
     return quant_codes(vblk, scale[:, None], zero[:, None], bits), scale, zero
 
 
+def quantize_k_block_grouped(kblk: np.ndarray, bits: int, group: int):
+    """Channel-wise K with a quantization group of `group` tokens (Sec. IV-C(1): K_p has shape
+    (T_n / group_size, d)): K block [128 tokens, D] fp16 -> codes [128, D], scale and zero
+    [128 / group, D]; the statistics of channel c, group j run over tokens j*group .. (j+1)*group-1."""
+    assert kblk.shape[0] == BLOCK and kblk.dtype == np.float16 and BLOCK % group == 0
+    ng = BLOCK // group
+    codes = np.empty(kblk.shape, np.uint8)
+    scale = np.empty((ng, kblk.shape[1]), np.float16)
+    zero = np.empty((ng, kblk.shape[1]), np.float16)
+    for j in range(ng):
+        sub = kblk[j * group:(j + 1) * group]
+        scale[j], zero[j] = quant_params(sub.min(axis=0), sub.max(axis=0), bits)
+        codes[j * group:(j + 1) * group] = quant_codes(sub, scale[j][None, :], zero[j][None, :], bits)
+    return codes, scale, zero
+
+
+def quantize_v_block_grouped(vblk: np.ndarray, bits: int, group: int):
+    """Per-token V with a quantization group of `group` channels (V_p has shape
+    (T_n, d / group_size)): V block [128 tokens, D] fp16 -> codes [128, D], scale and zero
+    [128, D / group]; the statistics of token t, group g run over channels g*group .. (g+1)*group-1."""
+    assert vblk.shape[0] == BLOCK and vblk.dtype == np.float16 and vblk.shape[1] % group == 0
+    ng = vblk.shape[1] // group
+    codes = np.empty(vblk.shape, np.uint8)
+    scale = np.empty((BLOCK, ng), np.float16)
+    zero = np.empty((BLOCK, ng), np.float16)
+    for g in range(ng):
+        sub = vblk[:, g * group:(g + 1) * group]
+        scale[:, g], zero[:, g] = quant_params(sub.min(axis=1), sub.max(axis=1), bits)
+        codes[:, g * group:(g + 1) * group] = quant_codes(sub, scale[:, g][:, None], zero[:, g][:, None], bits)
+    return codes, scale, zero
+
+
 def pack_words(codes: np.ndarray, bits: int) -> np.ndarray:
     """Pack the last axis: 32/bits codes per little-endian uint32, code n of a word at
     bit offset bits*n."""
@@ -133,19 +165,30 @@ class IntCache:
                                               (k_per_token: per token of the block, [.., 128])
       v_params uint32 [B, H, NBcap, 128]      half2 (scale, zero) per token
       k_res, v_res fp16 [B, H, 128, D]        residual tokens, slots [0, res_len) valid
+
+    group (32 or 64; 128 is the above): the quantization group is smaller than the residual block.
+    K statistics run over `group` tokens per channel, V statistics over `group` channels per
+    token; the codes stay where they are and the parameter arrays grow to
+      k_params uint32 [B, H, NBcap, 128/group, D]      v_params uint32 [B, H, NBcap, 128, D/group]
     """
 
     def __init__(self, batch: int, n_kv_heads: int, bits: int, capacity: int, head_dim: int = 128,
-                 k_per_token: bool = False):
+                 k_per_token: bool = False, group: int = BLOCK):
         assert capacity % BLOCK == 0 and head_dim == 128
+        assert group in (32, 64, BLOCK) and not (k_per_token and group != BLOCK)
         self.B, self.H, self.D, self.bits, self.capacity = batch, n_kv_heads, head_dim, bits, capacity
         self.k_per_token = k_per_token          # KT: K statistics per token instead of per channel
+        self.group = group
         nbc = capacity // BLOCK
         wpr = head_dim * bits // 32
         self.k_codes = np.zeros((batch, n_kv_heads, nbc, BLOCK, wpr), np.uint32)
         self.v_codes = np.zeros((batch, n_kv_heads, nbc, head_dim, BLOCK * bits // 32), np.uint32)
-        self.k_params = np.zeros((batch, n_kv_heads, nbc, head_dim), np.uint32)
-        self.v_params = np.zeros((batch, n_kv_heads, nbc, BLOCK), np.uint32)
+        if group == BLOCK:
+            self.k_params = np.zeros((batch, n_kv_heads, nbc, head_dim), np.uint32)
+            self.v_params = np.zeros((batch, n_kv_heads, nbc, BLOCK), np.uint32)
+        else:
+            self.k_params = np.zeros((batch, n_kv_heads, nbc, BLOCK // group, head_dim), np.uint32)
+            self.v_params = np.zeros((batch, n_kv_heads, nbc, BLOCK, head_dim // group), np.uint32)
         self.k_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.v_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.packed_len = 0
@@ -155,9 +198,13 @@ class IntCache:
     def _store_block(self, nb: int, kblk: np.ndarray, vblk: np.ndarray):
         for b in range(self.B):
             for h in range(self.H):
-                quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
-                kc, ks, kz = quant_k(kblk[b, h], self.bits)
-                vc, vs, vz = quantize_v_block(vblk[b, h], self.bits)
+                if self.group != BLOCK:
+                    kc, ks, kz = quantize_k_block_grouped(kblk[b, h], self.bits, self.group)
+                    vc, vs, vz = quantize_v_block_grouped(vblk[b, h], self.bits, self.group)
+                else:
+                    quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
+                    kc, ks, kz = quant_k(kblk[b, h], self.bits)
+                    vc, vs, vz = quantize_v_block(vblk[b, h], self.bits)
                 self.k_codes[b, h, nb] = pack_words(kc, self.bits)              # [token][channel words]
                 self.v_codes[b, h, nb] = pack_words(vc.T.copy(), self.bits)     # [channel][token words]
                 self.k_params[b, h, nb] = pack_half2(ks, kz)
@@ -201,6 +248,11 @@ class IntCache:
             vc = unpack_words(self.v_codes[b, h, n], self.bits).astype(np.float64).T    # [c][t] -> [t][c]
             ks, kz = unpack_half2(self.k_params[b, h, n])
             vs, vz = unpack_half2(self.v_params[b, h, n])
+            if self.group != BLOCK:      # ks, kz [128/group, D]; vs, vz [128, D/group]
+                ks, kz, vs, vz = (x.astype(np.float64) for x in (ks, kz, vs, vz))
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * np.repeat(ks, self.group, axis=0) + np.repeat(kz, self.group, axis=0)
+                Vh[n * BLOCK:(n + 1) * BLOCK] = vc * np.repeat(vs, self.group, axis=1) + np.repeat(vz, self.group, axis=1)
+                continue
             if self.k_per_token:
                 Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[:, None] + kz.astype(np.float64)[:, None]
             else:
