@@ -71,7 +71,16 @@ typedef enum {
   BD_FMT_INT2 = 1,
   BD_FMT_MXFP4 = 2,
   BD_FMT_INT4_KT = 3,   /* K per token as well (the paper's KT setting, Sec. IV-C(1)) */
-  BD_FMT_INT2_KT = 4
+  BD_FMT_INT2_KT = 4,
+  /* K channel-wise, V per token, with a quantization group smaller than the 128-token residual
+   * block (Sec. IV-C(1): K_p of shape (T_n/group, d), V_p of shape (T_n, d/group)): K statistics
+   * over 64 or 32 tokens per channel, V statistics over 64 or 32 channels per token.  Codes as
+   * in BD_FMT_INT4 / INT2; k_params uint32 [B][H][NBcap][128/group][D], v_params uint32
+   * [B][H][capacity][D/group].  Contiguous cache only. */
+  BD_FMT_INT4_G64 = 5,
+  BD_FMT_INT4_G32 = 6,
+  BD_FMT_INT2_G64 = 7,
+  BD_FMT_INT2_G32 = 8
 } bd_format;
 
 /* Shape and buffers of one layer's cache.  Plain data, filled by the caller, passed by

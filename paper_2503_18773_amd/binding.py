@@ -9,8 +9,10 @@ import ctypes
 import os
 
 BD_FMT_INT4, BD_FMT_INT2, BD_FMT_MXFP4, BD_FMT_INT4_KT, BD_FMT_INT2_KT = 0, 1, 2, 3, 4
+BD_FMT_INT4_G64, BD_FMT_INT4_G32, BD_FMT_INT2_G64, BD_FMT_INT2_G32 = 5, 6, 7, 8
 FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4, "int4_kt": BD_FMT_INT4_KT,
-           "int2_kt": BD_FMT_INT2_KT}
+           "int2_kt": BD_FMT_INT2_KT, "int4_g64": BD_FMT_INT4_G64, "int4_g32": BD_FMT_INT4_G32,
+           "int2_g64": BD_FMT_INT2_G64, "int2_g32": BD_FMT_INT2_G32}
 BLOCK = 128
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbitdecode.so")

@@ -67,10 +67,11 @@ size_t bd_cache_bytes(const bd_cache* c, int which) {
     }
   }
   const size_t bits = (size_t)bits_of(c->format);
+  const size_t groups = (size_t)(kBlock / fmt_group(c->format));   // K token groups per block, V channel groups per token
   switch (which) {
     case 0: case 1: return units * cap * kD * bits / 8;
-    case 2: return units * (cap / kBlock) * kD * 4;
-    case 3: return units * cap * 4;
+    case 2: return units * (cap / kBlock) * groups * kD * 4;
+    case 3: return units * cap * groups * 4;
     default: return units * kBlock * kD * 2;
   }
 }
@@ -183,6 +184,7 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
     s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, st));
   } else {
     if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
+    if (fmt_group(c->format) != kBlock) return BD_ERR_UNSUPPORTED;
     s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, nullptr,
                                      nullptr, st));
   }
@@ -202,10 +204,10 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   const int pl = *packed_len, r = *res_len;
-  const bool fusable = c->format != BD_FMT_MXFP4 && r < kBlock - 1;
+  const bool fusable = c->format != BD_FMT_MXFP4 && fmt_group(c->format) == kBlock && r < kBlock - 1;
   if (!fusable) {
     // a step that fills the residual block (or an MXFP4 cache, whose tokens are quantized on
-    // arrival) runs as the two calls it is defined by
+    // arrival, or a cache with a smaller quantization group) runs as the two calls it is defined by
     if ((s = bd_append_kv(c, k_new, v_new, packed_len, res_len, stream)) != BD_OK) return s;
     return bd_decode_attn(c, q, *packed_len, *res_len, softmax_scale, num_splits, workspace, out, stream);
   }
@@ -250,6 +252,7 @@ static bd_status check_paged_shape(const bd_paged_cache* c) {
   bd_status st = check_shape(&s);
   if (st != BD_OK) return st;
   if (c->num_pages <= 0 || c->max_pages_per_seq <= 0) return BD_ERR_INVALID_ARG;
+  if (fmt_group(c->format) != kBlock) return BD_ERR_UNSUPPORTED;   // smaller groups: contiguous cache only
   return BD_OK;
 }
 

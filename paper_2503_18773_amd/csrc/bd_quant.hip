@@ -94,9 +94,10 @@ __device__ __forceinline__ h2_t dpp_h2(h2_t x) {
 }
 template <int N>
 __device__ __forceinline__ h2_t lanes_min(h2_t m) {
+  static_assert(N == 4 || N == 8 || N == 16 || N == 32, "lanes per row group");
   m = __builtin_elementwise_min(m, dpp_h2<0xB1>(m));    // quad_perm [1,0,3,2]
   m = __builtin_elementwise_min(m, dpp_h2<0x4E>(m));    // quad_perm [2,3,0,1]
-  m = __builtin_elementwise_min(m, dpp_h2<0x141>(m));   // row_half_mirror: the other quad of each 8
+  if (N >= 8) m = __builtin_elementwise_min(m, dpp_h2<0x141>(m));   // row_half_mirror: the other quad of each 8
   if (N >= 16) m = __builtin_elementwise_min(m, dpp_h2<0x140>(m));   // row_mirror: the other half of the row
   if (N >= 32) m = __builtin_elementwise_min(m, as_h2(__shfl_xor(as_u32(m), 16)));
   return m;
@@ -105,18 +106,23 @@ __device__ __forceinline__ h2_t lanes_min(h2_t m) {
 // quant_block: the whole workgroup (256 threads) quantizes the 128 token rows at ksrc / vsrc
 // ([128][128] fp16) into packed block `dblk` of the four destination arrays.
 // KT: K statistics per token (over its 128 channels) instead of per channel (Sec. IV-C(1)).
+// G: quantization group (128, 64 or 32; not with KT): K statistics over G tokens per channel --
+//    a wave holds 32 tokens, so the cross-wave step of the ladder joins G/32 waves -- and V
+//    statistics over G channels per token; parameters [block][128/G][D] and [block][128][D/G].
 // A thread holds 64 values of each tensor: for K, 64/CPT tokens x CPT consecutive channels (one
 // K word per token); for V, CPT consecutive tokens x 64/CPT channels (one V word per channel),
 // CPT = codes per word.  Minima and maxima are taken on the fp16 pairs as loaded (packed
 // instructions), across lanes with shuffles and, for channel-wise K, across waves through LDS
 // (the reduction ladder of Sec. IV-B(2)).
-template <int BITS, bool KT>
+template <int BITS, bool KT, int G = kBlock>
 __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                                             uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes,
                                             uint32_t* __restrict__ k_params, uint32_t* __restrict__ v_params,
                                             size_t dblk) {
   constexpr int QMAX = (1 << BITS) - 1;
   constexpr int CPT = 32 / BITS;     // codes per word
+  constexpr int NG = kBlock / G;     // K token groups per block == V channel groups per token
+  static_assert(!KT || G == kBlock, "per-token K has one group per token");
   __shared__ uint32_t red_lo[4][kD / 2], red_hi[4][kD / 2];   // per wave: packed fp16 minima / maxima of channel pairs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
@@ -191,18 +197,22 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
 #pragma unroll
       for (int i = 0; i < C / 2; ++i) {
         const int pi = cg * (C / 2) + i;
-        h2_t a = as_h2(red_lo[0][pi]), b = as_h2(red_hi[0][pi]);
+        // the G/32 waves that hold this wave's token group
+        constexpr int WPG = G / 32;
+        const int w0 = wave / WPG * WPG;
+        h2_t a = as_h2(red_lo[w0][pi]), b = as_h2(red_hi[w0][pi]);
 #pragma unroll
-        for (int w = 1; w < 4; ++w) {
-          a = __builtin_elementwise_min(a, as_h2(red_lo[w][pi]));
-          b = __builtin_elementwise_max(b, as_h2(red_hi[w][pi]));
+        for (int w = 1; w < WPG; ++w) {
+          a = __builtin_elementwise_min(a, as_h2(red_lo[w0 + w][pi]));
+          b = __builtin_elementwise_max(b, as_h2(red_hi[w0 + w][pi]));
         }
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           uint32_t packed;
           group_params((float)a[e], (float)b[e], QMAX, ks[2 * i + e], kz[2 * i + e], packed);
           kr[2 * i + e] = safe_rcp(ks[2 * i + e]);
-          if (tg == 0) k_params[dblk * kD + C * cg + 2 * i + e] = packed;
+          // first thread row of the token group writes its parameters
+          if (tid == w0 * 64 + cg) k_params[(dblk * NG + wave / WPG) * kD + C * cg + 2 * i + e] = packed;
         }
       }
 #pragma unroll
@@ -243,12 +253,13 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
         raw[0] = ld[0]; raw[1] = ld[1];
       }
       h2_t m = min_negmax<C / 2>(raw);
-      m = lanes_min<NCG>(m);   // the NCG consecutive lanes of this token row
+      constexpr int LPG = NCG / NG;   // consecutive lanes that hold one channel group of this token row
+      m = lanes_min<LPG>(m);
       float vs, vz;
       uint32_t packed;
       group_params((float)m[0], -(float)m[1], QMAX, vs, vz, packed);
       const float vr = safe_rcp(vs);
-      if (cg == 0) v_params[dblk * kBlock + row] = packed;
+      if (cg % LPG == 0) v_params[(dblk * kBlock + row) * NG + cg / LPG] = packed;
       float x[C];
 #pragma unroll
       for (int i = 0; i < C / 2; ++i) {
@@ -276,7 +287,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
 }
 
 // Contiguous cache: block blockIdx.x of unit blockIdx.y.
-template <int BITS, bool KT>
+template <int BITS, bool KT, int G>
 __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __restrict__ ksrc,
                                                            const uint16_t* __restrict__ vsrc,
                                                            long src_unit_stride, int src_tok0,
@@ -288,7 +299,7 @@ __global__ __launch_bounds__(256) void quant_block_kernel(const uint16_t* __rest
   const int unit = blockIdx.y, blk = blockIdx.x;
   const size_t dblk = (size_t)unit * nbcap + dst_blk0 + blk;
   const size_t src_off = (size_t)unit * src_unit_stride + ((size_t)src_tok0 + (size_t)blk * kBlock) * kD;
-  quant_block<BITS, KT>(ksrc + src_off, vsrc + src_off, k_codes, v_codes, k_params, v_params, dblk);
+  quant_block<BITS, KT, G>(ksrc + src_off, vsrc + src_off, k_codes, v_codes, k_params, v_params, dblk);
 }
 
 // ---- paged cache (page = one 128-token block; pool index of (page, head) = page * H + head) ---
@@ -747,20 +758,23 @@ hipError_t launch_quant_blocks(const void* k, const void* v, long src_unit_strid
   const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
   uint32_t *kc = (uint32_t*)c->k_codes, *vc = (uint32_t*)c->v_codes, *kp = (uint32_t*)c->k_params,
            *vp = (uint32_t*)c->v_params;
+#define BD_QUANT_CASE(FMT, BITS, KT, G)                                                                          \
+  case FMT:                                                                                                      \
+    quant_block_kernel<BITS, KT, G><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, \
+                                                            nbcap, dst_blk0);                                    \
+    break;
   switch (c->format) {
-    case BD_FMT_INT4:
-      quant_block_kernel<4, false><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
-      break;
-    case BD_FMT_INT2:
-      quant_block_kernel<2, false><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
-      break;
-    case BD_FMT_INT4_KT:
-      quant_block_kernel<4, true><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
-      break;
-    default:
-      quant_block_kernel<2, true><<<grid, block, 0, st>>>(kk, vv, src_unit_stride, src_tok0, kc, vc, kp, vp, nbcap, dst_blk0);
-      break;
+    BD_QUANT_CASE(BD_FMT_INT4, 4, false, 128)
+    BD_QUANT_CASE(BD_FMT_INT2, 2, false, 128)
+    BD_QUANT_CASE(BD_FMT_INT4_KT, 4, true, 128)
+    BD_QUANT_CASE(BD_FMT_INT2_KT, 2, true, 128)
+    BD_QUANT_CASE(BD_FMT_INT4_G64, 4, false, 64)
+    BD_QUANT_CASE(BD_FMT_INT4_G32, 4, false, 32)
+    BD_QUANT_CASE(BD_FMT_INT2_G64, 2, false, 64)
+    BD_QUANT_CASE(BD_FMT_INT2_G32, 2, false, 32)
+    default: return hipErrorInvalidValue;
   }
+#undef BD_QUANT_CASE
   return hipGetLastError();
 }
 

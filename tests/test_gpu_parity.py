@@ -11,13 +11,16 @@ from tests.util import assert_attn_close, out_to_f64, to_dev
 
 pytestmark = pytest.mark.gpu
 
-BITS = {"int4": 4, "int2": 2, "int4_kt": 4, "int2_kt": 2}
+BITS = {"int4": 4, "int2": 2, "int4_kt": 4, "int2_kt": 2, "int4_g64": 4, "int4_g32": 4, "int2_g64": 2, "int2_g32": 2}
+GROUP = {"int4_g64": 64, "int4_g32": 32, "int2_g64": 64, "int2_g32": 32}
+GROUP_FORMATS = sorted(GROUP)
 
 
 def _int_cache_pair(w, capacity):
     """Oracle cache and GPU cache prefilled from the same K, V."""
     K, V = W.make_kv(w)
-    oc = O.IntCache(w.batch, w.n_kv_heads, BITS[w.fmt], capacity, k_per_token=w.fmt.endswith("_kt"))
+    oc = O.IntCache(w.batch, w.n_kv_heads, BITS[w.fmt], capacity, k_per_token=w.fmt.endswith("_kt"),
+                    group=GROUP.get(w.fmt, 128))
     oc.quant_pack_kv(K, V)
     gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, capacity)
     gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
@@ -719,6 +722,44 @@ def test_paged_fused_step_equals_append_then_attention(fmt):
         assert np.all(np.abs(got - ref)[mask] <= np.abs(ref[mask]) * 2.0 ** -7 + 2e-3)
     else:
         assert_attn_close(got, ref, f"{fmt} paged fused step", large_outputs=True)
+
+
+# ---------------------------------------------------------------------------- quantization groups of 32 / 64
+
+@pytest.mark.parametrize("fmt", GROUP_FORMATS)
+@pytest.mark.parametrize("L", [128 * 5 + 37, 128 * 3, 90])
+def test_group_quant_pack_bit_exact(fmt, L):
+    w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=8, n_kv_heads=2, context=L, fmt=fmt)
+    _, _, oc, gc = _int_cache_pair(w, 1024)
+    _assert_int_cache_equal(oc, gc)
+
+
+@pytest.mark.parametrize("fmt", GROUP_FORMATS)
+def test_group_quant_adversarial_and_append_bit_exact(fmt):
+    """Constant groups next to live ones, extremes, subnormals and exact ties inside single 32- and
+    64-groups; then appends across a flush."""
+    rng = np.random.default_rng(6)
+    K = rng.standard_normal((1, 2, 200, 128)).astype(np.float16)
+    V = rng.standard_normal((1, 2, 200, 128)).astype(np.float16)
+    K[0, 0, 32:64, 3] = 1.5                      # one constant 32-group of a channel
+    K[0, 0, 64:128, 4] = -0.0
+    K[0, 0, 0, 5] = 65504; K[0, 0, 33, 5] = -65504
+    K[0, 0, 96:128, 6] = (rng.integers(0, 4, 32) * 6e-8).astype(np.float16)
+    K[0, 0, 0:32, 7] = np.array([0, 15] + [2.5, 3.5, 0.5, 1.5] * 7 + [7, 7], np.float16)
+    V[0, 1, 7, 32:64] = -2.25
+    V[0, 1, 8, 0] = 65504; V[0, 1, 8, 70] = -65504
+    V[0, 1, 9, 64:128] = (rng.integers(0, 3, 64) * 6e-8).astype(np.float16)
+    V[0, 1, 10, 96:128] = np.array([0, 3] + [0.5, 1.5, 2.5, 1.0] * 7 + [2, 2], np.float16)
+    w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=2, n_kv_heads=2, context=200, fmt=fmt, seed=9)
+    oc = O.IntCache(1, 2, BITS[fmt], 384, group=GROUP[fmt]); oc.quant_pack_kv(K, V)
+    gc = B.KVCache(1, 2, 2, fmt, 384); gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+    _assert_int_cache_equal(oc, gc)
+    for i in range(60):
+        kn, vn = W.make_new_kv(w, i)
+        oc.append_kv(kn, vn)
+        gc.append_kv(to_dev(kn, "fp16"), to_dev(vn, "fp16"))
+    assert (gc.packed_len, gc.res_len) == (256, 4)
+    _assert_int_cache_equal(oc, gc)
 
 
 # ---------------------------------------------------------------------------- query groups
