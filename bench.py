@@ -26,7 +26,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 N_LAYERS = 32
 # packed K + packed V + their parameters, per token and KV head
-PER_TOKEN_BYTES = {"int4": 136, "int2": 72, "mxfp4": 136, "int4_kt": 136, "int2_kt": 72}
+PER_TOKEN_BYTES = {"int4": 136, "int2": 72, "mxfp4": 136, "int4_kt": 136, "int2_kt": 72,
+                   "int4_g64": 144, "int4_g32": 160, "int2_g64": 80, "int2_g32": 96}
 VARIANTS = {
     "": "the configuration as listed",
     "paged": "the same tokens in a paged cache (128-token pages scattered over a pool, lengths on the device): "
@@ -34,6 +35,8 @@ VARIANTS = {
     "kt": "K quantized per token instead of per channel (formats int4_kt / int2_kt)",
     "gq8": "8 query heads per KV head (64/8 heads)",
     "gq16": "16 query heads per KV head (128/8 heads)",
+    "g64": "quantization groups of 64 instead of 128 (formats int4_g64 / int2_g64)",
+    "g32": "quantization groups of 32 (formats int4_g32 / int2_g32)",
 }
 
 
@@ -102,8 +105,8 @@ def main() -> int:
         return 0
     B.lib()  # fail loudly if the HIP library is missing
     w = W.CONFIGS[args.workload]
-    if args.variant == "kt":
-        w = W.scaled(w, fmt=w.fmt + "_kt")
+    if args.variant in ("kt", "g64", "g32"):
+        w = W.scaled(w, fmt=w.fmt + "_" + args.variant)
     elif args.variant in ("gq8", "gq16"):
         w = W.scaled(w, n_q_heads=int(args.variant[2:]) * w.n_kv_heads)
     paged = args.variant == "paged"
@@ -243,7 +246,8 @@ def main() -> int:
     kernel_us = float(np.mean(per_rep))
     launch_bytes = algorithmic_bytes(w, *(lengths(w.context + total_steps) if paged else (c0.packed_len, c0.res_len)))
     achieved = launch_bytes / (kernel_us * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": "decode_int_kernel" if w.fmt != "mxfp4" else "decode_mx_kernel",
+    kernel_name = "decode_mx_kernel" if w.fmt == "mxfp4" else "decode_grp_kernel" if "_g" in w.fmt else "decode_int_kernel"
+    roofline = {"bound": "hbm", "kernel": kernel_name,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(w, args.variant),
                 "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(np.min(per_rep)), 3),
@@ -262,7 +266,8 @@ def main() -> int:
             if w.fmt == "mxfp4":
                 oc = O.MxCache(1, n_units, cap)
             else:
-                oc = O.IntCache(1, n_units, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token=w.fmt.endswith("_kt"))
+                oc = O.IntCache(1, n_units, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token=w.fmt.endswith("_kt"),
+                                group=64 if w.fmt.endswith("_g64") else 32 if w.fmt.endswith("_g32") else 128)
             oc.quant_pack_kv(K[:1, :n_units], V[:1, :n_units])          # untimed: prefill
             nsteps, sample_bytes = 0, 0
             tc0 = time.perf_counter()
@@ -287,7 +292,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"int4": "u4->f16 mfma, f32 accumulate", "int2": "u2->f16 mfma, f32 accumulate",
-                  "mxfp4": "e2m1 mfma, f32 accumulate"}[w.fmt.replace("_kt", "")],
+                  "mxfp4": "e2m1 mfma, f32 accumulate"}[w.fmt.split("_")[0]],
         "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads}/{w.n_kv_heads} heads, head_dim 128, "
                                f"context {w.context}, {w.fmt} KV" + (f", variant {args.variant}" if args.variant else ""),

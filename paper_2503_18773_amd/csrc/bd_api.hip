@@ -15,7 +15,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // workgroups per split and sequence: KV heads x pieces of the query group
 long group_workgroups(const bd_cache* c) {
   const int gq = c->n_q_heads / c->n_kv_heads;
-  const int pieces = c->format == BD_FMT_MXFP4 ? ((gq + 3) / 4 + 1) / 2 : (gq + 15) / 16;
+  const int pieces = c->format == BD_FMT_MXFP4 ? ((gq + 3) / 4 + 1) / 2
+                     : fmt_group(c->format) != kBlock ? (gq + 7) / 8 : (gq + 15) / 16;
   return (long)c->n_kv_heads * pieces;
 }
 
@@ -88,7 +89,9 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   // Up to three workgroups per compute unit fit when no wave has more than one block (that kernel
   // instance needs half the registers; groups of up to 8 heads, integer formats): then one block
   // per wave beats two blocks for some waves and one for others.  Measured at 40K and 48K tokens.
-  if (c->format != BD_FMT_MXFP4 && c->n_q_heads / c->n_kv_heads <= 8 && (long)quanta * units <= 768) return quanta;
+  if (c->format != BD_FMT_MXFP4 && fmt_group(c->format) == kBlock && c->n_q_heads / c->n_kv_heads <= 8 &&
+      (long)quanta * units <= 768)
+    return quanta;
   int want = (int)((512 + units - 1) / units);
   if (want < 1) want = 1;
   int splits = quanta < want ? quanta : want;
@@ -184,9 +187,11 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
     s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, st));
   } else {
     if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
-    if (fmt_group(c->format) != kBlock) return BD_ERR_UNSUPPORTED;
-    s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, nullptr,
-                                     nullptr, st));
+    if (fmt_group(c->format) != kBlock)
+      s = hip_status(launch_decode_grp(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, st));
+    else
+      s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml,
+                                       nullptr, nullptr, st));
   }
   if (s != BD_OK) return s;
   if (out) s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st));

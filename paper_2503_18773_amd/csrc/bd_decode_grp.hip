@@ -1,0 +1,458 @@
+// Decode attention over int4 / int2 caches whose quantization group is smaller than the
+// 128-token block (Sec. IV-C(1): K_p of shape (T_n/group, d), V_p of shape (T_n, d/group)),
+// gfx950.  Same contract as the group-128 kernel (split partials (m, l, O) per query head); a
+// plainer schedule, because the parameters now change inside a block:
+//
+//   S^T[token, head] = sum_c code[token, c] * Q'[c, head] + zq[head],  Q' = Q * s_c * log2(e) / sqrt(d).
+//     s_c and z_c belong to (channel, token group), so every 16-token tile lies inside one
+//     32-token chunk of the block and the B operand (Q', an fp16 high + low pair, two MFMAs per
+//     k-step) is rebuilt whenever the chunk enters a new token group.
+//   O^T[c, head] = sum_t code[t, c] * P'_g[t, head],  P'_g = p * s_(t, g) for the channel group g of
+//     c: one variant of P' per channel group, each feeding the M tiles of its channels.  The
+//     variants pass through LDS, which also carries them from the lanes that hold a token's
+//     score (its row of S^T) to the lanes that need it as contraction index.
+//   The centre of each token's codes is taken out of the second product and added back in fp32
+//   with the zero terms, as in the group-128 kernel, so that fp16 rounding of P' acts on
+//   centred codes.
+#include "bd_common.h"
+#include "bd_device.h"
+#include "bd_fmt.h"
+
+namespace bd {
+namespace {
+
+constexpr int kWaves = 4;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kTwo24 = 16777216.0f;   // codes enter the MFMAs as code * 2^-24
+constexpr int kGrpHeads = 8;            // query heads per workgroup, at most
+
+struct GrpArgs {
+  const uint32_t* k_codes;
+  const uint32_t* v_codes;
+  const uint32_t* k_params;
+  const uint32_t* v_params;
+  const uint16_t* k_res;
+  const uint16_t* v_res;
+  const uint16_t* q;
+  float* part_o;    // [nparts][B][Hq][128]
+  float* part_ml;   // [nparts][B][Hq][2]
+  int n_q_heads, n_kv_heads, gq;
+  int nb, nbcap, res_len, num_splits;
+  float scale_log2;
+};
+
+template <int GQP, int NV>
+struct GrpWaveLds {
+  uint16_t qhi[GQP][kD];       // Q' per head, high fp16 piece, in B-operand slot order
+  uint16_t qlo[GQP][kD];       // low piece
+  float2 vpar[NV][kBlock];     // per (channel group, token): (scale * position factor, zero + scale * centre code)
+  uint16_t c16[NV][kBlock];    // centre code * position factor, in A-operand slot order
+  uint16_t pbuf[GQP][kBlock];  // P' of the channel group in work, in B-operand slot order
+  float zq[GQP];               // per head: sum_c Q_c z_c of the token group in work
+};
+template <int GQP, int NV>
+struct GrpMergeLds {
+  float o[kWaves][GQP][kD];
+  float m[kWaves][GQP], l[kWaves][GQP], z[kWaves][GQP][NV];
+};
+
+constexpr size_t gmax(size_t x, size_t y) { return x > y ? x : y; }
+
+// G: quantization group (64 or 32).  GQP: heads per workgroup, padded to 4 or 8 (larger query groups
+// take ceil(g_q / 8) workgroups per split and KV head; 16 heads' LDS scratch would not fit); MFMA
+// column c carries head c % GQP (the copies compute the same numbers).
+template <int BITS, int G, int GQP>
+__global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
+  using F = Fmt<BITS>;
+  constexpr int WORDS = F::WORDS;
+  constexpr int KROW = kD * BITS / 32;       // K words per token
+  constexpr int VROW = kBlock * BITS / 32;   // V words per channel per block
+  constexpr int NG = kBlock / G;             // token groups per block == channel groups per token
+  constexpr int NV = NG;
+  constexpr int HP = GQP / 4;
+  using WL = GrpWaveLds<GQP, NV>;
+  using ML = GrpMergeLds<GQP, NV>;
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem_raw[gmax(sizeof(ML), kWaves * sizeof(WL))];
+  __shared__ float res_s[kBlock][GQP];
+  __shared__ __attribute__((aligned(16))) float q_s[GQP][kD];   // queries * softmax_scale * log2(e); padding heads zero
+
+  const int split = blockIdx.x, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, g = lane >> 4;
+  const int head = col % GQP;
+  int hkv = blockIdx.y, head0 = 0;
+  if (a.gq > kGrpHeads) {
+    const int nchunk = (a.gq + kGrpHeads - 1) / kGrpHeads;
+    hkv = blockIdx.y / nchunk;
+    head0 = kGrpHeads * (blockIdx.y % nchunk);
+  }
+  const int gq = min(a.gq - head0, kGrpHeads);
+  WL& wl = reinterpret_cast<WL*>(smem_raw)[wave];
+
+  const size_t unit = (size_t)b * a.n_kv_heads + hkv;
+  const int nb = a.nb, res_len = a.res_len;
+  const int blk0 = (int)(((long)nb * split) / a.num_splits);
+  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
+  const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * a.gq + head0) * kD;
+
+  // ---- queries, scaled, for everybody in the workgroup
+#pragma unroll
+  for (int p = 0; p < HP; ++p) {
+    const int h = 4 * p + wave;
+    const uint32_t raw = h < gq ? *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane) : 0u;
+    float2 qq = {h2f((uint16_t)(raw & 0xFFFFu)) * a.scale_log2, h2f((uint16_t)(raw >> 16)) * a.scale_log2};
+    *reinterpret_cast<float2*>(&q_s[h][2 * lane]) = qq;
+  }
+
+  // ---- residual slice, part 1: scores of this workgroup's fp16 tokens, 16 per MFMA chain
+  const int nres = rt1 - rt0, nres_groups = (nres + 15) >> 4;
+  if (wave < nres_groups) {
+    h8_t res_q[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const h8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      res_q[j] = col < gq ? *reinterpret_cast<const h8_t*>(qbase + col * kD + 32 * j + 8 * g) : zero;
+    }
+    for (int grp = wave; grp < nres_groups; grp += kWaves) {
+      const int t = min(rt0 + 16 * grp + col, rt1 - 1);   // rows past the slice repeat its last token
+      const uint16_t* row = a.k_res + (unit * kBlock + t) * kD + 8 * g;
+      f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<const h8_t*>(row + 32 * j), res_q[j], acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int tt = 16 * grp + 4 * g + r;
+        if (tt < nres && col < GQP) res_s[tt][col] = acc[r] * a.scale_log2;
+      }
+    }
+  }
+  __syncthreads();   // q_s and res_s are complete
+
+  float m_run = -INFINITY, l_run = 0.0f;
+  float z_run[NV];
+  f4_t xacc[NV], oacc[8];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    z_run[v] = 0.0f;
+    xacc[v] = (f4_t){0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+  // Row rho = 4*gamma + r of S^T tile T = 2*chunk + run holds block token run_base(4*chunk + gamma, run) + r:
+  // the tile lies inside one 32-token chunk, and lane group g ends up with exactly the 8 tokens
+  // (slot group 4*chunk + g) that one 16-byte piece of the second product's B operand holds.
+  const int row_gamma = col >> 2, row_r = col & 3;
+  const int prep_sg = lane & 15;
+  const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
+  RawTile<WORDS> kraw[8], vraw[8];
+  u4_t kp0[NG], kp1[NG];      // K parameters (half2) of this lane's two channel runs, per token group
+  uint32_t vp[2 * NV];        // V parameters (half2) of tokens 2*lane, 2*lane+1, per channel group
+
+  auto issue_params = [&](size_t bi) {
+#pragma unroll
+    for (int tg = 0; tg < NG; ++tg) {
+      const uint32_t* pp = a.k_params + (bi * NG + tg) * kD;
+      kp0[tg] = *reinterpret_cast<const u4_t*>(pp + run0);
+      kp1[tg] = *reinterpret_cast<const u4_t*>(pp + run1);
+    }
+    const uint32_t* vpp = a.v_params + (bi * kBlock + 2 * lane) * NV;
+    if constexpr (NV == 4) {
+      const u4_t x = *reinterpret_cast<const u4_t*>(vpp), y = *reinterpret_cast<const u4_t*>(vpp + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        vp[i] = x[i];
+        vp[4 + i] = y[i];
+      }
+    } else {
+      const u4_t x = *reinterpret_cast<const u4_t*>(vpp);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vp[i] = x[i];
+    }
+  };
+  auto issue_keys = [&](size_t bi) {
+    const uint32_t* kp = a.k_codes + bi * (size_t)(kBlock * KROW) + WORDS * g;
+#pragma unroll
+    for (int T = 0; T < 8; ++T) {
+      const int tok = F::run_base(4 * (T >> 1) + row_gamma, T & 1) + row_r;
+      kraw[T] = load_raw<WORDS>(kp + (size_t)tok * KROW);
+    }
+  };
+  auto issue_values = [&](size_t bi) {
+    const uint32_t* vpp = a.v_codes + bi * (size_t)(kD * VROW) + WORDS * g;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) vraw[mt] = load_raw<WORDS>(vpp + (size_t)(16 * mt + col) * VROW);
+  };
+
+  // Q' = Q * s_c as an fp16 high + low pair in B-operand order and the zero term sum_c Q_c z_c, per
+  // head, with the K parameters of token group tg: 16 lanes per head (slot group lane % 16).
+  auto prep_queries = [&](int tg) {
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int ph = 4 * p + (lane >> 4);
+      const f4_t qa = *reinterpret_cast<const f4_t*>(&q_s[ph][run0]);
+      const f4_t qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
+      float zsum = 0.0f;
+      uint16_t qh[8], ql[8];
+#pragma unroll
+      for (int run = 0; run < 2; ++run)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float qc = run ? qb[i] : qa[i];
+          const uint32_t pr = run ? kp1[tg][i] : kp0[tg][i];
+          const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
+          const float t = qc * s * F::un(i);
+          const uint16_t hi = f2h(t);
+          qh[2 * i + run] = hi;
+          ql[2 * i + run] = f2h(t - h2f(hi));
+          zsum = __builtin_fmaf(qc, z, zsum);
+        }
+      zsum = row_sum16(zsum);
+      u4_t phi, plo;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
+        plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
+      }
+      *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
+      *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
+      if (prep_sg == 0) wl.zq[ph] = zsum;
+    }
+  };
+
+  int blk = blk0 + wave;
+  size_t bi = unit * a.nbcap + blk;
+  if (blk < blk1) {
+    issue_params(bi);
+    issue_keys(bi);
+  }
+  // this lane's 8 tokens of chunk c are block tokens tok0 + 32*c + {run_base offsets}: slot group 4*c + g
+  while (blk < blk1) {
+    const int nblk = blk + kWaves;
+    const size_t nbi = bi + kWaves;
+    // ---- V parameters of the block's tokens, per channel group
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const uint32_t pr = vp[u * NV + v];
+        const float sv = h2f((uint16_t)(pr & 0xFFFFu)), zv = h2f((uint16_t)(pr >> 16));
+        const int t = 2 * lane + u;
+        const int r = t & 3;
+        const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
+        wl.vpar[v][t] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+        wl.c16[v][F::operand_pos(t)] = (uint16_t)(ct * F::inv_un(r));   // an integer: the fp16 subnormal code * 2^-24
+      }
+    // ---- S^T, chunk by chunk
+    float sc[8][4];
+    h8_t bqh[4], bql[4];
+    float zq = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if ((32 * c) % G == 0) {   // the chunk opens a token group: new Q'
+        wave_sync();             // the previous Q' has been read by every lane
+        prep_queries((32 * c) / G);
+        wave_sync();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
+          bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+        }
+        zq = wl.zq[head];
+      }
+#pragma unroll
+      for (int run = 0; run < 2; ++run) {
+        const int T = 2 * c + run;
+        f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const h8_t ak = F::dequant(kraw[T].w, j);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bqh[j], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sc[T][r] = __builtin_fmaf(acc[r], kTwo24, zq);
+      }
+    }
+    issue_values(bi);
+    const bool has_next = nblk < blk1;
+    if (has_next) issue_params(nbi);   // the registers are free: every Q' of this block is built
+    // ---- online softmax (Alg. 1) over this lane's 32 tokens of head `head`
+    float bmax = sc[0][0];
+#pragma unroll
+    for (int T = 0; T < 8; ++T)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[T][r]);
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+    const float m_new = fmaxf(m_run, bmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
+    m_run = m_new;
+    l_run *= alpha;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        xacc[v] *= alpha;
+        z_run[v] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int T = 0; T < 8; ++T)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        sc[T][r] = __builtin_amdgcn_exp2f(sc[T][r] - m_new);
+        l_run += sc[T][r];
+      }
+    // ---- O^T += V^T P'_v, one channel group after the other
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      wave_sync();   // the previous variant has been read by every lane
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int sg = 4 * c + g;
+        u4_t w;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          uint32_t hv[2];
+#pragma unroll
+          for (int run = 0; run < 2; ++run) {
+            const float p = sc[2 * c + run][r];
+            const float2 par = wl.vpar[v][F::run_base(sg, run) + r];
+            z_run[v] = __builtin_fmaf(p, par.y, z_run[v]);
+            hv[run] = (uint32_t)f2h(p * par.x);
+          }
+          w[r] = hv[0] | (hv[1] << 16);   // entries 2r, 2r + 1 of the slot group
+        }
+        if (col < GQP) *reinterpret_cast<u4_t*>(&wl.pbuf[col][8 * sg]) = w;
+      }
+      wave_sync();
+      h8_t bp[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bp[j] = *reinterpret_cast<const h8_t*>(&wl.pbuf[head][8 * (4 * g + j)]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const h8_t ac = *reinterpret_cast<const h8_t*>(&wl.c16[v][8 * (4 * g + j)]);
+        xacc[v] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac, bp[j], xacc[v], 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int mm = 0; mm < 8 / NV; ++mm) {
+          const int mt = v * (8 / NV) + mm;
+          oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[mt].w, j), bp[j], oacc[mt], 0, 0, 0);
+        }
+    }
+    if (has_next) issue_keys(nbi);
+    wave_sync();   // the next block's parameters overwrite this wave's LDS scratch
+    blk = nblk;
+    bi = nbi;
+  }
+
+  // ---- merge the waves of the workgroup (cross-wave step of the cooperative softmax)
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    z_run[v] += __shfl_xor(z_run[v], 16);
+    z_run[v] += __shfl_xor(z_run[v], 32);
+  }
+  __syncthreads();   // every wave is done with its per-wave LDS before the space is reused
+  ML& ml = *reinterpret_cast<ML*>(smem_raw);
+  if (col < GQP) {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        ml.o[wave][col][16 * mt + 4 * g + r] = (oacc[mt][r] - xacc[mt / (8 / NV)][0]) * kTwo24;
+    if (g == 0) {
+      ml.m[wave][col] = m_run;
+      ml.l[wave][col] = l_run;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) ml.z[wave][col][v] = z_run[v];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < HP; ++p) {
+    const int h = 4 * p + wave, c0 = 2 * lane;
+    if (h < gq) {
+      const int v = c0 / G;   // channel group of channels c0, c0 + 1
+      float M = ml.m[0][h];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
+      for (int t = 0; t < nres; ++t) M = fmaxf(M, res_s[t][h]);
+      float L = 0.f, Z = 0.f, o0 = 0.f, o1 = 0.f;
+      if (M > -INFINITY) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          const float f = __builtin_amdgcn_exp2f(ml.m[w][h] - M);
+          L += f * ml.l[w][h];
+          Z += f * ml.z[w][h][v];
+          o0 += f * ml.o[w][h][c0];
+          o1 += f * ml.o[w][h][c0 + 1];
+        }
+        // residual slice, part 2: fold the fp16 tokens in
+        for (int t = 0; t < nres; ++t) {
+          const float pr = __builtin_amdgcn_exp2f(res_s[t][h] - M);
+          const uint32_t raw = *reinterpret_cast<const uint32_t*>(a.v_res + (unit * kBlock + rt0 + t) * kD + c0);
+          L += pr;
+          o0 = __builtin_fmaf(pr, h2f((uint16_t)(raw & 0xFFFFu)), o0);
+          o1 = __builtin_fmaf(pr, h2f((uint16_t)(raw >> 16)), o1);
+        }
+      }
+      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * a.gq + head0 + h;
+      float2 o = {o0 + Z, o1 + Z};
+      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+      if (lane == 0) {
+        a.part_ml[row * 2] = M;
+        a.part_ml[row * 2 + 1] = L;
+      }
+    }
+  }
+}
+
+template <int BITS, int G>
+void launch_heads(const GrpArgs& a, dim3 grid, hipStream_t st) {
+  if (a.gq <= 4) decode_grp_kernel<BITS, G, 4><<<grid, dim3(256), 0, st>>>(a);
+  else decode_grp_kernel<BITS, G, 8><<<grid, dim3(256), 0, st>>>(a);
+}
+
+}  // namespace
+
+hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
+                             int num_splits, float* part_o, float* part_ml, hipStream_t st) {
+  GrpArgs a;
+  a.k_codes = (const uint32_t*)c->k_codes;
+  a.v_codes = (const uint32_t*)c->v_codes;
+  a.k_params = (const uint32_t*)c->k_params;
+  a.v_params = (const uint32_t*)c->v_params;
+  a.k_res = (const uint16_t*)c->k_res;
+  a.v_res = (const uint16_t*)c->v_res;
+  a.q = (const uint16_t*)q;
+  a.part_o = part_o;
+  a.part_ml = part_ml;
+  a.n_q_heads = c->n_q_heads;
+  a.n_kv_heads = c->n_kv_heads;
+  a.gq = c->n_q_heads / c->n_kv_heads;
+  a.nb = packed_len / kBlock;
+  a.nbcap = c->capacity / kBlock;
+  a.res_len = res_len;
+  a.num_splits = num_splits;
+  a.scale_log2 = softmax_scale * kLog2e;
+  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + kGrpHeads - 1) / kGrpHeads), c->batch);
+  switch (c->format) {
+    case BD_FMT_INT4_G64: launch_heads<4, 64>(a, grid, st); break;
+    case BD_FMT_INT4_G32: launch_heads<4, 32>(a, grid, st); break;
+    case BD_FMT_INT2_G64: launch_heads<2, 64>(a, grid, st); break;
+    case BD_FMT_INT2_G32: launch_heads<2, 32>(a, grid, st); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace bd

@@ -762,6 +762,66 @@ def test_group_quant_adversarial_and_append_bit_exact(fmt):
     _assert_int_cache_equal(oc, gc)
 
 
+@pytest.mark.parametrize("fmt", GROUP_FORMATS)
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (5, 1), (16, 2), (12, 1)])
+def test_group_decode_matches_oracle(fmt, hq, hkv):
+    """Attention over caches with 32- and 64-groups: several blocks per wave, a ragged residual,
+    split factors from 1 to more than there are blocks, then decode steps across a flush."""
+    import torch
+    L = 128 * 9 + 101
+    w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=hq, n_kv_heads=hkv, context=L, fmt=fmt, seed=70 + hq)
+    K, V, oc, gc = _int_cache_pair(w, 128 * 12)
+    q = W.make_q(w)
+    ref = O.decode_attn(oc, q, W.softmax_scale(w))
+    for ns in (1, 2, 3, 9, 14, gc.choose_splits()):
+        # (outputs on the x10 outlier channels reach magnitudes where half an fp16 step is 2e-3)
+        assert_attn_close(_decode(gc, w, q, num_splits=ns), ref, f"{fmt} {hq}/{hkv} splits={ns}", large_outputs=True)
+    out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float16, device="cuda:0")
+    for step in range(30):                      # residual 101 -> 127 -> flush -> 3
+        kn, vn = W.make_new_kv(w, step)
+        q = W.make_q(w, step + 1)
+        oc.append_kv(kn, vn)
+        gc.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=4)
+        if step in (0, 25, 26, 27, 29):
+            torch.cuda.synchronize()
+            assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} step {step}",
+                              large_outputs=True)
+    assert (gc.packed_len, gc.res_len) == (128 * 10, 3)
+    _assert_int_cache_equal(oc, gc)
+
+
+@pytest.mark.parametrize("fmt", ["int4_g32", "int2_g64"])
+def test_group_decode_short_and_empty(fmt):
+    import torch
+    for L in (0, 5, 128, 200):
+        w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=4, n_kv_heads=1, context=max(L, 1), fmt=fmt, seed=80)
+        K, V = W.make_kv(w)
+        K, V = np.ascontiguousarray(K[:, :, :L]), np.ascontiguousarray(V[:, :, :L])
+        oc = O.IntCache(1, 1, BITS[fmt], 256, group=GROUP[fmt]); oc.quant_pack_kv(K, V)
+        gc = B.KVCache(1, 4, 1, fmt, 256); gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+        q = W.make_q(w)
+        got = _decode(gc, w, q, num_splits=2)
+        if L == 0:
+            assert not got.any()
+        else:
+            assert_attn_close(got, O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} L={L}", large_outputs=True)
+
+
+def test_group_full_size_32k_sampled_heads():
+    """cfg1's shape with 32-groups, split factor as the library picks it; two KV heads against the oracle."""
+    w = W.scaled(W.CONFIGS["cfg1"], fmt="int4_g32", context=32768 + 77)
+    K, V = W.make_kv(w)
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, 32768 + 128)
+    gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+    q = W.make_q(w)
+    got = _decode(gc, w, q)
+    for h in (0, 5):
+        oc = O.IntCache(1, 1, 4, 32768 + 128, group=32)
+        oc.quant_pack_kv(K[:, h:h + 1], V[:, h:h + 1])
+        ref = O.decode_attn(oc, q[:, 4 * h:4 * h + 4], W.softmax_scale(w))
+        assert_attn_close(got[:, 4 * h:4 * h + 4], ref, f"int4_g32 32K head {h}")
+
+
 # ---------------------------------------------------------------------------- query groups
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])
