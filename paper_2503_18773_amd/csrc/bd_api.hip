@@ -92,7 +92,9 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   if (c->format != BD_FMT_MXFP4 && fmt_group(c->format) == kBlock && c->n_q_heads / c->n_kv_heads <= 8 &&
       (long)quanta * units <= 768)
     return quanta;
-  int want = (int)((512 + units - 1) / units);
+  // (the kernels for quantization groups of 64 / 32 run one workgroup per compute unit)
+  const long target = fmt_group(c->format) != kBlock ? 256 : 512;
+  int want = (int)((target + units - 1) / units);
   if (want < 1) want = 1;
   int splits = quanta < want ? quanta : want;
   const int per = (quanta + splits - 1) / splits;

@@ -230,9 +230,14 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
     issue_keys(bi);
   }
   // this lane's 8 tokens of chunk c are block tokens tok0 + 32*c + {run_base offsets}: slot group 4*c + g
+  // The kernel needs more than 256 registers, so one wave runs per SIMD and nothing but its own
+  // arithmetic hides its memory latency: the values of a block are requested before its keys are
+  // consumed, the keys and parameters of the next block as soon as this block's keys are.
   while (blk < blk1) {
     const int nblk = blk + kWaves;
     const size_t nbi = bi + kWaves;
+    const bool has_next = nblk < blk1;
+    issue_values(bi);
     // ---- V parameters of the block's tokens, per channel group
 #pragma unroll
     for (int u = 0; u < 2; ++u)
@@ -252,6 +257,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
     float zq = 0.0f;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
+      __builtin_amdgcn_sched_barrier(0);
       if ((32 * c) % G == 0) {   // the chunk opens a token group: new Q'
         wave_sync();             // the previous Q' has been read by every lane
         prep_queries((32 * c) / G);
@@ -277,9 +283,10 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
         for (int r = 0; r < 4; ++r) sc[T][r] = __builtin_fmaf(acc[r], kTwo24, zq);
       }
     }
-    issue_values(bi);
-    const bool has_next = nblk < blk1;
-    if (has_next) issue_params(nbi);   // the registers are free: every Q' of this block is built
+    if (has_next) {   // parameters first: they are the next block's first consumers
+      issue_params(nbi);
+      issue_keys(nbi);
+    }
     // ---- online softmax (Alg. 1) over this lane's 32 tokens of head `head`
     float bmax = sc[0][0];
 #pragma unroll
@@ -311,6 +318,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
     // ---- O^T += V^T P'_v, one channel group after the other
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
+      __builtin_amdgcn_sched_barrier(0);   // one variant at a time: interleaving them costs a wave per SIMD in registers
       wave_sync();   // the previous variant has been read by every lane
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
@@ -329,6 +337,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
           w[r] = hv[0] | (hv[1] << 16);   // entries 2r, 2r + 1 of the slot group
         }
         if (col < GQP) *reinterpret_cast<u4_t*>(&wl.pbuf[col][8 * sg]) = w;
+        __builtin_amdgcn_sched_barrier(0);   // chunk by chunk: the parameters of 8 tokens in flight, not of 32
       }
       wave_sync();
       h8_t bp[4];
@@ -347,7 +356,6 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
           oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[mt].w, j), bp[j], oacc[mt], 0, 0, 0);
         }
     }
-    if (has_next) issue_keys(nbi);
     wave_sync();   // the next block's parameters overwrite this wave's LDS scratch
     blk = nblk;
     bi = nbi;

@@ -50,6 +50,12 @@ def test_cache_bytes_match_the_format():
         assert sum(B.bd_cache_bytes(c_, i) for i in range(4)) == per * units * cap
     assert B.bd_cache_bytes(_desc(head_dim=64), 0) == 0
     assert B.bd_cache_bytes(c, 6) == 0
+    # quantization groups of 64 / 32: the codes stay, the parameter arrays grow by 128 / group
+    for fmt, per in [(B.BD_FMT_INT4_G64, 144), (B.BD_FMT_INT4_G32, 160), (B.BD_FMT_INT2_G64, 80), (B.BD_FMT_INT2_G32, 96)]:
+        cg = _desc(format=fmt)
+        assert sum(B.bd_cache_bytes(cg, i) for i in range(4)) == per * units * cap
+        assert B.bd_cache_bytes(cg, 4) == units * 128 * 128 * 2
+    assert B.bd_cache_bytes(_desc(format=9), 0) == 0
 
 
 @needs_lib
@@ -130,6 +136,7 @@ def test_paged_sizes_and_argument_validation():
     assert [B.bd_paged_cache_bytes(mx, i) for i in range(8)] == [
         pool * 128 * 64, pool * 128 * 64, pool * 128 * 4, pool * 128 * 4, 0, 0, 4 * 10 * 4, 4 * 4]
     assert B.bd_paged_cache_bytes(_paged(num_pages=0), 0) == 0
+    assert B.bd_paged_cache_bytes(_paged(format=B.BD_FMT_INT4_G32), 0) == 0       # smaller groups: contiguous cache only
     assert B.bd_paged_workspace_bytes(c, 16) == 16 * 4 * 32 * 130 * 4
     L = B.lib()
     # NULL buffers are refused before anything is launched
@@ -171,3 +178,6 @@ def test_split_heuristic_properties():
     assert B.bd_choose_splits(_desc(), 40960) == 80 and B.bd_choose_splits(_desc(), 49152) == 96
     assert B.bd_choose_splits(_desc(), 57344) == 56
     assert B.bd_choose_splits(_desc(format=B.BD_FMT_MXFP4), 49152) == 48
+    # the kernels for smaller quantization groups run one workgroup per compute unit: 256 workgroups
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT4_G32), 32768) == 32
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT2_G64, n_q_heads=128), 32768) == 16   # two workgroups per KV head
