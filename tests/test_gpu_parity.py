@@ -1009,3 +1009,86 @@ def test_seeded_shape_sweep():
             torch.cuda.synchronize()
             assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), what, large_outputs=True)
         _assert_int_cache_equal(oc, gc)
+
+
+def test_seeded_shape_sweep_groups_and_large_query_groups():
+    """Twenty more seeded shapes over the formats with quantization groups of 64 / 32 and over query
+    groups of up to 40 heads."""
+    import torch
+    rng = np.random.default_rng(2025)
+    fmts = GROUP_FORMATS + ["int4", "int2_kt"]
+    for case in range(20):
+        fmt = fmts[int(rng.integers(len(fmts)))]
+        gq = int(rng.integers(1, 41))
+        H = int(rng.integers(1, 3))
+        Bn = int(rng.integers(1, 3))
+        L = int(rng.integers(1, 128 * 20))
+        ns = int(rng.integers(1, 12))
+        w = W.scaled(W.CONFIGS["cfg1"], batch=Bn, n_q_heads=gq * H, n_kv_heads=H, context=L, fmt=fmt, seed=3000 + case)
+        K, V, oc, gc = _int_cache_pair(w, (L // 128 + 2) * 128)
+        _assert_int_cache_equal(oc, gc)
+        out = torch.empty((Bn, gq * H, 128), dtype=torch.float16, device="cuda:0")
+        what = f"case {case}: {fmt} gq={gq} H={H} B={Bn} L={L} ns={ns}"
+        for step in range(2):
+            kn, vn = W.make_new_kv(w, step)
+            q = W.make_q(w, step)
+            oc.append_kv(kn, vn)
+            gc.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=ns)
+            torch.cuda.synchronize()
+            assert_attn_close(out_to_f64(out), O.decode_attn(oc, q, W.softmax_scale(w)), what, large_outputs=True)
+        _assert_int_cache_equal(oc, gc)
+
+
+def test_seeded_paged_sweep():
+    """Sixteen seeded paged shapes (format incl. MXFP4, batch, heads, ragged lengths incl. empty
+    sequences, scattered pages, split factor; fused step or append + attention)."""
+    import torch
+    rng = np.random.default_rng(2026)
+    fmts = ["int4", "int2", "int4_kt", "mxfp4"]
+    for case in range(16):
+        fmt = fmts[case % 4]
+        mx = fmt == "mxfp4"
+        dt, tdt = ("bf16", torch.bfloat16) if mx else ("fp16", torch.float16)
+        gq = int(rng.integers(1, 13))
+        H = int(rng.integers(1, 4))
+        Bn = int(rng.integers(1, 5))
+        lens = [int(rng.integers(0, 1500)) if rng.random() > 0.15 else 0 for _ in range(Bn)]
+        ns = int(rng.integers(1, 9))
+        max_pages = 14
+        num_pages = Bn * max_pages + int(rng.integers(0, 9))
+        if mx:
+            oc, gc, _ = _paged_mx_pair(lens, H, gq * H, num_pages, max_pages, seed=4000 + case)
+        else:
+            table = np.random.default_rng(5000 + case).permutation(num_pages)[:Bn * max_pages].reshape(Bn, max_pages).astype(np.int32)
+            oc = O.PagedIntCache(Bn, H, BITS[fmt], num_pages, max_pages, table, k_per_token=fmt.endswith("_kt"))
+            gc = B.PagedKVCache(Bn, gq * H, H, fmt, num_pages, table)
+            for b_, L in enumerate(lens):
+                wk = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=gq * H, n_kv_heads=H, context=max(L, 1), seed=4000 + case + b_)
+                K, V = W.make_kv(wk)
+                K, V = np.ascontiguousarray(K[0, :, :L]), np.ascontiguousarray(V[0, :, :L])
+                oc.quant_pack_kv(b_, K, V)
+                gc.quant_pack_kv(b_, to_dev(K, "fp16"), to_dev(V, "fp16"))
+        w = W.scaled(W.CONFIGS["cfg4" if mx else "cfg1"], batch=Bn, n_q_heads=gq * H, n_kv_heads=H, context=128, seed=6000 + case)
+        out = torch.empty((Bn, gq * H, 128), dtype=tdt, device="cuda:0")
+        what = f"case {case}: {fmt} gq={gq} H={H} lens={lens} ns={ns}"
+        for step in range(3):
+            kn, vn = W.make_new_kv(w, step)
+            q = W.make_q(w, step)
+            oc.append_kv(kn, vn)
+            if (case + step) % 2:
+                gc.decode_step(to_dev(kn, dt), to_dev(vn, dt), to_dev(q, dt), W.softmax_scale(w), out, ns)
+            else:
+                gc.append_kv(to_dev(kn, dt), to_dev(vn, dt))
+                gc.decode_attn(to_dev(q, dt), W.softmax_scale(w), out, ns)
+            torch.cuda.synchronize()
+            ref = O.decode_attn(oc, q, W.softmax_scale(w))
+            got = out_to_f64(out)
+            if mx:      # bf16 output: one bf16 step around the oracle, plus the tolerance
+                assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 2e-3), what
+            else:
+                assert_attn_close(got, ref, what, large_outputs=True)
+        assert list(gc.seq_lens.cpu().numpy()) == [L + 3 for L in lens] and int(gc.status.item()) == 0, what
+        if mx:
+            _assert_paged_mx_equal(oc, gc, what)
+        else:
+            _assert_paged_equal(oc, gc, what)
