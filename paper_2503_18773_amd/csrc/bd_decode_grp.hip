@@ -70,6 +70,8 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   constexpr int NG = kBlock / G;             // token groups per block == channel groups per token
   constexpr int NV = NG;
   constexpr int HP = GQP / 4;
+  constexpr int COPIES = 16 / GQP;           // MFMA columns per head
+  constexpr int OWN = 4 / COPIES;            // 32-token chunks whose softmax a lane runs
   using WL = GrpWaveLds<GQP, NV>;
   using ML = GrpMergeLds<GQP, NV>;
 
@@ -80,7 +82,9 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   const int split = blockIdx.x, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;
-  const int head = col % GQP;
+  // Every copy of a head's column receives the same S^T; copy cp keeps the chunks c with
+  // c % COPIES == cp, runs their softmax and writes their P', so that work is shared out.
+  const int head = col % GQP, cp = col / GQP;
   int hkv = blockIdx.y, head0 = 0;
   if (a.gq > kGrpHeads) {
     const int nchunk = (a.gq + kGrpHeads - 1) / kGrpHeads;
@@ -252,7 +256,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
         wl.c16[v][F::operand_pos(t)] = (uint16_t)(ct * F::inv_un(r));   // an integer: the fp16 subnormal code * 2^-24
       }
     // ---- S^T, chunk by chunk
-    float sc[8][4];
+    float sc[OWN][2][4];   // [owned chunk][run][row]
     h8_t bqh[4], bql[4];
     float zq = 0.0f;
 #pragma unroll
@@ -279,22 +283,28 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bqh[j], acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
         }
+        const bool mine = c % COPIES == cp;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sc[T][r] = __builtin_fmaf(acc[r], kTwo24, zq);
+        for (int r = 0; r < 4; ++r) {
+          const float val = __builtin_fmaf(acc[r], kTwo24, zq);
+          if constexpr (COPIES == 1) sc[c][run][r] = val;
+          else sc[c / COPIES][run][r] = mine ? val : sc[c / COPIES][run][r];
+        }
       }
     }
     if (has_next) {   // parameters first: they are the next block's first consumers
       issue_params(nbi);
       issue_keys(nbi);
     }
-    // ---- online softmax (Alg. 1) over this lane's 32 tokens of head `head`
-    float bmax = sc[0][0];
+    // ---- online softmax (Alg. 1) over this lane's 8 * OWN tokens of head `head`
+    float bmax = sc[0][0][0];
 #pragma unroll
-    for (int T = 0; T < 8; ++T)
+    for (int o = 0; o < OWN; ++o)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[T][r]);
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+      for (int run = 0; run < 2; ++run)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[o][run][r]);
+    bmax = head_max<COPIES>(bmax);
     const float m_new = fmaxf(m_run, bmax);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
@@ -309,35 +319,36 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
       }
     }
 #pragma unroll
-    for (int T = 0; T < 8; ++T)
+    for (int o = 0; o < OWN; ++o)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        sc[T][r] = __builtin_amdgcn_exp2f(sc[T][r] - m_new);
-        l_run += sc[T][r];
-      }
+      for (int run = 0; run < 2; ++run)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          sc[o][run][r] = __builtin_amdgcn_exp2f(sc[o][run][r] - m_new);
+          l_run += sc[o][run][r];
+        }
     // ---- O^T += V^T P'_v, one channel group after the other
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       __builtin_amdgcn_sched_barrier(0);   // one variant at a time: interleaving them costs a wave per SIMD in registers
       wave_sync();   // the previous variant has been read by every lane
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int sg = 4 * c + g;
+      for (int o = 0; o < OWN; ++o) {
+        const int sg = 4 * (o * COPIES + cp) + g;   // slot group of this lane's 8 tokens of its o-th chunk
         u4_t w;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           uint32_t hv[2];
 #pragma unroll
           for (int run = 0; run < 2; ++run) {
-            const float p = sc[2 * c + run][r];
+            const float p = sc[o][run][r];
             const float2 par = wl.vpar[v][F::run_base(sg, run) + r];
             z_run[v] = __builtin_fmaf(p, par.y, z_run[v]);
             hv[run] = (uint32_t)f2h(p * par.x);
           }
           w[r] = hv[0] | (hv[1] << 16);   // entries 2r, 2r + 1 of the slot group
         }
-        if (col < GQP) *reinterpret_cast<u4_t*>(&wl.pbuf[col][8 * sg]) = w;
-        __builtin_amdgcn_sched_barrier(0);   // chunk by chunk: the parameters of 8 tokens in flight, not of 32
+        *reinterpret_cast<u4_t*>(&wl.pbuf[head][8 * sg]) = w;   // every (head, slot group) has one owner
       }
       wave_sync();
       h8_t bp[4];
@@ -362,13 +373,9 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   }
 
   // ---- merge the waves of the workgroup (cross-wave step of the cooperative softmax)
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
+  l_run = head_sum<COPIES>(l_run);
 #pragma unroll
-  for (int v = 0; v < NV; ++v) {
-    z_run[v] += __shfl_xor(z_run[v], 16);
-    z_run[v] += __shfl_xor(z_run[v], 32);
-  }
+  for (int v = 0; v < NV; ++v) z_run[v] = head_sum<COPIES>(z_run[v]);
   __syncthreads();   // every wave is done with its per-wave LDS before the space is reused
   ML& ml = *reinterpret_cast<ML*>(smem_raw);
   if (col < GQP) {
