@@ -276,19 +276,26 @@ class PagedIntCache:
       k_res, v_res fp16 [B, H, 128, D]
       block_table int32 [B, max_pages]                 seq_lens int32 [B]
 
-    Paging is a pure relocation: every block holds exactly the bytes IntCache would hold.
+    Paging is a pure relocation: every block holds exactly the bytes IntCache would hold
+    (with group = 64 or 32: k_params uint32 [P, H, 128/group, D], v_params uint32 [P, H, 128, D/group]).
     """
 
     def __init__(self, batch: int, n_kv_heads: int, bits: int, num_pages: int, max_pages: int,
-                 block_table: np.ndarray, head_dim: int = 128, k_per_token: bool = False):
+                 block_table: np.ndarray, head_dim: int = 128, k_per_token: bool = False, group: int = BLOCK):
         assert head_dim == 128 and block_table.shape == (batch, max_pages)
+        assert group in (32, 64, BLOCK) and not (k_per_token and group != BLOCK)
         self.B, self.H, self.D, self.bits = batch, n_kv_heads, head_dim, bits
         self.k_per_token = k_per_token
+        self.group = group
         self.P, self.max_pages = num_pages, max_pages
         self.k_codes = np.zeros((num_pages, n_kv_heads, BLOCK, head_dim * bits // 32), np.uint32)
         self.v_codes = np.zeros((num_pages, n_kv_heads, head_dim, BLOCK * bits // 32), np.uint32)
-        self.k_params = np.zeros((num_pages, n_kv_heads, head_dim), np.uint32)
-        self.v_params = np.zeros((num_pages, n_kv_heads, BLOCK), np.uint32)
+        if group == BLOCK:
+            self.k_params = np.zeros((num_pages, n_kv_heads, head_dim), np.uint32)
+            self.v_params = np.zeros((num_pages, n_kv_heads, BLOCK), np.uint32)
+        else:
+            self.k_params = np.zeros((num_pages, n_kv_heads, BLOCK // group, head_dim), np.uint32)
+            self.v_params = np.zeros((num_pages, n_kv_heads, BLOCK, head_dim // group), np.uint32)
         self.k_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.v_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.block_table = block_table.astype(np.int32).copy()
@@ -306,8 +313,12 @@ class PagedIntCache:
         p = self._page_of(b, n)
         quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
         for h in range(self.H):
-            kc, ks, kz = quant_k(kblk[h], self.bits)
-            vc, vs, vz = quantize_v_block(vblk[h], self.bits)
+            if self.group != BLOCK:
+                kc, ks, kz = quantize_k_block_grouped(kblk[h], self.bits, self.group)
+                vc, vs, vz = quantize_v_block_grouped(vblk[h], self.bits, self.group)
+            else:
+                kc, ks, kz = quant_k(kblk[h], self.bits)
+                vc, vs, vz = quantize_v_block(vblk[h], self.bits)
             self.k_codes[p, h] = pack_words(kc, self.bits)
             self.v_codes[p, h] = pack_words(vc.T.copy(), self.bits)
             self.k_params[p, h] = pack_half2(ks, kz)
@@ -351,6 +362,11 @@ class PagedIntCache:
             vc = unpack_words(self.v_codes[p, h], self.bits).astype(np.float64).T
             ks, kz = unpack_half2(self.k_params[p, h])
             vs, vz = unpack_half2(self.v_params[p, h])
+            if self.group != BLOCK:      # ks, kz [128/group, D]; vs, vz [128, D/group]
+                ks, kz, vs, vz = (x.astype(np.float64) for x in (ks, kz, vs, vz))
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * np.repeat(ks, self.group, axis=0) + np.repeat(kz, self.group, axis=0)
+                Vh[n * BLOCK:(n + 1) * BLOCK] = vc * np.repeat(vs, self.group, axis=1) + np.repeat(vz, self.group, axis=1)
+                continue
             if self.k_per_token:
                 Kh[n * BLOCK:(n + 1) * BLOCK] = kc * ks.astype(np.float64)[:, None] + kz.astype(np.float64)[:, None]
             else:

@@ -38,18 +38,18 @@ def test_identity_table_holds_the_contiguous_bytes(bits):
     assert list(p.seq_lens) == [L, L]
 
 
-@pytest.mark.parametrize("bits", [4, 2])
-def test_ragged_scattered_pages_equal_independent_caches(bits):
+@pytest.mark.parametrize("bits,group", [(4, 128), (2, 128), (4, 32), (2, 64)])
+def test_ragged_scattered_pages_equal_independent_caches(bits, group):
     rng = np.random.default_rng(5)
     B, H, Hq = 4, 2, 4
     lens = [300, 0, 128, 517]
     table = _table(rng, B, 6, 40)
-    p = O.PagedIntCache(B, H, bits, 40, 6, table)
+    p = O.PagedIntCache(B, H, bits, 40, 6, table, group=group)
     singles = []
     for b, L in enumerate(lens):
         K, V = _kv(20 + b, H, L)
         p.quant_pack_kv(b, K, V)
-        c = O.IntCache(1, H, bits, 6 * 128)
+        c = O.IntCache(1, H, bits, 6 * 128, group=group)
         c.quant_pack_kv(K[None], V[None])
         singles.append(c)
     # three decode steps: sequence 2 (128 tokens) stays aligned, sequence 3 crosses nothing, then
