@@ -259,7 +259,6 @@ static bd_status check_paged_shape(const bd_paged_cache* c) {
   bd_status st = check_shape(&s);
   if (st != BD_OK) return st;
   if (c->num_pages <= 0 || c->max_pages_per_seq <= 0) return BD_ERR_INVALID_ARG;
-  if (fmt_group(c->format) != kBlock) return BD_ERR_UNSUPPORTED;   // smaller groups: contiguous cache only
   return BD_OK;
 }
 
@@ -286,10 +285,11 @@ size_t bd_paged_cache_bytes(const bd_paged_cache* c, int which) {
       default: break;
     }
   }
+  const size_t groups = (size_t)(kBlock / fmt_group(c->format));
   switch (which) {
     case 0: case 1: return pool * kBlock * kD * bits / 8;
-    case 2: return pool * kD * 4;
-    case 3: return pool * kBlock * 4;
+    case 2: return pool * groups * kD * 4;
+    case 3: return pool * kBlock * groups * 4;
     case 4: case 5: return (size_t)c->batch * c->n_kv_heads * kBlock * kD * 2;
     case 6: return (size_t)c->batch * c->max_pages_per_seq * 4;
     default: return (size_t)c->batch * 4;
@@ -333,6 +333,8 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
   float* part_ml = ws_part_ml(&shape, workspace, num_splits);
   bd_status s = hip_status(c->format == BD_FMT_MXFP4
                                ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st)
+                           : fmt_group(c->format) != kBlock
+                               ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st)
                                : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st));
   if (s != BD_OK) return s;
   return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st, step ? c : nullptr));

@@ -58,6 +58,8 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
 // formats with a quantization group of 64 or 32
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, hipStream_t st);
+hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
+                                   float* part_o, float* part_ml, bool step, hipStream_t st);
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                   float* part_o, float* part_ml, bool step, hipStream_t st);
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale,

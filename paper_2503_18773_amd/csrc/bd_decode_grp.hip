@@ -39,6 +39,13 @@ struct GrpArgs {
   int n_q_heads, n_kv_heads, gq;
   int nb, nbcap, res_len, num_splits;
   float scale_log2;
+  // paged cache: block n of sequence b is page block_table[b][n], pool index page * Hkv + head;
+  // nb and res_len then come from seq_lens[b]
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  int32_t* status;
+  int max_pages, num_pages;
+  int step;   // paged: 1 when this launch is the attention of a fused step
 };
 
 template <int GQP, int NV>
@@ -61,7 +68,8 @@ constexpr size_t gmax(size_t x, size_t y) { return x > y ? x : y; }
 // G: quantization group (64 or 32).  GQP: heads per workgroup, padded to 4 or 8 (larger query groups
 // take ceil(g_q / 8) workgroups per split and KV head; 16 heads' LDS scratch would not fit); MFMA
 // column c carries head c % GQP (the copies compute the same numbers).
-template <int BITS, int G, int GQP>
+// PAGED: blocks are found through the block table and every sequence has its own length.
+template <int BITS, int G, int GQP, bool PAGED>
 __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   using F = Fmt<BITS>;
   constexpr int WORDS = F::WORDS;
@@ -95,7 +103,24 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   WL& wl = reinterpret_cast<WL*>(smem_raw)[wave];
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
-  const int nb = a.nb, res_len = a.res_len;
+  int nb = a.nb, res_len = a.res_len;
+  if (PAGED) {
+    int len = a.seq_lens[b];
+    if (a.step && len >= 0) {
+      // fused step: the preceding kernel has appended this step's token (unless it needed a page
+      // the table does not name) and the length is raised only after this kernel
+      bool ok = true;
+      if (len % kBlock == kBlock - 1) {
+        const int n = len / kBlock;
+        const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
+        ok = e >= 0 && e < a.num_pages;
+      }
+      len += ok ? 1 : 0;
+    }
+    len = len < 0 ? 0 : len;
+    nb = len / kBlock;
+    res_len = len % kBlock;
+  }
   const int blk0 = (int)(((long)nb * split) / a.num_splits);
   const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
@@ -227,8 +252,25 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
     }
   };
 
+  // Paged: table entry of block n (-1 past the end of the row), and the first block at or after
+  // n, in this wave's stride, whose entry names a page of the pool; entries that do not are
+  // skipped and reported in *status.
+  auto table_entry = [&](int n) { return n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1; };
+  auto first_valid = [&](int n, int entry, size_t& idx) {
+    while (n < blk1) {
+      if (entry >= 0 && entry < a.num_pages) {
+        idx = (size_t)entry * a.n_kv_heads + hkv;
+        break;
+      }
+      if (a.status && lane == 0) atomicOr(a.status, 1);
+      n += kWaves;
+      entry = n < blk1 ? table_entry(n) : -1;
+    }
+    return n;
+  };
   int blk = blk0 + wave;
   size_t bi = unit * a.nbcap + blk;
+  if (PAGED) blk = first_valid(blk, blk < blk1 ? table_entry(blk) : -1, bi);
   if (blk < blk1) {
     issue_params(bi);
     issue_keys(bi);
@@ -238,8 +280,9 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   // arithmetic hides its memory latency: the values of a block are requested before its keys are
   // consumed, the keys and parameters of the next block as soon as this block's keys are.
   while (blk < blk1) {
-    const int nblk = blk + kWaves;
-    const size_t nbi = bi + kWaves;
+    int nblk = blk + kWaves;
+    size_t nbi = bi + kWaves;
+    if (PAGED) nblk = first_valid(nblk, nblk < blk1 ? table_entry(nblk) : -1, nbi);
     const bool has_next = nblk < blk1;
     issue_values(bi);
     // ---- V parameters of the block's tokens, per channel group
@@ -432,9 +475,26 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
 }
 
 template <int BITS, int G>
-void launch_heads(const GrpArgs& a, dim3 grid, hipStream_t st) {
-  if (a.gq <= 4) decode_grp_kernel<BITS, G, 4><<<grid, dim3(256), 0, st>>>(a);
-  else decode_grp_kernel<BITS, G, 8><<<grid, dim3(256), 0, st>>>(a);
+void launch_heads(const GrpArgs& a, bool paged, dim3 grid, hipStream_t st) {
+  if (paged) {
+    if (a.gq <= 4) decode_grp_kernel<BITS, G, 4, true><<<grid, dim3(256), 0, st>>>(a);
+    else decode_grp_kernel<BITS, G, 8, true><<<grid, dim3(256), 0, st>>>(a);
+  } else {
+    if (a.gq <= 4) decode_grp_kernel<BITS, G, 4, false><<<grid, dim3(256), 0, st>>>(a);
+    else decode_grp_kernel<BITS, G, 8, false><<<grid, dim3(256), 0, st>>>(a);
+  }
+}
+
+hipError_t launch_format(int format, const GrpArgs& a, bool paged, int batch, hipStream_t st) {
+  dim3 grid(a.num_splits, a.n_kv_heads * ((a.gq + kGrpHeads - 1) / kGrpHeads), batch);
+  switch (format) {
+    case BD_FMT_INT4_G64: launch_heads<4, 64>(a, paged, grid, st); break;
+    case BD_FMT_INT4_G32: launch_heads<4, 32>(a, paged, grid, st); break;
+    case BD_FMT_INT2_G64: launch_heads<2, 64>(a, paged, grid, st); break;
+    case BD_FMT_INT2_G32: launch_heads<2, 32>(a, paged, grid, st); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -459,15 +519,38 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
   a.res_len = res_len;
   a.num_splits = num_splits;
   a.scale_log2 = softmax_scale * kLog2e;
-  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + kGrpHeads - 1) / kGrpHeads), c->batch);
-  switch (c->format) {
-    case BD_FMT_INT4_G64: launch_heads<4, 64>(a, grid, st); break;
-    case BD_FMT_INT4_G32: launch_heads<4, 32>(a, grid, st); break;
-    case BD_FMT_INT2_G64: launch_heads<2, 64>(a, grid, st); break;
-    case BD_FMT_INT2_G32: launch_heads<2, 32>(a, grid, st); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
+  a.block_table = nullptr;
+  a.seq_lens = nullptr;
+  a.status = nullptr;
+  a.max_pages = a.num_pages = a.step = 0;
+  return launch_format(c->format, a, false, c->batch, st);
+}
+
+hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
+                                   float* part_o, float* part_ml, bool step, hipStream_t st) {
+  GrpArgs a;
+  a.k_codes = (const uint32_t*)c->k_codes;
+  a.v_codes = (const uint32_t*)c->v_codes;
+  a.k_params = (const uint32_t*)c->k_params;
+  a.v_params = (const uint32_t*)c->v_params;
+  a.k_res = (const uint16_t*)c->k_res;
+  a.v_res = (const uint16_t*)c->v_res;
+  a.q = (const uint16_t*)q;
+  a.part_o = part_o;
+  a.part_ml = part_ml;
+  a.n_q_heads = c->n_q_heads;
+  a.n_kv_heads = c->n_kv_heads;
+  a.gq = c->n_q_heads / c->n_kv_heads;
+  a.nb = a.nbcap = a.res_len = 0;   // per sequence, from seq_lens
+  a.num_splits = num_splits;
+  a.scale_log2 = softmax_scale * kLog2e;
+  a.block_table = c->block_table;
+  a.seq_lens = c->seq_lens;
+  a.status = c->status;
+  a.max_pages = c->max_pages_per_seq;
+  a.num_pages = c->num_pages;
+  a.step = step ? 1 : 0;
+  return launch_format(c->format, a, true, c->batch, st);
 }
 
 }  // namespace bd

@@ -326,15 +326,15 @@ __device__ __forceinline__ int page_of(const PagedArgs& a, int b, int n, int fla
 }
 
 // Prefill of one sequence: block blockIdx.x of KV head blockIdx.y, source [H][L][128].
-template <int BITS, bool KT>
+template <int BITS, bool KT, int G>
 __global__ __launch_bounds__(256) void paged_quant_kernel(PagedArgs a, const uint16_t* __restrict__ ksrc,
                                                            const uint16_t* __restrict__ vsrc, int seq, int L) {
   const int blk = blockIdx.x, h = blockIdx.y;
   const int page = page_of(a, seq, blk, 2);
   if (page < 0) return;
   const size_t src_off = ((size_t)h * L + (size_t)blk * kBlock) * kD;
-  quant_block<BITS, KT>(ksrc + src_off, vsrc + src_off, a.k_codes, a.v_codes, a.k_params, a.v_params,
-                        (size_t)page * a.n_kv_heads + h);
+  quant_block<BITS, KT, G>(ksrc + src_off, vsrc + src_off, a.k_codes, a.v_codes, a.k_params, a.v_params,
+                           (size_t)page * a.n_kv_heads + h);
 }
 
 // Prefill, rest: the L mod 128 newest tokens of every head go to the sequence's residual and
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256) void paged_tail_kernel(PagedArgs a, const u4_t
 // slot len mod 128; if that fills the residual it is quantized into the sequence's next page
 // (Sec. IV-B(1)).  Lengths are bumped by paged_bump_kernel afterwards, so every workgroup of
 // the sequence sees the same length here.
-template <int BITS, bool KT>
+template <int BITS, bool KT, int G>
 __global__ __launch_bounds__(256) void paged_append_kernel(PagedArgs a, const uint16_t* __restrict__ k_new,
                                                             const uint16_t* __restrict__ v_new) {
   const int h = blockIdx.x, b = blockIdx.y;
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(256) void paged_append_kernel(PagedArgs a, const ui
   // the row just written is read back below by other threads of this workgroup
   __threadfence();
   __syncthreads();
-  quant_block<BITS, KT>(kr, vr, a.k_codes, a.v_codes, a.k_params, a.v_params, (size_t)page * a.n_kv_heads + h);
+  quant_block<BITS, KT, G>(kr, vr, a.k_codes, a.v_codes, a.k_params, a.v_params, (size_t)page * a.n_kv_heads + h);
 }
 
 // seq_lens[b] += 1 for every sequence whose step went through (same test as the append kernel:
@@ -828,10 +828,15 @@ hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k,
     dim3 grid(nb, c->n_kv_heads), block(256);
     const uint16_t *kk = (const uint16_t*)k, *vv = (const uint16_t*)v;
     switch (c->format) {
-      case BD_FMT_INT4: paged_quant_kernel<4, false><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
-      case BD_FMT_INT2: paged_quant_kernel<2, false><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
-      case BD_FMT_INT4_KT: paged_quant_kernel<4, true><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
-      default: paged_quant_kernel<2, true><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4: paged_quant_kernel<4, false, 128><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2: paged_quant_kernel<2, false, 128><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4_KT: paged_quant_kernel<4, true, 128><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2_KT: paged_quant_kernel<2, true, 128><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4_G64: paged_quant_kernel<4, false, 64><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4_G32: paged_quant_kernel<4, false, 32><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2_G64: paged_quant_kernel<2, false, 64><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2_G32: paged_quant_kernel<2, false, 32><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -853,10 +858,15 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
     return hipGetLastError();
   }
   switch (c->format) {
-    case BD_FMT_INT4: paged_append_kernel<4, false><<<grid, block, 0, st>>>(a, kk, vv); break;
-    case BD_FMT_INT2: paged_append_kernel<2, false><<<grid, block, 0, st>>>(a, kk, vv); break;
-    case BD_FMT_INT4_KT: paged_append_kernel<4, true><<<grid, block, 0, st>>>(a, kk, vv); break;
-    default: paged_append_kernel<2, true><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4: paged_append_kernel<4, false, 128><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2: paged_append_kernel<2, false, 128><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4_KT: paged_append_kernel<4, true, 128><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2_KT: paged_append_kernel<2, true, 128><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4_G64: paged_append_kernel<4, false, 64><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4_G32: paged_append_kernel<4, false, 32><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2_G64: paged_append_kernel<2, false, 64><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2_G32: paged_append_kernel<2, false, 32><<<grid, block, 0, st>>>(a, kk, vv); break;
+    default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !bump) return e;

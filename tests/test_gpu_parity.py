@@ -415,12 +415,12 @@ def test_decode_step_matches_oracle_on_cfg1():
 
 def _paged_pair(fmt, lens, H, Hq, num_pages, max_pages, seed=31, table=None):
     """Oracle and GPU paged caches prefilled with ragged sequences on scattered pages."""
-    bits = 4 if fmt == "int4" else 2
     B_ = len(lens)
     rng = np.random.default_rng(seed)
     if table is None:
         table = rng.permutation(num_pages)[:B_ * max_pages].reshape(B_, max_pages).astype(np.int32)
-    oc = O.PagedIntCache(B_, H, bits, num_pages, max_pages, table)
+    oc = O.PagedIntCache(B_, H, BITS[fmt], num_pages, max_pages, table, k_per_token=fmt.endswith("_kt"),
+                         group=GROUP.get(fmt, 128))
     gc = B.PagedKVCache(B_, Hq, H, fmt, num_pages, table)
     for b, L in enumerate(lens):
         w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=Hq, n_kv_heads=H, context=max(L, 1), seed=seed + b)
@@ -447,7 +447,7 @@ def _assert_paged_equal(oc, gc, what):
             assert np.array_equal(got[b, :, :r].view(np.uint16), ref[b, :, :r].view(np.uint16)), (what, name, b)
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_g32", "int2_g64", "int4_g64", "int2_g32"])
 def test_paged_prefill_append_and_decode_match_oracle(fmt):
     """Ragged batch on scattered pages: pool bytes bit-exact after prefill and after appends that
     carry two sequences over a flush; attention within tolerance at several split factors,
@@ -667,7 +667,7 @@ def test_paged_mx_long_batch_sampled_units():
     assert list(gc.seq_lens.cpu().numpy()) == [L + 1 for L in lens] and int(gc.status.item()) == 0
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32", "int2_g64"])
 def test_paged_fused_step_equals_append_then_attention(fmt):
     """bd_paged_decode_step against bd_paged_append_kv + bd_paged_decode_attn on a twin cache:
     outputs, pool bytes and lengths identical bit for bit over steps that cross block
@@ -1040,13 +1040,13 @@ def test_seeded_shape_sweep_groups_and_large_query_groups():
 
 
 def test_seeded_paged_sweep():
-    """Sixteen seeded paged shapes (format incl. MXFP4, batch, heads, ragged lengths incl. empty
+    """Eighteen seeded paged shapes (format incl. MXFP4 and smaller quantization groups, batch, heads, ragged lengths incl. empty
     sequences, scattered pages, split factor; fused step or append + attention)."""
     import torch
     rng = np.random.default_rng(2026)
-    fmts = ["int4", "int2", "int4_kt", "mxfp4"]
-    for case in range(16):
-        fmt = fmts[case % 4]
+    fmts = ["int4", "int2", "int4_kt", "mxfp4", "int4_g64", "int2_g32"]
+    for case in range(18):
+        fmt = fmts[case % 6]
         mx = fmt == "mxfp4"
         dt, tdt = ("bf16", torch.bfloat16) if mx else ("fp16", torch.float16)
         gq = int(rng.integers(1, 13))
@@ -1060,7 +1060,8 @@ def test_seeded_paged_sweep():
             oc, gc, _ = _paged_mx_pair(lens, H, gq * H, num_pages, max_pages, seed=4000 + case)
         else:
             table = np.random.default_rng(5000 + case).permutation(num_pages)[:Bn * max_pages].reshape(Bn, max_pages).astype(np.int32)
-            oc = O.PagedIntCache(Bn, H, BITS[fmt], num_pages, max_pages, table, k_per_token=fmt.endswith("_kt"))
+            oc = O.PagedIntCache(Bn, H, BITS[fmt], num_pages, max_pages, table, k_per_token=fmt.endswith("_kt"),
+                                 group=GROUP.get(fmt, 128))
             gc = B.PagedKVCache(Bn, gq * H, H, fmt, num_pages, table)
             for b_, L in enumerate(lens):
                 wk = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=gq * H, n_kv_heads=H, context=max(L, 1), seed=4000 + case + b_)

@@ -136,7 +136,9 @@ def test_paged_sizes_and_argument_validation():
     assert [B.bd_paged_cache_bytes(mx, i) for i in range(8)] == [
         pool * 128 * 64, pool * 128 * 64, pool * 128 * 4, pool * 128 * 4, 0, 0, 4 * 10 * 4, 4 * 4]
     assert B.bd_paged_cache_bytes(_paged(num_pages=0), 0) == 0
-    assert B.bd_paged_cache_bytes(_paged(format=B.BD_FMT_INT4_G32), 0) == 0       # smaller groups: contiguous cache only
+    g32 = _paged(format=B.BD_FMT_INT4_G32)               # smaller groups: the parameter arrays grow by 128 / group
+    assert [B.bd_paged_cache_bytes(g32, i) for i in range(4)] == [pool * 128 * 64, pool * 128 * 64, pool * 4 * 128 * 4,
+                                                                 pool * 128 * 4 * 4]
     assert B.bd_paged_workspace_bytes(c, 16) == 16 * 4 * 32 * 130 * 4
     L = B.lib()
     # NULL buffers are refused before anything is launched
