@@ -5,8 +5,9 @@
 //
 //   S^T[token, head] = sum_c code[token, c] * Q'[c, head] + zq[head],  Q' = Q * s_c * log2(e) / sqrt(d).
 //     s_c and z_c belong to (channel, token group), so every 16-token tile lies inside one
-//     32-token chunk of the block and the B operand (Q', an fp16 high + low pair, two MFMAs per
-//     k-step) is rebuilt whenever the chunk enters a new token group.
+//     32-token chunk of the block and the B operand (Q', an fp16 high + low pair: the high piece in
+//     the even copies of a head's MFMA column, the low piece in the odd ones, their partial
+//     products added with one DPP move) is rebuilt whenever the chunk enters a new token group.
 //   O^T[c, head] = sum_t code[t, c] * P'_g[t, head],  P'_g = p * s_(t, g) for the channel group g of
 //     c: one variant of P' per channel group, each feeding the M tiles of its channels.  The
 //     variants pass through LDS, which also carries them from the lanes that hold a token's
@@ -79,6 +80,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   constexpr int NV = NG;
   constexpr int HP = GQP / 4;
   constexpr int COPIES = 16 / GQP;           // MFMA columns per head
+  static_assert(COPIES >= 2 && COPIES % 2 == 0, "the high / low pieces of Q' need an even number of copies");
   constexpr int OWN = 4 / COPIES;            // 32-token chunks whose softmax a lane runs
   using WL = GrpWaveLds<GQP, NV>;
   using ML = GrpMergeLds<GQP, NV>;
@@ -300,7 +302,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
       }
     // ---- S^T, chunk by chunk
     float sc[OWN][2][4];   // [owned chunk][run][row]
-    h8_t bqh[4], bql[4];
+    h8_t bq[4];   // the high piece of Q' in the even copies of a head's column, the low piece in the odd ones
     float zq = 0.0f;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -311,8 +313,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
         wave_sync();
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          bqh[j] = *reinterpret_cast<const h8_t*>(&wl.qhi[head][8 * (4 * g + j)]);
-          bql[j] = *reinterpret_cast<const h8_t*>(&wl.qlo[head][8 * (4 * g + j)]);
+          bq[j] = *reinterpret_cast<const h8_t*>(cp & 1 ? &wl.qlo[head][8 * (4 * g + j)] : &wl.qhi[head][8 * (4 * g + j)]);
         }
         zq = wl.zq[head];
       }
@@ -323,15 +324,18 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const h8_t ak = F::dequant(kraw[T].w, j);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bqh[j], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bql[j], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, bq[j], acc, 0, 0, 0);
         }
+        // the chunk's owner (copy c % COPIES) adds the other piece's partial product, which the
+        // neighbouring copy computed: GQP lanes up for an even owner, GQP lanes down for an odd one
         const bool mine = c % COPIES == cp;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float val = __builtin_fmaf(acc[r], kTwo24, zq);
-          if constexpr (COPIES == 1) sc[c][run][r] = val;
-          else sc[c / COPIES][run][r] = mine ? val : sc[c / COPIES][run][r];
+          float x = acc[r];
+          if (c & 1) x += dpp_f<GQP == 4 ? kRowShr4 : kRowShr8>(x);
+          else x += dpp_f<GQP == 4 ? kRowShl4 : kRowShl8>(x);
+          const float val = __builtin_fmaf(x, kTwo24, zq);
+          sc[c / COPIES][run][r] = mine ? val : sc[c / COPIES][run][r];
         }
       }
     }
