@@ -92,8 +92,9 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   if (c->format != BD_FMT_MXFP4 && fmt_group(c->format) == kBlock && c->n_q_heads / c->n_kv_heads <= 8 &&
       (long)quanta * units <= 768)
     return quanta;
-  // (the kernels for quantization groups of 64 / 32 run one workgroup per compute unit)
-  const long target = fmt_group(c->format) != kBlock ? 256 : 512;
+  // (one kernel instance runs one workgroup per compute unit: 4-bit codes in groups of 32 with more than
+  // 4 query heads per KV head)
+  const long target = c->format == BD_FMT_INT4_G32 && c->n_q_heads / c->n_kv_heads > 4 ? 256 : 512;
   int want = (int)((target + units - 1) / units);
   if (want < 1) want = 1;
   int splits = quanta < want ? quanta : want;

@@ -57,6 +57,7 @@ struct GrpWaveLds {
   uint16_t c16[NV][kBlock];    // centre code * position factor, in A-operand slot order
   uint16_t pbuf[GQP][kBlock];  // P' of the channel group in work, in B-operand slot order
   float zq[GQP];               // per head: sum_c Q_c z_c of the token group in work
+  uint32_t kpar[NV][kD];       // K parameters (half2) of the block, per token group and channel
 };
 template <int GQP, int NV>
 struct GrpMergeLds {
@@ -66,12 +67,22 @@ struct GrpMergeLds {
 
 constexpr size_t gmax(size_t x, size_t y) { return x > y ? x : y; }
 
+// Every instance fits 256 registers (two waves per SIMD) but one: 4-bit codes in groups of 32 with
+// more than 4 heads per workgroup, which would spill and runs one wave per SIMD instead.
+constexpr int grp_waves_per_simd(int bits, int group, int gqp) { return bits == 4 && group == 32 && gqp == 8 ? 1 : 2; }
+
 // G: quantization group (64 or 32).  GQP: heads per workgroup, padded to 4 or 8 (larger query groups
 // take ceil(g_q / 8) workgroups per split and KV head; 16 heads' LDS scratch would not fit); MFMA
 // column c carries head c % GQP (the copies compute the same numbers).
 // PAGED: blocks are found through the block table and every sequence has its own length.
 template <int BITS, int G, int GQP, bool PAGED>
-__global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
+__global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_grp_kernel(GrpArgs a) {
+  // With one wave per SIMD nothing but the wave's own arithmetic hides its memory latency, so it
+  // requests a block's values before its keys are consumed and the next block's keys right after
+  // ("deep").  With two waves the other one covers and the short queue of the group-128 kernel is
+  // better (measured, groups of 64: 13.2 against 13.7 us at 32K, 30.9 against 33.2 us at 128K),
+  // except for 2-bit codes, whose blocks are half the bytes (42.9 against 45.3 us at 8 x 32K).
+  constexpr bool kDeep = BITS == 2 || grp_waves_per_simd(BITS, G, GQP) == 1;
   using F = Fmt<BITS>;
   constexpr int WORDS = F::WORDS;
   constexpr int KROW = kD * BITS / 32;       // K words per token
@@ -180,16 +191,15 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
   const int prep_sg = lane & 15;
   const int run0 = F::run_base(prep_sg, 0), run1 = F::run_base(prep_sg, 1);
   RawTile<WORDS> kraw[8], vraw[8];
-  u4_t kp0[NG], kp1[NG];      // K parameters (half2) of this lane's two channel runs, per token group
+  u4_t kp0, kp1;              // K parameters (half2) of this lane's two channel runs, token group g % NG
   uint32_t vp[2 * NV];        // V parameters (half2) of tokens 2*lane, 2*lane+1, per channel group
 
   auto issue_params = [&](size_t bi) {
-#pragma unroll
-    for (int tg = 0; tg < NG; ++tg) {
-      const uint32_t* pp = a.k_params + (bi * NG + tg) * kD;
-      kp0[tg] = *reinterpret_cast<const u4_t*>(pp + run0);
-      kp1[tg] = *reinterpret_cast<const u4_t*>(pp + run1);
-    }
+    // lane group g fetches token group g % NG (its 16 lanes cover the 128 channels); the token
+    // groups meet in LDS, which keeps 8 registers in flight instead of 8 per token group
+    const uint32_t* pp = a.k_params + (bi * NG + (g % NG)) * kD;
+    kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
+    kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
     const uint32_t* vpp = a.v_params + (bi * kBlock + 2 * lane) * NV;
     if constexpr (NV == 4) {
       const u4_t x = *reinterpret_cast<const u4_t*>(vpp), y = *reinterpret_cast<const u4_t*>(vpp + 4);
@@ -226,6 +236,8 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
       const int ph = 4 * p + (lane >> 4);
       const f4_t qa = *reinterpret_cast<const f4_t*>(&q_s[ph][run0]);
       const f4_t qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
+      const u4_t ka = *reinterpret_cast<const u4_t*>(&wl.kpar[tg][run0]);
+      const u4_t kb = *reinterpret_cast<const u4_t*>(&wl.kpar[tg][run1]);
       float zsum = 0.0f;
       uint16_t qh[8], ql[8];
 #pragma unroll
@@ -233,7 +245,7 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float qc = run ? qb[i] : qa[i];
-          const uint32_t pr = run ? kp1[tg][i] : kp0[tg][i];
+          const uint32_t pr = run ? kb[i] : ka[i];
           const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
           const float t = qc * s * F::un(i);
           const uint16_t hi = f2h(t);
@@ -278,15 +290,16 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
     issue_keys(bi);
   }
   // this lane's 8 tokens of chunk c are block tokens tok0 + 32*c + {run_base offsets}: slot group 4*c + g
-  // The kernel needs more than 256 registers, so one wave runs per SIMD and nothing but its own
-  // arithmetic hides its memory latency: the values of a block are requested before its keys are
-  // consumed, the keys and parameters of the next block as soon as this block's keys are.
   while (blk < blk1) {
     int nblk = blk + kWaves;
     size_t nbi = bi + kWaves;
     if (PAGED) nblk = first_valid(nblk, nblk < blk1 ? table_entry(nblk) : -1, nbi);
     const bool has_next = nblk < blk1;
-    issue_values(bi);
+    if constexpr (kDeep) issue_values(bi);
+    if (g < NG) {   // K parameters of the block: every token group from the lane group that fetched it
+      *reinterpret_cast<u4_t*>(&wl.kpar[g][run0]) = kp0;
+      *reinterpret_cast<u4_t*>(&wl.kpar[g][run1]) = kp1;
+    }
     // ---- V parameters of the block's tokens, per channel group
 #pragma unroll
     for (int u = 0; u < 2; ++u)
@@ -339,7 +352,8 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
         }
       }
     }
-    if (has_next) {   // parameters first: they are the next block's first consumers
+    if constexpr (!kDeep) issue_values(bi);
+    if (kDeep && has_next) {   // parameters first: they are the next block's first consumers
       issue_params(nbi);
       issue_keys(nbi);
     }
@@ -413,6 +427,10 @@ __global__ __launch_bounds__(256) void decode_grp_kernel(GrpArgs a) {
           const int mt = v * (8 / NV) + mm;
           oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(F::dequant(vraw[mt].w, j), bp[j], oacc[mt], 0, 0, 0);
         }
+    }
+    if (!kDeep && has_next) {
+      issue_params(nbi);
+      issue_keys(nbi);
     }
     wave_sync();   // the next block's parameters overwrite this wave's LDS scratch
     blk = nblk;

@@ -180,6 +180,7 @@ def test_split_heuristic_properties():
     assert B.bd_choose_splits(_desc(), 40960) == 80 and B.bd_choose_splits(_desc(), 49152) == 96
     assert B.bd_choose_splits(_desc(), 57344) == 56
     assert B.bd_choose_splits(_desc(format=B.BD_FMT_MXFP4), 49152) == 48
-    # the kernels for smaller quantization groups run one workgroup per compute unit: 256 workgroups
-    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT4_G32), 32768) == 32
-    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT2_G64, n_q_heads=128), 32768) == 16   # two workgroups per KV head
+    # one instance of the kernel for smaller quantization groups runs one workgroup per compute unit
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT4_G32), 32768) == 64
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT4_G32, n_q_heads=64), 32768) == 32
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT2_G64, n_q_heads=128), 32768) == 32   # two workgroups per KV head
