@@ -181,7 +181,29 @@ def main() -> int:
         step_bytes.append(nbytes)
 
     stream = torch.cuda.current_stream()
-    if args.mode == "graph":
+    if args.mode == "graph" and paged:
+        # lengths and the flush decision live on the device: ONE captured step (all layers) is replayed
+        # for every step, its inputs copied into static buffers before each replay
+        kn_s, vn_s, q_s = torch.zeros_like(new_kv[0][0]), torch.zeros_like(new_kv[0][1]), torch.zeros_like(qs[0])
+        g_step = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_step):
+            for li, c in enumerate(caches):
+                c.decode_step(kn_s, vn_s, q_s, sm_scale, outs[li], splits)
+
+        def replay_step(s: int):
+            kn_s.copy_(new_kv[s][0]); vn_s.copy_(new_kv[s][1]); q_s.copy_(qs[s])
+            g_step.replay()
+            step_bytes.append(len(caches) * algorithmic_bytes(w, *lengths(w.context + s + 1)))
+
+        for s in range(args.warmup):
+            replay_step(s)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.warmup, total_steps):
+            replay_step(s)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    elif args.mode == "graph":
         g_warm, g_timed = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
         if args.warmup:
             with torch.cuda.graph(g_warm):

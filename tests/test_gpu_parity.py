@@ -822,6 +822,53 @@ def test_group_full_size_32k_sampled_heads():
         assert_attn_close(got[:, 4 * h:4 * h + 4], ref, f"int4_g32 32K head {h}")
 
 
+@pytest.mark.parametrize("fmt", ["int4", "mxfp4"])
+def test_paged_step_replays_from_one_captured_graph(fmt):
+    """Lengths and the flush decision live on the device, so ONE captured bd_paged_decode_step serves
+    every later step: the graph is replayed with new inputs copied into its static buffers (eager
+    copies and synchronizations between the replays), across a block boundary, and every replay is
+    checked against the oracle.  The library enqueues kernels only (no memset or copy nodes)."""
+    import torch
+    mx = fmt == "mxfp4"
+    dt, tdt = ("bf16", torch.bfloat16) if mx else ("fp16", torch.float16)
+    H, Hq, lens = 2, 8, [125, 300, 5]
+    if mx:
+        oc, gc, _ = _paged_mx_pair(lens, H, Hq, num_pages=30, max_pages=5)
+    else:
+        oc, gc, _ = _paged_pair(fmt, lens, H, Hq, num_pages=30, max_pages=5)
+    w = W.scaled(W.CONFIGS["cfg4" if mx else "cfg1"], batch=3, n_q_heads=Hq, n_kv_heads=H, context=128, seed=88)
+    kn_s = torch.zeros((3, H, 128), dtype=tdt, device="cuda:0")
+    vn_s, q_s = torch.zeros_like(kn_s), torch.zeros((3, Hq, 128), dtype=tdt, device="cuda:0")
+    out_s = torch.zeros((3, Hq, 128), dtype=tdt, device="cuda:0")
+    gc.workspace(3)                                   # allocated before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gc.decode_step(kn_s, vn_s, q_s, W.softmax_scale(w), out_s, 3)
+    torch.cuda.synchronize()
+    assert list(gc.seq_lens.cpu().numpy()) == lens    # capturing runs nothing
+    for step in range(6):                             # sequence 0 fills its block at step 2
+        kn, vn = W.make_new_kv(w, step)
+        q = W.make_q(w, step)
+        kn_s.copy_(to_dev(kn, dt)); vn_s.copy_(to_dev(vn, dt)); q_s.copy_(to_dev(q, dt))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        oc.append_kv(kn, vn)
+        ref = O.decode_attn(oc, q, W.softmax_scale(w))
+        got = out_to_f64(out_s)
+        if mx:
+            assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 2e-3), step
+        else:
+            assert_attn_close(got, ref, f"{fmt} replay {step}", large_outputs=True)
+        assert list(gc.seq_lens.cpu().numpy()) == [L + step + 1 for L in lens]
+    assert int(gc.status.item()) == 0
+    if mx:
+        _assert_paged_mx_equal(oc, gc, "after replays")
+    else:
+        _assert_paged_equal(oc, gc, "after replays")
+
+
 # ---------------------------------------------------------------------------- query groups
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])
