@@ -49,31 +49,76 @@ struct MxArgs {
   int step;   // paged: 1 when this launch is the attention of a fused step
 };
 
-template <int NG>
 struct MergeLdsMx {
-  float o[kWaves][4 * NG][kD];
-  float m[kWaves][4 * NG], l[kWaves][4 * NG];
+  float o[kWaves][4][kD];
+  float m[kWaves][4], l[kWaves][4];
 };
 
 __device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-// The query group is taken four heads at a time ("sub-groups").  NG = sub-groups one workgroup runs
-// over the same loaded keys and values (1, or 2 for groups of more than 4 heads, at one wave per
-// SIMD: the second set of operands and accumulators does not fit two); groups of more than 8 heads take
-// ceil(g_q / 8) workgroups per (split, KV head), which read the cache once each.
+// The query as the B operand of the scaled MFMA: exact split of each bf16 into two e4m3 pieces.
+// Operand layout of the 8-bit side (measured): lane (column, g) holds contraction indices
+// 16g .. 16g+15 in bytes 0..15 and 64+16g .. 64+16g+15 in bytes 16..31, while the 4-bit
+// side holds 32g .. 32g+31 per lane.  One block scale per head (all 128 channels) is used
+// for B, so its value does not depend on which lane the instruction reads it from.
+// qp: the head's query row + 16 * (lane / 16), or nullptr for a padding column (all zero).
+// Every lane of the wave must call this (it exchanges the head's maximum across lane groups).
+__device__ __forceinline__ void mx_query_operand(const uint16_t* qp, i8_t& bhi, i8_t& blo, int& sb_hi, int& sb_lo) {
+  float x[32];
+  u4_t raw[4] = {};
+  if (qp) {
+    raw[0] = *reinterpret_cast<const u4_t*>(qp);
+    raw[1] = *reinterpret_cast<const u4_t*>(qp + 8);
+    raw[2] = *reinterpret_cast<const u4_t*>(qp + 64);
+    raw[3] = *reinterpret_cast<const u4_t*>(qp + 72);
+  }
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    x[i] = bf2f((raw[i >> 3][(i >> 1) & 3] >> (16 * (i & 1))) & 0xFFFFu);
+    amax = fmaxf(amax, fabsf(x[i]));
+  }
+  amax = fmaxf(amax, __shfl_xor(amax, 16));
+  amax = fmaxf(amax, __shfl_xor(amax, 32));
+  int eb = 0;
+  if (amax > 0.0f) eb = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 127 - 7;   // amax * 2^-eb in [128, 256)
+  eb = min(max(eb, -123), 127);
+  sb_hi = eb + 127;
+  sb_lo = eb - 4 + 127;
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    int hi = 0, lo = 0;
+    float rem[4];
+#pragma unroll
+    for (int hw = 0; hw < 2; ++hw) {
+      const float x0 = ldexpf(x[4 * v + 2 * hw], -eb), x1 = ldexpf(x[4 * v + 2 * hw + 1], -eb);
+      hi = hw ? __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi, true) : __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi, false);
+      rem[2 * hw] = x0;
+      rem[2 * hw + 1] = x1;
+    }
+    rem[0] = (rem[0] - __builtin_amdgcn_cvt_f32_fp8(hi, 0)) * 16.0f;
+    rem[1] = (rem[1] - __builtin_amdgcn_cvt_f32_fp8(hi, 1)) * 16.0f;
+    rem[2] = (rem[2] - __builtin_amdgcn_cvt_f32_fp8(hi, 2)) * 16.0f;
+    rem[3] = (rem[3] - __builtin_amdgcn_cvt_f32_fp8(hi, 3)) * 16.0f;
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[0], rem[1], lo, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[2], rem[3], lo, true);
+    bhi[v] = hi;
+    blo[v] = lo;
+  }
+}
+
+// Query groups of up to 4 heads: the 16 MFMA columns carry the heads four times, and the softmax work
+// of a block is shared out over the copies (larger groups: decode_mx8_kernel).
 // PAGED: blocks are found through the block table and every sequence has its own length.
-template <int NG, bool PAGED>
-__global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs a) {
-  __shared__ MergeLdsMx<NG> ml;
-  const int nsub = (a.gq + 3) >> 2;              // sub-groups of the query group
-  const int nwg = (nsub + NG - 1) / NG;          // workgroups per (split, KV head)
-  const int split = blockIdx.x, hkv = blockIdx.y / nwg, sub0 = NG * (blockIdx.y % nwg), b = blockIdx.z;
+template <bool PAGED>
+__global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
+  __shared__ MergeLdsMx ml;
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;
   const int head = col & 3, cg = col >> 2;
-  const int head0 = hkv * a.gq + 4 * sub0;       // first query head of this workgroup
-  // heads of sub-group gi of this workgroup (0 past the end of the group)
-  auto sub_heads = [&](int gi) { return max(0, min(4, a.gq - 4 * (sub0 + gi))); };
+  const int head0 = hkv * a.gq;                  // first query head of this workgroup
+  const int nheads = min(4, a.gq);
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int length = a.length;
   if (PAGED) {
@@ -93,8 +138,8 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   const int nbcap = a.capacity / kBlock;
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
 
-  i8_t bhi[NG], blo[NG];      // Q[head][32g .. 32g+31] as two fp8 (e4m3) pieces, per sub-group
-  int sb_hi[NG], sb_lo[NG];   // their e8m0 block scales
+  i8_t bhi, blo;      // Q[head][32g .. 32g+31] as two fp8 (e4m3) pieces
+  int sb_hi, sb_lo;   // their e8m0 block scales
   u4_t kraw[8], vraw[8];
   uint32_t ksc[8];
   u4_t vsc[2];
@@ -143,66 +188,13 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   if (PAGED) blk = first_valid(blk, blk < blk1 ? table_entry(blk) : -1, bi);
   if (blk < blk1) issue_k(bi);
 
-  // ---- the query as the B operand: exact split of each bf16 into two e4m3 pieces.
-  // Operand layout of the 8-bit side (measured): lane (column, g) holds contraction indices
-  // 16g .. 16g+15 in bytes 0..15 and 64+16g .. 64+16g+15 in bytes 16..31, while the 4-bit
-  // side holds 32g .. 32g+31 per lane.  One block scale per head (all 128 channels) is used
-  // for B, so its value does not depend on which lane the instruction reads it from.
-#pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-    float x[32];
-    u4_t raw[4] = {};
-    if (head < sub_heads(gi)) {
-      const uint16_t* qp = a.q + ((size_t)b * a.n_q_heads + head0 + 4 * gi + head) * kD + 16 * g;
-      raw[0] = *reinterpret_cast<const u4_t*>(qp);
-      raw[1] = *reinterpret_cast<const u4_t*>(qp + 8);
-      raw[2] = *reinterpret_cast<const u4_t*>(qp + 64);
-      raw[3] = *reinterpret_cast<const u4_t*>(qp + 72);
-    }
-    float amax = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      x[i] = bf2f((raw[i >> 3][(i >> 1) & 3] >> (16 * (i & 1))) & 0xFFFFu);
-      amax = fmaxf(amax, fabsf(x[i]));
-    }
-    amax = fmaxf(amax, __shfl_xor(amax, 16));
-    amax = fmaxf(amax, __shfl_xor(amax, 32));
-    int eb = 0;
-    if (amax > 0.0f) eb = (int)((__float_as_uint(amax) >> 23) & 0xFFu) - 127 - 7;   // amax * 2^-eb in [128, 256)
-    eb = min(max(eb, -123), 127);
-    sb_hi[gi] = eb + 127;
-    sb_lo[gi] = eb - 4 + 127;
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-      int hi = 0, lo = 0;
-      float rem[4];
-#pragma unroll
-      for (int hw = 0; hw < 2; ++hw) {
-        const float x0 = ldexpf(x[4 * v + 2 * hw], -eb), x1 = ldexpf(x[4 * v + 2 * hw + 1], -eb);
-        hi = hw ? __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi, true) : __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, hi, false);
-        rem[2 * hw] = x0;
-        rem[2 * hw + 1] = x1;
-      }
-      rem[0] = (rem[0] - __builtin_amdgcn_cvt_f32_fp8(hi, 0)) * 16.0f;
-      rem[1] = (rem[1] - __builtin_amdgcn_cvt_f32_fp8(hi, 1)) * 16.0f;
-      rem[2] = (rem[2] - __builtin_amdgcn_cvt_f32_fp8(hi, 2)) * 16.0f;
-      rem[3] = (rem[3] - __builtin_amdgcn_cvt_f32_fp8(hi, 3)) * 16.0f;
-      lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[0], rem[1], lo, false);
-      lo = __builtin_amdgcn_cvt_pk_fp8_f32(rem[2], rem[3], lo, true);
-      bhi[gi][v] = hi;
-      blo[gi][v] = lo;
-    }
-  }
+  mx_query_operand(head < nheads ? a.q + ((size_t)b * a.n_q_heads + head0 + head) * kD + 16 * g : nullptr, bhi, blo,
+                   sb_hi, sb_lo);
 
-  float m_run[NG], l_run[NG];
-  f4_t oacc[NG][8];
+  float m_run = -INFINITY, l_run = 0.0f;
+  f4_t oacc[8];
 #pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-    m_run[gi] = -INFINITY;
-    l_run[gi] = 0.0f;
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt) oacc[gi][mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
-  }
+  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
 
   while (blk < blk1) {
     int nblk = blk + kWaves;
@@ -210,8 +202,6 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
     int next_entry = -1;   // requested a block ahead
     if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
     issue_v(bi);
-#pragma unroll
-    for (int gi = 0; gi < NG; ++gi) {   // the sub-groups in turn, over the same loaded block
     // ---- S^T tiles straight from the packed codes; column group cg keeps tiles cg and 4+cg
     float s[2][4];
 #pragma unroll
@@ -223,8 +213,8 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
         const i8_t ak = {(int)kraw[T][0], (int)kraw[T][1], (int)kraw[T][2], (int)kraw[T][3], 0, 0, 0, 0};
         const int sa = (int)((ksc[T] >> (8 * g)) & 0xFFu);
         f4_t acc = {0.f, 0.f, 0.f, 0.f};
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, bhi[gi], acc, 4, 0, 0, sa, 0, sb_hi[gi]);
-        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, blo[gi], acc, 4, 0, 0, sa, 0, sb_lo[gi]);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, bhi, acc, 4, 0, 0, sa, 0, sb_hi);
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, blo, acc, 4, 0, 0, sa, 0, sb_lo);
         st[tt] = acc;
       }
 #pragma unroll
@@ -238,13 +228,13 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
     float bmax = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                        fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
     bmax = head_max<4>(bmax);
-    const float m_new = fmaxf(m_run[gi], bmax);
-    const float alpha = __builtin_amdgcn_exp2f(m_run[gi] - m_new);
-    m_run[gi] = m_new;
-    l_run[gi] *= alpha;
+    const float m_new = fmaxf(m_run, bmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
     if (__any(alpha != 1.0f)) {
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) oacc[gi][mt] *= alpha;
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
     }
     float p[2][4];
 #pragma unroll
@@ -252,7 +242,7 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         p[half][r] = __builtin_amdgcn_exp2f(s[half][r] - m_new);
-        l_run[gi] += p[half][r];
+        l_run += p[half][r];
       }
     // ---- O^T += V^T P'_cb for the four 32-channel blocks cb (M tiles 2cb, 2cb+1)
 #pragma unroll
@@ -295,11 +285,10 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
           h2_t c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2);
           h2_t c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3);
           const h8_t av = {c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
-          oacc[gi][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[gi][mt], 0, 0, 0);
+          oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[mt], 0, 0, 0);
         }
       }
     }
-    }   // sub-groups
     if (PAGED) nblk = first_valid(nblk, next_entry, nbi);
     if (nblk < blk1) issue_k(nbi);
     blk = nblk;
@@ -307,25 +296,244 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
   }
 
   // ---- merge the waves of the workgroup
+  l_run = head_sum<4>(l_run);
+  if (col < 4) {
 #pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-    l_run[gi] = head_sum<4>(l_run[gi]);
-    if (col < 4) {
+    for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt)
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
+    if (g == 0) {
+      ml.m[wave][col] = m_run;
+      ml.l[wave][col] = l_run;
+    }
+  }
+  __syncthreads();
+  {
+    const int h = tid >> 6, c0 = 2 * (tid & 63);
+    if (h < nheads) {
+      float M = ml.m[0][h];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ml.o[wave][4 * gi + col][16 * mt + 4 * g + r] = oacc[gi][mt][r];
-      if (g == 0) {
-        ml.m[wave][4 * gi + col] = m_run[gi];
-        ml.l[wave][4 * gi + col] = l_run[gi];
+      for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
+      float L = 0.f, o0 = 0.f, o1 = 0.f;
+      if (M > -INFINITY) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          const float f = __builtin_amdgcn_exp2f(ml.m[w][h] - M);
+          L += f * ml.l[w][h];
+          o0 += f * ml.o[w][h][c0];
+          o1 += f * ml.o[w][h][c0 + 1];
+        }
       }
+      const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + head0 + h;
+      float2 o = {o0, o1};
+      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+      if ((tid & 63) == 0) {
+        a.part_ml[row * 2] = M;
+        a.part_ml[row * 2 + 1] = L;
+      }
+    }
+  }
+}
+
+
+// ---- groups of 5..8 heads (per workgroup): the 16 MFMA columns carry 8 heads twice ------------
+//
+// Both copies of a head's column receive the same S^T.  Copy cg keeps the four tiles of half cg
+// (tokens 32g + 16cg .. + 15 of every lane group g), runs their softmax, and presents their P' as
+// its part of the B operand of the second product: k-steps 2cg and 2cg+1, zero in the other two.
+// Nothing moves between lanes; the two copies' partial O^T are added once, after the loop.  The
+// keys, the values and every matrix instruction are shared by the 8 heads, so a group of 8 costs
+// what a group of 4 costs, except for twice the softmax work per lane.
+struct MergeLdsMx8 {
+  float o[kWaves][8][kD];
+  float m[kWaves][8], l[kWaves][8];
+};
+
+template <bool PAGED>
+__global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
+  __shared__ MergeLdsMx8 ml;
+  const int nwg = (a.gq + 7) >> 3;               // workgroups per (split, KV head)
+  const int split = blockIdx.x, hkv = blockIdx.y / nwg, sub0 = 8 * (blockIdx.y % nwg), b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, g = lane >> 4;
+  const int head = col & 7, cg = col >> 3;
+  const int head0 = hkv * a.gq + sub0;           // first query head of this workgroup
+  const int nheads = min(8, a.gq - sub0);
+  const size_t unit = (size_t)b * a.n_kv_heads + hkv;
+  int length = a.length;
+  if (PAGED) {
+    length = a.seq_lens[b];
+    if (a.step && length >= 0) {
+      const int n = length / kBlock;
+      const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
+      length += (e >= 0 && e < a.num_pages) ? 1 : 0;
+    }
+    length = max(0, length);
+  }
+  const int nb = (length + kBlock - 1) / kBlock;
+  const int blk0 = (int)(((long)nb * split) / a.num_splits);
+  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  const int nbcap = a.capacity / kBlock;
+  const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
+
+  i8_t bhi, blo;
+  int sb_hi, sb_lo;
+  u4_t kraw[8], vraw[8];
+  uint32_t ksc[8];
+  u4_t vsc[4];   // e8m0 scales (4 channel blocks) of this lane's 16 tokens, 4 tokens per register
+  auto issue_k = [&](size_t bi) {
+    const size_t tok0 = bi * kBlock;
+#pragma unroll
+    for (int T = 0; T < 8; ++T) {
+      const size_t t = tok0 + tok_base + 4 * T;
+      ksc[T] = *reinterpret_cast<const uint32_t*>(a.k_scales + t * 4);
+      kraw[T] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(a.k_codes + t * 64 + 16 * g));
+    }
+  };
+  auto issue_v = [&](size_t bi) {
+    const size_t tok0 = bi * kBlock;
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+      vsc[tt] = *reinterpret_cast<const u4_t*>(a.v_scales + (tok0 + 32 * g + 16 * cg + 4 * tt) * 4);
+    const uint8_t* vp = a.v_codes + bi * (size_t)(kD * 64) + 16 * g;
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+      vraw[mt] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(vp + (size_t)(16 * mt + col) * 64));
+  };
+  auto table_entry = [&](int n) { return n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1; };
+  auto first_valid = [&](int n, int entry, size_t& bi) {
+    while (n < blk1) {
+      if (entry >= 0 && entry < a.num_pages) {
+        bi = (size_t)entry * a.n_kv_heads + hkv;
+        break;
+      }
+      if (a.status && lane == 0) atomicOr(a.status, 1);
+      n += kWaves;
+      entry = n < blk1 ? table_entry(n) : -1;
+    }
+    return n;
+  };
+  int blk = blk0 + wave;
+  size_t bi = unit * nbcap + blk;
+  if (PAGED) blk = first_valid(blk, blk < blk1 ? table_entry(blk) : -1, bi);
+  if (blk < blk1) issue_k(bi);
+
+  mx_query_operand(head < nheads ? a.q + ((size_t)b * a.n_q_heads + head0 + head) * kD + 16 * g : nullptr, bhi, blo,
+                   sb_hi, sb_lo);
+
+  float m_run = -INFINITY, l_run = 0.0f;
+  f4_t oacc[8];
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+  while (blk < blk1) {
+    int nblk = blk + kWaves;
+    size_t nbi = bi + kWaves;
+    int next_entry = -1;
+    if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
+    issue_v(bi);
+    // ---- S^T tiles straight from the packed codes; copy cg keeps tiles 4cg .. 4cg+3
+    float s[4][4];
+#pragma unroll
+    for (int T = 0; T < 8; ++T) {
+      const i8_t ak = {(int)kraw[T][0], (int)kraw[T][1], (int)kraw[T][2], (int)kraw[T][3], 0, 0, 0, 0};
+      const int sa = (int)((ksc[T] >> (8 * g)) & 0xFFu);
+      f4_t acc = {0.f, 0.f, 0.f, 0.f};
+      acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, bhi, acc, 4, 0, 0, sa, 0, sb_hi);
+      acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ak, blo, acc, 4, 0, 0, sa, 0, sb_lo);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int t = blk * kBlock + 32 * g + 4 * T + r;
+        const float v = t < length ? acc[r] * a.scale_log2 : -INFINITY;   // tokens past the end
+        if (T < 4) s[T][r] = v;                       // half 0, kept where cg == 0
+        else s[T - 4][r] = cg ? v : s[T - 4][r];      // half 1 replaces it in the other copy
+      }
+    }
+    // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16cg + 4tt + r
+    float bmax = s[0][0];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, s[tt][r]);
+    bmax = head_max<2>(bmax);
+    const float m_new = fmaxf(m_run, bmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[tt][r] = __builtin_amdgcn_exp2f(s[tt][r] - m_new);
+        l_run += s[tt][r];
+      }
+    // ---- O^T += V^T P'_cb for the four 32-channel blocks cb (M tiles 2cb, 2cb+1)
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+      uint32_t pk[4][2];   // [tile][rows 0,1 | rows 2,3] as packed fp16
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        float pe[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          int e = (int)((vsc[tt][r] >> (8 * cb)) & 0xFFu) - 127;
+          e = min(e, 15);   // keeps P' inside fp16; larger scales mean |V| > 2e5
+          pe[r] = ldexpf(s[tt][r], e);
+        }
+        pk[tt][0] = (uint32_t)f2h(pe[0]) | ((uint32_t)f2h(pe[1]) << 16);
+        pk[tt][1] = (uint32_t)f2h(pe[2]) | ((uint32_t)f2h(pe[3]) << 16);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        // k-step j contracts tokens 32g + 8j .. + 7: tiles 2j and 2j+1, owned by copy j / 2
+        const int jo = j & 1;
+        u4_t pb = {pk[2 * jo][0], pk[2 * jo][1], pk[2 * jo + 1][0], pk[2 * jo + 1][1]};
+        if ((j >> 1) != cg) pb = (u4_t){0u, 0u, 0u, 0u};
+        const h8_t bp = __builtin_bit_cast(h8_t, pb);
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+          const int mt = 2 * cb + mm;
+          const uint32_t w = vraw[mt][j];
+          h2_t c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0);
+          h2_t c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1);
+          h2_t c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2);
+          h2_t c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3);
+          const h8_t av = {c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
+          oacc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bp, oacc[mt], 0, 0, 0);
+        }
+      }
+    }
+    if (PAGED) nblk = first_valid(nblk, next_entry, nbi);
+    if (nblk < blk1) issue_k(nbi);
+    blk = nblk;
+    bi = nbi;
+  }
+
+  // ---- the two copies' partial O^T, then the waves of the workgroup
+  l_run = head_sum<2>(l_run);
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) oacc[mt][r] += dpp_f<kRowShl8>(oacc[mt][r]);
+  if (col < 8) {
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
+    if (g == 0) {
+      ml.m[wave][col] = m_run;
+      ml.l[wave][col] = l_run;
     }
   }
   __syncthreads();
 #pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-    const int h = 4 * gi + (tid >> 6), c0 = 2 * (tid & 63);
-    if ((tid >> 6) < sub_heads(gi)) {
+  for (int p = 0; p < 2; ++p) {
+    const int h = 4 * p + (tid >> 6), c0 = 2 * (tid & 63);
+    if (h < nheads) {
       float M = ml.m[0][h];
 #pragma unroll
       for (int w = 1; w < kWaves; ++w) M = fmaxf(M, ml.m[w][h]);
@@ -354,12 +562,11 @@ __global__ __launch_bounds__(256, NG == 1 ? 2 : 1) void decode_mx_kernel(MxArgs 
 
 template <bool PAGED>
 static hipError_t launch_mx(const MxArgs& a, int batch, hipStream_t st) {
-  const int nsub = (a.gq + 3) / 4;
   dim3 block(256);
-  if (nsub == 1)
-    decode_mx_kernel<1, PAGED><<<dim3(a.num_splits, a.n_kv_heads, batch), block, 0, st>>>(a);
+  if (a.gq <= 4)
+    decode_mx_kernel<PAGED><<<dim3(a.num_splits, a.n_kv_heads, batch), block, 0, st>>>(a);
   else
-    decode_mx_kernel<2, PAGED><<<dim3(a.num_splits, a.n_kv_heads * ((nsub + 1) / 2), batch), block, 0, st>>>(a);
+    decode_mx8_kernel<PAGED><<<dim3(a.num_splits, a.n_kv_heads * ((a.gq + 7) / 8), batch), block, 0, st>>>(a);
   return hipGetLastError();
 }
 
