@@ -15,7 +15,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // workgroups per split and sequence: KV heads x pieces of the query group
 long group_workgroups(const bd_cache* c) {
   const int gq = c->n_q_heads / c->n_kv_heads;
-  const int pieces = c->format == BD_FMT_MXFP4 ? (gq + 7) / 8
+  const int pieces = c->format == BD_FMT_MXFP4 ? (gq + 15) / 16
                      : fmt_group(c->format) != kBlock ? (gq + 7) / 8 : (gq + 15) / 16;
   return (long)c->n_kv_heads * pieces;
 }
@@ -28,7 +28,7 @@ bd_status check_shape(const bd_cache* c) {
   if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
   if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;
   // query heads per KV head: the int4 / int2 kernels pad the group to 4, 8 or 16 MFMA columns and
-  // take larger groups 16 heads per workgroup; the MXFP4 kernels take up to 8 heads per workgroup.
+  // take larger groups 16 heads per workgroup; the MXFP4 kernels take up to 16 heads per workgroup.
   // The workgroups of one split must fit grid dimension y.
   if (group_workgroups(c) > 65535) return BD_ERR_UNSUPPORTED;
   return BD_OK;

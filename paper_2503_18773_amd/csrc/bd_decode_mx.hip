@@ -108,7 +108,7 @@ __device__ __forceinline__ void mx_query_operand(const uint16_t* qp, i8_t& bhi, 
 }
 
 // Query groups of up to 4 heads: the 16 MFMA columns carry the heads four times, and the softmax work
-// of a block is shared out over the copies (larger groups: decode_mx8_kernel).
+// of a block is shared out over the copies (larger groups: decode_mxg_kernel).
 // PAGED: blocks are found through the block table and every sequence has its own length.
 template <bool PAGED>
 __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
@@ -336,29 +336,33 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
 }
 
 
-// ---- groups of 5..8 heads (per workgroup): the 16 MFMA columns carry 8 heads twice ------------
+// ---- groups of 5..16 heads per workgroup: GQP = 8 (the 16 MFMA columns carry 8 heads twice) or 16
 //
-// Both copies of a head's column receive the same S^T.  Copy cg keeps the four tiles of half cg
-// (tokens 32g + 16cg .. + 15 of every lane group g), runs their softmax, and presents their P' as
-// its part of the B operand of the second product: k-steps 2cg and 2cg+1, zero in the other two.
-// Nothing moves between lanes; the two copies' partial O^T are added once, after the loop.  The
-// keys, the values and every matrix instruction are shared by the 8 heads, so a group of 8 costs
-// what a group of 4 costs, except for twice the softmax work per lane.
-struct MergeLdsMx8 {
-  float o[kWaves][8][kD];
-  float m[kWaves][8], l[kWaves][8];
+// Every copy of a head's column receives the same S^T.  Copy cg keeps the tiles of its share of
+// the block (GQP = 8: the four tiles of half cg, tokens 32g + 16cg .. + 15 of every lane group g;
+// GQP = 16: all eight), runs their softmax, and presents their P' as its part of the B operand of
+// the second product: the k-steps that contract those tokens, zero in the others.  Nothing moves
+// between lanes; the copies' partial O^T are added once, after the loop.  The keys, the values
+// and every matrix instruction are shared by all heads, so a group of 8 or 16 costs what a
+// group of 4 costs, except for 2x / 4x the softmax work per lane.
+template <int GQP>
+struct MergeLdsMxG {
+  float o[kWaves][GQP][kD];
+  float m[kWaves][GQP], l[kWaves][GQP];
 };
 
-template <bool PAGED>
-__global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
-  __shared__ MergeLdsMx8 ml;
-  const int nwg = (a.gq + 7) >> 3;               // workgroups per (split, KV head)
-  const int split = blockIdx.x, hkv = blockIdx.y / nwg, sub0 = 8 * (blockIdx.y % nwg), b = blockIdx.z;
+template <int GQP, bool PAGED>
+__global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_kernel(MxArgs a) {
+  constexpr int COPIES = 16 / GQP;     // 2 or 1
+  constexpr int NT = 8 / COPIES;       // S^T tiles a lane keeps
+  __shared__ MergeLdsMxG<GQP> ml;
+  const int nwg = (a.gq + GQP - 1) / GQP;        // workgroups per (split, KV head)
+  const int split = blockIdx.x, hkv = blockIdx.y / nwg, sub0 = GQP * (blockIdx.y % nwg), b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;
-  const int head = col & 7, cg = col >> 3;
+  const int head = col % GQP, cg = col / GQP;
   const int head0 = hkv * a.gq + sub0;           // first query head of this workgroup
-  const int nheads = min(8, a.gq - sub0);
+  const int nheads = min(GQP, a.gq - sub0);
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int length = a.length;
   if (PAGED) {
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
   int sb_hi, sb_lo;
   u4_t kraw[8], vraw[8];
   uint32_t ksc[8];
-  u4_t vsc[4];   // e8m0 scales (4 channel blocks) of this lane's 16 tokens, 4 tokens per register
+  u4_t vsc[NT];   // e8m0 scales (4 channel blocks) of this lane's 4 * NT tokens, 4 tokens per register
   auto issue_k = [&](size_t bi) {
     const size_t tok0 = bi * kBlock;
 #pragma unroll
@@ -393,8 +397,8 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
   auto issue_v = [&](size_t bi) {
     const size_t tok0 = bi * kBlock;
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
-      vsc[tt] = *reinterpret_cast<const u4_t*>(a.v_scales + (tok0 + 32 * g + 16 * cg + 4 * tt) * 4);
+    for (int tt = 0; tt < NT; ++tt)
+      vsc[tt] = *reinterpret_cast<const u4_t*>(a.v_scales + (tok0 + 32 * g + 4 * NT * cg + 4 * tt) * 4);
     const uint8_t* vp = a.v_codes + bi * (size_t)(kD * 64) + 16 * g;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
@@ -432,8 +436,8 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
     int next_entry = -1;
     if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
     issue_v(bi);
-    // ---- S^T tiles straight from the packed codes; copy cg keeps tiles 4cg .. 4cg+3
-    float s[4][4];
+    // ---- S^T tiles straight from the packed codes; copy cg keeps tiles NT*cg .. NT*cg + NT-1
+    float s[NT][4];
 #pragma unroll
     for (int T = 0; T < 8; ++T) {
       const i8_t ak = {(int)kraw[T][0], (int)kraw[T][1], (int)kraw[T][2], (int)kraw[T][3], 0, 0, 0, 0};
@@ -445,17 +449,17 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
       for (int r = 0; r < 4; ++r) {
         const int t = blk * kBlock + 32 * g + 4 * T + r;
         const float v = t < length ? acc[r] * a.scale_log2 : -INFINITY;   // tokens past the end
-        if (T < 4) s[T][r] = v;                       // half 0, kept where cg == 0
-        else s[T - 4][r] = cg ? v : s[T - 4][r];      // half 1 replaces it in the other copy
+        if (T < NT) s[T][r] = v;                      // (first half: kept where cg == 0)
+        else s[T - NT][r] = cg ? v : s[T - NT][r];    // the second half replaces it in the other copy
       }
     }
-    // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 16cg + 4tt + r
+    // ---- online softmax (Alg. 1): this lane owns head `head`, tokens 32g + 4*NT*cg + 4tt + r
     float bmax = s[0][0];
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
+    for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, s[tt][r]);
-    bmax = head_max<2>(bmax);
+    bmax = head_max<COPIES>(bmax);
     const float m_new = fmaxf(m_run, bmax);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
       for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
     }
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt)
+    for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         s[tt][r] = __builtin_amdgcn_exp2f(s[tt][r] - m_new);
@@ -474,9 +478,9 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
     // ---- O^T += V^T P'_cb for the four 32-channel blocks cb (M tiles 2cb, 2cb+1)
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) {
-      uint32_t pk[4][2];   // [tile][rows 0,1 | rows 2,3] as packed fp16
+      uint32_t pk[NT][2];   // [tile][rows 0,1 | rows 2,3] as packed fp16
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
+      for (int tt = 0; tt < NT; ++tt) {
         float pe[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -489,10 +493,10 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        // k-step j contracts tokens 32g + 8j .. + 7: tiles 2j and 2j+1, owned by copy j / 2
-        const int jo = j & 1;
+        // k-step j contracts tokens 32g + 8j .. + 7: tiles 2j and 2j+1, owned by copy 2j / NT
+        const int jo = j % (NT / 2);
         u4_t pb = {pk[2 * jo][0], pk[2 * jo][1], pk[2 * jo + 1][0], pk[2 * jo + 1][1]};
-        if ((j >> 1) != cg) pb = (u4_t){0u, 0u, 0u, 0u};
+        if (COPIES > 1 && (2 * j) / NT != cg) pb = (u4_t){0u, 0u, 0u, 0u};
         const h8_t bp = __builtin_bit_cast(h8_t, pb);
 #pragma unroll
         for (int mm = 0; mm < 2; ++mm) {
@@ -513,13 +517,15 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
     bi = nbi;
   }
 
-  // ---- the two copies' partial O^T, then the waves of the workgroup
-  l_run = head_sum<2>(l_run);
+  // ---- the copies' partial O^T, then the waves of the workgroup
+  l_run = head_sum<COPIES>(l_run);
+  if (COPIES == 2) {
 #pragma unroll
-  for (int mt = 0; mt < 8; ++mt)
+    for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) oacc[mt][r] += dpp_f<kRowShl8>(oacc[mt][r]);
-  if (col < 8) {
+      for (int r = 0; r < 4; ++r) oacc[mt][r] += dpp_f<kRowShl8>(oacc[mt][r]);
+  }
+  if (col < GQP) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
@@ -531,7 +537,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx8_kernel(MxArgs a) {
   }
   __syncthreads();
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
+  for (int p = 0; p < GQP / 4; ++p) {
     const int h = 4 * p + (tid >> 6), c0 = 2 * (tid & 63);
     if (h < nheads) {
       float M = ml.m[0][h];
@@ -565,8 +571,10 @@ static hipError_t launch_mx(const MxArgs& a, int batch, hipStream_t st) {
   dim3 block(256);
   if (a.gq <= 4)
     decode_mx_kernel<PAGED><<<dim3(a.num_splits, a.n_kv_heads, batch), block, 0, st>>>(a);
+  else if (a.gq <= 8)
+    decode_mxg_kernel<8, PAGED><<<dim3(a.num_splits, a.n_kv_heads, batch), block, 0, st>>>(a);
   else
-    decode_mx8_kernel<PAGED><<<dim3(a.num_splits, a.n_kv_heads * ((a.gq + 7) / 8), batch), block, 0, st>>>(a);
+    decode_mxg_kernel<16, PAGED><<<dim3(a.num_splits, a.n_kv_heads * ((a.gq + 15) / 16), batch), block, 0, st>>>(a);
   return hipGetLastError();
 }
 
