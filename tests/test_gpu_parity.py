@@ -869,6 +869,32 @@ def test_paged_step_replays_from_one_captured_graph(fmt):
         _assert_paged_equal(oc, gc, "after replays")
 
 
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64", "mxfp4"])
+def test_peaked_and_flat_attention(fmt):
+    """Queries scaled by 6 (logits of several tens: a handful of tokens take all the weight and the
+    running maximum moves across blocks and splits; much larger logits only test the conditioning of
+    softmax itself, an fp32 rounding of a logit of 400 moves a weight by 1e-3) and by 1e-3
+    (uniform weights over 1500 tokens)."""
+    import torch
+    mx = fmt == "mxfp4"
+    base = "cfg4" if mx else "cfg1"
+    L = 128 * 11 + 93
+    w = W.scaled(W.CONFIGS[base], batch=2, n_q_heads=8, n_kv_heads=2, context=L, fmt=fmt, seed=123)
+    if mx:
+        K, V, oc, gc = _mx_pair(w, 128 * 13)
+    else:
+        K, V, oc, gc = _int_cache_pair(w, 128 * 13)
+    for factor in (6.0, 1e-3):
+        q = W.make_q(w, 3) * np.float32(factor)
+        q = W.round_to_bf16(q) if mx else q.astype(np.float16)
+        ref = O.decode_attn(oc, q, W.softmax_scale(w))
+        for ns in (1, 4, 12):
+            if mx:
+                _mx_decode_check(gc, ref, w, q, ns, f"mx q x {factor} splits {ns}")
+            else:
+                assert_attn_close(_decode(gc, w, q, num_splits=ns), ref, f"{fmt} q x {factor} splits {ns}", large_outputs=True)
+
+
 # ---------------------------------------------------------------------------- query groups
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])
