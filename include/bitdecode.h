@@ -135,7 +135,9 @@ bd_status bd_append_kv(const bd_cache* c, const void* k_new, const void* v_new,
  * q device [B][n_q_heads][D] (fp16; bf16 for MXFP4); query head h attends KV head h / g_q
  * over the packed_len quantized tokens and the res_len residual tokens, logits scaled by
  * softmax_scale.  Writes num_splits partials into `workspace` (device, at least
- * bd_workspace_bytes(c, num_splits), 16-byte aligned).  If `out` is non-NULL (device,
+ * bd_workspace_bytes(c, num_splits), 16-byte aligned; with num_splits == 1 and `out` given the
+ * partials are not written: the attention kernel stores `out` itself, the same values, and no
+ * merge kernel runs).  If `out` is non-NULL (device,
  * [B][n_q_heads][D], fp16 / bf16) the merge of the partials is enqueued too, so `out`
  * is complete when the stream passes this call; if NULL, call bd_splitk_combine.
  * num_splits >= 1 (any value; splits beyond the number of 128-token blocks stay empty).

@@ -187,17 +187,18 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
   float* part_ml = ws_part_ml(c, workspace, num_splits);
   if (c->format == BD_FMT_MXFP4) {
     if (res_len != 0) return BD_ERR_INVALID_ARG;
-    s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, st));
+    s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, out, st));
   } else {
     if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
     if (fmt_group(c->format) != kBlock)
-      s = hip_status(launch_decode_grp(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, st));
+      s = hip_status(launch_decode_grp(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, out, st));
     else
       s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml,
-                                       nullptr, nullptr, st));
+                                       nullptr, nullptr, out, st));
   }
   if (s != BD_OK) return s;
-  if (out) s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st));
+  // (one split: the attention kernel has written `out` itself, there is nothing to merge)
+  if (out && num_splits > 1) s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st));
   return s;
 }
 
@@ -224,9 +225,9 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(c, workspace, num_splits);
   if ((s = hip_status(launch_decode_int(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new,
-                                        st))) != BD_OK)
+                                        out, st))) != BD_OK)
     return s;
-  if ((s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
+  if (num_splits > 1 && (s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
   *res_len = r + 1;
   return BD_OK;
 }
@@ -332,12 +333,14 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
   const bd_cache shape = shape_of(c);
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(&shape, workspace, num_splits);
+  // one split and no lengths to raise afterwards: the attention kernel writes `out` itself, no merge
+  void* direct = (num_splits == 1 && !step) ? out : nullptr;
   bd_status s = hip_status(c->format == BD_FMT_MXFP4
-                               ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st)
+                               ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
                            : fmt_group(c->format) != kBlock
-                               ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st)
-                               : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, st));
-  if (s != BD_OK) return s;
+                               ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
+                               : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st));
+  if (s != BD_OK || direct) return s;
   return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st, step ? c : nullptr));
 }
 

@@ -47,23 +47,25 @@ hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k,
                                 hipStream_t st);
 hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const void* v_new, bool bump,
                                hipStream_t st);
+// `out` (all decode launchers): with num_splits == 1 and out != nullptr the kernel writes the final output
+// rows itself and no merge is needed; otherwise it writes the split partials.
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                               float* part_o, float* part_ml, bool step, hipStream_t st);
+                               float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
 
 // k_new / v_new non-null: fused step -- residual token res_len-1 is read from k_new / v_new
 // ([B][Hkv][128]) and also stored into the residual buffers by the kernel.
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,
                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
-                             const void* k_new, const void* v_new, hipStream_t st);
+                             const void* k_new, const void* v_new, void* out, hipStream_t st);
 // formats with a quantization group of 64 or 32
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
-                             int num_splits, float* part_o, float* part_ml, hipStream_t st);
+                             int num_splits, float* part_o, float* part_ml, void* out, hipStream_t st);
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                   float* part_o, float* part_ml, bool step, hipStream_t st);
+                                   float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                  float* part_o, float* part_ml, bool step, hipStream_t st);
+                                  float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale,
-                            int num_splits, float* part_o, float* part_ml, hipStream_t st);
+                            int num_splits, float* part_o, float* part_ml, void* out, hipStream_t st);
 // step_of: the paged cache whose fused step this merge ends (it then raises the lengths), or nullptr
 hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* part_ml, int nparts,
                           void* out, hipStream_t st, const bd_paged_cache* step_of = nullptr);

@@ -71,6 +71,7 @@ struct DecodeArgs {
   int new_slot;            // its residual slot (res_len - 1), or -1 when the residual buffers are complete
   float* part_o;    // [nparts][B][Hq][128]
   float* part_ml;   // [nparts][B][Hq][2]   (running max in log2 units, running sum)
+  uint16_t* out;    // one split only: the output [B][Hq][128] (fp16), written instead of the partials; else nullptr
   int n_q_heads, n_kv_heads, gq;
   int nb;           // packed 128-token blocks
   int nbcap;
@@ -696,10 +697,14 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * a.gq + head0 + h;
       float2 o = {o0 + Z, o1 + Z};
-      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
-      if ((tid & 63) == 0) {
-        a.part_ml[row * 2] = M;
-        a.part_ml[row * 2 + 1] = L;
+      if (a.out) {   // one split: row == the output row
+        store_final_pair(a.out + row * kD + c0, 0, o.x, o.y, L);
+      } else {
+        *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+        if ((tid & 63) == 0) {
+          a.part_ml[row * 2] = M;
+          a.part_ml[row * 2 + 1] = L;
+        }
       }
     }
   }
@@ -827,8 +832,9 @@ void launch_instance(int format, int gq, bool single, bool paged, const DecodeAr
 
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
-                             hipStream_t st) {
+                             void* out, hipStream_t st) {
   DecodeArgs a;
+  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;
@@ -861,9 +867,10 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
 }
 
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                               float* part_o, float* part_ml, bool step, hipStream_t st) {
+                               float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
   DecodeArgs a;
   a.step = step ? 1 : 0;
+  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;

@@ -37,6 +37,7 @@ struct GrpArgs {
   const uint16_t* q;
   float* part_o;    // [nparts][B][Hq][128]
   float* part_ml;   // [nparts][B][Hq][2]
+  uint16_t* out;    // one split only: the output [B][Hq][128] (fp16), written instead of the partials; else nullptr
   int n_q_heads, n_kv_heads, gq;
   int nb, nbcap, res_len, num_splits;
   float scale_log2;
@@ -487,10 +488,14 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * a.gq + head0 + h;
       float2 o = {o0 + Z, o1 + Z};
-      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
-      if (lane == 0) {
-        a.part_ml[row * 2] = M;
-        a.part_ml[row * 2 + 1] = L;
+      if (a.out) {   // one split: row == the output row
+        store_final_pair(a.out + row * kD + c0, 0, o.x, o.y, L);
+      } else {
+        *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+        if (lane == 0) {
+          a.part_ml[row * 2] = M;
+          a.part_ml[row * 2 + 1] = L;
+        }
       }
     }
   }
@@ -522,8 +527,9 @@ hipError_t launch_format(int format, const GrpArgs& a, bool paged, int batch, hi
 }  // namespace
 
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
-                             int num_splits, float* part_o, float* part_ml, hipStream_t st) {
+                             int num_splits, float* part_o, float* part_ml, void* out, hipStream_t st) {
   GrpArgs a;
+  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;
@@ -549,8 +555,9 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
 }
 
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                   float* part_o, float* part_ml, bool step, hipStream_t st) {
+                                   float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
   GrpArgs a;
+  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;

@@ -36,6 +36,7 @@ struct MxArgs {
   const uint16_t* q;
   float* part_o;
   float* part_ml;
+  uint16_t* out;   // one split only: the output [B][Hq][128] (bf16), written instead of the partials; else nullptr
   int n_q_heads, n_kv_heads, gq;
   int length;      // tokens in the cache
   int capacity;
@@ -325,11 +326,15 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
         }
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + head0 + h;
-      float2 o = {o0, o1};
-      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
-      if ((tid & 63) == 0) {
-        a.part_ml[row * 2] = M;
-        a.part_ml[row * 2 + 1] = L;
+      if (a.out) {   // one split: row == the output row
+        store_final_pair(a.out + row * kD + c0, 1, o0, o1, L);
+      } else {
+        float2 o = {o0, o1};
+        *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+        if ((tid & 63) == 0) {
+          a.part_ml[row * 2] = M;
+          a.part_ml[row * 2 + 1] = L;
+        }
       }
     }
   }
@@ -554,11 +559,15 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
         }
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + head0 + h;
-      float2 o = {o0, o1};
-      *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
-      if ((tid & 63) == 0) {
-        a.part_ml[row * 2] = M;
-        a.part_ml[row * 2 + 1] = L;
+      if (a.out) {   // one split: row == the output row
+        store_final_pair(a.out + row * kD + c0, 1, o0, o1, L);
+      } else {
+        float2 o = {o0, o1};
+        *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
+        if ((tid & 63) == 0) {
+          a.part_ml[row * 2] = M;
+          a.part_ml[row * 2 + 1] = L;
+        }
       }
     }
   }
@@ -579,8 +588,9 @@ static hipError_t launch_mx(const MxArgs& a, int batch, hipStream_t st) {
 }
 
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale, int num_splits,
-                            float* part_o, float* part_ml, hipStream_t st) {
+                            float* part_o, float* part_ml, void* out, hipStream_t st) {
   MxArgs a{};
+  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;
   a.k_scales = (const uint8_t*)c->k_params;
@@ -599,8 +609,9 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
 }
 
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                  float* part_o, float* part_ml, bool step, hipStream_t st) {
+                                  float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
   MxArgs a{};
+  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.step = step ? 1 : 0;
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;

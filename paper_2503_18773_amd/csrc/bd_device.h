@@ -58,6 +58,25 @@ __device__ __forceinline__ float head_max(float x) {
   return x;
 }
 
+// A launch with one split needs no merge: the workgroup's (L, o) is the result, stored as two
+// adjacent fp16 / bf16 outputs o / L exactly as the merge kernel would compute them (a head that
+// attended nothing, L == 0, gives zeros).
+__device__ __forceinline__ void store_final_pair(uint16_t* out, int bf16, float o0, float o1, float L) {
+  const float r0 = L > 0.f ? o0 / L : 0.f, r1 = L > 0.f ? o1 / L : 0.f;
+  uint32_t lo, hi;
+  if (bf16) {
+    uint32_t u0 = __float_as_uint(r0), u1 = __float_as_uint(r1);
+    u0 += 0x7FFFu + ((u0 >> 16) & 1u);
+    u1 += 0x7FFFu + ((u1 >> 16) & 1u);
+    lo = u0 >> 16;
+    hi = u1 >> 16;
+  } else {
+    lo = f2h(r0);
+    hi = f2h(r1);
+  }
+  *reinterpret_cast<uint32_t*>(out) = lo | (hi << 16);
+}
+
 __device__ __forceinline__ void wave_sync() {
   // LDS operations of one wave execute in order; this only stops the compiler from moving
   // accesses across the exchange point.
