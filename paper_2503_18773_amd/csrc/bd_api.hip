@@ -333,14 +333,16 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
   const bd_cache shape = shape_of(c);
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(&shape, workspace, num_splits);
-  // one split and no lengths to raise afterwards: the attention kernel writes `out` itself, no merge
-  void* direct = (num_splits == 1 && !step) ? out : nullptr;
+  // one split: the attention kernel writes `out` itself and no merge runs (a fused step then raises the
+  // lengths with the small kernel of bd_paged_append_kv instead of in the merge)
+  void* direct = num_splits == 1 ? out : nullptr;
   bd_status s = hip_status(c->format == BD_FMT_MXFP4
                                ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
                            : fmt_group(c->format) != kBlock
                                ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
                                : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st));
-  if (s != BD_OK || direct) return s;
+  if (s != BD_OK) return s;
+  if (direct) return step ? hip_status(launch_paged_bump(c, st)) : BD_OK;
   return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st, step ? c : nullptr));
 }
 

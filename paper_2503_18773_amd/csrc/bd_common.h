@@ -49,6 +49,8 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
                                hipStream_t st);
 // `out` (all decode launchers): with num_splits == 1 and out != nullptr the kernel writes the final output
 // rows itself and no merge is needed; otherwise it writes the split partials.
+// raises the length of every sequence whose step's token was appended (launch_paged_append with bump = false)
+hipError_t launch_paged_bump(const bd_paged_cache* c, hipStream_t st);
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
 

@@ -874,6 +874,11 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
   return hipGetLastError();
 }
 
+hipError_t launch_paged_bump(const bd_paged_cache* c, hipStream_t st) {
+  paged_bump_kernel<<<dim3((c->batch + 63) / 64), dim3(64), 0, st>>>(paged_args(c), c->batch, c->format == BD_FMT_MXFP4);
+  return hipGetLastError();
+}
+
 hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0, void* kdst,
                             void* vdst, long dst_unit_stride, int dst_tok0, int ntok, int units,
                             hipStream_t st) {
