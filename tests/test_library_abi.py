@@ -176,6 +176,9 @@ def test_split_heuristic_properties():
             prev = s
     assert B.bd_choose_splits(_desc(), 32768) == 64 and B.bd_choose_splits(_desc(), 131072) == 64
     assert B.bd_choose_splits(_desc(batch=8), 32768) == 8
+    # a chip already full of units takes one split (no merge kernel) unless the call is long
+    assert B.bd_choose_splits(_desc(batch=48), 4096) == 1 and B.bd_choose_splits(_desc(batch=32), 4096) == 1
+    assert B.bd_choose_splits(_desc(batch=32), 16384) == 2
     # one block per wave is kept up to three workgroups per compute unit (integer formats, groups <= 8)
     assert B.bd_choose_splits(_desc(), 40960) == 80 and B.bd_choose_splits(_desc(), 49152) == 96
     assert B.bd_choose_splits(_desc(), 57344) == 56
