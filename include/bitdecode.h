@@ -76,8 +76,7 @@ typedef enum {
    * block (Sec. IV-C(1): K_p of shape (T_n/group, d), V_p of shape (T_n, d/group)): K statistics
    * over 64 or 32 tokens per channel, V statistics over 64 or 32 channels per token.  Codes as
    * in BD_FMT_INT4 / INT2; k_params uint32 [B][H][NBcap][128/group][D], v_params uint32
-   * [B][H][capacity][D/group] (paged: [P][H][128/group][D] and [P][H][128][D/group]).
-   * bd_decode_step runs as bd_append_kv + bd_decode_attn. */
+   * [B][H][capacity][D/group] (paged: [P][H][128/group][D] and [P][H][128][D/group]). */
   BD_FMT_INT4_G64 = 5,
   BD_FMT_INT4_G32 = 6,
   BD_FMT_INT2_G64 = 7,

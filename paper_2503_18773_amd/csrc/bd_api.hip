@@ -195,7 +195,8 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
   } else {
     if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
     if (fmt_group(c->format) != kBlock)
-      s = hip_status(launch_decode_grp(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, out, st));
+      s = hip_status(launch_decode_grp(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, nullptr,
+                                       nullptr, out, st));
     else
       s = hip_status(launch_decode_int(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml,
                                        nullptr, nullptr, out, st));
@@ -217,10 +218,10 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   const int pl = *packed_len, r = *res_len;
-  const bool fusable = c->format != BD_FMT_MXFP4 && fmt_group(c->format) == kBlock && r < kBlock - 1;
+  const bool fusable = c->format != BD_FMT_MXFP4 && r < kBlock - 1;
   if (!fusable) {
     // a step that fills the residual block (or an MXFP4 cache, whose tokens are quantized on
-    // arrival, or a cache with a smaller quantization group) runs as the two calls it is defined by
+    // arrival) runs as the two calls it is defined by
     if ((s = bd_append_kv(c, k_new, v_new, packed_len, res_len, stream)) != BD_OK) return s;
     return bd_decode_attn(c, q, *packed_len, *res_len, softmax_scale, num_splits, workspace, out, stream);
   }
@@ -228,9 +229,10 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
   hipStream_t st = (hipStream_t)stream;
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(c, workspace, num_splits);
-  if ((s = hip_status(launch_decode_int(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new,
-                                        out, st))) != BD_OK)
-    return s;
+  s = hip_status(fmt_group(c->format) != kBlock
+                     ? launch_decode_grp(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
+                     : launch_decode_int(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st));
+  if (s != BD_OK) return s;
   if (num_splits > 1 && (s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
   *res_len = r + 1;
   return BD_OK;

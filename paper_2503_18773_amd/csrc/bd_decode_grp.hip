@@ -35,6 +35,9 @@ struct GrpArgs {
   const uint16_t* k_res;
   const uint16_t* v_res;
   const uint16_t* q;
+  const uint16_t* k_new;   // fused step: the newest token, [B][Hkv][128], not yet in the residual buffers
+  const uint16_t* v_new;
+  int new_slot;            // its residual slot (res_len - 1), or -1 when the residual buffers are complete
   float* part_o;    // [nparts][B][Hq][128]
   float* part_ml;   // [nparts][B][Hq][2]
   uint16_t* out;    // one split only: the output [B][Hq][128] (fp16), written instead of the partials; else nullptr
@@ -160,7 +163,8 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     }
     for (int grp = wave; grp < nres_groups; grp += kWaves) {
       const int t = min(rt0 + 16 * grp + col, rt1 - 1);   // rows past the slice repeat its last token
-      const uint16_t* row = a.k_res + (unit * kBlock + t) * kD + 8 * g;
+      // (the newest token of a fused step is read from where the caller left it)
+      const uint16_t* row = (t == a.new_slot ? a.k_new + unit * kD : a.k_res + (unit * kBlock + t) * kD) + 8 * g;
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 4; ++j)
@@ -171,6 +175,12 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
         if (tt < nres && col < GQP) res_s[tt][col] = acc[r] * a.scale_log2;
       }
     }
+  }
+  if (a.new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
+    const bool is_v = tid >= 16;
+    const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+    uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
+    *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
   __syncthreads();   // q_s and res_s are complete
 
@@ -480,7 +490,8 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
         // residual slice, part 2: fold the fp16 tokens in
         for (int t = 0; t < nres; ++t) {
           const float pr = __builtin_amdgcn_exp2f(res_s[t][h] - M);
-          const uint32_t raw = *reinterpret_cast<const uint32_t*>(a.v_res + (unit * kBlock + rt0 + t) * kD + c0);
+          const uint16_t* vrow = rt0 + t == a.new_slot ? a.v_new + unit * kD : a.v_res + (unit * kBlock + rt0 + t) * kD;
+          const uint32_t raw = *reinterpret_cast<const uint32_t*>(vrow + c0);
           L += pr;
           o0 = __builtin_fmaf(pr, h2f((uint16_t)(raw & 0xFFFFu)), o0);
           o1 = __builtin_fmaf(pr, h2f((uint16_t)(raw >> 16)), o1);
@@ -527,8 +538,12 @@ hipError_t launch_format(int format, const GrpArgs& a, bool paged, int batch, hi
 }  // namespace
 
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
-                             int num_splits, float* part_o, float* part_ml, void* out, hipStream_t st) {
+                             int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
+                             void* out, hipStream_t st) {
   GrpArgs a;
+  a.k_new = (const uint16_t*)k_new;
+  a.v_new = (const uint16_t*)v_new;
+  a.new_slot = k_new ? res_len - 1 : -1;
   a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
@@ -557,6 +572,8 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                    float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
   GrpArgs a;
+  a.k_new = a.v_new = nullptr;
+  a.new_slot = -1;
   a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;

@@ -365,7 +365,7 @@ def test_cfg4_mxfp4_full_size_sampled():
 
 # ---------------------------------------------------------------------------- fused step
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32", "int2_g64"])
 def test_decode_step_equals_append_then_attention(fmt):
     """bd_decode_step is defined as bd_append_kv + bd_decode_attn: same output bits, same cache,
     same lengths, on ordinary steps, on the step that fills the residual block and after it."""
