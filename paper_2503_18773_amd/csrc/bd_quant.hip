@@ -109,9 +109,8 @@ __device__ __forceinline__ h2_t lanes_min(h2_t m) {
 // G: quantization group (128, 64 or 32; not with KT): K statistics over G tokens per channel --
 //    a wave holds 32 tokens, so the cross-wave step of the ladder joins G/32 waves -- and V
 //    statistics over G channels per token; parameters [block][128/G][D] and [block][128][D/G].
-// A thread holds 64 values of each tensor: for K, 64/CPT tokens x CPT consecutive channels (one
-// K word per token); for V, CPT consecutive tokens x 64/CPT channels (one V word per channel),
-// CPT = codes per word.  Minima and maxima are taken on the fp16 pairs as loaded (packed
+// A thread holds 64 values of each tensor: 8 token rows x 8 consecutive channels, i.e. one K word per
+// token and one V word per channel at 4 bits, half words at 2 bits.  Minima and maxima are taken on the fp16 pairs as loaded (packed
 // instructions), across lanes with shuffles and, for channel-wise K, across waves through LDS
 // (the reduction ladder of Sec. IV-B(2)).
 template <int BITS, bool KT, int G = kBlock>
@@ -126,10 +125,15 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
   __shared__ uint32_t red_lo[4][kD / 2], red_hi[4][kD / 2];   // per wave: packed fp16 minima / maxima of channel pairs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // ---- K: T token rows x C = CPT channels per thread
+  // ---- K: 8 token rows x 8 consecutive channels per thread: one K word of a token at 4 bits, half a
+  //      word at 2 bits (stored as such: the two halves of a word come from neighbouring lanes)
   {
-    constexpr int C = CPT, T = 64 / CPT, NCG = kD / C;   // int4: 8, 8, 16;  int2: 16, 4, 8
+    constexpr int C = 8, T = 8, NCG = kD / C;   // 16 lanes per token row; a wave holds 32 tokens
     const int cg = tid % NCG, tg = tid / NCG;
+    auto store_codes = [&](int row, uint32_t w) {
+      if constexpr (BITS == 4) k_codes[(dblk * kBlock + (size_t)row) * NCG + cg] = w;
+      else reinterpret_cast<uint16_t*>(k_codes)[(dblk * kBlock + (size_t)row) * NCG + cg] = (uint16_t)w;
+    };
     uint32_t raw[T][C / 2];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
@@ -162,7 +166,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
         quant_codes<C, true>(x, &ks, &kr, &kz, QMAX, codes);
 #pragma unroll
         for (int c = 0; c < C; ++c) w |= codes[c] << (BITS * c);
-        k_codes[(dblk * kBlock + (size_t)row) * NCG + cg] = w;
+        store_codes(row, w);
       }
     } else {
       h2_t lo[C / 2], hi[C / 2];
@@ -175,10 +179,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
           lo[i] = __builtin_elementwise_min(lo[i], as_h2(raw[t][i]));
           hi[i] = __builtin_elementwise_max(hi[i], as_h2(raw[t][i]));
         }
-        if (NCG == 8) {   // lanes holding the same channels: the other half of the row, then the other rows
-          lo[i] = __builtin_elementwise_min(lo[i], dpp_h2<0x128>(lo[i]));   // row_ror 8
-          hi[i] = __builtin_elementwise_max(hi[i], dpp_h2<0x128>(hi[i]));
-        }
+        // lanes holding the same channels: the other three token rows of the wave
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
           lo[i] = __builtin_elementwise_min(lo[i], as_h2(__shfl_xor(as_u32(lo[i]), off)));
@@ -228,14 +229,15 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
         quant_codes<C, false>(x, ks, kr, kz, QMAX, codes);
 #pragma unroll
         for (int c = 0; c < C; ++c) w |= codes[c] << (BITS * c);
-        k_codes[(dblk * kBlock + (size_t)(T * tg + t)) * NCG + cg] = w;
+        store_codes(T * tg + t, w);
       }
     }
   }
 
-  // ---- V: T = CPT consecutive tokens x C channels per thread, statistics per token
+  // ---- V: 8 consecutive tokens x 8 channels per thread, statistics per token.  8 tokens of a channel
+  //      are one V word at 4 bits and half a word at 2 bits (the halves meet in LDS).
   {
-    constexpr int T = CPT, C = 64 / CPT, NCG = kD / C, WPC = kBlock / CPT;   // int4: 8, 8, 16, 16;  int2: 16, 4, 32, 8
+    constexpr int T = 8, C = 8, NCG = kD / C, WPC = kBlock / CPT;   // 16 lanes per token row; int4: 16 words per channel, int2: 8
     const int cg = tid % NCG, tg = tid / NCG;
     uint32_t words[C];
 #pragma unroll
@@ -245,13 +247,8 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
       const int row = T * tg + t;
       const uint16_t* rp = vsrc + (size_t)row * kD + C * cg;
       uint32_t raw[C / 2];
-      if constexpr (C == 8) {
-        const u4_t ld = *reinterpret_cast<const u4_t*>(rp);
-        raw[0] = ld[0]; raw[1] = ld[1]; raw[2] = ld[2]; raw[3] = ld[3];
-      } else {
-        const u2_t ld = *reinterpret_cast<const u2_t*>(rp);
-        raw[0] = ld[0]; raw[1] = ld[1];
-      }
+      const u4_t ld = *reinterpret_cast<const u4_t*>(rp);
+      raw[0] = ld[0]; raw[1] = ld[1]; raw[2] = ld[2]; raw[3] = ld[3];
       h2_t m = min_negmax<C / 2>(raw);
       constexpr int LPG = NCG / NG;   // consecutive lanes that hold one channel group of this token row
       m = lanes_min<LPG>(m);
@@ -272,11 +269,15 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
 #pragma unroll
       for (int c = 0; c < C; ++c) words[c] |= codes[c] << (BITS * t);
     }
-    // word tg of channel C*cg + c: block tokens CPT*tg .. CPT*tg + CPT - 1.  Through LDS, so that the
-    // block's words leave in address order (a thread's own words are WPC apart).
+    // Block tokens 8*tg .. 8*tg + 7 of channel C*cg + c: word tg (4 bits), or half tg % 2 of word tg / 2
+    // (2 bits).  Through LDS, so that the block's words leave in address order (a thread's own words
+    // are WPC apart).
     __shared__ uint32_t vw[kD][WPC + 1];
 #pragma unroll
-    for (int c = 0; c < C; ++c) vw[C * cg + c][tg] = words[c];
+    for (int c = 0; c < C; ++c) {
+      if constexpr (BITS == 4) vw[C * cg + c][tg] = words[c];
+      else reinterpret_cast<uint16_t*>(&vw[C * cg + c][tg >> 1])[tg & 1] = (uint16_t)words[c];
+    }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < kD * WPC / 256; ++k) {
