@@ -35,7 +35,10 @@ __device__ __forceinline__ void group_params(float mn, float mx, int qmax, float
   // difference of two finite fp16 values)
   const float c = 1.0f / (float)qmax, d = mx - mn;
   const float q0 = d * c;
-  const float s = __builtin_fmaf(__builtin_fmaf(-(float)qmax, q0, d), c, q0);
+  float s = __builtin_fmaf(__builtin_fmaf(-(float)qmax, q0, d), c, q0);
+  // The scale is this fp32 quotient rounded to fp16 -- two roundings.  Kept opaque here, or the compiler
+  // merges the last fma and the conversion into one mixed-precision fma that rounds once.
+  asm("" : "+v"(s));
   uint16_t sb = float_to_half_bits(s);
   scale_f = half_bits_to_float(sb);
   packed = (uint32_t)sb | ((uint32_t)float_to_half_bits(zero_f) << 16);
@@ -264,10 +267,18 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
   // ---- K: one K word of a token at 4 bits, half a word at 2 bits (stored as such: the two halves of a
   //      word come from neighbouring lanes)
   {
-    uint32_t lo[T], hi[T];
+    auto store_k_row = [&](int t, uint32_t lo, uint32_t hi) {
+      const uint32_t w = pack_code_bytes<BITS>(lo, hi);
+      const size_t at = (dblk * kBlock + (size_t)krow(t)) * NCG + cg;
+      if constexpr (BITS == 4) k_codes[at] = w;
+      else reinterpret_cast<uint16_t*>(k_codes)[at] = (uint16_t)w;
+    };
     if constexpr (KT) {
+      uint32_t lo[T], hi[T];
       token_rows(kraw, std::integral_constant<int, NCG>{},
                  [&](int t, uint32_t packed) { if (cg == 0) k_params[dblk * kBlock + krow(t)] = packed; }, lo, hi);
+#pragma unroll
+      for (int t = 0; t < T; ++t) store_k_row(t, lo[t], hi[t]);
     } else {
       uint32_t mn[C / 2], mx[C / 2];
 #pragma unroll
@@ -318,22 +329,22 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
           if (tid == w0 * 64 + cg) k_params[(dblk * NG + wave / WPG) * kD + C * cg + 2 * i + e] = packed;
         }
       }
-#pragma unroll
-      for (int t = 0; t < T; ++t) code_bytes<false>(kraw[t], ks, kr, kz, lo[t], hi[t]);
-      if (__builtin_expect(tiny, 0)) {
+      // a row's codes leave as soon as they are made (the clamped variant runs for threads with an fp16-subnormal scale)
+      if (__builtin_expect(!tiny, 1)) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-          lo[t] = clamp_code_bytes<BITS>(lo[t]);
-          hi[t] = clamp_code_bytes<BITS>(hi[t]);
+          uint32_t lo, hi;
+          code_bytes<false>(kraw[t], ks, kr, kz, lo, hi);
+          store_k_row(t, lo, hi);
+        }
+      } else {
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+          uint32_t lo, hi;
+          code_bytes<false>(kraw[t], ks, kr, kz, lo, hi);
+          store_k_row(t, clamp_code_bytes<BITS>(lo), clamp_code_bytes<BITS>(hi));
         }
       }
-    }
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-      const uint32_t w = pack_code_bytes<BITS>(lo[t], hi[t]);
-      const size_t at = (dblk * kBlock + (size_t)krow(t)) * NCG + cg;
-      if constexpr (BITS == 4) k_codes[at] = w;
-      else reinterpret_cast<uint16_t*>(k_codes)[at] = (uint16_t)w;
     }
   }
 

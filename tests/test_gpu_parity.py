@@ -73,6 +73,29 @@ def test_quant_adversarial_values_bit_exact(fmt):
 
 
 @pytest.mark.parametrize("fmt", ["int4", "int2"])
+def test_quant_scale_rounding_sweep_bit_exact(fmt):
+    """The scale is an fp32 quotient rounded again to fp16, and both roundings must be the oracle's: every
+    positive fp16 value as the range of a V group and of a K group (minimum 0, head 0), and ranges that are no
+    fp16 value (negative minimum, head 1).  A scale that is one fp16 step off also moves codes."""
+    rng = np.random.default_rng(11)
+    vals = np.arange(1, 0x7c00, dtype=np.uint16).view(np.float16)        # all positive finite fp16 values
+    n = 31744                                                            # 248 blocks of 128
+    mx = np.concatenate([vals, vals[:n - vals.size]]).astype(np.float64)
+    mn = np.stack([np.zeros(n), -mx[rng.permutation(n)] * 0.37])         # per head
+    mn = mn.astype(np.float16).astype(np.float64)
+    frac = rng.random((2, n, 128))
+    # V: token r is one group; K: (block, channel) is one group -- same values, blocks transposed
+    V = (mn[:, :, None] + frac * (mx[None, :, None] - mn[:, :, None])).astype(np.float16)
+    V = np.clip(V.astype(np.float64), mn[:, :, None], mx[None, :, None]).astype(np.float16)
+    V[:, :, 0] = mn.astype(np.float16); V[:, :, 1] = mx.astype(np.float16)[None]
+    K = V.reshape(2, n // 128, 128, 128).transpose(0, 1, 3, 2).reshape(2, n, 128)
+    K, V = np.ascontiguousarray(K[None]), np.ascontiguousarray(V[None])
+    oc = O.IntCache(1, 2, BITS[fmt], n + 128); oc.quant_pack_kv(K, V)
+    gc = B.KVCache(1, 2, 2, fmt, n + 128); gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+    _assert_int_cache_equal(oc, gc)
+
+
+@pytest.mark.parametrize("fmt", ["int4", "int2"])
 @pytest.mark.parametrize("L,k", [(100, 27), (100, 28), (200, 190), (0, 130)])
 def test_append_state_machine_bit_exact(fmt, L, k):
     w = W.scaled(W.CONFIGS["cfg1"], n_q_heads=8, n_kv_heads=2, context=L, fmt=fmt)
