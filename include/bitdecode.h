@@ -16,8 +16,9 @@
  *  - For bd_cache, lengths are host integers and are uniform across the batch (the paper's
  *    "Batches" setting, Sec. V-A: same length, padded); bd_paged_cache (further down) keeps
  *    per-sequence lengths on the device (the "Page" setting).
- *  - head_dim is 128.  The residual block N_r (Eq. 1) and the quantization group are both
- *    128 for BD_FMT_INT4 / BD_FMT_INT2; the MX group is 32 for BD_FMT_MXFP4.
+ *  - head_dim is 128.  The residual block N_r (Eq. 1) is 128 tokens for every integer format; the
+ *    quantization group is 128 as well, except for the _G64 / _G32 formats (64 / 32); the MX group
+ *    is 32 for BD_FMT_MXFP4, which keeps no residual.
  *  - Arguments are validated before anything is launched; on error nothing is enqueued
  *    and no state changes.  Non-finite K/V/Q values are undefined behaviour.
  *
@@ -232,15 +233,17 @@ bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const v
  * sequence with no tokens gets a zero output row.  Every sequence is split num_splits ways
  * (pick it for the longest sequence, e.g. with bd_choose_splits on a bd_cache of the same
  * shape); workspace at least bd_paged_workspace_bytes(c, num_splits); `out` (device,
- * [B][n_q_heads][D] fp16; bf16 for MXFP4) must be non-NULL. */
+ * [B][n_q_heads][D] fp16; bf16 for MXFP4) must be non-NULL.  With num_splits == 1 the attention
+ * kernel writes `out` itself and no merge runs. */
 bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float softmax_scale,
                                int32_t num_splits, void* workspace, void* out, void* stream);
 
 /* One decode step of every sequence (Sec. III-A(1), IV-B: the step's append and its attention
  * in one call): the same results, bit for bit, as bd_paged_append_kv followed by
  * bd_paged_decode_attn, in three kernel launches instead of four (the lengths are raised by
- * the merge, the last kernel, instead of by a launch of their own).  A sequence whose token
- * is dropped for want of a valid page (bit 1 of *status) attends the tokens it had. */
+ * the merge, the last kernel, instead of by a launch of their own; with num_splits == 1 there is
+ * no merge and a small kernel raises them).  A sequence whose token is dropped for want of a
+ * valid page (bit 1 of *status) attends the tokens it had. */
 bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const void* v_new,
                                const void* q, float softmax_scale, int32_t num_splits,
                                void* workspace, void* out, void* stream);
