@@ -226,16 +226,19 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
   // thread (one V word of a channel at 4 bits, half a word at 2 bits).
   auto krow = [&](int t) { return 32 * wave + (lane >> 4) + 4 * t; };
   auto vrow = [&](int t) { return T * (tid / NCG) + t; };
-  // Both tensors' rows are requested up front: V arrives while K is being worked on.
+  // Both tensors' rows are requested up front: V arrives while K is being worked on.  (The block's
+  // address is the same for the whole workgroup; a thread adds a 32-bit byte offset.  K rows are 4 rows
+  // apart, V rows consecutive.)
   uint32_t kraw[T][C / 2], vraw[T][C / 2];
+  const uint32_t koff = (uint32_t)(krow(0) * kD + C * cg) * 2u, voff = (uint32_t)(vrow(0) * kD + C * cg) * 2u;
 #pragma unroll
   for (int t = 0; t < T; ++t) {
-    const u4_t ld = *reinterpret_cast<const u4_t*>(ksrc + (size_t)krow(t) * kD + C * cg);
+    const u4_t ld = *reinterpret_cast<const u4_t*>(reinterpret_cast<const char*>(ksrc) + koff + t * (4 * kD * 2));
     kraw[t][0] = ld[0]; kraw[t][1] = ld[1]; kraw[t][2] = ld[2]; kraw[t][3] = ld[3];
   }
 #pragma unroll
   for (int t = 0; t < T; ++t) {
-    const u4_t ld = *reinterpret_cast<const u4_t*>(vsrc + (size_t)vrow(t) * kD + C * cg);
+    const u4_t ld = *reinterpret_cast<const u4_t*>(reinterpret_cast<const char*>(vsrc) + voff + t * (kD * 2));
     vraw[t][0] = ld[0]; vraw[t][1] = ld[1]; vraw[t][2] = ld[2]; vraw[t][3] = ld[3];
   }
 
@@ -269,14 +272,14 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
   {
     auto store_k_row = [&](int t, uint32_t lo, uint32_t hi) {
       const uint32_t w = pack_code_bytes<BITS>(lo, hi);
-      const size_t at = (dblk * kBlock + (size_t)krow(t)) * NCG + cg;
-      if constexpr (BITS == 4) k_codes[at] = w;
-      else reinterpret_cast<uint16_t*>(k_codes)[at] = (uint16_t)w;
+      const uint32_t at = (uint32_t)(krow(t) * NCG + cg);   // inside the block
+      if constexpr (BITS == 4) (k_codes + dblk * (kBlock * NCG))[at] = w;
+      else (reinterpret_cast<uint16_t*>(k_codes) + dblk * (kBlock * NCG))[at] = (uint16_t)w;
     };
     if constexpr (KT) {
       uint32_t lo[T], hi[T];
       token_rows(kraw, std::integral_constant<int, NCG>{},
-                 [&](int t, uint32_t packed) { if (cg == 0) k_params[dblk * kBlock + krow(t)] = packed; }, lo, hi);
+                 [&](int t, uint32_t packed) { if (cg == 0) (k_params + dblk * kBlock)[(uint32_t)krow(t)] = packed; }, lo, hi);
 #pragma unroll
       for (int t = 0; t < T; ++t) store_k_row(t, lo[t], hi[t]);
     } else {
@@ -326,24 +329,19 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
           kr[2 * i + e] = exact_rcp(ks[2 * i + e]);
           tiny |= is_tiny_scale(ks[2 * i + e]);
           // first thread row of the token group writes its parameters
-          if (tid == w0 * 64 + cg) k_params[(dblk * NG + wave / WPG) * kD + C * cg + 2 * i + e] = packed;
+          if (tid == w0 * 64 + cg) (k_params + dblk * (NG * kD))[(uint32_t)((wave / WPG) * kD + C * cg + 2 * i + e)] = packed;
         }
       }
-      // a row's codes leave as soon as they are made (the clamped variant runs for threads with an fp16-subnormal scale)
-      if (__builtin_expect(!tiny, 1)) {
+      // a row's codes leave as soon as they are made
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-          uint32_t lo, hi;
-          code_bytes<false>(kraw[t], ks, kr, kz, lo, hi);
-          store_k_row(t, lo, hi);
+      for (int t = 0; t < T; ++t) {
+        uint32_t lo, hi;
+        code_bytes<false>(kraw[t], ks, kr, kz, lo, hi);
+        if (__builtin_expect(tiny, 0)) {
+          lo = clamp_code_bytes<BITS>(lo);
+          hi = clamp_code_bytes<BITS>(hi);
         }
-      } else {
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-          uint32_t lo, hi;
-          code_bytes<false>(kraw[t], ks, kr, kz, lo, hi);
-          store_k_row(t, clamp_code_bytes<BITS>(lo), clamp_code_bytes<BITS>(hi));
-        }
+        store_k_row(t, lo, hi);
       }
     }
   }
@@ -357,7 +355,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
     uint32_t lo[T], hi[T];   // per token: the codes of channels 0..3 / 4..7, one per byte
     token_rows(vraw, std::integral_constant<int, LPG>{},
                [&](int t, uint32_t packed) {
-                 if (cg % LPG == 0) v_params[(dblk * kBlock + vrow(t)) * NG + cg / LPG] = packed;
+                 if (cg % LPG == 0) (v_params + dblk * (kBlock * NG))[(uint32_t)(vrow(t) * NG + cg / LPG)] = packed;
                },
                lo, hi);
     uint32_t words[C];   // channel c: its 8 tokens' codes, token t at bit BITS * t
@@ -376,7 +374,7 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
 #pragma unroll
     for (int k = 0; k < kD * WPC / 256; ++k) {
       const int idx = tid + 256 * k;
-      v_codes[dblk * (size_t)(kD * WPC) + idx] = vw[idx / WPC][idx % WPC];
+      (v_codes + dblk * (size_t)(kD * WPC))[(uint32_t)idx] = vw[idx / WPC][idx % WPC];
     }
   }
 }
