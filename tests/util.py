@@ -24,15 +24,22 @@ def attn_errors(got: np.ndarray, ref: np.ndarray):
     return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-30))
 
 
-def assert_attn_close(got: np.ndarray, ref: np.ndarray, what="", large_outputs=False):
+def assert_attn_close(got: np.ndarray, ref: np.ndarray, what="", large_outputs=False, noise=None):
     """The bar of the benchmark configurations: max-abs 2e-3 and relative L2 1e-3.  With
-    `large_outputs` (sequences of a few tokens, whose outputs are single V rows: magnitudes of
-    10 and more with the x10 outlier channels, where half an fp16 step alone is 8e-3) the
-    max-abs bar is taken per element as 2e-3 + 2^-10 |ref| instead."""
+    `large_outputs` (sequences of a few tokens or peaked weights, whose outputs are close to single V
+    rows: magnitudes of 10 and more with the x10 outlier channels, where half an fp16 step alone is
+    8e-3) the max-abs bar is taken per element as 2e-3 + 2^-10 |ref| instead.
+    `noise` (the oracle's rounding_noise_scale, one value per head) adds 2^-11 * noise to that: the
+    probabilities enter the second product as fp16, so a head in which one token with large values
+    holds most of the weight carries that token's rounding error into every channel, also into
+    those whose value is small after cancellation.  For the random shapes of the sweeps."""
     mask = ~np.isnan(ref)
     ma, rl = attn_errors(got[mask], ref[mask])
     if large_outputs:
-        excess = np.abs(got[mask] - ref[mask]) - (MAX_ABS_TOL + 2.0 ** -10 * np.abs(ref[mask]))
+        bar = MAX_ABS_TOL + 2.0 ** -10 * np.abs(ref)
+        if noise is not None:
+            bar = bar + 2.0 ** -11 * np.asarray(noise)[..., None]
+        excess = np.abs(got[mask] - ref[mask]) - bar[mask]
         assert excess.max() <= 0 and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
     else:
         assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
