@@ -90,8 +90,10 @@ struct DecodeArgs {
 // Per-wave LDS scratch.  GQP = query heads per KV head, padded to 4, 8 or 16.
 template <int GQP>
 struct WaveLds {
-  uint16_t qhi[GQP][kD];   // Q' per head, high fp16 piece, in B-operand slot order
-  uint16_t qlo[GQP][kD];   // low piece
+  // (rows padded by 16 bytes: lanes of different heads read the same offset of their rows, and rows a
+  // multiple of 256 bytes apart would all fall on the same LDS banks)
+  uint16_t qhi[GQP][kD + 8];   // Q' per head, high fp16 piece, in B-operand slot order
+  uint16_t qlo[GQP][kD + 8];   // low piece
   float2 vpar[kBlock];     // per V token of the block: (scale * position factor, zero + scale * centre code)
   float2 kpar[kBlock];     // per-token K only: (scale * 2^24, zero) of the block's tokens
   uint16_t c16[kBlock];    // per V token: centre code * position factor, in the A-operand order of P'

@@ -55,11 +55,13 @@ struct GrpArgs {
 
 template <int GQP, int NV>
 struct GrpWaveLds {
-  uint16_t qhi[GQP][kD];       // Q' per head, high fp16 piece, in B-operand slot order
-  uint16_t qlo[GQP][kD];       // low piece
+  // (rows of qhi, qlo and pbuf padded by 16 bytes: lanes of different heads read the same offset of
+  // their rows, and rows a multiple of 256 bytes apart would all fall on the same LDS banks)
+  uint16_t qhi[GQP][kD + 8];   // Q' per head, high fp16 piece, in B-operand slot order
+  uint16_t qlo[GQP][kD + 8];   // low piece
   float2 vpar[NV][kBlock];     // per (channel group, token): (scale * position factor, zero + scale * centre code)
   uint16_t c16[NV][kBlock];    // centre code * position factor, in A-operand slot order
-  uint16_t pbuf[GQP][kBlock];  // P' of the channel group in work, in B-operand slot order
+  uint16_t pbuf[GQP][kBlock + 8];  // P' of the channel group in work, in B-operand slot order
   float zq[GQP];               // per head: sum_c Q_c z_c of the token group in work
   uint32_t kpar[NV][kD];       // K parameters (half2) of the block, per token group and channel
 };
