@@ -94,8 +94,8 @@ struct WaveLds {
   // multiple of 256 bytes apart would all fall on the same LDS banks)
   uint16_t qhi[GQP][kD + 8];   // Q' per head, high fp16 piece, in B-operand slot order
   uint16_t qlo[GQP][kD + 8];   // low piece
-  float2 vpar[kBlock];     // per V token of the block: (scale * position factor, zero + scale * centre code)
-  float2 kpar[kBlock];     // per-token K only: (scale * 2^24, zero) of the block's tokens
+  float2 vpar[kParSlots];  // per V token of the block: (scale * position factor, zero + scale * centre code)
+  float2 kpar[kParSlots];  // per-token K only: (scale * 2^24, zero) of the block's tokens
   uint16_t c16[kBlock];    // per V token: centre code * position factor, in the A-operand order of P'
   float zq[GQP];           // per head: sum_c Q_c z_c * scale_log2 * 2^-24
 };
@@ -448,7 +448,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const float sk = h2f((uint16_t)(kp2[u] & 0xFFFFu)), zk = h2f((uint16_t)(kp2[u] >> 16));
-        wl.kpar[2 * lane + u] = make_float2(sk * kTwo24, zk);
+        wl.kpar[par_slot(2 * lane + u)] = make_float2(sk * kTwo24, zk);
       }
     }
     // V parameters of the block's 128 tokens
@@ -458,7 +458,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       const int t = 2 * lane + u;
       const int r = t & 3;                // row of the token inside its S^T tile
       const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
-      wl.vpar[t] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+      wl.vpar[par_slot(t)] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
       wl.c16[F::p_slot(t)] = (uint16_t)(ct * F::inv_un(r));
     }
     wave_sync();
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
         for (int lh = 0; lh < 2; ++lh)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const float2 kq = wl.kpar[tb[o][lh] + r];
+            const float2 kq = wl.kpar[par_slot(tb[o][lh]) + r];
             sc[o][lh][r] = __builtin_fmaf(sc[o][lh][r], kq.x, kq.y * qsum);
           }
     }
@@ -574,7 +574,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kS, zoff));
-          const float2 par = wl.vpar[tb[0][half] + r];
+          const float2 par = wl.vpar[par_slot(tb[0][half]) + r];
           l_run += p;
           z_run = __builtin_fmaf(p, par.y, z_run);
           // gather the column groups' fp16 values into the B-operand register pairs
@@ -593,7 +593,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
           for (int lh = 0; lh < 2; ++lh) {
             const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kS, zoff));
-            const float2 par = wl.vpar[tb[o][lh] + r];
+            const float2 par = wl.vpar[par_slot(tb[o][lh]) + r];
             l_run += p;
             z_run = __builtin_fmaf(p, par.y, z_run);
             hv[lh] = (uint32_t)f2h(p * par.x);

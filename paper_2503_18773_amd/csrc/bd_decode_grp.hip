@@ -59,7 +59,7 @@ struct GrpWaveLds {
   // their rows, and rows a multiple of 256 bytes apart would all fall on the same LDS banks)
   uint16_t qhi[GQP][kD + 8];   // Q' per head, high fp16 piece, in B-operand slot order
   uint16_t qlo[GQP][kD + 8];   // low piece
-  float2 vpar[NV][kBlock];     // per (channel group, token): (scale * position factor, zero + scale * centre code)
+  float2 vpar[NV][kParSlots];  // per (channel group, token): (scale * position factor, zero + scale * centre code)
   uint16_t c16[NV][kBlock];    // centre code * position factor, in A-operand slot order
   uint16_t pbuf[GQP][kBlock + 8];  // P' of the channel group in work, in B-operand slot order
   float zq[GQP];               // per head: sum_c Q_c z_c of the token group in work
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
         const int t = 2 * lane + u;
         const int r = t & 3;
         const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
-        wl.vpar[v][t] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+        wl.vpar[v][par_slot(t)] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
         wl.c16[v][F::operand_pos(t)] = (uint16_t)(ct * F::inv_un(r));   // an integer: the fp16 subnormal code * 2^-24
       }
     // ---- S^T, chunk by chunk
@@ -416,7 +416,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
 #pragma unroll
           for (int run = 0; run < 2; ++run) {
             const float p = sc[o][run][r];
-            const float2 par = wl.vpar[v][F::run_base(sg, run) + r];
+            const float2 par = wl.vpar[v][par_slot(F::run_base(sg, run)) + r];
             z_run[v] = __builtin_fmaf(p, par.y, z_run[v]);
             hv[run] = (uint32_t)f2h(p * par.x);
           }

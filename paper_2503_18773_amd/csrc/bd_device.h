@@ -85,6 +85,11 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Index of per-token float2 parameters staged in LDS: lanes that work on different 32-token chunks read
+// the same offset of their chunks at once, and entries 32 apart (256 bytes) share their banks, so every
+// chunk is shifted by two entries (arrays hold kParSlots entries).
+constexpr int kParSlots = 128 + 8;
+__device__ __forceinline__ int par_slot(int t) { return t + 2 * (t >> 5); }
 
 }  // namespace
 }  // namespace bd
