@@ -61,7 +61,7 @@ extern "C" {
 typedef enum {
   BD_OK = 0,
   BD_ERR_INVALID_ARG = -1,   /* NULL pointer, non-positive size, bad enum, bad length */
-  BD_ERR_UNSUPPORTED = -2,   /* a shape this build has no kernel for (head_dim != 128; batch, or KV heads times pieces of the query group, beyond the launch grid) */
+  BD_ERR_UNSUPPORTED = -2,   /* a shape this build has no kernel for (head_dim != 128; batch, KV heads times pieces of the query group, or batch times KV heads, beyond 65535, a launch grid dimension) */
   BD_ERR_ALIGNMENT = -3,     /* a device pointer is not 16-byte aligned */
   BD_ERR_CAPACITY = -4,      /* the cache cannot hold the tokens asked for */
   BD_ERR_HIP = -5            /* a HIP runtime call failed; see bd_last_hip_error() */

@@ -24,6 +24,7 @@ bd_status check_shape(const bd_cache* c) {
   if (!c) return BD_ERR_INVALID_ARG;
   if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->capacity <= 0) return BD_ERR_INVALID_ARG;
   if (c->batch > 65535 || c->n_kv_heads > 65535) return BD_ERR_UNSUPPORTED;   // grid dimensions y and z
+  if ((long)c->batch * c->n_kv_heads > 65535) return BD_ERR_UNSUPPORTED;      // the quantizer's grid: (block, sequence x KV head)
   if (!fmt_is_int(c->format) && c->format != BD_FMT_MXFP4) return BD_ERR_INVALID_ARG;
   if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
   if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;

@@ -107,6 +107,9 @@ def test_argument_validation_happens_before_any_launch():
     bad = _desc(batch=65536)                                           # beyond the launch grid
     assert L.bd_decode_attn(ctypes.byref(bad), 4096, 1024, 0, 0.1, 4, 4096, 4096, None) == -2
     assert B.bd_cache_bytes(bad, 0) == 0
+    bad = _desc(batch=8192, n_kv_heads=8, n_q_heads=32)                # 65536 (sequence, KV head) units
+    assert L.bd_quant_pack_kv(ctypes.byref(bad), 4096, 4096, 128, ctypes.byref(pl), ctypes.byref(rl), None) == -2
+    assert B.bd_cache_bytes(_desc(batch=8191, n_kv_heads=8, n_q_heads=32), 0) > 0
     assert L.bd_strerror(-4) == b"cache capacity exceeded"
 
 
