@@ -173,8 +173,11 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     nb = len / kBlock;
     res_len = len % kBlock;
   }
-  const int blk0 = (int)(((long)nb * split) / a.num_splits);
-  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  // Blocks are dealt to the splits four at a time (one per wave), round robin: at any moment the
+  // workgroups of a (sequence, KV head) unit read one contiguous window of the cache.  (Contiguous
+  // ranges per split put the workgroups' streams a power of two apart for the usual split counts,
+  // and then all of them march over the same memory channels.)
+  const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
   // this workgroup's slice of the fp16 residual tokens
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
   const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * a.gq + head0) * kD;
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   }
   // (Where exactly the values are requested is fixed at compile time, so that the compiler knows
   // how many loads are in flight behind the one it waits for: half way through QK^T.)
-  const int my_blocks = (blk1 - blk0 - wave + kWaves - 1) / kWaves;
+  const int my_blocks = blk1 > blk0 + wave ? (blk1 - blk0 - wave + bstep - 1) / bstep : 0;
   // Paged: table entry of block n (-1 past the end of the row), and the first block at or after
   // n, in this wave's stride, whose entry names a page of the pool; entries that do not are
   // skipped and reported in *status.
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
         break;
       }
       if (a.status && lane == 0) atomicOr(a.status, 1);
-      n += kWaves;
+      n += bstep;
       entry = n < blk1 ? table_entry(n) : -1;
     }
     return n;
@@ -431,8 +434,8 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   int done = 0;
   bool first = true;
   while (blk < blk1) {
-    int nblk = SINGLE ? blk1 : blk + kWaves;
-    size_t nbi = bi + kWaves;
+    int nblk = SINGLE ? blk1 : blk + bstep;
+    size_t nbi = bi + bstep;
     int next_entry = -1;   // requested a block ahead, like the parameters
     if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
     if (!SINGLE) {

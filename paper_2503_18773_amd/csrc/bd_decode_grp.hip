@@ -140,8 +140,9 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     nb = len / kBlock;
     res_len = len % kBlock;
   }
-  const int blk0 = (int)(((long)nb * split) / a.num_splits);
-  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
+  // unit read one contiguous window of the cache at any moment
+  const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
   const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * a.gq + head0) * kD;
 
@@ -290,7 +291,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
         break;
       }
       if (a.status && lane == 0) atomicOr(a.status, 1);
-      n += kWaves;
+      n += bstep;
       entry = n < blk1 ? table_entry(n) : -1;
     }
     return n;
@@ -304,8 +305,8 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
   }
   // this lane's 8 tokens of chunk c are block tokens tok0 + 32*c + {run_base offsets}: slot group 4*c + g
   while (blk < blk1) {
-    int nblk = blk + kWaves;
-    size_t nbi = bi + kWaves;
+    int nblk = blk + bstep;
+    size_t nbi = bi + bstep;
     if (PAGED) nblk = first_valid(nblk, nblk < blk1 ? table_entry(nblk) : -1, nbi);
     const bool has_next = nblk < blk1;
     if constexpr (kDeep) issue_values(bi);

@@ -134,8 +134,9 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
     length = max(0, length);
   }
   const int nb = (length + kBlock - 1) / kBlock;
-  const int blk0 = (int)(((long)nb * split) / a.num_splits);
-  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
+  // unit read one contiguous window of the cache at any moment
+  const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
   const int nbcap = a.capacity / kBlock;
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
 
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
         break;
       }
       if (a.status && lane == 0) atomicOr(a.status, 1);
-      n += kWaves;
+      n += bstep;
       entry = n < blk1 ? table_entry(n) : -1;
     }
     return n;
@@ -198,8 +199,8 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
 
   while (blk < blk1) {
-    int nblk = blk + kWaves;
-    size_t nbi = bi + kWaves;
+    int nblk = blk + bstep;
+    size_t nbi = bi + bstep;
     int next_entry = -1;   // requested a block ahead
     if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
     issue_v(bi);
@@ -380,8 +381,9 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
     length = max(0, length);
   }
   const int nb = (length + kBlock - 1) / kBlock;
-  const int blk0 = (int)(((long)nb * split) / a.num_splits);
-  const int blk1 = (int)(((long)nb * (split + 1)) / a.num_splits);
+  // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
+  // unit read one contiguous window of the cache at any moment
+  const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
   const int nbcap = a.capacity / kBlock;
   const int tok_base = 32 * (col >> 2) + (col & 3);   // row `col` of tile T holds token tok_base + 4T
 
@@ -417,7 +419,7 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
         break;
       }
       if (a.status && lane == 0) atomicOr(a.status, 1);
-      n += kWaves;
+      n += bstep;
       entry = n < blk1 ? table_entry(n) : -1;
     }
     return n;
@@ -436,8 +438,8 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
 
   while (blk < blk1) {
-    int nblk = blk + kWaves;
-    size_t nbi = bi + kWaves;
+    int nblk = blk + bstep;
+    size_t nbi = bi + bstep;
     int next_entry = -1;
     if (PAGED && nblk < blk1) next_entry = table_entry(nblk);
     issue_v(bi);
