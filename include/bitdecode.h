@@ -240,10 +240,12 @@ bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float sof
 
 /* One decode step of every sequence (Sec. III-A(1), IV-B: the step's append and its attention
  * in one call): the same results, bit for bit, as bd_paged_append_kv followed by
- * bd_paged_decode_attn, in three kernel launches instead of four (the lengths are raised by
- * the merge, the last kernel, instead of by a launch of their own; with num_splits == 1 there is
- * no merge and a small kernel raises them).  A sequence whose token is dropped for want of a
- * valid page (bit 1 of *status) attends the tokens it had. */
+ * bd_paged_decode_attn, in fewer kernel launches.  For BD_FMT_INT4 / INT2 and their _KT variants
+ * with up to 16 query heads per KV head: two -- the attention kernel reads the new token from
+ * k_new / v_new and files it, the workgroup that reads the block a step fills quantizes it first,
+ * and the merge, the last kernel, raises the lengths.  Otherwise three: append, attention, merge.
+ * (With num_splits == 1 there is no merge and a small kernel raises the lengths.)  A sequence
+ * whose token is dropped for want of a valid page (bit 1 of *status) attends the tokens it had. */
 bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const void* v_new,
                                const void* q, float softmax_scale, int32_t num_splits,
                                void* workspace, void* out, void* stream);

@@ -333,10 +333,12 @@ bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const v
   return hip_status(launch_paged_append(c, k_new, v_new, true, (hipStream_t)stream));
 }
 
-// attention over the paged cache; `step`: the lengths still lack the token a preceding
-// launch_paged_append(bump = false) filed, and the merge raises them
+// attention over the paged cache; `step`: the lengths still lack this step's token, and the merge raises
+// them.  The token has been filed by a preceding launch_paged_append(bump = false), or, with k_new / v_new
+// (main integer kernel only), is appended by the attention launch itself.
 static bd_status paged_attention(const bd_paged_cache* c, const void* q, float softmax_scale, int32_t num_splits,
-                                 void* workspace, void* out, bool step, hipStream_t st) {
+                                 void* workspace, void* out, bool step, hipStream_t st,
+                                 const void* k_new = nullptr, const void* v_new = nullptr) {
   const bd_cache shape = shape_of(c);
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(&shape, workspace, num_splits);
@@ -347,7 +349,8 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
                                ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
                            : fmt_group(c->format) != kBlock
                                ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
-                               : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st));
+                               : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
+                                                     direct, st));
   if (s != BD_OK) return s;
   if (direct) return step ? hip_status(launch_paged_bump(c, st)) : BD_OK;
   return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st, step ? c : nullptr));
@@ -372,8 +375,13 @@ bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   hipStream_t st = (hipStream_t)stream;
-  // three launches instead of four: the append leaves the lengths alone, the attention kernel
-  // counts the new token in, and the merge, last in line, raises the lengths
+  // Main integer kernel, one workgroup per split and KV head (query groups of up to 16 heads): two
+  // launches.  The attention kernel reads the new token from the caller's buffers and files it, the
+  // workgroup that reads the block a step fills quantizes it first, and the merge raises the lengths.
+  if (fmt_is_int(c->format) && fmt_group(c->format) == kBlock && c->n_q_heads / c->n_kv_heads <= 16)
+    return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, st, k_new, v_new);
+  // otherwise three launches instead of four: the append leaves the lengths alone, the attention
+  // kernel counts the new token in, and the merge, last in line, raises the lengths
   if ((s = hip_status(launch_paged_append(c, k_new, v_new, false, st))) != BD_OK) return s;
   return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, st);
 }

@@ -51,8 +51,11 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
 // rows itself and no merge is needed; otherwise it writes the split partials.
 // raises the length of every sequence whose step's token was appended (launch_paged_append with bump = false)
 hipError_t launch_paged_bump(const bd_paged_cache* c, hipStream_t st);
+// k_new / v_new non-null (with step): the launch appends the step's token itself -- no launch_paged_append
+// before it; query groups of up to 16 heads only
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                               float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
+                               float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
+                               void* out, hipStream_t st);
 
 // k_new / v_new non-null: fused step -- residual token res_len-1 is read from k_new / v_new
 // ([B][Hkv][128]) and also stored into the residual buffers by the kernel.

@@ -49,6 +49,7 @@
 #include "bd_common.h"
 #include "bd_device.h"
 #include "bd_fmt.h"
+#include "bd_quant_block.h"
 
 namespace bd {
 namespace {
@@ -156,16 +157,31 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int nb = a.nb, res_len = a.res_len;
+  int new_slot = a.new_slot;   // fused step: residual slot of the token that is still in the caller's buffer, or -1
+  int flush_page = -1;         // paged fused step that fills the residual: the page the block goes to
   if (PAGED) {
     int len = a.seq_lens[b];
+    new_slot = -1;
     if (a.step && len >= 0) {
-      // fused step: the preceding kernel has appended this step's token (unless it needed a page
-      // the table does not name) and the length is raised only after this kernel
+      // fused step: this step's token counts (unless it needs a page the table does not name) and
+      // the length is raised only after this kernel.  With a.k_new the token has not been appended
+      // by a kernel of its own: it is read from the caller's buffer and filed by this launch, and
+      // if it fills the residual, the workgroup that reads the new block quantizes it first.
       bool ok = true;
+      int e = -1;
       if (len % kBlock == kBlock - 1) {
         const int n = len / kBlock;
-        const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
+        e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
         ok = e >= 0 && e < a.num_pages;
+      }
+      if (a.k_new) {
+        if (!ok) {
+          if (a.status && tid == 0 && split == 0) atomicOr(a.status, 2);   // the token is dropped
+        } else if (len % kBlock < kBlock - 1) {
+          new_slot = len % kBlock;
+        } else {
+          flush_page = e;
+        }
       }
       len += ok ? 1 : 0;
     }
@@ -178,6 +194,25 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   // ranges per split put the workgroups' streams a power of two apart for the usual split counts,
   // and then all of them march over the same memory channels.)
   const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
+  if (PAGED && flush_page >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) {
+    // This step's token completes the residual (Sec. IV-B(1)): the 128 rows become block nb - 1, which
+    // this workgroup alone reads in this launch.  (One workgroup per split and KV head: the host takes
+    // this path only for query groups of up to 16 heads.)
+    uint16_t* kr = const_cast<uint16_t*>(a.k_res) + unit * kBlock * kD;
+    uint16_t* vr = const_cast<uint16_t*>(a.v_res) + unit * kBlock * kD;
+    if (tid < 32) {
+      const bool is_v = tid >= 16;
+      const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+      *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
+    }
+    __threadfence();   // the row is read back below, and the block further down, by other threads of this workgroup
+    __syncthreads();
+    quant_block<BITS, KT, kBlock>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
+                                  const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
+                                  (size_t)flush_page * a.n_kv_heads + hkv);
+    __threadfence();
+    __syncthreads();
+  }
   // this workgroup's slice of the fp16 residual tokens
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
   const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * a.gq + head0) * kD;
@@ -244,7 +279,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   }
   const uint16_t* kres = a.k_res + unit * kBlock * kD;
   // row t of the residual keys: the newest token of a fused step is read from where the caller left it
-  auto kres_row = [&](int t) { return t == a.new_slot ? a.k_new + unit * kD : kres + (size_t)t * kD; };
+  auto kres_row = [&](int t) { return t == new_slot ? a.k_new + unit * kD : kres + (size_t)t * kD; };
   // The residual tokens are scored 16 at a time on the matrix unit: S[token, head] with the fp16
   // key rows as A and the fp16 queries as B, four k-steps of 32 channels.  Wave w takes token
   // groups w, w + 4, ...; the operands of its first group are requested here.
@@ -265,10 +300,10 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     }
     load_res_keys(wave);
   }
-  if (a.new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
+  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
-    uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
+    uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + new_slot) * kD + 8 * (tid & 15);
     *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
   // (Where exactly the values are requested is fixed at compile time, so that the compiler knows
@@ -304,7 +339,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   // that the final merge does not wait on memory (thread tid: channels 2*(tid%64), +1).
   constexpr int kResPre = 2;
   auto vres_row = [&](int t) {
-    return t == a.new_slot ? a.v_new + unit * kD : a.v_res + (unit * kBlock + t) * kD;
+    return t == new_slot ? a.v_new + unit * kD : a.v_res + (unit * kBlock + t) * kD;
   };
   uint32_t vres_pre[kResPre];
 #pragma unroll
@@ -872,7 +907,8 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
 }
 
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                               float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
+                               float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
+                               void* out, hipStream_t st) {
   DecodeArgs a;
   a.step = step ? 1 : 0;
   a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
@@ -883,7 +919,8 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.k_res = (const uint16_t*)c->k_res;
   a.v_res = (const uint16_t*)c->v_res;
   a.q = (const uint16_t*)q;
-  a.k_new = a.v_new = nullptr;
+  a.k_new = (const uint16_t*)k_new;   // non-null: the step's token, which this launch appends itself
+  a.v_new = (const uint16_t*)v_new;
   a.new_slot = -1;
   a.part_o = part_o;
   a.part_ml = part_ml;

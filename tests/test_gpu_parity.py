@@ -751,6 +751,47 @@ def test_paged_fused_step_equals_append_then_attention(fmt):
         assert_attn_close(got, ref, f"{fmt} paged fused step", large_outputs=True)
 
 
+@pytest.mark.parametrize("fmt", ["int4", "int2_kt", "int4_g32", "mxfp4"])
+def test_paged_fused_step_drops_the_token_that_has_no_page(fmt):
+    """A sequence whose residual the step's token would fill (integer formats), or whose token starts a new
+    block (MXFP4), while the table names no page for that block: the token is dropped, the length stays,
+    the sequence attends what it had, bit 1 of the status word is set -- the same, bit for bit, from
+    bd_paged_decode_step (which appends inside the attention launch for the main integer kernel) and from
+    bd_paged_append_kv + bd_paged_decode_attn; the other sequences go on."""
+    import torch
+    mx = fmt == "mxfp4"
+    dt, tdt = ("bf16", torch.bfloat16) if mx else ("fp16", torch.float16)
+    H, Hq = 2, 8
+    lens = [255, 130, 127] if not mx else [256, 130, 127]
+    table = np.random.default_rng(9).permutation(30)[:3 * 5].reshape(3, 5).astype(np.int32)
+    twins = []
+    for _ in range(2):
+        if mx:
+            _, gc, _ = _paged_mx_pair(lens, H, Hq, num_pages=30, max_pages=5, table=table)
+        else:
+            _, gc, _ = _paged_pair(fmt, lens, H, Hq, num_pages=30, max_pages=5, table=table)
+        twins.append(gc)
+    bad = table.copy(); bad[0, 2 if mx else 1] = 77          # out of the pool: sequence 0 cannot take its next token
+    for gc in twins:
+        gc.block_table.copy_(torch.from_numpy(bad))
+    a, b = twins
+    w = W.scaled(W.CONFIGS["cfg4" if mx else "cfg1"], batch=3, n_q_heads=Hq, n_kv_heads=H, context=128, seed=62)
+    outs = [torch.empty((3, Hq, 128), dtype=tdt, device="cuda:0") for _ in range(2)]
+    for step in range(3):
+        kn, vn, q = (to_dev(x, dt) for x in (*W.make_new_kv(w, step), W.make_q(w, step)))
+        ns = (2, 1, 3)[step]
+        a.decode_step(kn, vn, q, W.softmax_scale(w), outs[0], ns)
+        b.append_kv(kn, vn)
+        b.decode_attn(q, W.softmax_scale(w), outs[1], ns)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16)), step
+        assert torch.equal(a.seq_lens, b.seq_lens), step
+        assert list(a.seq_lens.cpu().numpy()) == [lens[0], lens[1] + step + 1, lens[2] + step + 1]
+        assert int(a.status.item()) == int(b.status.item()) == 2
+    for i in range(4 if mx else 6):
+        assert torch.equal(a.buffers[i], b.buffers[i]), i
+
+
 # ---------------------------------------------------------------------------- quantization groups of 32 / 64
 
 @pytest.mark.parametrize("fmt", GROUP_FORMATS)
