@@ -151,8 +151,9 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
  * on steps that do not fill the residual block the new token is attended straight from
  * k_new / v_new and filed into the residual by the attention kernel itself, which saves the
  * separate append launch (the fusion of the paper's Residual Kernel, Sec. III-A(1) /
- * Sec. IV-B, without its lazy flush).  All pointers as in the two calls; `out` must be
- * non-NULL.  On error nothing is enqueued by the failing part and the lengths are those
+ * Sec. IV-B, without its lazy flush).  BD_FMT_MXFP4 (up to 16 query heads per KV head): the
+ * workgroup that reads the token's block quantizes the token into the cache before it attends.
+ * All pointers as in the two calls; `out` must be non-NULL.  On error nothing is enqueued by the failing part and the lengths are those
  * reached so far. */
 bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
                          int32_t* packed_len, int32_t* res_len, float softmax_scale,
@@ -240,10 +241,12 @@ bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float sof
 
 /* One decode step of every sequence (Sec. III-A(1), IV-B: the step's append and its attention
  * in one call): the same results, bit for bit, as bd_paged_append_kv followed by
- * bd_paged_decode_attn, in fewer kernel launches.  For BD_FMT_INT4 / INT2 and their _KT variants
- * with up to 16 query heads per KV head: two -- the attention kernel reads the new token from
- * k_new / v_new and files it, the workgroup that reads the block a step fills quantizes it first,
- * and the merge, the last kernel, raises the lengths.  Otherwise three: append, attention, merge.
+ * bd_paged_decode_attn, in fewer kernel launches.  For BD_FMT_INT4 / INT2, their _KT variants and
+ * BD_FMT_MXFP4 with up to 16 query heads per KV head: two -- the attention kernel reads the new
+ * token from k_new / v_new and files it (integer formats: the workgroup that reads the block a
+ * step fills quantizes it first; MXFP4: the workgroup that reads the token's block quantizes the
+ * token), and the merge, the last kernel, raises the lengths.  Otherwise three: append,
+ * attention, merge.
  * (With num_splits == 1 there is no merge and a small kernel raises the lengths.)  A sequence
  * whose token is dropped for want of a valid page (bit 1 of *status) attends the tokens it had. */
 bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const void* v_new,

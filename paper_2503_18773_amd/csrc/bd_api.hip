@@ -192,7 +192,8 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
   float* part_ml = ws_part_ml(c, workspace, num_splits);
   if (c->format == BD_FMT_MXFP4) {
     if (res_len != 0) return BD_ERR_INVALID_ARG;
-    s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, out, st));
+    s = hip_status(launch_decode_mx(c, q, packed_len, softmax_scale, num_splits, part_o, part_ml, nullptr, nullptr, out,
+                                    st));
   } else {
     if (packed_len % kBlock != 0 || res_len < 0 || res_len >= kBlock) return BD_ERR_INVALID_ARG;
     if (fmt_group(c->format) != kBlock)
@@ -219,6 +220,21 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   const int pl = *packed_len, r = *res_len;
+  if (c->format == BD_FMT_MXFP4 && c->n_q_heads / c->n_kv_heads <= 16) {
+    // MXFP4, one workgroup per split and KV head: the attention launch quantizes the token into the cache
+    // itself (the workgroup that reads its block does, first thing)
+    if (pl < 0 || r != 0) return BD_ERR_INVALID_ARG;
+    if (pl + 1 > c->capacity) return BD_ERR_CAPACITY;
+    hipStream_t st = (hipStream_t)stream;
+    float* part_o = ws_part_o(workspace);
+    float* part_ml = ws_part_ml(c, workspace, num_splits);
+    if ((s = hip_status(launch_decode_mx(c, q, pl, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out,
+                                         st))) != BD_OK)
+      return s;
+    if (num_splits > 1 && (s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
+    *packed_len = pl + 1;
+    return BD_OK;
+  }
   const bool fusable = c->format != BD_FMT_MXFP4 && r < kBlock - 1;
   if (!fusable) {
     // a step that fills the residual block (or an MXFP4 cache, whose tokens are quantized on
@@ -346,7 +362,8 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
   // lengths with the small kernel of bd_paged_append_kv instead of in the merge)
   void* direct = num_splits == 1 ? out : nullptr;
   bd_status s = hip_status(c->format == BD_FMT_MXFP4
-                               ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
+                               ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
+                                                        direct, st)
                            : fmt_group(c->format) != kBlock
                                ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
                                : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
@@ -375,10 +392,11 @@ bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   hipStream_t st = (hipStream_t)stream;
-  // Main integer kernel, one workgroup per split and KV head (query groups of up to 16 heads): two
-  // launches.  The attention kernel reads the new token from the caller's buffers and files it, the
-  // workgroup that reads the block a step fills quantizes it first, and the merge raises the lengths.
-  if (fmt_is_int(c->format) && fmt_group(c->format) == kBlock && c->n_q_heads / c->n_kv_heads <= 16)
+  // Main integer kernel and MXFP4, one workgroup per split and KV head (query groups of up to 16 heads):
+  // two launches.  The attention kernel reads the new token from the caller's buffers and files it
+  // (integer: the workgroup that reads the block a step fills quantizes it first; MXFP4: the workgroup
+  // that reads the token's block quantizes the token into it), and the merge raises the lengths.
+  if ((c->format == BD_FMT_MXFP4 || fmt_group(c->format) == kBlock) && c->n_q_heads / c->n_kv_heads <= 16)
     return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, st, k_new, v_new);
   // otherwise three launches instead of four: the append leaves the lengths alone, the attention
   // kernel counts the new token in, and the merge, last in line, raises the lengths

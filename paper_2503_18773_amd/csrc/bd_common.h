@@ -68,10 +68,14 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
                              void* out, hipStream_t st);
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                    float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
+// k_new / v_new non-null: the launch quantizes the step's token into the cache itself (contiguous: at index
+// `length`, and attends length + 1 tokens; paged: with `step`); query groups of up to 16 heads only
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                  float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
+                                  float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
+                                  void* out, hipStream_t st);
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale,
-                            int num_splits, float* part_o, float* part_ml, void* out, hipStream_t st);
+                            int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
+                            void* out, hipStream_t st);
 // step_of: the paged cache whose fused step this merge ends (it then raises the lengths), or nullptr
 hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* part_ml, int nparts,
                           void* out, hipStream_t st, const bd_paged_cache* step_of = nullptr);

@@ -205,13 +205,11 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
       *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
     }
-    __threadfence();   // the row is read back below, and the block further down, by other threads of this workgroup
-    __syncthreads();
+    workgroup_global_sync();   // the row is read back below, and the block further down, by other threads of this workgroup
     quant_block<BITS, KT, kBlock>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
                                   const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
                                   (size_t)flush_page * a.n_kv_heads + hkv);
-    __threadfence();
-    __syncthreads();
+    workgroup_global_sync();
   }
   // this workgroup's slice of the fp16 residual tokens
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;

@@ -20,6 +20,7 @@
 //   A operand of the second product is contraction-contiguous: 16-byte loads, no transposition.
 #include "bd_common.h"
 #include "bd_device.h"
+#include "bd_mx_token.h"
 
 namespace bd {
 namespace {
@@ -48,7 +49,23 @@ struct MxArgs {
   int32_t* status;
   int max_pages, num_pages;
   int step;   // paged: 1 when this launch is the attention of a fused step
+  // fused step without an append launch: the step's token ([B][Hkv][128] bf16), which the workgroup that
+  // reads its block quantizes into the cache first (contiguous: at index `length`, and the kernel attends
+  // length + 1 tokens; paged: at seq_lens[b], with `step`); nullptr otherwise
+  const uint16_t* k_new;
+  const uint16_t* v_new;
 };
+
+// Fused step: the workgroup that reads block `blk` (the one the step's token falls into; one workgroup per
+// split and KV head) quantizes the token into position i of that block (array index bi) before it
+// requests anything of the block.
+__device__ __forceinline__ void mx_append_here(const MxArgs& a, size_t unit, size_t bi, int i) {
+  if (threadIdx.x < 128)
+    mx_quantize_token(a.k_new + unit * kD, a.v_new + unit * kD, const_cast<uint8_t*>(a.k_codes),
+                      const_cast<uint8_t*>(a.k_scales), const_cast<uint8_t*>(a.v_codes),
+                      const_cast<uint8_t*>(a.v_scales), (long)bi, i);
+  workgroup_global_sync();   // read back below by other threads of this workgroup
+}
 
 struct MergeLdsMx {
   float o[kWaves][4][kD];
@@ -122,18 +139,34 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
   const int nheads = min(4, a.gq);
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int length = a.length;
+  long app_bi = -1;   // fused step without an append launch: array index of the block the token goes to
+  int app_pos = 0;
   if (PAGED) {
     length = a.seq_lens[b];
     if (a.step && length >= 0) {
-      // fused step: the preceding kernel has appended this step's token if the table names a
-      // page for it; the length is raised only after this kernel
+      // fused step: this step's token counts if the table names a page for it (a preceding kernel
+      // has appended it, or, with a.k_new, this launch does); the length is raised only after this kernel
       const int n = length / kBlock;
       const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
-      length += (e >= 0 && e < a.num_pages) ? 1 : 0;
+      const bool ok = e >= 0 && e < a.num_pages;
+      if (a.k_new) {
+        if (ok) {
+          app_bi = (long)e * a.n_kv_heads + hkv;
+          app_pos = length % kBlock;
+        } else if (a.status && tid == 0 && split == 0) {
+          atomicOr(a.status, 2);   // the token is dropped
+        }
+      }
+      length += ok ? 1 : 0;
     }
     length = max(0, length);
+  } else if (a.k_new) {
+    app_bi = (long)(unit * (a.capacity / kBlock) + length / kBlock);
+    app_pos = length % kBlock;
+    length += 1;
   }
   const int nb = (length + kBlock - 1) / kBlock;
+  if (app_bi >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) mx_append_here(a, unit, (size_t)app_bi, app_pos);
   // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
   // unit read one contiguous window of the cache at any moment
   const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
@@ -371,16 +404,32 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
   const int nheads = min(GQP, a.gq - sub0);
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int length = a.length;
+  long app_bi = -1;   // fused step without an append launch (see decode_mx_kernel)
+  int app_pos = 0;
   if (PAGED) {
     length = a.seq_lens[b];
     if (a.step && length >= 0) {
       const int n = length / kBlock;
       const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
-      length += (e >= 0 && e < a.num_pages) ? 1 : 0;
+      const bool ok = e >= 0 && e < a.num_pages;
+      if (a.k_new) {
+        if (ok) {
+          app_bi = (long)e * a.n_kv_heads + hkv;
+          app_pos = length % kBlock;
+        } else if (a.status && tid == 0 && split == 0) {
+          atomicOr(a.status, 2);   // the token is dropped
+        }
+      }
+      length += ok ? 1 : 0;
     }
     length = max(0, length);
+  } else if (a.k_new) {
+    app_bi = (long)(unit * (a.capacity / kBlock) + length / kBlock);
+    app_pos = length % kBlock;
+    length += 1;
   }
   const int nb = (length + kBlock - 1) / kBlock;
+  if (app_bi >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) mx_append_here(a, unit, (size_t)app_bi, app_pos);
   // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
   // unit read one contiguous window of the cache at any moment
   const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
@@ -590,8 +639,11 @@ static hipError_t launch_mx(const MxArgs& a, int batch, hipStream_t st) {
 }
 
 hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float softmax_scale, int num_splits,
-                            float* part_o, float* part_ml, void* out, hipStream_t st) {
+                            float* part_o, float* part_ml, const void* k_new, const void* v_new, void* out,
+                            hipStream_t st) {
   MxArgs a{};
+  a.k_new = (const uint16_t*)k_new;
+  a.v_new = (const uint16_t*)v_new;
   a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;
@@ -611,8 +663,11 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
 }
 
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                  float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
+                                  float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
+                                  void* out, hipStream_t st) {
   MxArgs a{};
+  a.k_new = (const uint16_t*)k_new;
+  a.v_new = (const uint16_t*)v_new;
   a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.step = step ? 1 : 0;
   a.k_codes = (const uint8_t*)c->k_codes;

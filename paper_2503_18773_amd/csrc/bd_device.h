@@ -85,6 +85,20 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Makes global stores of this workgroup visible to its own later loads, for data that the workgroup
+// writes and then reads back inside one launch: wait until the stores have been written through to
+// L2, then meet.  The waves of a workgroup share their compute unit's vector cache, which its own
+// stores keep current, so workgroup scope is all this needs -- and all it can afford: measured at one
+// such workgroup per (sequence, KV head) and decode step, a device-scope release (__threadfence(),
+// which also writes back the XCD's L2) cost 45 us per launch and a device-scope acquire (which
+// invalidates the vector cache) 7 us.
+__device__ __forceinline__ void workgroup_global_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // Index of per-token float2 parameters staged in LDS: lanes that work on different 32-token chunks read
 // the same offset of their chunks at once, and entries 32 apart (256 bytes) share their banks, so every
 // chunk is shifted by two entries (arrays hold kParSlots entries).
