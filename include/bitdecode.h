@@ -241,12 +241,11 @@ bd_status bd_paged_decode_attn(const bd_paged_cache* c, const void* q, float sof
 
 /* One decode step of every sequence (Sec. III-A(1), IV-B: the step's append and its attention
  * in one call): the same results, bit for bit, as bd_paged_append_kv followed by
- * bd_paged_decode_attn, in fewer kernel launches.  For BD_FMT_INT4 / INT2, their _KT variants and
- * BD_FMT_MXFP4 with up to 16 query heads per KV head: two -- the attention kernel reads the new
- * token from k_new / v_new and files it (integer formats: the workgroup that reads the block a
- * step fills quantizes it first; MXFP4: the workgroup that reads the token's block quantizes the
- * token), and the merge, the last kernel, raises the lengths.  Otherwise three: append,
- * attention, merge.
+ * bd_paged_decode_attn, in fewer kernel launches.  With up to 16 query heads per KV head (8 for
+ * the _G64 / _G32 formats): two -- the attention kernel reads the new token from k_new / v_new
+ * and files it (integer formats: the workgroup that reads the block a step fills quantizes it
+ * first; MXFP4: the workgroup that reads the token's block quantizes the token), and the merge,
+ * the last kernel, raises the lengths.  Larger query groups: three -- append, attention, merge.
  * (With num_splits == 1 there is no merge and a small kernel raises the lengths.)  A sequence
  * whose token is dropped for want of a valid page (bit 1 of *status) attends the tokens it had. */
 bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const void* v_new,

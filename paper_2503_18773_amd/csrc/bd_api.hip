@@ -365,7 +365,8 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
                                ? launch_decode_mx_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
                                                         direct, st)
                            : fmt_group(c->format) != kBlock
-                               ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, direct, st)
+                               ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
+                                                         direct, st)
                                : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
                                                      direct, st));
   if (s != BD_OK) return s;
@@ -392,11 +393,12 @@ bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   hipStream_t st = (hipStream_t)stream;
-  // Main integer kernel and MXFP4, one workgroup per split and KV head (query groups of up to 16 heads):
+  // One workgroup per split and KV head (query groups of up to 16 heads; 8 for the group-64/32 formats):
   // two launches.  The attention kernel reads the new token from the caller's buffers and files it
   // (integer: the workgroup that reads the block a step fills quantizes it first; MXFP4: the workgroup
   // that reads the token's block quantizes the token into it), and the merge raises the lengths.
-  if ((c->format == BD_FMT_MXFP4 || fmt_group(c->format) == kBlock) && c->n_q_heads / c->n_kv_heads <= 16)
+  // (the kernel of the group-64/32 formats takes 8 heads per workgroup, the others 16)
+  if (c->n_q_heads / c->n_kv_heads <= (fmt_is_int(c->format) && fmt_group(c->format) != kBlock ? 8 : 16))
     return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, st, k_new, v_new);
   // otherwise three launches instead of four: the append leaves the lengths alone, the attention
   // kernel counts the new token in, and the merge, last in line, raises the lengths

@@ -66,8 +66,10 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
                              void* out, hipStream_t st);
+// (k_new / v_new as in launch_decode_paged; query groups of up to 8 heads only)
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                   float* part_o, float* part_ml, bool step, void* out, hipStream_t st);
+                                   float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
+                                   void* out, hipStream_t st);
 // k_new / v_new non-null: the launch quantizes the step's token into the cache itself (contiguous: at index
 // `length`, and attends length + 1 tokens; paged: with `step`); query groups of up to 16 heads only
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,

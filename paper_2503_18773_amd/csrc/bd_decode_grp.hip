@@ -18,6 +18,7 @@
 #include "bd_common.h"
 #include "bd_device.h"
 #include "bd_fmt.h"
+#include "bd_quant_block.h"
 
 namespace bd {
 namespace {
@@ -123,16 +124,31 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
 
   const size_t unit = (size_t)b * a.n_kv_heads + hkv;
   int nb = a.nb, res_len = a.res_len;
+  int new_slot = a.new_slot;   // fused step: residual slot of the token that is still in the caller's buffer, or -1
+  int flush_page = -1;         // paged fused step that fills the residual: the page the block goes to
   if (PAGED) {
     int len = a.seq_lens[b];
+    new_slot = -1;
     if (a.step && len >= 0) {
-      // fused step: the preceding kernel has appended this step's token (unless it needed a page
-      // the table does not name) and the length is raised only after this kernel
+      // fused step: this step's token counts (unless it needs a page the table does not name) and
+      // the length is raised only after this kernel.  With a.k_new no kernel has appended the token:
+      // it is read from the caller's buffer and filed by this launch, and if it fills the residual,
+      // the workgroup that reads the new block quantizes it first (as in the main kernel).
       bool ok = true;
+      int e = -1;
       if (len % kBlock == kBlock - 1) {
         const int n = len / kBlock;
-        const int e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
+        e = n < a.max_pages ? a.block_table[(size_t)b * a.max_pages + n] : -1;
         ok = e >= 0 && e < a.num_pages;
+      }
+      if (a.k_new) {
+        if (!ok) {
+          if (a.status && tid == 0 && split == 0) atomicOr(a.status, 2);   // the token is dropped
+        } else if (len % kBlock < kBlock - 1) {
+          new_slot = len % kBlock;
+        } else {
+          flush_page = e;
+        }
       }
       len += ok ? 1 : 0;
     }
@@ -143,6 +159,22 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
   // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
   // unit read one contiguous window of the cache at any moment
   const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
+  if (PAGED && flush_page >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) {
+    // the 128 residual rows become block nb - 1, which this workgroup alone reads in this launch (one
+    // workgroup per split and KV head: the host takes this path for up to 8 heads per KV head)
+    uint16_t* kr = const_cast<uint16_t*>(a.k_res) + unit * kBlock * kD;
+    uint16_t* vr = const_cast<uint16_t*>(a.v_res) + unit * kBlock * kD;
+    if (tid < 32) {
+      const bool is_v = tid >= 16;
+      const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+      *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
+    }
+    workgroup_global_sync();
+    quant_block<BITS, false, G>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
+                                const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
+                                (size_t)flush_page * a.n_kv_heads + hkv);
+    workgroup_global_sync();
+  }
   const int rt0 = (res_len * split) / a.num_splits, rt1 = (res_len * (split + 1)) / a.num_splits;
   const uint16_t* qbase = a.q + ((size_t)b * a.n_q_heads + hkv * a.gq + head0) * kD;
 
@@ -167,7 +199,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     for (int grp = wave; grp < nres_groups; grp += kWaves) {
       const int t = min(rt0 + 16 * grp + col, rt1 - 1);   // rows past the slice repeat its last token
       // (the newest token of a fused step is read from where the caller left it)
-      const uint16_t* row = (t == a.new_slot ? a.k_new + unit * kD : a.k_res + (unit * kBlock + t) * kD) + 8 * g;
+      const uint16_t* row = (t == new_slot ? a.k_new + unit * kD : a.k_res + (unit * kBlock + t) * kD) + 8 * g;
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 4; ++j)
@@ -179,10 +211,10 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       }
     }
   }
-  if (a.new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
+  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
-    uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + a.new_slot) * kD + 8 * (tid & 15);
+    uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + new_slot) * kD + 8 * (tid & 15);
     *reinterpret_cast<u4_t*>(dst) = *reinterpret_cast<const u4_t*>(src);
   }
   __syncthreads();   // q_s and res_s are complete
@@ -493,7 +525,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
         // residual slice, part 2: fold the fp16 tokens in
         for (int t = 0; t < nres; ++t) {
           const float pr = __builtin_amdgcn_exp2f(res_s[t][h] - M);
-          const uint16_t* vrow = rt0 + t == a.new_slot ? a.v_new + unit * kD : a.v_res + (unit * kBlock + rt0 + t) * kD;
+          const uint16_t* vrow = rt0 + t == new_slot ? a.v_new + unit * kD : a.v_res + (unit * kBlock + rt0 + t) * kD;
           const uint32_t raw = *reinterpret_cast<const uint32_t*>(vrow + c0);
           L += pr;
           o0 = __builtin_fmaf(pr, h2f((uint16_t)(raw & 0xFFFFu)), o0);
@@ -573,9 +605,11 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
 }
 
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
-                                   float* part_o, float* part_ml, bool step, void* out, hipStream_t st) {
+                                   float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
+                                   void* out, hipStream_t st) {
   GrpArgs a;
-  a.k_new = a.v_new = nullptr;
+  a.k_new = (const uint16_t*)k_new;   // non-null: the step's token, which this launch appends itself
+  a.v_new = (const uint16_t*)v_new;
   a.new_slot = -1;
   a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
   a.k_codes = (const uint32_t*)c->k_codes;
