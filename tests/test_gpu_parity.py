@@ -792,6 +792,42 @@ def test_paged_fused_step_drops_the_token_that_has_no_page(fmt):
         assert torch.equal(a.buffers[i], b.buffers[i]), i
 
 
+@pytest.mark.parametrize("fmt", ["int4", "int2_kt", "int4_g32", "mxfp4"])
+def test_paged_fused_step_on_the_filling_step_for_any_split(fmt):
+    """The step that fills a residual (or, MXFP4, lands anywhere in a block) is quantized inside the attention
+    launch by the workgroup that reads that block -- whichever split that is: sequences whose next block has
+    index 0, 3, 4, 6 and 9, split counts 1 to 8; two steps (the fill, and the step after it) against
+    append + attention on a twin, bit for bit, pool included."""
+    import torch
+    mx = fmt == "mxfp4"
+    dt, tdt = ("bf16", torch.bfloat16) if mx else ("fp16", torch.float16)
+    H, Hq = 2, 8
+    lens = [127, 128 * 3 + 127, 128 * 4 + 127, 128 * 6 + 127, 128 * 9 + 127, 128 * 2 + 5]
+    for ns in (1, 2, 3, 5, 8):
+        table = np.random.default_rng(20 + ns).permutation(80)[:6 * 12].reshape(6, 12).astype(np.int32)
+        twins = []
+        for _ in range(2):
+            if mx:
+                _, gc, _ = _paged_mx_pair(lens, H, Hq, num_pages=80, max_pages=12, table=table)
+            else:
+                _, gc, _ = _paged_pair(fmt, lens, H, Hq, num_pages=80, max_pages=12, table=table)
+            twins.append(gc)
+        a, b = twins
+        w = W.scaled(W.CONFIGS["cfg4" if mx else "cfg1"], batch=6, n_q_heads=Hq, n_kv_heads=H, context=128, seed=63 + ns)
+        outs = [torch.empty((6, Hq, 128), dtype=tdt, device="cuda:0") for _ in range(2)]
+        for step in range(2):
+            kn, vn, q = (to_dev(x, dt) for x in (*W.make_new_kv(w, step), W.make_q(w, step)))
+            a.decode_step(kn, vn, q, W.softmax_scale(w), outs[0], ns)
+            b.append_kv(kn, vn)
+            b.decode_attn(q, W.softmax_scale(w), outs[1], ns)
+            torch.cuda.synchronize()
+            assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16)), (ns, step)
+            assert torch.equal(a.seq_lens, b.seq_lens), (ns, step)
+        assert list(a.seq_lens.cpu().numpy()) == [L + 2 for L in lens] and int(a.status.item()) == 0
+        for i in range(4 if mx else 6):
+            assert torch.equal(a.buffers[i], b.buffers[i]), (ns, i)
+
+
 # ---------------------------------------------------------------------------- quantization groups of 32 / 64
 
 @pytest.mark.parametrize("fmt", GROUP_FORMATS)
