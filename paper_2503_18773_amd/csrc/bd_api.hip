@@ -82,8 +82,7 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   if (check_shape(c) != BD_OK || packed_len <= 0) return 1;
   // Each workgroup runs 4 waves that take 128-token blocks in turn, so the natural work
   // quantum is 4 blocks.  The kernel keeps 2 workgroups resident per compute unit (256 CUs):
-  // aim at one full round of 512 workgroups over all (sequence, KV head) units, then
-  // rebalance so that every split gets the same number of quanta.
+  // aim at one full round of 512 workgroups over all (sequence, KV head) units.
   const long units = (long)c->batch * group_workgroups(c);
   const int nb = (packed_len + kBlock - 1) / kBlock;
   const int quanta = (nb + 3) / 4;
@@ -102,9 +101,9 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   const long target = c->format == BD_FMT_INT4_G32 && c->n_q_heads / c->n_kv_heads > 4 ? 256 : 512;
   int want = (int)((target + units - 1) / units);
   if (want < 1) want = 1;
-  int splits = quanta < want ? quanta : want;
-  const int per = (quanta + splits - 1) / splits;
-  splits = (quanta + per - 1) / per;
+  // (no rebalancing: quanta are dealt to the splits round robin, so a count that does not divide them
+  // leaves a few workgroups one quantum short, which is faster than fewer workgroups of equal length)
+  const int splits = quanta < want ? quanta : want;
   return splits < 1 ? 1 : splits;
 }
 

@@ -184,8 +184,9 @@ def test_split_heuristic_properties():
     assert B.bd_choose_splits(_desc(batch=32), 16384) == 2
     # one block per wave is kept up to three workgroups per compute unit (integer formats, groups <= 8)
     assert B.bd_choose_splits(_desc(), 40960) == 80 and B.bd_choose_splits(_desc(), 49152) == 96
-    assert B.bd_choose_splits(_desc(), 57344) == 56
-    assert B.bd_choose_splits(_desc(format=B.BD_FMT_MXFP4), 49152) == 48
+    assert B.bd_choose_splits(_desc(), 57344) == 64                     # beyond that: one round of 512 workgroups
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_MXFP4), 49152) == 64
+    assert B.bd_choose_splits(_desc(format=B.BD_FMT_MXFP4), 32768 + 1) == 64   # quanta need not divide evenly
     # one instance of the kernel for smaller quantization groups runs one workgroup per compute unit
     assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT4_G32), 32768) == 64
     assert B.bd_choose_splits(_desc(format=B.BD_FMT_INT4_G32, n_q_heads=64), 32768) == 32
