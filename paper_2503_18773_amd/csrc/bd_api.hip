@@ -95,7 +95,9 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   // With one workgroup per compute unit already, a single split needs no merge kernel at all; that beats
   // the better occupancy of two splits until the call is long enough to amortize the merge (measured at
   // 256 and 384 units: 30.0 against 32.4 us and 41.9 against 47.1 us at 4K tokens, 99.5 against 94.2 us at 16K).
-  if (units >= 256 && (long)nb * units <= 16384) return 1;
+  // (2-bit codes: the kernel is bound by arithmetic and the second split pays earlier -- 40.7 against 44.6 us
+  // at 32 sequences x 8K tokens)
+  if (units >= 256 && (long)nb * units <= (fmt_is_int(c->format) && fmt_bits(c->format) == 2 ? 12288 : 16384)) return 1;
   // (one kernel instance runs one workgroup per compute unit: 4-bit codes in groups of 32 with more than
   // 4 query heads per KV head)
   const long target = c->format == BD_FMT_INT4_G32 && c->n_q_heads / c->n_kv_heads > 4 ? 256 : 512;
