@@ -763,12 +763,12 @@ struct StepBump {
   int every_token;              // a page is needed by every token (MXFP4), not only by the 128th
 };
 
-template <bool BF16>
-__global__ __launch_bounds__(128 * kCombineGroups) void combine_kernel(const float* __restrict__ part_o,
-                                                                        const float* __restrict__ part_ml,
-                                                                        int nparts, int nrows,
-                                                                        uint16_t* __restrict__ out, StepBump bump) {
-  constexpr int G = kCombineGroups, kBatch = kCombineBatch;
+template <bool BF16, int G>
+__global__ __launch_bounds__(128 * G) void combine_kernel(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_ml,
+                                                           int nparts, int nrows,
+                                                           uint16_t* __restrict__ out, StepBump bump) {
+  constexpr int kBatch = kCombineBatch;
   __shared__ float sm[G][128], sl[G][128], so[G][128];
   const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, grp = tid >> 7;
   if (bump.seq_lens && tid == 128 * G - 1 && row % bump.n_q_heads == 0) {   // one thread per sequence
@@ -950,10 +950,20 @@ hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* p
     bump.num_pages = step_of->num_pages;
     bump.every_token = step_of->format == BD_FMT_MXFP4;
   }
-  if (c->format == BD_FMT_MXFP4)
-    combine_kernel<true><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out, bump);
-  else
-    combine_kernel<false><<<dim3(nrows), dim3(128 * kCombineGroups), 0, st>>>(part_o, part_ml, nparts, nrows, (uint16_t*)out, bump);
+  // thread groups per row: enough to request every partial in one round (8 per group), no more -- a launch of
+  // 1024-thread workgroups costs about a microsecond more than one of 128-thread workgroups
+  const bool bf16 = c->format == BD_FMT_MXFP4;
+  uint16_t* o = (uint16_t*)out;
+#define BD_COMBINE(G)                                                                                        \
+  do {                                                                                                       \
+    if (bf16) combine_kernel<true, G><<<dim3(nrows), dim3(128 * G), 0, st>>>(part_o, part_ml, nparts, nrows, o, bump); \
+    else combine_kernel<false, G><<<dim3(nrows), dim3(128 * G), 0, st>>>(part_o, part_ml, nparts, nrows, o, bump);     \
+  } while (0)
+  if (nparts <= kCombineBatch) BD_COMBINE(1);
+  else if (nparts <= 2 * kCombineBatch) BD_COMBINE(2);
+  else if (nparts <= 4 * kCombineBatch) BD_COMBINE(4);
+  else BD_COMBINE(kCombineGroups);
+#undef BD_COMBINE
   return hipGetLastError();
 }
 
