@@ -146,6 +146,18 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
                          float softmax_scale, int32_t num_splits, void* workspace, void* out,
                          void* stream);
 
+/* bd_decode_attn for callers that cannot allocate device memory or pass a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the split partials go to a
+ * static device array inside the library, BD_STATIC_SCRATCH_BYTES per GPU, held until the process
+ * ends, instead of a caller's workspace.  Same kernels, same output bits as bd_decode_attn with
+ * `out` given; `out` must be non-NULL.  Calls no allocating routine.  BD_ERR_CAPACITY if
+ * bd_workspace_bytes(c, num_splits) exceeds BD_STATIC_SCRATCH_BYTES.  All calls on one GPU share
+ * the array: calls that may overlap there (different streams, no ordering between them) race.  The
+ * first call on a device looks the array's address up (do that call outside a graph capture). */
+#define BD_STATIC_SCRATCH_BYTES (4u << 20)
+bd_status bd_decode_attn_static(const bd_cache* c, const void* q, int32_t packed_len, int32_t res_len,
+                                float softmax_scale, int32_t num_splits, void* out, void* stream);
+
 /* One decode step in one call: exactly bd_append_kv(k_new, v_new) followed by
  * bd_decode_attn(q, ..., out) -- same cache contents, same lengths, same output bits -- but
  * on steps that do not fill the residual block the new token is attended straight from

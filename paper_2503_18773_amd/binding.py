@@ -14,6 +14,7 @@ FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4, "int
            "int2_kt": BD_FMT_INT2_KT, "int4_g64": BD_FMT_INT4_G64, "int4_g32": BD_FMT_INT4_G32,
            "int2_g64": BD_FMT_INT2_G64, "int2_g32": BD_FMT_INT2_G32}
 BLOCK = 128
+BD_STATIC_SCRATCH_BYTES = 4 << 20   # include/bitdecode.h
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbitdecode.so")
 _lib = None
@@ -65,6 +66,7 @@ def lib() -> ctypes.CDLL:
         L.bd_quant_pack_kv.restype, L.bd_quant_pack_kv.argtypes = ctypes.c_int, [P, V, V, I, IP, IP, V]
         L.bd_append_kv.restype, L.bd_append_kv.argtypes = ctypes.c_int, [P, V, V, IP, IP, V]
         L.bd_decode_attn.restype, L.bd_decode_attn.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V, V]
+        L.bd_decode_attn_static.restype, L.bd_decode_attn_static.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V]
         L.bd_splitk_combine.restype, L.bd_splitk_combine.argtypes = ctypes.c_int, [P, V, I, V, V]
         L.bd_decode_step.restype, L.bd_decode_step.argtypes = ctypes.c_int, [P, V, V, V, IP, IP, F, I, V, V, V]
         PP = ctypes.POINTER(bd_paged_cache)
@@ -81,7 +83,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
-           "bd_decode_attn", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
+           "bd_decode_attn", "bd_decode_attn_static", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
            "bd_paged_cache_bytes", "bd_paged_workspace_bytes", "bd_paged_quant_pack_kv", "bd_paged_append_kv",
            "bd_paged_decode_attn", "bd_paged_decode_step"]
 
@@ -135,6 +137,12 @@ def bd_decode_attn(c: bd_cache, q, packed_len: int, res_len: int, softmax_scale:
                    workspace, out=None, stream=None):
     _check(lib().bd_decode_attn(ctypes.byref(c), _ptr(q), packed_len, res_len, softmax_scale, num_splits,
                                 _ptr(workspace), _ptr(out), _stream(stream)), "bd_decode_attn")
+
+
+def bd_decode_attn_static(c: bd_cache, q, packed_len: int, res_len: int, softmax_scale: float, num_splits: int, out,
+                          stream=None):
+    _check(lib().bd_decode_attn_static(ctypes.byref(c), _ptr(q), packed_len, res_len, softmax_scale, num_splits,
+                                       _ptr(out), _stream(stream)), "bd_decode_attn_static")
 
 
 def bd_decode_step(c: bd_cache, k_new, v_new, q, packed_len: int, res_len: int, softmax_scale: float,

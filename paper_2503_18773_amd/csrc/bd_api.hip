@@ -1,10 +1,17 @@
 // C-ABI entry points of libbitdecode.so: argument validation and kernel sequencing only.
+#include <mutex>
+
 #include "bd_common.h"
 
 namespace bd {
 static thread_local int g_last_hip_error = 0;
 void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 }  // namespace bd
+
+// Split partials of bd_decode_attn_static: one array per GPU, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address is looked up once per
+// device (static_scratch_ptr) and that pointer is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[BD_STATIC_SCRATCH_BYTES];
 
 using namespace bd;
 
@@ -53,6 +60,28 @@ bd_status hip_status(hipError_t e) {
 }
 
 int bits_of(int format) { return fmt_bits(format); }
+
+// Device address of `scratch` on the current device, looked up on the first call per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+bd_status static_scratch_ptr(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_status(e);
+  if (dev < 0 || dev >= kMaxDevices) return BD_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_status(e);
+    if (!p) return BD_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return BD_OK;
+}
 
 }  // namespace
 
@@ -208,6 +237,19 @@ bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, i
   // (one split: the attention kernel has written `out` itself, there is nothing to merge)
   if (out && num_splits > 1) s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st));
   return s;
+}
+
+bd_status bd_decode_attn_static(const bd_cache* c, const void* q, int32_t packed_len, int32_t res_len,
+                                float softmax_scale, int32_t num_splits, void* out, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if (!out || num_splits < 1 || num_splits > 65534) return BD_ERR_INVALID_ARG;
+  if (bd_workspace_bytes(c, num_splits) > (size_t)BD_STATIC_SCRATCH_BYTES) return BD_ERR_CAPACITY;
+  void* ws = nullptr;
+  if ((s = static_scratch_ptr(&ws)) != BD_OK) return s;
+  // Every partial the merge reads is written by this call's attention launch first (empty splits
+  // store m = -inf, l = 0), so nothing of the previous call's contents has to be cleared.
+  return bd_decode_attn(c, q, packed_len, res_len, softmax_scale, num_splits, ws, out, stream);
 }
 
 bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
