@@ -19,8 +19,10 @@
  *  - head_dim is 128.  The residual block N_r (Eq. 1) is 128 tokens for every integer format; the
  *    quantization group is 128 as well, except for the _G64 / _G32 formats (64 / 32); the MX group
  *    is 32 for BD_FMT_MXFP4, which keeps no residual.
- *  - Arguments are validated before anything is launched; on error nothing is enqueued
- *    and no state changes.  Non-finite K/V/Q values are undefined behaviour.
+ *  - Arguments are validated before anything is launched: a validation error (any status but
+ *    BD_ERR_HIP) means nothing was enqueued and no state changed.  BD_ERR_HIP is a failed launch
+ *    in the middle of a call: kernels enqueued before it stay enqueued, and the in-out lengths
+ *    are those reached so far (see bd_decode_step).  Non-finite K/V/Q values are undefined behaviour.
  *
  * Cache layout (all little-endian, contiguous, 16-byte aligned), B = batch, H = n_kv_heads,
  * NBcap = capacity/128, D = 128, bits = 4 or 2, cpw = 32/bits codes per 32-bit word:
@@ -84,6 +86,12 @@ typedef enum {
   BD_FMT_INT2_G32 = 8
 } bd_format;
 
+/* Element type of the attention output rows `out` (Fig. 2 caption: Out = softmax(Q D(K')^T) D(V')). */
+typedef enum {
+  BD_OUT_HALF = 0,   /* the type of the inputs: fp16 for the integer formats, bf16 for BD_FMT_MXFP4 */
+  BD_OUT_F32 = 1     /* fp32: the kernels' fp32 result without the final rounding to 11 (fp16) or 8 (bf16) bits */
+} bd_out_type;
+
 /* Shape and buffers of one layer's cache.  Plain data, filled by the caller, passed by
  * const pointer; the six buffers are device pointers with the layouts given above. */
 typedef struct bd_cache {
@@ -96,6 +104,7 @@ typedef struct bd_cache {
   void *k_codes, *v_codes;
   void *k_params, *v_params;
   void *k_res, *v_res;
+  int32_t out_type;      /* bd_out_type of every `out` argument used with this cache (0 = BD_OUT_HALF) */
 } bd_cache;
 
 /* Size in bytes of buffer `which` (0 k_codes, 1 v_codes, 2 k_params, 3 v_params, 4 k_res,
@@ -139,7 +148,8 @@ bd_status bd_append_kv(const bd_cache* c, const void* k_new, const void* v_new,
  * partials are not written: the attention kernel stores `out` itself, the same values, and no
  * merge kernel runs).  If `out` is non-NULL (device,
  * [B][n_q_heads][D], fp16 / bf16) the merge of the partials is enqueued too, so `out`
- * is complete when the stream passes this call; if NULL, call bd_splitk_combine.
+ * is complete when the stream passes this call; if NULL, call bd_splitk_combine.  (`out` has
+ * the element type c->out_type names here and in every other call: fp16 / bf16, or fp32.)
  * num_splits >= 1 (any value; splits beyond the number of 128-token blocks stay empty).
  * With no tokens at all the output is zero. */
 bd_status bd_decode_attn(const bd_cache* c, const void* q, int32_t packed_len, int32_t res_len,
@@ -165,8 +175,9 @@ bd_status bd_decode_attn_static(const bd_cache* c, const void* q, int32_t packed
  * separate append launch (the fusion of the paper's Residual Kernel, Sec. III-A(1) /
  * Sec. IV-B, without its lazy flush).  BD_FMT_MXFP4 (up to 16 query heads per KV head): the
  * workgroup that reads the token's block quantizes the token into the cache before it attends.
- * All pointers as in the two calls; `out` must be non-NULL.  On error nothing is enqueued by the failing part and the lengths are those
- * reached so far. */
+ * All pointers as in the two calls; `out` must be non-NULL.  Every argument is validated before the
+ * append; only BD_ERR_HIP (a failed launch) can leave the token appended without the attention
+ * having been enqueued, and *packed_len / *res_len then say so. */
 bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
                          int32_t* packed_len, int32_t* res_len, float softmax_scale,
                          int32_t num_splits, void* workspace, void* out, void* stream);
@@ -220,6 +231,7 @@ typedef struct bd_paged_cache {
   int32_t* block_table;
   int32_t* seq_lens;
   int32_t* status;
+  int32_t out_type;            /* bd_out_type, as in bd_cache */
 } bd_paged_cache;
 
 /* Size in bytes of buffer `which` (0..5 as bd_cache_bytes, 6 block_table, 7 seq_lens). */

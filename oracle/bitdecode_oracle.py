@@ -588,26 +588,3 @@ def decode_attn(cache, q: np.ndarray, sm_scale: float, units=None) -> np.ndarray
             w = attention_weights(np.asarray(q[b, h * g + j], dtype=np.float64), Kh, sm_scale)
             out[b, h * g + j] = w @ Vh
     return out
-
-
-def rounding_noise_scale(cache, q: np.ndarray, sm_scale: float, units=None) -> np.ndarray:
-    """A yardstick for tolerances, not a step of the method: for every query head,
-    sqrt(sum_t (w_t * max_c |V_hat[t, c]|)^2) with w the exact softmax weights.  An implementation that
-    feeds probabilities or values to a matrix unit in an 11-bit format (fp16) commits a rounding error
-    of up to 2^-11 of each term w_t * V_hat[t, c]; over many tokens these add like noise, and this is
-    the scale of that sum.  It is large where single tokens with large values dominate a head, however
-    small the head's outputs are after cancellation.  float64 [B, Hq]; NaN outside `units`."""
-    B, Hq, D = q.shape
-    g = Hq // cache.H
-    out = np.full((B, Hq), np.nan, np.float64)
-    todo = [(b, h) for b in range(B) for h in range(cache.H)] if units is None else list(units)
-    for b, h in todo:
-        Kh, Vh = cache.dequant(b, h)
-        if Kh.shape[0] == 0:
-            out[b, h * g:(h + 1) * g] = 0.0
-            continue
-        vmax = np.abs(Vh).max(axis=1)
-        for j in range(g):
-            w = attention_weights(np.asarray(q[b, h * g + j], dtype=np.float64), Kh, sm_scale)
-            out[b, h * g + j] = np.sqrt(np.sum((w * vmax) ** 2))
-    return out

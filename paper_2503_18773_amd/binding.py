@@ -14,6 +14,7 @@ FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4, "int
            "int2_kt": BD_FMT_INT2_KT, "int4_g64": BD_FMT_INT4_G64, "int4_g32": BD_FMT_INT4_G32,
            "int2_g64": BD_FMT_INT2_G64, "int2_g32": BD_FMT_INT2_G32}
 BLOCK = 128
+BD_OUT_HALF, BD_OUT_F32 = 0, 1
 BD_STATIC_SCRATCH_BYTES = 4 << 20   # include/bitdecode.h
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbitdecode.so")
@@ -27,6 +28,7 @@ class bd_cache(ctypes.Structure):
         ("k_codes", ctypes.c_void_p), ("v_codes", ctypes.c_void_p),
         ("k_params", ctypes.c_void_p), ("v_params", ctypes.c_void_p),
         ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
+        ("out_type", ctypes.c_int32),
     ]
 
 
@@ -39,6 +41,7 @@ class bd_paged_cache(ctypes.Structure):
         ("k_params", ctypes.c_void_p), ("v_params", ctypes.c_void_p),
         ("k_res", ctypes.c_void_p), ("v_res", ctypes.c_void_p),
         ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p), ("status", ctypes.c_void_p),
+        ("out_type", ctypes.c_int32),
     ]
 
 
@@ -210,7 +213,7 @@ class KVCache:
         self.res_len = 0
         self.device = device
         self._ws = None
-        self._ws_splits = -1
+        self._retired = []
 
     @property
     def length(self) -> int:
@@ -224,10 +227,14 @@ class KVCache:
         self.packed_len, self.res_len = bd_append_kv(self.desc, k_new, v_new, self.packed_len, self.res_len, stream)
 
     def workspace(self, num_splits: int):
+        """A device buffer of at least bd_workspace_bytes(num_splits).  It only grows, and a buffer it
+        outgrows is kept alive (kernels queued on any stream may still be writing partials into it)."""
         import torch
-        if self._ws_splits != num_splits:
-            self._ws = torch.empty(bd_workspace_bytes(self.desc, num_splits), dtype=torch.uint8, device=self.device)
-            self._ws_splits = num_splits
+        need = bd_workspace_bytes(self.desc, num_splits)
+        if self._ws is None or self._ws.numel() < need:
+            if self._ws is not None:
+                self._retired.append(self._ws)
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._ws
 
     def choose_splits(self) -> int:
@@ -281,7 +288,7 @@ class PagedKVCache:
         self.desc.status = self.status.data_ptr()
         self.device = device
         self._ws = None
-        self._ws_splits = -1
+        self._retired = []
 
     def quant_pack_kv(self, seq: int, k, v, stream=None):
         assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
@@ -291,11 +298,13 @@ class PagedKVCache:
         bd_paged_append_kv(self.desc, k_new, v_new, stream)
 
     def workspace(self, num_splits: int):
+        """As KVCache.workspace: grows only, outgrown buffers stay alive."""
         import torch
-        if self._ws_splits != num_splits:
-            self._ws = torch.empty(bd_paged_workspace_bytes(self.desc, num_splits), dtype=torch.uint8,
-                                   device=self.device)
-            self._ws_splits = num_splits
+        need = bd_paged_workspace_bytes(self.desc, num_splits)
+        if self._ws is None or self._ws.numel() < need:
+            if self._ws is not None:
+                self._retired.append(self._ws)
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._ws
 
     def decode_attn(self, q, softmax_scale: float, out, num_splits: int, stream=None):

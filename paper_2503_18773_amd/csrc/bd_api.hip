@@ -35,6 +35,7 @@ bd_status check_shape(const bd_cache* c) {
   if (!fmt_is_int(c->format) && c->format != BD_FMT_MXFP4) return BD_ERR_INVALID_ARG;
   if (c->n_q_heads % c->n_kv_heads != 0 || c->capacity % kBlock != 0) return BD_ERR_INVALID_ARG;
   if (c->head_dim != kD) return BD_ERR_UNSUPPORTED;
+  if (c->out_type != BD_OUT_HALF && c->out_type != BD_OUT_F32) return BD_ERR_INVALID_ARG;
   // query heads per KV head: the int4 / int2 kernels pad the group to 4, 8 or 16 MFMA columns and
   // take larger groups 16 heads per workgroup; the MXFP4 kernels take up to 16 heads per workgroup.
   // The workgroups of one split must fit grid dimension y.
@@ -278,6 +279,9 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
     *packed_len = pl + 1;
     return BD_OK;
   }
+  if (c->format == BD_FMT_MXFP4 ? (pl < 0 || r != 0 || pl > c->capacity)
+                                : (pl < 0 || pl % kBlock != 0 || r < 0 || r >= kBlock || pl > c->capacity))
+    return BD_ERR_INVALID_ARG;
   const bool fusable = c->format != BD_FMT_MXFP4 && r < kBlock - 1;
   if (!fusable) {
     // a step that fills the residual block (or an MXFP4 cache, whose tokens are quantized on
@@ -318,6 +322,7 @@ static bd_cache shape_of(const bd_paged_cache* c) {
   s.head_dim = c->head_dim;
   s.format = c->format;
   s.capacity = kBlock;
+  s.out_type = c->out_type;
   return s;
 }
 

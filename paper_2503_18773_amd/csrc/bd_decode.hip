@@ -72,7 +72,8 @@ struct DecodeArgs {
   int new_slot;            // its residual slot (res_len - 1), or -1 when the residual buffers are complete
   float* part_o;    // [nparts][B][Hq][128]
   float* part_ml;   // [nparts][B][Hq][2]   (running max in log2 units, running sum)
-  uint16_t* out;    // one split only: the output [B][Hq][128] (fp16), written instead of the partials; else nullptr
+  void* out;    // one split only: the output [B][Hq][128], written instead of the partials; else nullptr
+  int out_kind;     // element type of `out` (kOutF16 / kOutBf16 / kOutF32)
   int n_q_heads, n_kv_heads, gq;
   int nb;           // packed 128-token blocks
   int nbcap;
@@ -736,7 +737,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * a.gq + head0 + h;
       float2 o = {o0 + Z, o1 + Z};
       if (a.out) {   // one split: row == the output row
-        store_final_pair(a.out + row * kD + c0, 0, o.x, o.y, L);
+        store_final_pair(a.out, row * kD + c0, a.out_kind, o.x, o.y, L);
       } else {
         *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
         if ((tid & 63) == 0) {
@@ -763,11 +764,11 @@ struct StepBump {
   int every_token;              // a page is needed by every token (MXFP4), not only by the 128th
 };
 
-template <bool BF16, int G>
+template <int G>
 __global__ __launch_bounds__(128 * G) void combine_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_ml,
                                                            int nparts, int nrows,
-                                                           uint16_t* __restrict__ out, StepBump bump) {
+                                                           void* __restrict__ out, int kind, StepBump bump) {
   constexpr int kBatch = kCombineBatch;
   __shared__ float sm[G][128], sl[G][128], so[G][128];
   const int row = blockIdx.x, tid = threadIdx.x, c = tid & 127, grp = tid >> 7;
@@ -827,13 +828,9 @@ __global__ __launch_bounds__(128 * G) void combine_kernel(const float* __restric
       }
       res = Lt > 0.f ? ot / Lt : 0.f;
     }
-    if (BF16) {
-      uint32_t u = __float_as_uint(res);
-      u += 0x7FFFu + ((u >> 16) & 1u);
-      out[(size_t)row * kD + c] = (uint16_t)(u >> 16);
-    } else {
-      out[(size_t)row * kD + c] = f2h(res);
-    }
+    const size_t idx = (size_t)row * kD + c;
+    if (kind == kOutF32) reinterpret_cast<float*>(out)[idx] = res;
+    else reinterpret_cast<uint16_t*>(out)[idx] = kind == kOutBf16 ? f2bf(res) : f2h(res);
   }
 }
 
@@ -872,7 +869,8 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
                              void* out, hipStream_t st) {
   DecodeArgs a;
-  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
+  a.out = num_splits == 1 ? out : nullptr;
+  a.out_kind = out_kind(c->format, c->out_type);
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;
@@ -909,7 +907,8 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
                                void* out, hipStream_t st) {
   DecodeArgs a;
   a.step = step ? 1 : 0;
-  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
+  a.out = num_splits == 1 ? out : nullptr;
+  a.out_kind = out_kind(c->format, c->out_type);
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;
@@ -952,13 +951,8 @@ hipError_t launch_combine(const bd_cache* c, const float* part_o, const float* p
   }
   // thread groups per row: enough to request every partial in one round (8 per group), no more -- a launch of
   // 1024-thread workgroups costs about a microsecond more than one of 128-thread workgroups
-  const bool bf16 = c->format == BD_FMT_MXFP4;
-  uint16_t* o = (uint16_t*)out;
-#define BD_COMBINE(G)                                                                                        \
-  do {                                                                                                       \
-    if (bf16) combine_kernel<true, G><<<dim3(nrows), dim3(128 * G), 0, st>>>(part_o, part_ml, nparts, nrows, o, bump); \
-    else combine_kernel<false, G><<<dim3(nrows), dim3(128 * G), 0, st>>>(part_o, part_ml, nparts, nrows, o, bump);     \
-  } while (0)
+  const int kind = out_kind(c->format, c->out_type);
+#define BD_COMBINE(G) combine_kernel<G><<<dim3(nrows), dim3(128 * G), 0, st>>>(part_o, part_ml, nparts, nrows, out, kind, bump)
   if (nparts <= kCombineBatch) BD_COMBINE(1);
   else if (nparts <= 2 * kCombineBatch) BD_COMBINE(2);
   else if (nparts <= 4 * kCombineBatch) BD_COMBINE(4);

@@ -41,7 +41,8 @@ struct GrpArgs {
   int new_slot;            // its residual slot (res_len - 1), or -1 when the residual buffers are complete
   float* part_o;    // [nparts][B][Hq][128]
   float* part_ml;   // [nparts][B][Hq][2]
-  uint16_t* out;    // one split only: the output [B][Hq][128] (fp16), written instead of the partials; else nullptr
+  void* out;    // one split only: the output [B][Hq][128], written instead of the partials; else nullptr
+  int out_kind;     // element type of `out` (kOutF16 / kOutBf16 / kOutF32)
   int n_q_heads, n_kv_heads, gq;
   int nb, nbcap, res_len, num_splits;
   float scale_log2;
@@ -535,7 +536,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + hkv * a.gq + head0 + h;
       float2 o = {o0 + Z, o1 + Z};
       if (a.out) {   // one split: row == the output row
-        store_final_pair(a.out + row * kD + c0, 0, o.x, o.y, L);
+        store_final_pair(a.out, row * kD + c0, a.out_kind, o.x, o.y, L);
       } else {
         *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
         if (lane == 0) {
@@ -579,7 +580,8 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
   a.k_new = (const uint16_t*)k_new;
   a.v_new = (const uint16_t*)v_new;
   a.new_slot = k_new ? res_len - 1 : -1;
-  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
+  a.out = num_splits == 1 ? out : nullptr;
+  a.out_kind = out_kind(c->format, c->out_type);
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;
@@ -611,7 +613,8 @@ hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float
   a.k_new = (const uint16_t*)k_new;   // non-null: the step's token, which this launch appends itself
   a.v_new = (const uint16_t*)v_new;
   a.new_slot = -1;
-  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
+  a.out = num_splits == 1 ? out : nullptr;
+  a.out_kind = out_kind(c->format, c->out_type);
   a.k_codes = (const uint32_t*)c->k_codes;
   a.v_codes = (const uint32_t*)c->v_codes;
   a.k_params = (const uint32_t*)c->k_params;

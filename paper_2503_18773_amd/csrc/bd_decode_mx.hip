@@ -37,7 +37,8 @@ struct MxArgs {
   const uint16_t* q;
   float* part_o;
   float* part_ml;
-  uint16_t* out;   // one split only: the output [B][Hq][128] (bf16), written instead of the partials; else nullptr
+  void* out;   // one split only: the output [B][Hq][128], written instead of the partials; else nullptr
+  int out_kind;     // element type of `out` (kOutF16 / kOutBf16 / kOutF32)
   int n_q_heads, n_kv_heads, gq;
   int length;      // tokens in the cache
   int capacity;
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + head0 + h;
       if (a.out) {   // one split: row == the output row
-        store_final_pair(a.out + row * kD + c0, 1, o0, o1, L);
+        store_final_pair(a.out, row * kD + c0, a.out_kind, o0, o1, L);
       } else {
         float2 o = {o0, o1};
         *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
@@ -611,7 +612,7 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
       }
       const size_t row = ((size_t)split * gridDim.z + b) * a.n_q_heads + head0 + h;
       if (a.out) {   // one split: row == the output row
-        store_final_pair(a.out + row * kD + c0, 1, o0, o1, L);
+        store_final_pair(a.out, row * kD + c0, a.out_kind, o0, o1, L);
       } else {
         float2 o = {o0, o1};
         *reinterpret_cast<float2*>(a.part_o + row * kD + c0) = o;
@@ -644,7 +645,8 @@ hipError_t launch_decode_mx(const bd_cache* c, const void* q, int length, float 
   MxArgs a{};
   a.k_new = (const uint16_t*)k_new;
   a.v_new = (const uint16_t*)v_new;
-  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
+  a.out = num_splits == 1 ? out : nullptr;
+  a.out_kind = out_kind(c->format, c->out_type);
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;
   a.k_scales = (const uint8_t*)c->k_params;
@@ -668,7 +670,8 @@ hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float 
   MxArgs a{};
   a.k_new = (const uint16_t*)k_new;
   a.v_new = (const uint16_t*)v_new;
-  a.out = num_splits == 1 ? (uint16_t*)out : nullptr;
+  a.out = num_splits == 1 ? out : nullptr;
+  a.out_kind = out_kind(c->format, c->out_type);
   a.step = step ? 1 : 0;
   a.k_codes = (const uint8_t*)c->k_codes;
   a.v_codes = (const uint8_t*)c->v_codes;

@@ -58,23 +58,29 @@ __device__ __forceinline__ float head_max(float x) {
   return x;
 }
 
+// Element type of the output rows: the format's own half type (fp16; bf16 for MXFP4) or fp32
+// (bd_cache.out_type).
+constexpr int kOutF16 = 0, kOutBf16 = 1, kOutF32 = 2;
+__host__ __device__ __forceinline__ int out_kind(int format, int out_type) {
+  return out_type == BD_OUT_F32 ? kOutF32 : format == BD_FMT_MXFP4 ? kOutBf16 : kOutF16;
+}
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
 // A launch with one split needs no merge: the workgroup's (L, o) is the result, stored as two
-// adjacent fp16 / bf16 outputs o / L exactly as the merge kernel would compute them (a head that
-// attended nothing, L == 0, gives zeros).
-__device__ __forceinline__ void store_final_pair(uint16_t* out, int bf16, float o0, float o1, float L) {
+// adjacent outputs o / L at elements idx, idx + 1 of `out`, exactly as the merge kernel would
+// compute them (a head that attended nothing, L == 0, gives zeros).
+__device__ __forceinline__ void store_final_pair(void* out, size_t idx, int kind, float o0, float o1, float L) {
   const float r0 = L > 0.f ? o0 / L : 0.f, r1 = L > 0.f ? o1 / L : 0.f;
-  uint32_t lo, hi;
-  if (bf16) {
-    uint32_t u0 = __float_as_uint(r0), u1 = __float_as_uint(r1);
-    u0 += 0x7FFFu + ((u0 >> 16) & 1u);
-    u1 += 0x7FFFu + ((u1 >> 16) & 1u);
-    lo = u0 >> 16;
-    hi = u1 >> 16;
-  } else {
-    lo = f2h(r0);
-    hi = f2h(r1);
+  if (kind == kOutF32) {
+    *reinterpret_cast<float2*>(reinterpret_cast<float*>(out) + idx) = make_float2(r0, r1);
+    return;
   }
-  *reinterpret_cast<uint32_t*>(out) = lo | (hi << 16);
+  const uint32_t lo = kind == kOutBf16 ? f2bf(r0) : f2h(r0), hi = kind == kOutBf16 ? f2bf(r1) : f2h(r1);
+  *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(out) + idx) = lo | (hi << 16);
 }
 
 __device__ __forceinline__ void wave_sync() {

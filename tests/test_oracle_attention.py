@@ -122,22 +122,3 @@ def test_online_softmax_recurrence_equals_two_pass():
         Lsum = sum(p[1] * math.exp(p[0] - M) for p in parts)
         out = sum(p[2] * math.exp(p[0] - M) for p in parts) / Lsum
         assert np.allclose(out, ref, rtol=1e-12, atol=1e-14)
-
-
-def test_rounding_noise_scale_is_the_weighted_row_maximum():
-    """The tolerance yardstick against its definition on a case small enough to do by hand: uniform
-    weights over n tokens whose largest |value| is v give v / sqrt(n); one token holding all the
-    weight gives that token's largest |value|."""
-    class Plain:   # a cache that holds K, V as they are
-        H = 1
-        def __init__(self, K, V): self.K, self.V = K, V
-        def dequant(self, b, h): return self.K, self.V
-    n, D = 16, 128
-    V = np.zeros((n, D)); V[:, 5] = -3.0; V[:, 7] = 2.0
-    flat = O.rounding_noise_scale(Plain(np.zeros((n, D)), V), np.ones((1, 1, D)), 1.0)
-    assert flat.shape == (1, 1) and abs(flat[0, 0] - 3.0 / np.sqrt(n)) < 1e-12
-    K = np.zeros((n, D)); K[3, 0] = 100.0
-    V[3, 9] = 11.0
-    q = np.zeros((1, 1, D)); q[0, 0, 0] = 1.0
-    peaked = O.rounding_noise_scale(Plain(K, V), q, 1.0)
-    assert abs(peaked[0, 0] - 11.0) < 1e-9
