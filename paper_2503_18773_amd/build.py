@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["bd_api.hip", "bd_quant.hip", "bd_decode.hip", "bd_decode_mx.hip", "bd_decode_grp.hip"]
+SOURCES = ["bd_api.hip", "bd_quant.hip", "bd_decode.hip", "bd_decode_mx.hip", "bd_decode_grp.hip", "bd_decode_coop.hip"]
 LIB = os.path.join(HERE, "libbitdecode.so")
 
 FLAGS = [
@@ -18,7 +18,7 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, jobs: int = 4) -> str:
+def build(verbose: bool = False, jobs: int = 6) -> str:
     """Compile every source and link the shared library; returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")

@@ -868,6 +868,8 @@ void launch_instance(int format, int gq, bool single, bool paged, const DecodeAr
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
                              void* out, hipStream_t st) {
+  if (decode_coop_takes(c))
+    return launch_decode_coop(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st);
   DecodeArgs a;
   a.out = num_splits == 1 ? out : nullptr;
   a.out_kind = out_kind(c->format, c->out_type);
