@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["bd_api.hip", "bd_quant.hip", "bd_decode.hip", "bd_decode_mx.hip", "bd_decode_grp.hip", "bd_decode_coop.hip"]
+SOURCES = ["bd_api.hip", "bd_quant.hip", "bd_decode.hip", "bd_decode_mx.hip", "bd_decode_grp.hip"]
 LIB = os.path.join(HERE, "libbitdecode.so")
 
 FLAGS = [

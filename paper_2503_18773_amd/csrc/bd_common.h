@@ -62,12 +62,6 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,
                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
                              const void* k_new, const void* v_new, void* out, hipStream_t st);
-// the cooperative kernel (four waves per block): int4 / int2 with channel-wise K, up to 4 query heads per
-// KV head, contiguous cache; launch_decode_int hands such calls to it
-bool decode_coop_takes(const bd_cache* c);
-hipError_t launch_decode_coop(const bd_cache* c, const void* q, int packed_len, int res_len,
-                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
-                              const void* k_new, const void* v_new, void* out, hipStream_t st);
 // formats with a quantization group of 64 or 32 (k_new / v_new as in launch_decode_int)
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,

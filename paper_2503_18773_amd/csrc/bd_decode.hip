@@ -42,6 +42,13 @@
 //     is left outside the MFMAs is sum_t P_t (z_t + s_t c_t), at most half a quantization step
 //     per token.
 //
+// Range.  The fp16 operands are kept clear of overflow and of the subnormals whatever the magnitudes
+// of Q, K and V are: every head's queries are scaled by a power of two to below 2^7 before they meet the
+// K scales (a column of the B operand may carry any factor; it comes out of that column's scores), so
+// |Q'| < 2^15 with the block's K scales normalised likewise; and the per-token V scale is folded into the exponent of the softmax,
+// P'_t = 2^(S_t + log2 scale_t - m) with m the running maximum of S + log2 scale, so P' <= 1 with the
+// largest term at 1, while the weights proper are P'_t / scale_t in fp32.
+//
 // The fp16 residual tail (Sec. IV-B) is shared out evenly over the workgroups of a
 // (sequence, KV head): each takes a slice of the <= 127 residual tokens, scores them with
 // plain dot products and folds them into its partial in the final merge, so no workgroup
@@ -96,10 +103,10 @@ struct WaveLds {
   // multiple of 256 bytes apart would all fall on the same LDS banks)
   uint16_t qhi[GQP][kD + 8];   // Q' per head, high fp16 piece, in B-operand slot order
   uint16_t qlo[GQP][kD + 8];   // low piece
-  float2 vpar[kParSlots];  // per V token of the block: (scale * position factor, zero + scale * centre code)
+  float4 vpar[kParSlots];  // per V token of the block: (log2 scale, 1 / scale, value of the centre code / scale, -)
   float2 kpar[kParSlots];  // per-token K only: (scale * 2^24, zero) of the block's tokens
   uint16_t c16[kBlock];    // per V token: centre code * position factor, in the A-operand order of P'
-  float zq[GQP];           // per head: sum_c Q_c z_c * scale_log2 * 2^-24
+  float zq[GQP];           // per head: sum_c Q_c z_c * 2^-24 (Q as normalised below)
 };
 template <int GQP>
 struct MergeLds {
@@ -108,6 +115,22 @@ struct MergeLds {
 };
 
 constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
+
+// 2^e for e in [-126, 127]
+__device__ __forceinline__ float pow2i(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }
+// the power of two that brings fp16 magnitudes up to `bits` (the largest one's bit pattern) below 2^top
+__device__ __forceinline__ int norm_exponent(uint32_t bits, int top) { return top + 14 - (int)(bits >> 10); }
+// Q' = q * scale * position factor goes to the matrix unit as an fp16 high + low pair: queries are brought
+// below 2^7 and a block's K scales below 2^8, so |Q'| < 2^15 (finite) and the low pieces of all but
+// negligible entries stay above the subnormals.
+constexpr int kQTop = 7, kSTop = 8;
+__device__ __forceinline__ uint32_t row_max16_u(uint32_t m) {
+  m = max(m, dpp_u<kQuadSwap1>(m));
+  m = max(m, dpp_u<kQuadSwap2>(m));
+  m = max(m, dpp_u<kRowHalfMirror>(m));
+  m = max(m, dpp_u<kRowMirror>(m));
+  return m;
+}
 
 // GQP: the query group padded to 4, 8 or 16 heads; the 16 MFMA columns carry it 16/GQP times
 //      (column c holds head c % GQP, "column group" c / GQP) and the softmax work of a block
@@ -139,7 +162,8 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 
   __shared__ __attribute__((aligned(16))) unsigned char smem_raw[cmax(sizeof(ML), kWaves * sizeof(WL))];
   __shared__ float res_s[kBlock][GQP];       // scores of this workgroup's residual tokens, per head
-  __shared__ __attribute__((aligned(16))) float q_s[HP > 1 ? GQP : 1][kD];   // larger groups: queries * softmax_scale * log2(e); padding heads zero
+  __shared__ __attribute__((aligned(16))) float q_s[HP > 1 ? GQP : 1][kD];   // larger groups: queries, normalised; padding heads zero
+  __shared__ int kq_s[HP > 1 ? GQP : 1];                                     // larger groups: each head's normalising exponent
 
   const int split = blockIdx.x, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -349,9 +373,15 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   if constexpr (HP > 1) {
 #pragma unroll
     for (int p = 0; p < HP; ++p) {
-      const int h = 4 * p + (tid >> 6);
-      float2 qq = {h2f((uint16_t)(qld[p] & 0xFFFFu)) * a.scale_log2, h2f((uint16_t)(qld[p] >> 16)) * a.scale_log2};
+      const int h = 4 * p + (tid >> 6);   // this wave holds all 128 channels of head h
+      uint32_t qb = row_max16_u(max(qld[p] & 0x7FFFu, (qld[p] >> 16) & 0x7FFFu));
+      qb = max(max(__builtin_amdgcn_readlane(qb, 0), __builtin_amdgcn_readlane(qb, 16)),
+               max(__builtin_amdgcn_readlane(qb, 32), __builtin_amdgcn_readlane(qb, 48)));
+      const int kqh = norm_exponent(qb, kQTop);
+      const float f = pow2i(kqh);
+      float2 qq = {h2f((uint16_t)(qld[p] & 0xFFFFu)) * f, h2f((uint16_t)(qld[p] >> 16)) * f};
       *reinterpret_cast<float2*>(&q_s[h][2 * lane]) = qq;
+      if (lane == 0) kq_s[h] = kqh;
     }
     __syncthreads();
   }
@@ -374,12 +404,30 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   // tokens whose softmax this lane runs: for its o-th owned k-step j = cg * OWN + o, the low
   // (lh = 0) and high (lh = 1) fp16 halves of the P' registers come from tiles tile_lo / tile_hi
   // of half j / 2; token = 32 g + 4 tile + row
+  // Every head's queries times the power of two that brings the largest below 1 (kq); the factor comes
+  // back out of the scores, together with softmax_scale * log2(e) and the 2^24 of the subnormal codes (kS).
   float qv[2][4];
+  int kq_head = 0;   // of the head this lane's column carries
+  if constexpr (HP == 1) {
+    uint32_t qb = 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    qv[0][i] = h2f((uint16_t)((qraw0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
-    qv[1][i] = h2f((uint16_t)((qraw1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * a.scale_log2;
+    for (int i = 0; i < 2; ++i)
+      qb = max(max(qb, max(qraw0[i] & 0x7FFFu, (qraw0[i] >> 16) & 0x7FFFu)), max(qraw1[i] & 0x7FFFu, (qraw1[i] >> 16) & 0x7FFFu));
+    qb = row_max16_u(qb);   // largest |q| of head lane / 16
+    const float f = pow2i(norm_exponent(qb, kQTop));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      qv[0][i] = h2f((uint16_t)((qraw0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * f;
+      qv[1][i] = h2f((uint16_t)((qraw1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * f;
+    }
+    const int k0 = norm_exponent(__builtin_amdgcn_readlane(qb, 0), kQTop), k1 = norm_exponent(__builtin_amdgcn_readlane(qb, 16), kQTop);
+    const int k2 = norm_exponent(__builtin_amdgcn_readlane(qb, 32), kQTop), k3 = norm_exponent(__builtin_amdgcn_readlane(qb, 48), kQTop);
+    kq_head = head == 0 ? k0 : head == 1 ? k1 : head == 2 ? k2 : k3;
+  } else {
+    kq_head = kq_s[head];
   }
+  const float kS = a.scale_log2 * pow2i((KT ? 0 : 24) - kq_head);   // what the kept scores still have to be multiplied by
+  const float kZ = a.scale_log2 * pow2i(-kq_head);                  // ... and the zero term sum_c Q_c z_c
   int tb[OWN][2];
 #pragma unroll
   for (int o = 0; o < OWN; ++o) {
@@ -395,7 +443,19 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   // Q' = Q * s_c as an fp16 high + low pair in B-operand order, and the zero term sum_c Q_c z_c, per
   // head: once per block for channel-wise K (with the block's parameters), once per kernel for
   // per-token K.  16 lanes per head (slot group lane % 16: two runs of 4 consecutive channels).
-  auto prep_queries = [&]() {
+  // Channel-wise K: the block's scales are first brought below 1 by a power of two (2^-ek, from the largest
+  // of the block), so that with |q| < 1 the products neither overflow nor sink into the fp16 subnormals;
+  // the factor comes back out of the scores with kS.  Returns ek.
+  auto prep_queries = [&]() -> int {
+    int ek = 0;
+    float nrm = 1.0f;
+    if constexpr (!KT) {
+      uint32_t sb = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sb = max(sb, max(kp0[i] & 0xFFFFu, kp1[i] & 0xFFFFu));
+      ek = -norm_exponent(row_max16_u(sb), kSTop);   // scale * 2^-ek < 2^kSTop for every channel of the block
+      nrm = pow2i(-ek);
+    }
 #pragma unroll
     for (int p = 0; p < HP; ++p) {
       const int ph = 4 * p + (lane >> 4);
@@ -417,7 +477,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
           float s = 1.0f, z = 1.0f;   // per-token K: Q' = Q, and the "zero term" is sum_c Q_c
           if constexpr (!KT) {
             const uint32_t pr = run ? kp1[i] : kp0[i];
-            s = h2f((uint16_t)(pr & 0xFFFFu));
+            s = h2f((uint16_t)(pr & 0xFFFFu)) * nrm;
             z = h2f((uint16_t)(pr >> 16));
           }
           const float t = qc * s * F::un(i);
@@ -435,8 +495,9 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       }
       *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
       *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
-      if (prep_sg == 0) wl.zq[ph] = KT ? zsum : zsum * kTwoM24;
+      if (prep_sg == 0) wl.zq[ph] = zsum;
     }
+    return ek;
   };
   // Groups of up to 8 heads: the high piece of Q' goes to the even column groups and the low piece to
   // the odd ones, so one MFMA per k-step produces both partial products (added across the column
@@ -453,7 +514,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   };
   float zq = 0.0f, qsum = 0.0f;
   if constexpr (KT) {
-    prep_queries();
+    (void)prep_queries();
     wave_sync();
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -480,7 +541,8 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       else __builtin_amdgcn_s_setprio(0);
       ++done;
     }
-    if constexpr (!KT) prep_queries();
+    float kSb = kS;   // kS for this block's K exponent
+    if constexpr (!KT) kSb = kS * pow2i(prep_queries());
     if constexpr (KT) {   // K parameters of the block's 128 tokens
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -494,8 +556,10 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       const float sv = h2f((uint16_t)(vp2[u] & 0xFFFFu)), zv = h2f((uint16_t)(vp2[u] >> 16));
       const int t = 2 * lane + u;
       const int r = t & 3;                // row of the token inside its S^T tile
-      const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
-      wl.vpar[par_slot(t)] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+      // (a token whose values are all equal has scale 0 and all-zero codes: any scale does, take 1)
+      const float se = sv > 0.0f ? sv : 1.0f, rs = __builtin_amdgcn_rcpf(se);
+      const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * rs, 0.0f), F::kQmax)) : 0.0f;
+      wl.vpar[par_slot(t)] = make_float4(__builtin_amdgcn_logf(se), rs, __builtin_fmaf(ct, sv, zv) * rs, 0.0f);
       wl.c16[F::p_slot(t)] = (uint16_t)(ct * F::inv_un(r));
     }
     wave_sync();
@@ -582,8 +646,15 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
             sc[o][lh][r] = __builtin_fmaf(sc[o][lh][r], kq.x, kq.y * qsum);
           }
     }
-    constexpr float kS = KT ? 1.0f : kTwo24;   // what the kept values still have to be multiplied by
-    // ---- online softmax (Alg. 1) over this lane's 8 * OWN tokens of head `head`
+    // ---- online softmax (Alg. 1) over this lane's 8 * OWN tokens of head `head`, on S + log2 of the
+    //      token's V scale (see "Range" at the top): av = score in log2 units, but for the block's zero term
+#pragma unroll
+    for (int o = 0; o < OWN; ++o)
+#pragma unroll
+      for (int lh = 0; lh < 2; ++lh)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          sc[o][lh][r] = __builtin_fmaf(sc[o][lh][r], kSb, wl.vpar[par_slot(tb[o][lh]) + r].x);
     float bmax = sc[0][0][0];
 #pragma unroll
     for (int o = 0; o < OWN; ++o)
@@ -592,9 +663,10 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) bmax = fmaxf(bmax, sc[o][lh][r]);
     bmax = head_max<COPIES>(bmax);
-    // channel-wise K: every score of the head still lacks the block's zero term zq (times kS)
-    const float m_new = fmaxf(m_run, (bmax + zq) * kS);
-    const float zoff = __builtin_fmaf(zq, kS, -m_new);
+    // channel-wise K: every score of the head still lacks the block's zero term
+    const float zqs = zq * kZ;
+    const float m_new = fmaxf(m_run, bmax + zqs);
+    const float zoff = zqs - m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
     l_run *= alpha;
@@ -610,12 +682,12 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       for (int half = 0; half < 2; ++half)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][half][r], kS, zoff));
-          const float2 par = wl.vpar[par_slot(tb[0][half]) + r];
-          l_run += p;
-          z_run = __builtin_fmaf(p, par.y, z_run);
+          const float e = __builtin_amdgcn_exp2f(sc[0][half][r] + zoff);   // P' = weight * V scale, <= 1
+          const float4& par = wl.vpar[par_slot(tb[0][half]) + r];
+          l_run = __builtin_fmaf(e, par.y, l_run);
+          z_run = __builtin_fmaf(e, par.z, z_run);
           // gather the column groups' fp16 values into the B-operand register pairs
-          const uint32_t x = (uint32_t)f2h(p * par.x);
+          const uint32_t x = (uint32_t)f2h(e * F::un(r));
           const uint32_t pr = x | dpp_u<F::kPairShift>(x << 16);
           pb[2 * half][r] = pr;
           pb[2 * half + 1][r] = dpp_u<F::kStepShift>(pr);
@@ -629,11 +701,11 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
           uint32_t hv[2];
 #pragma unroll
           for (int lh = 0; lh < 2; ++lh) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[o][lh][r], kS, zoff));
-            const float2 par = wl.vpar[par_slot(tb[o][lh]) + r];
-            l_run += p;
-            z_run = __builtin_fmaf(p, par.y, z_run);
-            hv[lh] = (uint32_t)f2h(p * par.x);
+            const float e = __builtin_amdgcn_exp2f(sc[o][lh][r] + zoff);
+            const float4& par = wl.vpar[par_slot(tb[o][lh]) + r];
+            l_run = __builtin_fmaf(e, par.y, l_run);
+            z_run = __builtin_fmaf(e, par.z, z_run);
+            hv[lh] = (uint32_t)f2h(e * F::un(r));
           }
           pair[o][r] = hv[0] | (hv[1] << 16);
         }
@@ -669,6 +741,13 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     if (has_next) {
 #pragma unroll
       for (int T = 0; T < 8; ++T) issue_ktile(nbi, T);
+    }
+    // Both sums grow with the number of tokens, their difference (the signal) with its square root: every
+    // 16 blocks the centre sum is taken out of the accumulators and starts again from zero.
+    if (!SINGLE && (done & 15) == 0) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] -= xacc[0];
+      xacc = (f4_t){0.f, 0.f, 0.f, 0.f};
     }
     wave_sync();   // the next block's prep overwrites this wave's LDS scratch
     first = false;
@@ -868,8 +947,6 @@ void launch_instance(int format, int gq, bool single, bool paged, const DecodeAr
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
                              void* out, hipStream_t st) {
-  if (decode_coop_takes(c))
-    return launch_decode_coop(c, q, packed_len, res_len, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st);
   DecodeArgs a;
   a.out = num_splits == 1 ? out : nullptr;
   a.out_kind = out_kind(c->format, c->out_type);

@@ -25,11 +25,6 @@ struct Fmt<4> {
   __device__ static int run_base(int sg, int run) { return 8 * sg + 4 * run; }
   __device__ static constexpr float un(int v) { return (v & 1) ? (1.0f / 16.0f) : 1.0f; }
   __device__ static constexpr float inv_un(int v) { return (v & 1) ? 16.0f : 1.0f; }
-  // operand entry e (0..7) of k-step j of a 32-token (or 32-channel) group: which of the group's
-  // codes it is (VGPR e / 2 holds nibbles e / 2 and e / 2 + 4 of word j), and its position factor
-  __device__ static constexpr int tok_of_entry(int j, int e) { return 8 * j + (e >> 1) + 4 * (e & 1); }
-  __device__ static constexpr float un_entry(int e) { return un(e >> 1); }
-  __device__ static constexpr float inv_un_entry(int e) { return inv_un(e >> 1); }
   // k-step j = 2*half + jj of the second product contracts the tokens of two S^T tiles of that
   // half: tile_lo(jj) fills the low fp16 half of the P' registers, tile_hi(jj) the high one
   __device__ static constexpr int tile_lo(int jj) { return 2 * jj; }
@@ -65,10 +60,6 @@ struct Fmt<2> {
   __device__ static int run_base(int sg, int run) { return 16 * (sg >> 1) + 4 * (sg & 1) + 8 * run; }
   __device__ static constexpr float un(int v) { return 1.0f / (float)(1 << (2 * v)); }
   __device__ static constexpr float inv_un(int v) { return (float)(1 << (2 * v)); }
-  // operand entry e of k-step j: crumb e / 2 + 4 (j % 2) + 8 (e % 2) of word j / 2
-  __device__ static constexpr int tok_of_entry(int j, int e) { return 16 * (j >> 1) + 4 * (j & 1) + (e >> 1) + 8 * (e & 1); }
-  __device__ static constexpr float un_entry(int e) { return un(e >> 1); }
-  __device__ static constexpr float inv_un_entry(int e) { return inv_un(e >> 1); }
   __device__ static constexpr int tile_lo(int jj) { return jj; }
   __device__ static constexpr int tile_hi(int jj) { return jj + 2; }
   static constexpr int kPairShift = kRowShl8, kStepShift = kRowShl4;

@@ -957,6 +957,37 @@ def test_paged_step_replays_from_one_captured_graph(fmt):
         _assert_paged_equal(oc, gc, "after replays")
 
 
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int2_kt"])
+@pytest.mark.parametrize("gq", [4, 8, 16])
+def test_outputs_do_not_depend_on_the_magnitude_of_k_and_v(fmt, gq):
+    """K, V (and Q, inversely, so that the logits stay those of the unit-variance case) scaled by 2^-10 and
+    2^10: the fp16 operands of the matrix unit are normalised inside the kernel, so the relative error stays
+    where it is at unit scale (the same 1e-3 relative L2; the max-abs bar scales with the outputs)."""
+    import torch
+    w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=gq * 2, n_kv_heads=2, context=128 * 33 + 70, fmt=fmt, seed=77)
+    K0, V0 = W.make_kv(w)
+    q0 = W.make_q(w)
+    for ks, vs in [(2.0 ** -10, 2.0 ** -10), (2.0 ** 10, 2.0 ** -10), (2.0 ** -10, 2.0 ** 10), (1.0, 2.0 ** -14), (2.0 ** 10, 2.0 ** 10)]:
+        K = (K0.astype(np.float32) * np.float32(min(ks, 2.0 ** 10 / 10))).astype(np.float16)   # (x10 outlier channels: keep fp16 finite)
+        V = (V0.astype(np.float32) * np.float32(min(vs, 2.0 ** 10 / 10))).astype(np.float16)
+        q = (q0.astype(np.float32) / np.float32(min(ks, 2.0 ** 10 / 10))).astype(np.float16)
+        oc = O.IntCache(w.batch, w.n_kv_heads, BITS[fmt], 128 * 35, k_per_token=fmt.endswith("_kt"))
+        oc.quant_pack_kv(K, V)
+        gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, 128 * 35)
+        gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+        _assert_int_cache_equal(oc, gc)
+        ref = O.decode_attn(oc, q, W.softmax_scale(w))
+        gc.desc.out_type = B.BD_OUT_F32          # (fp16 output rows would underflow at the small scales)
+        for ns in (1, 5):
+            out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float32, device="cuda:0")
+            gc.decode_attn(to_dev(q, "fp16"), W.softmax_scale(w), out, num_splits=ns)
+            torch.cuda.synchronize()
+            got = out_to_f64(out)
+            rl = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+            ma = np.abs(got - ref).max() / np.abs(ref).max()
+            assert rl <= 1e-3 and ma <= 2e-3, f"{fmt} gq={gq} K x {ks} V x {vs} splits {ns}: rel-L2 {rl:.2e}, max-abs / max |ref| {ma:.2e}"
+
+
 @pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64", "mxfp4"])
 def test_peaked_and_flat_attention(fmt):
     """Queries scaled by 6 (logits of several tens: a handful of tokens take all the weight and the
