@@ -63,6 +63,115 @@ def measured_traffic(w, variant: str):
     return None
 
 
+def _oracle_worker(job):
+    """One host process of the cpu_baseline leg: the oracle's decode steps (append + attention) on one
+    (sequence, KV head) unit for at least `seconds`; returns (steps, algorithmic bytes, seconds)."""
+    from threadpoolctl import threadpool_limits
+    from oracle import bitdecode_oracle as O
+    from paper_2503_18773_amd import workloads as W
+    w, unit, K1, V1, cap, seconds, sm_scale = job
+    per_tok = PER_TOKEN_BYTES[w.fmt]
+    with threadpool_limits(limits=1):
+        if w.fmt == "mxfp4":
+            oc = O.MxCache(1, 1, cap)
+        else:
+            oc = O.IntCache(1, 1, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token=w.fmt.endswith("_kt"),
+                            group=64 if w.fmt.endswith("_g64") else 32 if w.fmt.endswith("_g32") else 128)
+        oc.quant_pack_kv(K1, V1)          # untimed: prefill
+        b, h = divmod(unit, w.n_kv_heads)
+        new = [(W.make_new_kv(w, s), W.make_q(w, s)) for s in range(4)]   # drawn before the clock starts
+        nsteps, nbytes = 0, 0
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            (kn, vn), q = new[nsteps % 4]
+            oc.append_kv(kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+            O.decode_attn(oc, q[b:b + 1, h * w.g_q:(h + 1) * w.g_q], sm_scale)
+            nsteps += 1
+            plen = getattr(oc, "packed_len", getattr(oc, "length", 0))
+            nbytes += plen * per_tok + getattr(oc, "res_len", 0) * 512 + 2 * w.g_q * 256
+        return nsteps, nbytes, time.perf_counter() - t0
+
+
+def oracle_baseline(w, K, V, cap, seconds, sm_scale):
+    """The oracle as it stands on the host cores: one process per (sequence, KV head) unit, up to 16."""
+    import multiprocessing as mp
+    units = list(range(min(16, w.batch * w.n_kv_heads, os.cpu_count() or 1)))
+    jobs = []
+    for u in units:
+        b, h = divmod(u, w.n_kv_heads)
+        jobs.append((w, u, np.ascontiguousarray(K[b:b + 1, h:h + 1]), np.ascontiguousarray(V[b:b + 1, h:h + 1]), cap,
+                     seconds, sm_scale))
+    with mp.get_context("spawn").Pool(len(jobs)) as pool:
+        res = pool.map(_oracle_worker, jobs, chunksize=1)
+    steps = sum(r[0] for r in res)
+    wall = max(r[2] for r in res)
+    return {"value": round(sum(r[1] for r in res) / wall / 1e9, 4), "unit": "GB/s", "cores": len(jobs), "kind": "oracle",
+            "seconds": round(wall, 2),
+            "sample": f"{steps} decode steps (append + attention) in all, on {len(jobs)} of the "
+                      f"{w.batch * w.n_kv_heads} (sequence, KV head) units of one layer at context {w.context}, one "
+                      f"single-threaded process per unit (numpy float64)"}
+
+
+def kernel_roofline(B, W, torch, w, caches, qs_last, outs, splits, paged, sm_scale, variant, total_steps):
+    """Roofline of the dominant kernel (decode attention), measured live with HIP events on the stream the
+    kernels run on: one event pair around the bd_decode_attn launches (partials only, no combine) of all
+    layers, enqueued back to back; the kernels run without gaps, so elapsed / launches is the average
+    launch duration (cold caches: each layer has its own).  Also the streaming-read floor over the same
+    caches (bd_probe_stream_read: the same loads, no arithmetic), measured the same way."""
+    stream = torch.cuda.current_stream()
+    mx = w.fmt == "mxfp4"
+    c0 = caches[0]
+    reps = 5
+
+    def timed(launch):
+        per_rep = []
+        for rep_ in range(reps + 1):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for li, c in enumerate(caches):
+                launch(li, c)
+            b.record(stream)
+            torch.cuda.synchronize()
+            if rep_:
+                per_rep.append(a.elapsed_time(b) * 1e3 / len(caches))
+        return per_rep
+
+    def decode(li, c):
+        if paged:   # this entry point always merges: the figure includes the combine kernel
+            c.decode_attn(qs_last, sm_scale, outs[li], splits)
+        else:
+            B.bd_decode_attn(c.desc, qs_last, c.packed_len, c.res_len, sm_scale, splits, c.workspace(splits), None)
+
+    per_rep = timed(decode)
+    kernel_us = float(np.mean(per_rep))
+    if paged:
+        n = w.context + total_steps
+        pl, rl = (n, 0) if mx else (n - n % 128, n % 128)
+    else:
+        pl, rl = c0.packed_len, c0.res_len
+    launch_bytes = algorithmic_bytes(w, pl, rl)
+    achieved = launch_bytes / (kernel_us * 1e-6) / 1e9
+    kernel_name = "decode_mx_kernel" if mx else "decode_grp_kernel" if "_g" in w.fmt else "decode_int_kernel"
+    roofline = {"bound": "hbm", "kernel": kernel_name,
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(w, variant),
+                "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(np.min(per_rep)), 3),
+                "bytes_per_launch": launch_bytes, "num_splits": splits,
+                "timing": f"hip events around {len(caches)} back-to-back launches (one per cold layer cache), "
+                          f"{reps} repetitions" + (" (paged entry point: decode + combine kernels)" if paged else "")}
+    stream_roof = None
+    if not paged and not mx:
+        probe = timed(lambda li, c: B.bd_probe_stream_read(c.desc, c.packed_len))
+        code_bytes = w.batch * w.n_kv_heads * c0.packed_len * 128 * (4 if w.fmt.startswith("int4") else 2) // 8 * 2
+        us = float(np.mean(probe))
+        stream_roof = {"avg_launch_us": round(us, 3), "min_launch_us": round(float(np.min(probe)), 3),
+                       "bytes_per_launch": code_bytes, "GB/s": round(code_bytes / us / 1e3, 1),
+                       "frac_of_peak": round(code_bytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                       "what": "bd_probe_stream_read: the packed K and V codes of the same caches read with the decode "
+                               "kernel's loads and nothing else; same timing as the roofline (context, not a target)"}
+    return roofline, stream_roof
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +190,7 @@ def main() -> int:
                          "(step, packed_len, res_len, microseconds) to FILE; steps that fill the residual block show "
                          "as spikes (they run the quantize kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-128k", action="store_true", help="cfg1 only: skip the second measurement at 128K (cfg3)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="lower bound on the oracle's timed CPU work")
     ap.add_argument("--calib-copy", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
@@ -104,13 +214,33 @@ def main() -> int:
         print(json.dumps({"calib_copy_bytes": 1 << 30, "launches": 5}))
         return 0
     B.lib()  # fail loudly if the HIP library is missing
-    w = W.CONFIGS[args.workload]
+    rec = run(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    if args.workload == "cfg1" and not args.variant and not args.no_128k:
+        # the metric is quoted at 32K and at 128K: the same measurement on cfg3 (fewer steps: each moves 4x the bytes)
+        torch.cuda.empty_cache()
+        r3 = run(args, "cfg3", max(args.steps // 4, 3), min(args.warmup, 2), False)
+        rec["roofline_128k"] = r3["roofline"]
+        rec["stream_roof_128k"] = r3["stream_roof"]
+        rec["step_128k"] = {k: r3[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "us_per_layer_call",
+                                                 "pct_hbm_peak", "prefill_quant_pack_ms_per_layer")}
+        rec["step_128k"]["workload"] = r3["config"]["workload"]
+        rec["step_128k"]["num_splits"] = r3["config"]["num_splits"]
+    print(json.dumps(rec))
+    return 0
+
+
+def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
+    """Everything bench.py measures on one workload; returns the record."""
+    import torch
+    from paper_2503_18773_amd import binding as B
+    from paper_2503_18773_amd import workloads as W
+    w = W.CONFIGS[workload]
     if args.variant in ("kt", "g64", "g32"):
         w = W.scaled(w, fmt=w.fmt + "_" + args.variant)
     elif args.variant in ("gq8", "gq16"):
         w = W.scaled(w, n_q_heads=int(args.variant[2:]) * w.n_kv_heads)
     paged = args.variant == "paged"
-    total_steps = args.warmup + args.steps
+    total_steps = warmup + steps
     cap = ((w.context + total_steps + 1 + 127) // 128) * 128 + 128
     tdt = torch.float16 if w.in_dtype == "fp16" else torch.bfloat16
 
@@ -195,24 +325,24 @@ def main() -> int:
             g_step.replay()
             step_bytes.append(len(caches) * algorithmic_bytes(w, *lengths(w.context + s + 1)))
 
-        for s in range(args.warmup):
+        for s in range(warmup):
             replay_step(s)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for s in range(args.warmup, total_steps):
+        for s in range(warmup, total_steps):
             replay_step(s)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     elif args.mode == "graph":
         g_warm, g_timed = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
-        if args.warmup:
+        if warmup:
             with torch.cuda.graph(g_warm):
-                for s in range(args.warmup):
+                for s in range(warmup):
                     run_step(s)
         with torch.cuda.graph(g_timed):
-            for s in range(args.warmup, total_steps):
+            for s in range(warmup, total_steps):
                 run_step(s)
-        if args.warmup:
+        if warmup:
             g_warm.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -220,12 +350,12 @@ def main() -> int:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     else:
-        for s in range(args.warmup):
+        for s in range(warmup):
             run_step(s)
         torch.cuda.synchronize()
         step_events = []
         t0 = time.perf_counter()
-        for s in range(args.warmup, total_steps):
+        for s in range(warmup, total_steps):
             if args.per_step:
                 ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 ea.record(stream)
@@ -242,76 +372,20 @@ def main() -> int:
                 for s, pl, rl, ea, eb in step_events:
                     f.write(f"{s} {pl} {rl} {ea.elapsed_time(eb) * 1e3:.1f}\n")
     elapsed = t1 - t0
-    timed_bytes = sum(step_bytes[args.warmup:])
-    ms_per_step = elapsed * 1e3 / args.steps
+    timed_bytes = sum(step_bytes[warmup:])
+    ms_per_step = elapsed * 1e3 / steps
     value = timed_bytes / elapsed / 1e9
 
-    # ---- roofline of the dominant kernel (decode attention), measured live with HIP events on
-    # the stream the kernels run on: one event pair around the bd_decode_attn launches (partials
-    # only, no combine) of all layers, enqueued back to back; the kernels run without gaps, so
-    # elapsed / launches is the average launch duration (cold caches: each layer has its own).
-    c0 = caches[0]
-    reps = 5
-    per_rep = []
-    for rep in range(reps + 1):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
-        for li, c in enumerate(caches):
-            if paged:   # this entry point always merges: the figure includes the combine kernel
-                c.decode_attn(qs[-1], sm_scale, outs[li], splits)
-            else:
-                B.bd_decode_attn(c.desc, qs[-1], c.packed_len, c.res_len, sm_scale, splits, c.workspace(splits), None)
-        b.record(stream)
-        torch.cuda.synchronize()
-        if rep:
-            per_rep.append(a.elapsed_time(b) * 1e3 / len(caches))
-    kernel_us = float(np.mean(per_rep))
-    launch_bytes = algorithmic_bytes(w, *(lengths(w.context + total_steps) if paged else (c0.packed_len, c0.res_len)))
-    achieved = launch_bytes / (kernel_us * 1e-6) / 1e9
-    kernel_name = "decode_mx_kernel" if w.fmt == "mxfp4" else "decode_grp_kernel" if "_g" in w.fmt else "decode_int_kernel"
-    roofline = {"bound": "hbm", "kernel": kernel_name,
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(w, args.variant),
-                "avg_launch_us": round(kernel_us, 3), "min_launch_us": round(float(np.min(per_rep)), 3),
-                "bytes_per_launch": launch_bytes,
-                "timing": f"hip events around {len(caches)} back-to-back launches (one per cold layer cache), "
-                          f"{reps} repetitions" + (" (paged entry point: decode + combine kernels)" if paged else "")}
-
+    roofline, stream_roof = kernel_roofline(B, W, torch, w, caches, qs[-1], outs, splits, paged, sm_scale, args.variant,
+                                            total_steps)
+    del caches, outs, new_kv, qs
     # ---- the oracle on the host cores, on a bounded sample of the same workload
-    cpu = None
-    if not args.no_cpu_baseline:
-        from threadpoolctl import threadpool_limits
-        from oracle import bitdecode_oracle as O
-        n_units = min(2, w.batch * w.n_kv_heads)
-        per_tok = PER_TOKEN_BYTES[w.fmt]
-        with threadpool_limits(limits=1):
-            if w.fmt == "mxfp4":
-                oc = O.MxCache(1, n_units, cap)
-            else:
-                oc = O.IntCache(1, n_units, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token=w.fmt.endswith("_kt"),
-                                group=64 if w.fmt.endswith("_g64") else 32 if w.fmt.endswith("_g32") else 128)
-            oc.quant_pack_kv(K[:1, :n_units], V[:1, :n_units])          # untimed: prefill
-            nsteps, sample_bytes = 0, 0
-            tc0 = time.perf_counter()
-            while time.perf_counter() - tc0 < args.cpu_seconds:
-                kn, vn = W.make_new_kv(w, nsteps)
-                q0 = W.make_q(w, nsteps)[:1, :n_units * w.g_q]
-                oc.append_kv(kn[:1, :n_units], vn[:1, :n_units])
-                O.decode_attn(oc, q0, sm_scale)
-                nsteps += 1
-                plen = getattr(oc, "packed_len", getattr(oc, "length", 0))
-                sample_bytes += n_units * (plen * per_tok + getattr(oc, "res_len", 0) * 512) + 2 * n_units * w.g_q * 256
-            tc1 = time.perf_counter()
-        cpu = {"value": round(sample_bytes / (tc1 - tc0) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "seconds": round(tc1 - tc0, 2),
-               "sample": f"{nsteps} decode steps (append + attention) of {n_units} of the "
-                         f"{w.batch * w.n_kv_heads} (sequence, KV head) units of one layer at context {w.context}; "
-                         f"numpy float64, 1 thread (includes drawing the step's inputs)"}
+    cpu = oracle_baseline(w, K, V, cap, args.cpu_seconds, sm_scale) if with_cpu else None
 
     rec = {
         "metric": "effective KV GB/s per decode step (32-layer LLaMA-8B-shape step: append + split-K attention "
                   "over the packed cache)",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"int4": "u4->f16 mfma, f32 accumulate", "int2": "u2->f16 mfma, f32 accumulate",
                   "mxfp4": "e2m1 mfma, f32 accumulate"}[w.fmt.split("_")[0]],
@@ -325,10 +399,10 @@ def main() -> int:
         "prefill_quant_pack_ms_per_layer": round(prefill_ms, 4),
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
+        "stream_roof": stream_roof,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(rec))
-    return 0
+    return rec
 
 
 if __name__ == "__main__":

@@ -182,6 +182,13 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
                          int32_t* packed_len, int32_t* res_len, float softmax_scale,
                          int32_t num_splits, void* workspace, void* out, void* stream);
 
+/* Measurement aid, no part of the method: one launch that reads the packed K and V codes of the first
+ * packed_len tokens of every (sequence, KV head) unit of an integer-format cache, with the loads
+ * bd_decode_attn uses, and computes nothing.  Its duration is the floor the memory system sets for a
+ * decode launch over the same cache (the "KV loading dominates" end of Sec. V-C's breakdown).  `sink`
+ * (device, 4 bytes, may be NULL) is written only for one value of the loaded data's checksum. */
+bd_status bd_probe_stream_read(const bd_cache* c, int32_t packed_len, void* sink, void* stream);
+
 /* Merge the num_splits partials left in `workspace` by bd_decode_attn (log-sum-exp
  * merge: m = max m_s, l = sum l_s 2^(m_s-m), O = sum O_s 2^(m_s-m) / l) into
  * out (device, [B][n_q_heads][D], fp16 / bf16). */

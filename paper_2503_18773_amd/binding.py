@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.bd_append_kv.restype, L.bd_append_kv.argtypes = ctypes.c_int, [P, V, V, IP, IP, V]
         L.bd_decode_attn.restype, L.bd_decode_attn.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V, V]
         L.bd_decode_attn_static.restype, L.bd_decode_attn_static.argtypes = ctypes.c_int, [P, V, I, I, F, I, V, V]
+        L.bd_probe_stream_read.restype, L.bd_probe_stream_read.argtypes = ctypes.c_int, [P, I, V, V]
         L.bd_splitk_combine.restype, L.bd_splitk_combine.argtypes = ctypes.c_int, [P, V, I, V, V]
         L.bd_decode_step.restype, L.bd_decode_step.argtypes = ctypes.c_int, [P, V, V, V, IP, IP, F, I, V, V, V]
         PP = ctypes.POINTER(bd_paged_cache)
@@ -86,7 +87,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
-           "bd_decode_attn", "bd_decode_attn_static", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
+           "bd_decode_attn", "bd_decode_attn_static", "bd_probe_stream_read", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
            "bd_paged_cache_bytes", "bd_paged_workspace_bytes", "bd_paged_quant_pack_kv", "bd_paged_append_kv",
            "bd_paged_decode_attn", "bd_paged_decode_step"]
 
@@ -146,6 +147,10 @@ def bd_decode_attn_static(c: bd_cache, q, packed_len: int, res_len: int, softmax
                           stream=None):
     _check(lib().bd_decode_attn_static(ctypes.byref(c), _ptr(q), packed_len, res_len, softmax_scale, num_splits,
                                        _ptr(out), _stream(stream)), "bd_decode_attn_static")
+
+
+def bd_probe_stream_read(c: bd_cache, packed_len: int, sink=None, stream=None):
+    _check(lib().bd_probe_stream_read(ctypes.byref(c), packed_len, _ptr(sink), _stream(stream)), "bd_probe_stream_read")
 
 
 def bd_decode_step(c: bd_cache, k_new, v_new, q, packed_len: int, res_len: int, softmax_scale: float,

@@ -253,6 +253,17 @@ bd_status bd_decode_attn_static(const bd_cache* c, const void* q, int32_t packed
   return bd_decode_attn(c, q, packed_len, res_len, softmax_scale, num_splits, ws, out, stream);
 }
 
+bd_status bd_probe_stream_read(const bd_cache* c, int32_t packed_len, void* sink, void* stream) {
+  bd_status s = check_shape(c);
+  if (s != BD_OK) return s;
+  if ((s = check_buffers(c)) != BD_OK) return s;
+  if (!fmt_is_int(c->format)) return BD_ERR_UNSUPPORTED;
+  if ((long)c->batch * c->n_kv_heads > 32767) return BD_ERR_UNSUPPORTED;   // the probe's grid: two rows per unit
+  if (packed_len < 0 || packed_len % kBlock != 0 || packed_len > c->capacity) return BD_ERR_INVALID_ARG;
+  if (sink && (reinterpret_cast<uintptr_t>(sink) & 3u)) return BD_ERR_ALIGNMENT;
+  return hip_status(launch_stream_probe(c, packed_len, sink, (hipStream_t)stream));
+}
+
 bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
                          int32_t* packed_len, int32_t* res_len, float softmax_scale, int32_t num_splits,
                          void* workspace, void* out, void* stream) {

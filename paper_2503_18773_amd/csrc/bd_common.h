@@ -40,6 +40,8 @@ static inline int fmt_group(int f) {
 hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0,
                             void* kdst, void* vdst, long dst_unit_stride, int dst_tok0, int ntok,
                             int units, hipStream_t st);
+// measurement aid: streams the packed K and V codes of the first packed_len tokens and nothing else
+hipError_t launch_stream_probe(const bd_cache* c, int packed_len, void* sink, hipStream_t st);
 hipError_t launch_mx_quant(const void* k, const void* v, long src_unit_stride, int ntok, int units,
                            const bd_cache* c, int dst_tok0, hipStream_t st);
 

@@ -563,6 +563,43 @@ hipError_t launch_paged_bump(const bd_paged_cache* c, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Measurement aid: reads the packed codes of the first `packed_len` tokens of every (sequence, KV head)
+// unit with the decode kernel's loads (16 bytes per lane, non-temporal) and does nothing else: the time
+// of this launch is the floor that the memory system sets for a decode launch over the same cache.
+__global__ __launch_bounds__(256) void stream_probe_kernel(const u4_t* __restrict__ kc, const u4_t* __restrict__ vc,
+                                                             size_t unit_stride_u4, size_t unit_u4, uint32_t* sink) {
+  // blockIdx.y = 2 * unit + tensor.  Workgroup x: the 1 KB pieces x * 4 + wave, + 4 * gridDim.x, ... of that
+  // unit's K (or V) codes, eight in flight per wave.
+  const size_t pieces = unit_u4 / 64;   // whole 1 KB pieces (unit_u4 is a multiple of 64: blocks are 8 KB or 4 KB)
+  const u4_t* base = (blockIdx.y & 1 ? vc : kc) + (blockIdx.y >> 1) * unit_stride_u4;
+  const int lane = threadIdx.x & 63;
+  const size_t first = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6), step = (size_t)gridDim.x * 4;
+  u4_t acc = {0u, 0u, 0u, 0u};
+  for (size_t p0 = first; p0 < pieces; p0 += 8 * step) {
+    u4_t x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const size_t p = p0 + u * step < pieces ? p0 + u * step : p0;   // (past the end: the piece at p0 again)
+      x[u] = __builtin_nontemporal_load(base + p * 64 + lane);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= x[u];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u && sink) sink[0] = 1u;   // keeps the loads alive
+}
+
+hipError_t launch_stream_probe(const bd_cache* c, int packed_len, void* sink, hipStream_t st) {
+  const int units = c->batch * c->n_kv_heads;
+  const size_t block_bytes = (size_t)kBlock * kD * fmt_bits(c->format) / 8;   // K codes (and V codes) of one block
+  const size_t unit_u4 = (size_t)(packed_len / kBlock) * block_bytes / 16;
+  const size_t stride_u4 = (size_t)(c->capacity / kBlock) * block_bytes / 16;
+  if (unit_u4 == 0) return hipSuccess;
+  int wgs = (1024 + 2 * units - 1) / (2 * units);   // about 1024 workgroups in all: four resident per compute unit
+  stream_probe_kernel<<<dim3(wgs, 2 * units), dim3(256), 0, st>>>((const u4_t*)c->k_codes, (const u4_t*)c->v_codes, stride_u4,
+                                                                  unit_u4, (uint32_t*)sink);
+  return hipGetLastError();
+}
+
 hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0, void* kdst,
                             void* vdst, long dst_unit_stride, int dst_tok0, int ntok, int units,
                             hipStream_t st) {
