@@ -169,18 +169,30 @@ bd_status bd_decode_attn_static(const bd_cache* c, const void* q, int32_t packed
                                 float softmax_scale, int32_t num_splits, void* out, void* stream);
 
 /* One decode step in one call: exactly bd_append_kv(k_new, v_new) followed by
- * bd_decode_attn(q, ..., out) -- same cache contents, same lengths, same output bits -- but
- * on steps that do not fill the residual block the new token is attended straight from
- * k_new / v_new and filed into the residual by the attention kernel itself, which saves the
- * separate append launch (the fusion of the paper's Residual Kernel, Sec. III-A(1) /
- * Sec. IV-B, without its lazy flush).  BD_FMT_MXFP4 (up to 16 query heads per KV head): the
- * workgroup that reads the token's block quantizes the token into the cache before it attends.
- * All pointers as in the two calls; `out` must be non-NULL.  Every argument is validated before the
+ * bd_decode_attn(q, ..., out) -- same cache contents, same lengths, same output bits -- in one
+ * attention launch (plus the merge): the new token is attended straight from k_new / v_new and
+ * filed into the residual by the attention kernel itself, and on the step that fills the residual
+ * block the one workgroup that reads the new packed block quantizes it first (the fusion of the
+ * paper's Residual Kernel, Sec. III-A(1) / Sec. IV-B, with the flush before the attention).
+ * BD_FMT_MXFP4: the workgroup that reads the token's block quantizes the token into the cache before
+ * it attends.  (Query groups above 16 heads, and the filling step of the _G64 / _G32 formats, run as
+ * the two calls.)  All pointers as in the two calls; `out` must be non-NULL.  Every argument is validated before the
  * append; only BD_ERR_HIP (a failed launch) can leave the token appended without the attention
  * having been enqueued, and *packed_len / *res_len then say so. */
 bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
                          int32_t* packed_len, int32_t* res_len, float softmax_scale,
                          int32_t num_splits, void* workspace, void* out, void* stream);
+
+/* The same step with the paper's own flush order (Sec. III-A(1), Sec. IV-B(1): the Residual Kernel
+ * attends the half-precision residual block and "optionally quantizes it" when it has reached N_r
+ * tokens): identical to bd_decode_step on every step but the one that fills the residual block.  On
+ * that step the attention reads the block's 128 tokens in fp16 -- no quantization error on them yet --
+ * and the same launch packs them (one extra workgroup per KV head); on return the lengths and the
+ * cache bytes are those bd_decode_step leaves.  Integer formats; BD_FMT_MXFP4 keeps no residual and
+ * behaves as in bd_decode_step. */
+bd_status bd_decode_step_lazy(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
+                              int32_t* packed_len, int32_t* res_len, float softmax_scale,
+                              int32_t num_splits, void* workspace, void* out, void* stream);
 
 /* Measurement aid, no part of the method: one launch that reads the packed K and V codes of the first
  * packed_len tokens of every (sequence, KV head) unit of an integer-format cache, with the loads

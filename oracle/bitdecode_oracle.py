@@ -222,15 +222,26 @@ class IntCache:
         self.v_res[:, :, :r] = V[:, :, nb * BLOCK:]
         self.packed_len, self.res_len = nb * BLOCK, r
 
-    def append_kv(self, k_new: np.ndarray, v_new: np.ndarray):
+    def append_kv(self, k_new: np.ndarray, v_new: np.ndarray, flush: bool = True):
         """Decode step: the new token goes to the residual; a residual that reaches 128
-        tokens is quantized into the next packed block at once."""
+        tokens is quantized into the next packed block at once.
+
+        flush=False is the order of the paper's Residual Kernel (Sec. III-A(1), Sec. IV-B(1): it attends
+        the half-precision residual and only then "optionally quantizes it (when res_len = N_r)"):
+        the token is appended, a full residual (res_len == 128) stays in fp16 for the attention of this
+        step, and flush_if_full() after that attention packs it."""
         assert k_new.shape == v_new.shape == (self.B, self.H, self.D)
+        assert self.res_len < BLOCK, "a full residual must be flushed before the next append"
         if self.res_len == BLOCK - 1 and self.packed_len + BLOCK > self.capacity:
             raise OverflowError("cache capacity exceeded")
         self.k_res[:, :, self.res_len] = k_new
         self.v_res[:, :, self.res_len] = v_new
         self.res_len += 1
+        if flush:
+            self.flush_if_full()
+
+    def flush_if_full(self):
+        """Sec. IV-B(1): a residual of N_r = 128 tokens becomes the next packed block."""
         if self.res_len == BLOCK:
             self._store_block(self.packed_len // BLOCK, self.k_res, self.v_res)
             self.packed_len += BLOCK

@@ -73,6 +73,7 @@ def lib() -> ctypes.CDLL:
         L.bd_probe_stream_read.restype, L.bd_probe_stream_read.argtypes = ctypes.c_int, [P, I, V, V]
         L.bd_splitk_combine.restype, L.bd_splitk_combine.argtypes = ctypes.c_int, [P, V, I, V, V]
         L.bd_decode_step.restype, L.bd_decode_step.argtypes = ctypes.c_int, [P, V, V, V, IP, IP, F, I, V, V, V]
+        L.bd_decode_step_lazy.restype, L.bd_decode_step_lazy.argtypes = ctypes.c_int, [P, V, V, V, IP, IP, F, I, V, V, V]
         PP = ctypes.POINTER(bd_paged_cache)
         L.bd_paged_cache_bytes.restype, L.bd_paged_cache_bytes.argtypes = S, [PP, ctypes.c_int]
         L.bd_paged_workspace_bytes.restype, L.bd_paged_workspace_bytes.argtypes = S, [PP, I]
@@ -87,7 +88,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
-           "bd_decode_attn", "bd_decode_attn_static", "bd_probe_stream_read", "bd_decode_step", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
+           "bd_decode_attn", "bd_decode_attn_static", "bd_probe_stream_read", "bd_decode_step", "bd_decode_step_lazy", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
            "bd_paged_cache_bytes", "bd_paged_workspace_bytes", "bd_paged_quant_pack_kv", "bd_paged_append_kv",
            "bd_paged_decode_attn", "bd_paged_decode_step"]
 
@@ -160,6 +161,16 @@ def bd_decode_step(c: bd_cache, k_new, v_new, q, packed_len: int, res_len: int, 
     _check(lib().bd_decode_step(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), ctypes.byref(pl),
                                 ctypes.byref(rl), softmax_scale, num_splits, _ptr(workspace), _ptr(out),
                                 _stream(stream)), "bd_decode_step")
+    return pl.value, rl.value
+
+
+def bd_decode_step_lazy(c: bd_cache, k_new, v_new, q, packed_len: int, res_len: int, softmax_scale: float,
+                        num_splits: int, workspace, out, stream=None):
+    """Returns the updated (packed_len, res_len)."""
+    pl, rl = ctypes.c_int32(packed_len), ctypes.c_int32(res_len)
+    _check(lib().bd_decode_step_lazy(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), ctypes.byref(pl),
+                                     ctypes.byref(rl), softmax_scale, num_splits, _ptr(workspace), _ptr(out),
+                                     _stream(stream)), "bd_decode_step_lazy")
     return pl.value, rl.value
 
 
@@ -256,10 +267,12 @@ class KVCache:
             bd_splitk_combine(self.desc, ws, ns, out, stream)
         return out
 
-    def decode_step(self, k_new, v_new, q, softmax_scale: float, out, num_splits: int | None = None, stream=None):
+    def decode_step(self, k_new, v_new, q, softmax_scale: float, out, num_splits: int | None = None, stream=None,
+                    lazy: bool = False):
         ns = self.choose_splits() if num_splits is None else num_splits
-        self.packed_len, self.res_len = bd_decode_step(self.desc, k_new, v_new, q, self.packed_len, self.res_len,
-                                                       softmax_scale, ns, self.workspace(ns), out, stream)
+        step = bd_decode_step_lazy if lazy else bd_decode_step
+        self.packed_len, self.res_len = step(self.desc, k_new, v_new, q, self.packed_len, self.res_len,
+                                             softmax_scale, ns, self.workspace(ns), out, stream)
         return out
 
     def host_buffer(self, i: int):

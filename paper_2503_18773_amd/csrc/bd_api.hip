@@ -264,9 +264,12 @@ bd_status bd_probe_stream_read(const bd_cache* c, int32_t packed_len, void* sink
   return hip_status(launch_stream_probe(c, packed_len, sink, (hipStream_t)stream));
 }
 
-bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
-                         int32_t* packed_len, int32_t* res_len, float softmax_scale, int32_t num_splits,
-                         void* workspace, void* out, void* stream) {
+// One decode step of a contiguous cache.  lazy: the paper's Residual Kernel (Sec. III-A(1), IV-B(1)) -- the
+// step that fills the residual block attends its 128 half-precision rows and packs them afterwards;
+// otherwise the block is packed first and attended quantized (bd_append_kv + bd_decode_attn).
+static bd_status decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
+                             int32_t* packed_len, int32_t* res_len, float softmax_scale, int32_t num_splits,
+                             void* workspace, void* out, void* stream, bool lazy) {
   bd_status s = check_shape(c);
   if (s != BD_OK) return s;
   if ((s = check_buffers(c)) != BD_OK) return s;
@@ -275,14 +278,19 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
     return BD_ERR_ALIGNMENT;
   const int pl = *packed_len, r = *res_len;
-  if (c->format == BD_FMT_MXFP4 && c->n_q_heads / c->n_kv_heads <= 16) {
-    // MXFP4, one workgroup per split and KV head: the attention launch quantizes the token into the cache
-    // itself (the workgroup that reads its block does, first thing)
-    if (pl < 0 || r != 0) return BD_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  float* part_o = ws_part_o(workspace);
+  float* part_ml = ws_part_ml(c, workspace, num_splits);
+  const int gq = c->n_q_heads / c->n_kv_heads;
+  if (c->format == BD_FMT_MXFP4) {
+    if (pl < 0 || r != 0 || pl > c->capacity) return BD_ERR_INVALID_ARG;
     if (pl + 1 > c->capacity) return BD_ERR_CAPACITY;
-    hipStream_t st = (hipStream_t)stream;
-    float* part_o = ws_part_o(workspace);
-    float* part_ml = ws_part_ml(c, workspace, num_splits);
+    if (gq > 16) {   // several workgroups read the token's block: the append stays a launch of its own
+      if ((s = bd_append_kv(c, k_new, v_new, packed_len, res_len, stream)) != BD_OK) return s;
+      return bd_decode_attn(c, q, *packed_len, *res_len, softmax_scale, num_splits, workspace, out, stream);
+    }
+    // one workgroup per split and KV head: the attention launch quantizes the token into the cache itself
+    // (the workgroup that reads its block does, first thing)
     if ((s = hip_status(launch_decode_mx(c, q, pl, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out,
                                          st))) != BD_OK)
       return s;
@@ -290,27 +298,52 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
     *packed_len = pl + 1;
     return BD_OK;
   }
-  if (c->format == BD_FMT_MXFP4 ? (pl < 0 || r != 0 || pl > c->capacity)
-                                : (pl < 0 || pl % kBlock != 0 || r < 0 || r >= kBlock || pl > c->capacity))
-    return BD_ERR_INVALID_ARG;
-  const bool fusable = c->format != BD_FMT_MXFP4 && r < kBlock - 1;
-  if (!fusable) {
-    // a step that fills the residual block (or an MXFP4 cache, whose tokens are quantized on
-    // arrival) runs as the two calls it is defined by
+  if (pl < 0 || pl % kBlock != 0 || r < 0 || r >= kBlock || pl > c->capacity) return BD_ERR_INVALID_ARG;
+  const bool fills = r == kBlock - 1;
+  if (fills && pl + kBlock > c->capacity) return BD_ERR_CAPACITY;
+  const bool grp = fmt_group(c->format) != kBlock;
+  if (fills && (grp || gq > 16)) {
+    // no kernel packs the block inside the attention launch for these (smaller quantization groups; several
+    // workgroups per split and KV head): the step runs as the calls it is defined by
+    if (lazy) {   // attention over the 128 fp16 rows (the token read from k_new / v_new and filed), then the flush
+      s = hip_status(grp ? launch_decode_grp(c, q, pl, kBlock, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
+                         : launch_decode_int(c, q, pl, kBlock, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st));
+      if (s != BD_OK) return s;
+      if (num_splits > 1 && (s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
+      if ((s = hip_status(launch_quant_blocks(c->k_res, c->v_res, (long)kBlock * kD, 0, 1, c->batch * c->n_kv_heads, c,
+                                              pl / kBlock, st))) != BD_OK)
+        return s;
+      *packed_len = pl + kBlock;
+      *res_len = 0;
+      return BD_OK;
+    }
     if ((s = bd_append_kv(c, k_new, v_new, packed_len, res_len, stream)) != BD_OK) return s;
     return bd_decode_attn(c, q, *packed_len, *res_len, softmax_scale, num_splits, workspace, out, stream);
   }
-  if (pl < 0 || pl % kBlock != 0 || r < 0 || pl > c->capacity) return BD_ERR_INVALID_ARG;
-  hipStream_t st = (hipStream_t)stream;
-  float* part_o = ws_part_o(workspace);
-  float* part_ml = ws_part_ml(c, workspace, num_splits);
-  s = hip_status(fmt_group(c->format) != kBlock
-                     ? launch_decode_grp(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
-                     : launch_decode_int(c, q, pl, r + 1, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st));
+  // one attention launch: it reads the new token from k_new / v_new and files it, and on the step that fills
+  // the residual block it packs the block as well (before attending it, or, lazy, after)
+  const int flush = !fills ? 0 : lazy ? 2 : 1;
+  const int att_pl = flush == 1 ? pl + kBlock : pl, att_r = flush == 1 ? 0 : r + 1;
+  s = hip_status(grp ? launch_decode_grp(c, q, att_pl, att_r, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
+                     : launch_decode_int(c, q, att_pl, att_r, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st,
+                                         flush));
   if (s != BD_OK) return s;
   if (num_splits > 1 && (s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
-  *res_len = r + 1;
+  *packed_len = fills ? pl + kBlock : pl;
+  *res_len = fills ? 0 : r + 1;
   return BD_OK;
+}
+
+bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
+                         int32_t* packed_len, int32_t* res_len, float softmax_scale, int32_t num_splits,
+                         void* workspace, void* out, void* stream) {
+  return decode_step(c, k_new, v_new, q, packed_len, res_len, softmax_scale, num_splits, workspace, out, stream, false);
+}
+
+bd_status bd_decode_step_lazy(const bd_cache* c, const void* k_new, const void* v_new, const void* q,
+                              int32_t* packed_len, int32_t* res_len, float softmax_scale, int32_t num_splits,
+                              void* workspace, void* out, void* stream) {
+  return decode_step(c, k_new, v_new, q, packed_len, res_len, softmax_scale, num_splits, workspace, out, stream, true);
 }
 
 bd_status bd_splitk_combine(const bd_cache* c, const void* workspace, int32_t num_splits, void* out, void* stream) {

@@ -61,9 +61,12 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
 
 // k_new / v_new non-null: fused step -- residual token res_len-1 is read from k_new / v_new
 // ([B][Hkv][128]) and also stored into the residual buffers by the kernel.
+// flush (with k_new / v_new, query groups of up to 16 heads): the step's token fills the residual block and
+// the launch packs it as well -- 1: before attending it (packed_len counts the block, res_len == 0);
+// 2: after attending its 128 fp16 rows (res_len == 128; one more workgroup per KV head does the packing)
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,
                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
-                             const void* k_new, const void* v_new, void* out, hipStream_t st);
+                             const void* k_new, const void* v_new, void* out, hipStream_t st, int flush = 0);
 // formats with a quantization group of 64 or 32 (k_new / v_new as in launch_decode_int)
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,

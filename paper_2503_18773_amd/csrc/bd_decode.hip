@@ -94,7 +94,16 @@ struct DecodeArgs {
   int32_t* status;
   int max_pages, num_pages;
   int step;            // paged: 1 when this launch is the attention of a fused step (see the kernel)
+  // Contiguous cache, fused step whose token fills the residual block (Sec. IV-B(1)): the 127 rows of the
+  // residual buffers plus k_new / v_new become packed block flush_blk inside this launch.
+  //   kFlushFirst: block flush_blk counts as packed (nb includes it); the one workgroup that reads it
+  //                quantizes it before it attends (the step is append, flush, then attention).
+  //   kFlushAfter: the step attends the 128 fp16 rows (the paper's Residual Kernel: attention on the
+  //                half-precision block, quantization of it in the same launch); one extra workgroup per
+  //                (sequence, KV head), blockIdx.x == 0, does nothing but quantize.
+  int flush_mode, flush_blk;
 };
+constexpr int kFlushNone = 0, kFlushFirst = 1, kFlushAfter = 2;
 
 // Per-wave LDS scratch.  GQP = query heads per KV head, padded to 4, 8 or 16.
 template <int GQP>
@@ -165,8 +174,10 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   __shared__ __attribute__((aligned(16))) float q_s[HP > 1 ? GQP : 1][kD];   // larger groups: queries, normalised; padding heads zero
   __shared__ int kq_s[HP > 1 ? GQP : 1];                                     // larger groups: each head's normalising exponent
 
-  const int split = blockIdx.x, b = blockIdx.z;
+  const int b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool flush_after = !PAGED && a.flush_mode == kFlushAfter;
+  const int split = (int)blockIdx.x - (flush_after ? 1 : 0);
   const int col = lane & 15, g = lane >> 4;            // MFMA column and contraction group
   const int head = col % GQP, cg = col / GQP;          // head carried by the column; column group
   // Query groups of more than 16 heads are taken 16 at a time by ceil(g_q / 16) workgroups per
@@ -219,6 +230,27 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   // ranges per split put the workgroups' streams a power of two apart for the usual split counts,
   // and then all of them march over the same memory channels.)
   const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
+  if (flush_after && split < 0 && head0 != 0) return;   // (one quantizing workgroup per KV head is enough)
+  if (!PAGED && a.flush_mode != kFlushNone && head0 == 0 &&
+      (flush_after ? split < 0 : split == (a.flush_blk / kWaves) % a.num_splits)) {
+    // The step's token completes the residual block: file it, then quantize the 128 rows as block
+    // flush_blk.  kFlushFirst: this workgroup is the block's only reader in this launch (one workgroup per
+    // split and KV head: query groups of up to 16 heads).  kFlushAfter: nobody reads the block here, and
+    // the others read the residual rows, which only gain the row they take from k_new / v_new anyway.
+    uint16_t* kr = const_cast<uint16_t*>(a.k_res) + unit * kBlock * kD;
+    uint16_t* vr = const_cast<uint16_t*>(a.v_res) + unit * kBlock * kD;
+    if (tid < 32) {
+      const bool is_v = tid >= 16;
+      const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+      *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
+    }
+    workgroup_global_sync();
+    quant_block<BITS, KT, kBlock>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
+                                  const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
+                                  unit * a.nbcap + a.flush_blk);
+    if (flush_after) return;   // (the whole workgroup: split < 0 is uniform)
+    workgroup_global_sync();
+  }
   if (PAGED && flush_page >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) {
     // This step's token completes the residual (Sec. IV-B(1)): the 128 rows become block nb - 1, which
     // this workgroup alone reads in this launch.  (One workgroup per split and KV head: the host takes
@@ -323,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     }
     load_res_keys(wave);
   }
-  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
+  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32 && (PAGED || a.flush_mode == kFlushNone)) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
     uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + new_slot) * kD + 8 * (tid & 15);
@@ -946,7 +978,7 @@ void launch_instance(int format, int gq, bool single, bool paged, const DecodeAr
 
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
-                             void* out, hipStream_t st) {
+                             void* out, hipStream_t st, int flush) {
   DecodeArgs a;
   a.out = num_splits == 1 ? out : nullptr;
   a.out_kind = out_kind(c->format, c->out_type);
@@ -959,7 +991,11 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.q = (const uint16_t*)q;
   a.k_new = (const uint16_t*)k_new;
   a.v_new = (const uint16_t*)v_new;
-  a.new_slot = k_new ? res_len - 1 : -1;
+  // flush 1: the step's token fills the residual block, which this launch packs first (packed_len counts it,
+  // res_len is 0); flush 2: ... which this launch attends in fp16 (res_len is 128) and packs as well
+  a.flush_mode = flush == 1 ? kFlushFirst : flush == 2 ? kFlushAfter : kFlushNone;
+  a.flush_blk = flush == 1 ? packed_len / kBlock - 1 : packed_len / kBlock;
+  a.new_slot = k_new && flush != 1 ? res_len - 1 : -1;
   a.part_o = part_o;
   a.part_ml = part_ml;
   a.n_q_heads = c->n_q_heads;
@@ -975,7 +1011,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
   a.status = nullptr;
   a.max_pages = a.num_pages = 0;
   a.step = 0;
-  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
+  dim3 grid(num_splits + (flush == 2 ? 1 : 0), c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
   const bool single = (a.nb + num_splits - 1) / num_splits <= kWaves;   // at most one block per wave
   launch_instance(c->format, a.gq, single, false, a, grid, block, st);
   return hipGetLastError();
@@ -998,6 +1034,8 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.k_new = (const uint16_t*)k_new;   // non-null: the step's token, which this launch appends itself
   a.v_new = (const uint16_t*)v_new;
   a.new_slot = -1;
+  a.flush_mode = kFlushNone;
+  a.flush_blk = 0;
   a.part_o = part_o;
   a.part_ml = part_ml;
   a.n_q_heads = c->n_q_heads;

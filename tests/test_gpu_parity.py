@@ -399,6 +399,74 @@ def test_decode_step_equals_append_then_attention(fmt):
         assert np.array_equal(a.host_buffer(i), b.host_buffer(i)), (fmt, i)
 
 
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int2_kt"])
+@pytest.mark.parametrize("gq", [4, 8, 16, 20])
+def test_decode_step_packs_the_full_block_inside_the_attention_launch(fmt, gq):
+    """The step that fills the residual block: bd_decode_step (flush first: the workgroup that reads the new
+    block quantizes it) against bd_append_kv + bd_decode_attn, bit for bit, for split counts that put the new
+    block with different workgroups and waves, short and long caches (both loop structures of the kernel)."""
+    import torch
+    for nblocks in (1, 6, 37):
+        for ns in (1, 2, 5, 16):
+            w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=2 * gq, n_kv_heads=2, context=128 * nblocks + 126, fmt=fmt,
+                         seed=900 + nblocks)
+            K, V = W.make_kv(w)
+            cap = 128 * (nblocks + 3)
+            a = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, cap)
+            b = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, cap)
+            for c in (a, b):
+                c.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+            oa = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float16, device="cuda:0")
+            ob = torch.empty_like(oa)
+            for step in range(3):        # residual 126 -> 127 -> flush -> 1
+                kn, vn = (to_dev(x, "fp16") for x in W.make_new_kv(w, step))
+                q = to_dev(W.make_q(w, step), "fp16")
+                a.append_kv(kn, vn)
+                a.decode_attn(q, W.softmax_scale(w), oa, num_splits=ns)
+                b.decode_step(kn, vn, q, W.softmax_scale(w), ob, num_splits=ns)
+                torch.cuda.synchronize()
+                assert (a.packed_len, a.res_len) == (b.packed_len, b.res_len)
+                assert torch.equal(oa.view(torch.int16), ob.view(torch.int16)), f"{fmt} gq={gq} blocks {nblocks} ns {ns} step {step}"
+            for i in range(6):
+                assert np.array_equal(a.host_buffer(i), b.host_buffer(i)), (fmt, gq, nblocks, ns, i)
+
+
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64"])
+@pytest.mark.parametrize("gq", [4, 20])
+def test_lazy_decode_step_attends_the_full_residual_in_fp16(fmt, gq):
+    """bd_decode_step_lazy (the paper's flush order): on the step that fills the residual block the attention sees
+    the block's 128 tokens in fp16 -- the oracle's lazy mode -- and the cache afterwards is the one the eager
+    step leaves, bit for bit; every other step equals bd_decode_step bit for bit."""
+    import torch
+    for nblocks, ns in ((0, 1), (2, 3), (9, 4), (37, 16)):
+        w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=2 * gq, n_kv_heads=2, context=128 * nblocks + 126, fmt=fmt,
+                     seed=950 + nblocks)
+        cap = 128 * (nblocks + 3)
+        K, V, oc, lazy = _int_cache_pair(w, cap)
+        eager = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, cap)
+        eager.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
+        ol = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float16, device="cuda:0")
+        oe = torch.empty_like(ol)
+        for step in range(3):            # residual 126 -> 127 -> 128 (attended in fp16, then packed) -> 1
+            kn, vn = W.make_new_kv(w, step)
+            q = W.make_q(w, step)
+            knd, vnd, qd = to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16")
+            lazy.decode_step(knd, vnd, qd, W.softmax_scale(w), ol, num_splits=ns, lazy=True)
+            eager.decode_step(knd, vnd, qd, W.softmax_scale(w), oe, num_splits=ns)
+            torch.cuda.synchronize()
+            oc.append_kv(kn, vn, flush=False)
+            fills = oc.res_len == 128
+            ref = O.decode_attn(oc, q, W.softmax_scale(w))
+            oc.flush_if_full()
+            assert (lazy.packed_len, lazy.res_len) == (eager.packed_len, eager.res_len) == (oc.packed_len, oc.res_len)
+            assert_attn_close(out_to_f64(ol), ref, f"lazy {fmt} gq={gq} blocks {nblocks} step {step}", large_outputs=True)
+            if not fills:
+                assert torch.equal(ol.view(torch.int16), oe.view(torch.int16)), (fmt, gq, nblocks, step)
+            _assert_int_cache_equal(oc, lazy)
+        for i in range(6):
+            assert np.array_equal(lazy.host_buffer(i), eager.host_buffer(i)), (fmt, gq, nblocks, i)
+
+
 def test_decode_step_matches_oracle_on_cfg1():
     w = W.CONFIGS["cfg1"]
     K, V, oc, gc = _int_cache_pair(w, w.context + 256)

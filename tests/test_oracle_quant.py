@@ -210,3 +210,35 @@ def test_layout_orientation(bits):
     assert (word >> (bits * (ch % cpw))) & ((1 << bits) - 1) == kc[t, ch]
     word = int(c.v_codes[0, 0, 0, ch, t // cpw])
     assert (word >> (bits * (t % cpw))) & ((1 << bits) - 1) == vc[t, ch]
+
+
+def test_lazy_flush_attends_fp16_and_leaves_the_eager_cache():
+    """The Residual Kernel's order (Sec. III-A(1), IV-B(1)): append without flushing keeps a full residual of 128
+    tokens in fp16 for that step's attention -- with nothing packed yet the output is textbook softmax
+    attention on the raw fp16 K, V (brute force below) -- and flush_if_full() then leaves exactly the cache the
+    eager append leaves."""
+    w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=4, n_kv_heads=2, context=127)
+    K, V = W.make_kv(w)
+    kn, vn = W.make_new_kv(w, 0)
+    q = W.make_q(w)
+    lazy, eager = O.IntCache(1, 2, 4, 256), O.IntCache(1, 2, 4, 256)
+    lazy.quant_pack_kv(K, V); eager.quant_pack_kv(K, V)
+    lazy.append_kv(kn, vn, flush=False)
+    assert (lazy.packed_len, lazy.res_len) == (0, 128)
+    out = O.decode_attn(lazy, q, W.softmax_scale(w))
+    Kall = np.concatenate([K, kn[:, :, None, :]], axis=2).astype(np.float64)
+    Vall = np.concatenate([V, vn[:, :, None, :]], axis=2).astype(np.float64)
+    for hq in range(4):
+        h = hq // 2
+        s = np.array([W.softmax_scale(w) * sum(float(q[0, hq, c]) * Kall[0, h, t, c] for c in range(128)) for t in range(128)])
+        p = np.exp(s - s.max()); p /= p.sum()
+        brute = sum(p[t] * Vall[0, h, t] for t in range(128))
+        assert np.allclose(out[0, hq], brute, rtol=1e-12, atol=1e-13)
+    lazy.flush_if_full()
+    eager.append_kv(kn, vn)
+    assert (lazy.packed_len, lazy.res_len) == (eager.packed_len, eager.res_len) == (128, 0)
+    for name in ("k_codes", "v_codes", "k_params", "v_params"):
+        assert np.array_equal(getattr(lazy, name), getattr(eager, name)), name
+    # and the eager step's attention sees the quantized block: not the same output
+    assert not np.allclose(O.decode_attn(eager, q, W.softmax_scale(w)), out, atol=1e-6)
+
