@@ -189,6 +189,10 @@ def main() -> int:
                     help="eager mode only: also time every step with its own event pair and write the list "
                          "(step, packed_len, res_len, microseconds) to FILE; steps that fill the residual block show "
                          "as spikes (they run the quantize kernel)")
+    ap.add_argument("--flush", default="first", choices=["first", "lazy"],
+                    help="the step that fills the residual block packs it before attending it (bd_decode_step = "
+                         "bd_append_kv + bd_decode_attn) or attends it in fp16 and packs it afterwards "
+                         "(bd_decode_step_lazy, the paper's Residual Kernel order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-128k", action="store_true", help="cfg1 only: skip the second measurement at 128K (cfg3)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="lower bound on the oracle's timed CPU work")
@@ -306,7 +310,7 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
                 c.decode_step(kn, vn, qs[s], sm_scale, outs[li], splits)
                 nbytes += algorithmic_bytes(w, *lengths(w.context + s + 1))
             else:
-                c.decode_step(kn, vn, qs[s], sm_scale, outs[li], num_splits=splits)
+                c.decode_step(kn, vn, qs[s], sm_scale, outs[li], num_splits=splits, lazy=args.flush == "lazy")
                 nbytes += algorithmic_bytes(w, c.packed_len, c.res_len)
         step_bytes.append(nbytes)
 
@@ -392,7 +396,7 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
         "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads}/{w.n_kv_heads} heads, head_dim 128, "
                                f"context {w.context}, {w.fmt} KV" + (f", variant {args.variant}" if args.variant else ""),
-                   "layers": args.layers, "mode": args.mode, "num_splits": splits},
+                   "layers": args.layers, "mode": args.mode, "num_splits": splits, "flush": args.flush},
         "us_per_layer_call": round(ms_per_step * 1e3 / args.layers, 3),
         "us_per_decode_step": round(ms_per_step * 1e3, 2),
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
