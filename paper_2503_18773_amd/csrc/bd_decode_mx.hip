@@ -76,6 +76,33 @@ struct MergeLdsMx {
 __device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
 // The query as the B operand of the scaled MFMA: exact split of each bf16 into two e4m3 pieces.
+// P' = p * 2^(e - e_run + kPTop) goes to the second product as fp16, with e the e8m0 exponent of the token's
+// channel block and e_run the largest exponent the wave has met so far (a running value, carried like the
+// running maximum: the accumulators are rescaled when it grows).  So P' < 2^(kPTop + 1) whatever the
+// magnitude of V is, the largest terms sit at the top of the fp16 range, and only blocks far below the
+// largest one sink into the subnormals.
+constexpr int kPTop = 13;
+// largest byte of a u4_t, over all lanes of the wave
+template <int N>
+__device__ __forceinline__ int wave_max_byte(const u4_t (&x)[N]) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int i = 0; i < N; ++i)
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t w = x[i][d];
+      m = max(max(m, w >> 24), max(max(w & 0xFFu, (w >> 8) & 0xFFu), (w >> 16) & 0xFFu));
+    }
+  m = max(m, dpp_u<kQuadSwap1>(m));
+  m = max(m, dpp_u<kQuadSwap2>(m));
+  m = max(m, dpp_u<kRowHalfMirror>(m));
+  m = max(m, dpp_u<kRowMirror>(m));
+  return (int)max(max(__builtin_amdgcn_readlane(m, 0), __builtin_amdgcn_readlane(m, 16)),
+                  max(__builtin_amdgcn_readlane(m, 32), __builtin_amdgcn_readlane(m, 48)));
+}
+// 2^e as a float, e clamped to the normal range
+__device__ __forceinline__ float pow2_clamped(int e) { return __uint_as_float((uint32_t)(min(max(e, -126), 127) + 127) << 23); }
+
 // Operand layout of the 8-bit side (measured): lane (column, g) holds contraction indices
 // 16g .. 16g+15 in bytes 0..15 and 64+16g .. 64+16g+15 in bytes 16..31, while the 4-bit
 // side holds 32g .. 32g+31 per lane.  One block scale per head (all 128 channels) is used
@@ -228,6 +255,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
                    sb_hi, sb_lo);
 
   float m_run = -INFINITY, l_run = 0.0f;
+  int e_run = 0;   // largest V exponent byte so far (biased by 127)
   f4_t oacc[8];
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
@@ -268,9 +296,12 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
     l_run *= alpha;
-    if (__any(alpha != 1.0f)) {
+    const int e_new = max(e_run, wave_max_byte(vsc));
+    const float alpha_o = alpha * pow2_clamped(e_run - e_new);
+    e_run = e_new;
+    if (__any(alpha_o != 1.0f)) {
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha_o;
     }
     float p[2][4];
 #pragma unroll
@@ -289,8 +320,7 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
         float pe[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          int e = (int)((vsc[half][r] >> (8 * cb)) & 0xFFu) - 127;
-          e = min(e, 15);   // keeps P' inside fp16; larger scales mean |V| > 2e5
+          const int e = (int)((vsc[half][r] >> (8 * cb)) & 0xFFu) - e_run + kPTop;   // <= kPTop
           pe[r] = ldexpf(p[half][r], e);
         }
         pk[half][0] = (uint32_t)f2h(pe[0]) | ((uint32_t)f2h(pe[1]) << 16);
@@ -331,13 +361,14 @@ __global__ __launch_bounds__(256, 2) void decode_mx_kernel(MxArgs a) {
     bi = nbi;
   }
 
-  // ---- merge the waves of the workgroup
+  // ---- merge the waves of the workgroup (the accumulators go back to the true scale first)
+  const float back = pow2_clamped(e_run - 127 - kPTop);
   l_run = head_sum<4>(l_run);
   if (col < 4) {
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r] * back;
     if (g == 0) {
       ml.m[wave][col] = m_run;
       ml.l[wave][col] = l_run;
@@ -483,6 +514,7 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
                    sb_hi, sb_lo);
 
   float m_run = -INFINITY, l_run = 0.0f;
+  int e_run = 0;   // largest V exponent byte so far (biased by 127)
   f4_t oacc[8];
 #pragma unroll
   for (int mt = 0; mt < 8; ++mt) oacc[mt] = (f4_t){0.f, 0.f, 0.f, 0.f};
@@ -521,9 +553,12 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     m_run = m_new;
     l_run *= alpha;
-    if (__any(alpha != 1.0f)) {
+    const int e_new = max(e_run, wave_max_byte(vsc));
+    const float alpha_o = alpha * pow2_clamped(e_run - e_new);
+    e_run = e_new;
+    if (__any(alpha_o != 1.0f)) {
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha_o;
     }
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt)
@@ -541,8 +576,7 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
         float pe[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          int e = (int)((vsc[tt][r] >> (8 * cb)) & 0xFFu) - 127;
-          e = min(e, 15);   // keeps P' inside fp16; larger scales mean |V| > 2e5
+          const int e = (int)((vsc[tt][r] >> (8 * cb)) & 0xFFu) - e_run + kPTop;   // <= kPTop
           pe[r] = ldexpf(s[tt][r], e);
         }
         pk[tt][0] = (uint32_t)f2h(pe[0]) | ((uint32_t)f2h(pe[1]) << 16);
@@ -575,6 +609,7 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
   }
 
   // ---- the copies' partial O^T, then the waves of the workgroup
+  const float back = pow2_clamped(e_run - 127 - kPTop);   // the accumulators go back to the true scale
   l_run = head_sum<COPIES>(l_run);
   if (COPIES == 2) {
 #pragma unroll
@@ -586,7 +621,7 @@ __global__ __launch_bounds__(256, (GQP == 8 || !PAGED) ? 2 : 1) void decode_mxg_
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r];
+      for (int r = 0; r < 4; ++r) ml.o[wave][col][16 * mt + 4 * g + r] = oacc[mt][r] * back;
     if (g == 0) {
       ml.m[wave][col] = m_run;
       ml.l[wave][col] = l_run;

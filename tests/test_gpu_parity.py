@@ -1056,6 +1056,35 @@ def test_outputs_do_not_depend_on_the_magnitude_of_k_and_v(fmt, gq):
             assert rl <= 1e-3 and ma <= 2e-3, f"{fmt} gq={gq} K x {ks} V x {vs} splits {ns}: rel-L2 {rl:.2e}, max-abs / max |ref| {ma:.2e}"
 
 
+@pytest.mark.parametrize("gq", [4, 8, 16])
+def test_mx_outputs_do_not_depend_on_the_magnitude_of_k_and_v(gq):
+    """MXFP4: K, V scaled by 2^-30 .. 2^30 (and Q inversely): the probabilities meet V's block exponents
+    relative to a running exponent, so the error relative to the outputs stays where it is at unit scale."""
+    import torch
+    w = W.scaled(W.CONFIGS["cfg4"], batch=1, n_q_heads=gq * 2, n_kv_heads=2, context=128 * 20 + 70, seed=79)
+    K0, V0 = W.make_kv(w)
+    q0 = W.make_q(w)
+    for ks, vs in [(2.0 ** -30, 2.0 ** -30), (2.0 ** 20, 2.0 ** -20), (2.0 ** -10, 2.0 ** 30), (1.0, 2.0 ** 20)]:
+        K, V, q = (W.round_to_bf16(x) for x in (K0 * np.float32(ks), V0 * np.float32(vs), q0 / np.float32(ks)))
+        # (one stretch of the sequence far smaller than the rest: the running exponent has to grow on the way)
+        V[:, :, :700] = W.round_to_bf16(V[:, :, :700] * np.float32(2.0 ** -12))
+        oc = O.MxCache(w.batch, w.n_kv_heads, 128 * 22)
+        oc.quant_pack_kv(K, V)
+        gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, "mxfp4", 128 * 22)
+        gc.quant_pack_kv(to_dev(K, "bf16"), to_dev(V, "bf16"))
+        _assert_mx_cache_equal(oc, gc)
+        ref = O.decode_attn(oc, q, W.softmax_scale(w))
+        gc.desc.out_type = B.BD_OUT_F32
+        for ns in (1, 5):
+            out = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.float32, device="cuda:0")
+            gc.decode_attn(to_dev(q, "bf16"), W.softmax_scale(w), out, num_splits=ns)
+            torch.cuda.synchronize()
+            got = out_to_f64(out)
+            rl = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+            ma = np.abs(got - ref).max() / np.abs(ref).max()
+            assert rl <= 1e-3 and ma <= 2e-3, f"mxfp4 gq={gq} K x {ks} V x {vs} splits {ns}: rel-L2 {rl:.2e}, max-abs / max |ref| {ma:.2e}"
+
+
 @pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64", "mxfp4"])
 def test_peaked_and_flat_attention(fmt):
     """Queries scaled by 6 (logits of several tens: a handful of tokens take all the weight and the
