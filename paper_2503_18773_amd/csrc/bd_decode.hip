@@ -452,9 +452,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
       qv[0][i] = h2f((uint16_t)((qraw0[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * f;
       qv[1][i] = h2f((uint16_t)((qraw1[i >> 1] >> (16 * (i & 1))) & 0xFFFFu)) * f;
     }
-    const int k0 = norm_exponent(__builtin_amdgcn_readlane(qb, 0), kQTop), k1 = norm_exponent(__builtin_amdgcn_readlane(qb, 16), kQTop);
-    const int k2 = norm_exponent(__builtin_amdgcn_readlane(qb, 32), kQTop), k3 = norm_exponent(__builtin_amdgcn_readlane(qb, 48), kQTop);
-    kq_head = head == 0 ? k0 : head == 1 ? k1 : head == 2 ? k2 : k3;
+    kq_head = norm_exponent((uint32_t)__shfl((int)qb, 16 * head), kQTop);   // (head h's queries sit in lanes 16h ..)
   } else {
     kq_head = kq_s[head];
   }
@@ -480,13 +478,17 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
   // the factor comes back out of the scores with kS.  Returns ek.
   auto prep_queries = [&]() -> int {
     int ek = 0;
-    float nrm = 1.0f;
+    float nrm[4];   // 2^-ek times the position factor of register i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) nrm[i] = F::un(i);
     if constexpr (!KT) {
       uint32_t sb = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) sb = max(sb, max(kp0[i] & 0xFFFFu, kp1[i] & 0xFFFFu));
       ek = -norm_exponent(row_max16_u(sb), kSTop);   // scale * 2^-ek < 2^kSTop for every channel of the block
-      nrm = pow2i(-ek);
+      const float f = pow2i(-ek);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) nrm[i] = f * F::un(i);
     }
 #pragma unroll
     for (int p = 0; p < HP; ++p) {
@@ -500,30 +502,31 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
         qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
       }
       float zsum = 0.0f;
-      uint16_t qh[8], ql[8];
+      h2_t qh[4], ql[4];   // register i: entries 2i (run 0) and 2i + 1 (run 1)
 #pragma unroll
       for (int run = 0; run < 2; ++run)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float qc = run ? qb[i] : qa[i];
-          float s = 1.0f, z = 1.0f;   // per-token K: Q' = Q, and the "zero term" is sum_c Q_c
+          float t = qc;   // per-token K: Q' = Q, and the "zero term" is sum_c Q_c
+          float z = 1.0f;
           if constexpr (!KT) {
-            const uint32_t pr = run ? kp1[i] : kp0[i];
-            s = h2f((uint16_t)(pr & 0xFFFFu)) * nrm;
-            z = h2f((uint16_t)(pr >> 16));
+            const h2_t pr = __builtin_bit_cast(h2_t, run ? kp1[i] : kp0[i]);   // (scale, zero)
+            t = qc * (float)pr[0];   // exact: 11 bits times 11 bits
+            z = (float)pr[1];
           }
-          const float t = qc * s * F::un(i);
-          const uint16_t hi = f2h(t);
-          qh[2 * i + run] = hi;
-          ql[2 * i + run] = f2h(t - h2f(hi));
+          // high piece, and the rest in one rounding: fma(t, nrm, -high)
+          const _Float16 hi = (_Float16)(t * nrm[i]);
+          qh[i][run] = hi;
+          ql[i][run] = (_Float16)__builtin_fmaf(t, nrm[i], -(float)hi);
           zsum = __builtin_fmaf(qc, z, zsum);
         }
       zsum = row_sum16(zsum);
       u4_t phi, plo;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
-        plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
+        phi[v] = __builtin_bit_cast(uint32_t, qh[v]);
+        plo[v] = __builtin_bit_cast(uint32_t, ql[v]);
       }
       *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
       *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
