@@ -125,22 +125,6 @@ struct MergeLds {
 
 constexpr size_t cmax(size_t x, size_t y) { return x > y ? x : y; }
 
-// 2^e for e in [-126, 127]
-__device__ __forceinline__ float pow2i(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }
-// the power of two that brings fp16 magnitudes up to `bits` (the largest one's bit pattern) below 2^top
-__device__ __forceinline__ int norm_exponent(uint32_t bits, int top) { return top + 14 - (int)(bits >> 10); }
-// Q' = q * scale * position factor goes to the matrix unit as an fp16 high + low pair: queries are brought
-// below 2^7 and a block's K scales below 2^8, so |Q'| < 2^15 (finite) and the low pieces of all but
-// negligible entries stay above the subnormals.
-constexpr int kQTop = 7, kSTop = 8;
-__device__ __forceinline__ uint32_t row_max16_u(uint32_t m) {
-  m = max(m, dpp_u<kQuadSwap1>(m));
-  m = max(m, dpp_u<kQuadSwap2>(m));
-  m = max(m, dpp_u<kRowHalfMirror>(m));
-  m = max(m, dpp_u<kRowMirror>(m));
-  return m;
-}
-
 // GQP: the query group padded to 4, 8 or 16 heads; the 16 MFMA columns carry it 16/GQP times
 //      (column c holds head c % GQP, "column group" c / GQP) and the softmax work of a block
 //      is shared out over the column groups.

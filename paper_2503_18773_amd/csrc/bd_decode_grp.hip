@@ -15,6 +15,11 @@
 //   The centre of each token's codes is taken out of the second product and added back in fp32
 //   with the zero terms, as in the group-128 kernel, so that fp16 rounding of P' acts on
 //   centred codes.
+//   Both fp16 operands are range-normalised by powers of two, so accuracy does not depend on the
+//   magnitude of K, V or Q: each head's query is brought below 2^7 and a token group's K scales
+//   below 2^8 before Q' is formed (undone when the first product becomes a score), and channel
+//   group v's P' carries s * 2^(15 - e_run[v]) with e_run[v] the largest exponent field of the
+//   group's V scales so far (accumulators rescaled when it grows, undone before the waves merge).
 #include "bd_common.h"
 #include "bd_device.h"
 #include "bd_fmt.h"
@@ -65,6 +70,7 @@ struct GrpWaveLds {
   uint16_t c16[NV][kBlock];    // centre code * position factor, in A-operand slot order
   uint16_t pbuf[GQP][kBlock + 8];  // P' of the channel group in work, in B-operand slot order
   float zq[GQP];               // per head: sum_c Q_c z_c of the token group in work
+  float ksb[GQP];              // per head: what turns the first product into scores (undoes the range normalisation of Q')
   uint32_t kpar[NV][kD];       // K parameters (half2) of the block, per token group and channel
 };
 template <int GQP, int NV>
@@ -106,7 +112,10 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
 
   __shared__ __attribute__((aligned(16))) unsigned char smem_raw[gmax(sizeof(ML), kWaves * sizeof(WL))];
   __shared__ float res_s[kBlock][GQP];
-  __shared__ __attribute__((aligned(16))) float q_s[GQP][kD];   // queries * softmax_scale * log2(e); padding heads zero
+  // queries * softmax_scale * log2(e), each head brought below 2^kQTop by a power of two whose inverse is
+  // qinv_s[head]; padding heads zero
+  __shared__ __attribute__((aligned(16))) float q_s[GQP][kD];
+  __shared__ float qinv_s[GQP];
 
   const int split = blockIdx.x, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -185,7 +194,13 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     const int h = 4 * p + wave;
     const uint32_t raw = h < gq ? *reinterpret_cast<const uint32_t*>(qbase + h * kD + 2 * lane) : 0u;
     float2 qq = {h2f((uint16_t)(raw & 0xFFFFu)) * a.scale_log2, h2f((uint16_t)(raw >> 16)) * a.scale_log2};
+    const uint32_t mb = wave_max_u(max(__float_as_uint(fabsf(qq.x)), __float_as_uint(fabsf(qq.y))));
+    const int kq = mb ? min(max(kQTop - 1 - ((int)(mb >> 23) - 127), -60), 60) : 0;   // max |q| * 2^kq < 2^kQTop
+    const float up = pow2i(kq);
+    qq.x *= up;
+    qq.y *= up;
     *reinterpret_cast<float2*>(&q_s[h][2 * lane]) = qq;
+    if (lane == 0) qinv_s[h] = pow2i(-kq);
   }
 
   // ---- residual slice, part 1: scores of this workgroup's fp16 tokens, 16 per MFMA chain
@@ -222,10 +237,15 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
 
   float m_run = -INFINITY, l_run = 0.0f;
   float z_run[NV];
+  // Channel group v's products accumulate in units of 2^(e_run[v] - 15): e_run is the largest exponent field
+  // seen so far among the group's (fp16) V scales, so that scale * 2^(15 - e_run) < 2 whatever the magnitude
+  // of V, and the accumulators are rescaled when it grows, together with the softmax's own rescaling.
+  int e_run[NV];
   f4_t xacc[NV], oacc[8];
 #pragma unroll
   for (int v = 0; v < NV; ++v) {
     z_run[v] = 0.0f;
+    e_run[v] = 0;
     xacc[v] = (f4_t){0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
@@ -285,6 +305,12 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       const f4_t qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
       const u4_t ka = *reinterpret_cast<const u4_t*>(&wl.kpar[tg][run0]);
       const u4_t kb = *reinterpret_cast<const u4_t*>(&wl.kpar[tg][run1]);
+      // the token group's K scales are brought below 2^kSTop (queries are below 2^kQTop): |Q'| < 2^15
+      uint32_t sb = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sb = max(sb, max(ka[i] & 0xFFFFu, kb[i] & 0xFFFFu));
+      const int ek = -norm_exponent(row_max16_u(sb), kSTop);
+      const float dn = pow2i(-ek);
       float zsum = 0.0f;
       uint16_t qh[8], ql[8];
 #pragma unroll
@@ -294,13 +320,14 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
           const float qc = run ? qb[i] : qa[i];
           const uint32_t pr = run ? kb[i] : ka[i];
           const float s = h2f((uint16_t)(pr & 0xFFFFu)), z = h2f((uint16_t)(pr >> 16));
-          const float t = qc * s * F::un(i);
+          const float t = qc * (s * dn) * F::un(i);
           const uint16_t hi = f2h(t);
           qh[2 * i + run] = hi;
           ql[2 * i + run] = f2h(t - h2f(hi));
           zsum = __builtin_fmaf(qc, z, zsum);
         }
-      zsum = row_sum16(zsum);
+      const float qinv = qinv_s[ph];
+      zsum = row_sum16(zsum) * qinv;
       u4_t phi, plo;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
@@ -309,7 +336,10 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       }
       *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
       *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
-      if (prep_sg == 0) wl.zq[ph] = zsum;
+      if (prep_sg == 0) {
+        wl.zq[ph] = zsum;
+        wl.ksb[ph] = pow2i(24 + ek) * qinv;   // codes enter as code * 2^-24
+      }
     }
   };
 
@@ -348,6 +378,10 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       *reinterpret_cast<u4_t*>(&wl.kpar[g][run1]) = kp1;
     }
     // ---- V parameters of the block's tokens, per channel group
+    int e_new[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+      e_new[v] = max(e_run[v], (int)(wave_max_u(max(vp[v] & 0x7FFFu, vp[NV + v] & 0x7FFFu)) >> 10));
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -357,13 +391,13 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
         const int t = 2 * lane + u;
         const int r = t & 3;
         const float ct = sv > 0.0f ? rintf(fminf(fmaxf(-zv * __builtin_amdgcn_rcpf(sv), 0.0f), F::kQmax)) : 0.0f;
-        wl.vpar[v][par_slot(t)] = make_float2(sv * F::un(r), __builtin_fmaf(ct, sv, zv));
+        wl.vpar[v][par_slot(t)] = make_float2(sv * pow2i(15 - e_new[v]) * F::un(r), __builtin_fmaf(ct, sv, zv));
         wl.c16[v][F::operand_pos(t)] = (uint16_t)(ct * F::inv_un(r));   // an integer: the fp16 subnormal code * 2^-24
       }
     // ---- S^T, chunk by chunk
     float sc[OWN][2][4];   // [owned chunk][run][row]
     h8_t bq[4];   // the high piece of Q' in the even copies of a head's column, the low piece in the odd ones
-    float zq = 0.0f;
+    float zq = 0.0f, ksb = 0.0f;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       __builtin_amdgcn_sched_barrier(0);
@@ -376,6 +410,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
           bq[j] = *reinterpret_cast<const h8_t*>(cp & 1 ? &wl.qlo[head][8 * (4 * g + j)] : &wl.qhi[head][8 * (4 * g + j)]);
         }
         zq = wl.zq[head];
+        ksb = wl.ksb[head];
       }
 #pragma unroll
       for (int run = 0; run < 2; ++run) {
@@ -394,7 +429,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
           float x = acc[r];
           if (c & 1) x += dpp_f<GQP == 4 ? kRowShr4 : kRowShr8>(x);
           else x += dpp_f<GQP == 4 ? kRowShl4 : kRowShl8>(x);
-          const float val = __builtin_fmaf(x, kTwo24, zq);
+          const float val = __builtin_fmaf(x, ksb, zq);
           sc[c / COPIES][run][r] = mine ? val : sc[c / COPIES][run][r];
         }
       }
@@ -417,13 +452,18 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
     m_run = m_new;
     l_run *= alpha;
-    if (__any(alpha != 1.0f)) {
+    bool grew = false;
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt) oacc[mt] *= alpha;
+    for (int v = 0; v < NV; ++v) grew |= e_new[v] != e_run[v];
+    if (grew || __any(alpha != 1.0f)) {
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
-        xacc[v] *= alpha;
+        const float av = alpha * pow2i(e_run[v] - e_new[v]);
+#pragma unroll
+        for (int mm = 0; mm < 8 / NV; ++mm) oacc[v * (8 / NV) + mm] *= av;
+        xacc[v] *= av;
         z_run[v] *= alpha;
+        e_run[v] = e_new[v];
       }
     }
 #pragma unroll
@@ -495,7 +535,8 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     for (int mt = 0; mt < 8; ++mt)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        ml.o[wave][col][16 * mt + 4 * g + r] = (oacc[mt][r] - xacc[mt / (8 / NV)][0]) * kTwo24;
+        ml.o[wave][col][16 * mt + 4 * g + r] =
+            (oacc[mt][r] - xacc[mt / (8 / NV)][0]) * (kTwo24 * pow2i(e_run[mt / (8 / NV)] - 15));
     if (g == 0) {
       ml.m[wave][col] = m_run;
       ml.l[wave][col] = l_run;

@@ -1025,7 +1025,7 @@ def test_paged_step_replays_from_one_captured_graph(fmt):
         _assert_paged_equal(oc, gc, "after replays")
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int2_kt"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int2_kt"] + GROUP_FORMATS)
 @pytest.mark.parametrize("gq", [4, 8, 16])
 def test_outputs_do_not_depend_on_the_magnitude_of_k_and_v(fmt, gq):
     """K, V (and Q, inversely, so that the logits stay those of the unit-variance case) scaled by 2^-10 and
@@ -1039,7 +1039,12 @@ def test_outputs_do_not_depend_on_the_magnitude_of_k_and_v(fmt, gq):
         K = (K0.astype(np.float32) * np.float32(min(ks, 2.0 ** 10 / 10))).astype(np.float16)   # (x10 outlier channels: keep fp16 finite)
         V = (V0.astype(np.float32) * np.float32(min(vs, 2.0 ** 10 / 10))).astype(np.float16)
         q = (q0.astype(np.float32) / np.float32(min(ks, 2.0 ** 10 / 10))).astype(np.float16)
-        oc = O.IntCache(w.batch, w.n_kv_heads, BITS[fmt], 128 * 35, k_per_token=fmt.endswith("_kt"))
+        if fmt in GROUP:
+            # one channel group of V far smaller than the others, and for a stretch of the sequence smaller still
+            V[..., 32:64] = (V[..., 32:64].astype(np.float32) * np.float32(2.0 ** -6)).astype(np.float16)
+            V[:, :, :900, 32:64] = (V[:, :, :900, 32:64].astype(np.float32) * np.float32(2.0 ** -4)).astype(np.float16)
+        oc = O.IntCache(w.batch, w.n_kv_heads, BITS[fmt], 128 * 35, k_per_token=fmt.endswith("_kt"),
+                        group=GROUP.get(fmt, 128))
         oc.quant_pack_kv(K, V)
         gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, 128 * 35)
         gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
@@ -1054,6 +1059,10 @@ def test_outputs_do_not_depend_on_the_magnitude_of_k_and_v(fmt, gq):
             rl = np.linalg.norm(got - ref) / np.linalg.norm(ref)
             ma = np.abs(got - ref).max() / np.abs(ref).max()
             assert rl <= 1e-3 and ma <= 2e-3, f"{fmt} gq={gq} K x {ks} V x {vs} splits {ns}: rel-L2 {rl:.2e}, max-abs / max |ref| {ma:.2e}"
+            if GROUP.get(fmt) == 32 and np.linalg.norm(ref[..., 32:64]) > 0:
+                # the small channel group on its own: its P' is normalised against its own scales
+                rg = np.linalg.norm((got - ref)[..., 32:64]) / np.linalg.norm(ref[..., 32:64])
+                assert rg <= 1e-3, f"{fmt} gq={gq} K x {ks} V x {vs} splits {ns}: channels 32..63 rel-L2 {rg:.2e}"
 
 
 @pytest.mark.parametrize("gq", [4, 8, 16])
