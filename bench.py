@@ -12,6 +12,7 @@ algorithmic bytes of the attention calls of a step / wall time of the step.
 from __future__ import annotations
 
 import argparse
+import gc
 import ctypes
 import json
 import os
@@ -315,6 +316,8 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
         step_bytes.append(nbytes)
 
     stream = torch.cuda.current_stream()
+    gc.collect()
+    gc.disable()   # (a collection inside the timed loop shows up as one multi-millisecond step)
     if args.mode == "graph" and paged:
         # lengths and the flush decision live on the device: ONE captured step (all layers) is replayed
         # for every step, its inputs copied into static buffers before each replay
@@ -375,6 +378,7 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
                 f.write("# step packed_len res_len(after the step) microseconds\n")
                 for s, pl, rl, ea, eb in step_events:
                     f.write(f"{s} {pl} {rl} {ea.elapsed_time(eb) * 1e3:.1f}\n")
+    gc.enable()
     elapsed = t1 - t0
     timed_bytes = sum(step_bytes[warmup:])
     ms_per_step = elapsed * 1e3 / steps

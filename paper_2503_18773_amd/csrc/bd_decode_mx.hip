@@ -82,17 +82,25 @@ __device__ __forceinline__ float bf2f(uint32_t bits16) { return __uint_as_float(
 // magnitude of V is, the largest terms sit at the top of the fp16 range, and only blocks far below the
 // largest one sink into the subnormals.
 constexpr int kPTop = 13;
-// largest byte of a u4_t, over all lanes of the wave
+// largest byte of a u4_t, over all lanes of the wave.  Bytes are compared as the high bytes of 16-bit halves
+// (packed 16-bit maxima: the odd bytes of a word as it is, the even ones after a shift by 8; whatever sits in
+// the low byte of a half cannot change which high byte wins).
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  uint32_t d;
+  asm("v_pk_max_u16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+  return d;
+}
 template <int N>
 __device__ __forceinline__ int wave_max_byte(const u4_t (&x)[N]) {
-  uint32_t m = 0;
+  uint32_t mo = 0, me = 0;
 #pragma unroll
   for (int i = 0; i < N; ++i)
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-      const uint32_t w = x[i][d];
-      m = max(max(m, w >> 24), max(max(w & 0xFFu, (w >> 8) & 0xFFu), (w >> 16) & 0xFFu));
+      mo = pk_max_u16(mo, x[i][d]);
+      me = pk_max_u16(me, x[i][d] << 8);
     }
+  uint32_t m = max(max(mo >> 24, (mo >> 8) & 0xFFu), max(me >> 24, (me >> 8) & 0xFFu));
   m = max(m, dpp_u<kQuadSwap1>(m));
   m = max(m, dpp_u<kQuadSwap2>(m));
   m = max(m, dpp_u<kRowHalfMirror>(m));
