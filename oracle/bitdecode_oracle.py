@@ -123,6 +123,14 @@ def quantize_v_block_grouped(vblk: np.ndarray, bits: int, group: int):
     return codes, scale, zero
 
 
+def quantize_k_block_per_token_grouped(kblk: np.ndarray, bits: int, group: int):
+    """The KT setting with a quantization group (Sec. IV-C(1): tensor-wise parameters have shape
+    (T_n, d / group_size)): K block [128 tokens, D] fp16 -> codes [128, D], scale and zero [128, D / group];
+    the statistics of token t, group g run over channels g*group .. (g+1)*group-1 -- what
+    quantize_v_block_grouped does to V, applied to K."""
+    return quantize_v_block_grouped(kblk, bits, group)
+
+
 def pack_words(codes: np.ndarray, bits: int) -> np.ndarray:
     """Pack the last axis: 32/bits codes per little-endian uint32, code n of a word at
     bit offset bits*n."""
@@ -170,12 +178,14 @@ class IntCache:
     K statistics run over `group` tokens per channel, V statistics over `group` channels per
     token; the codes stay where they are and the parameter arrays grow to
       k_params uint32 [B, H, NBcap, 128/group, D]      v_params uint32 [B, H, NBcap, 128, D/group]
+    (k_per_token with a group: K statistics over `group` channels per token like V's,
+      k_params uint32 [B, H, NBcap, 128, D/group])
     """
 
     def __init__(self, batch: int, n_kv_heads: int, bits: int, capacity: int, head_dim: int = 128,
                  k_per_token: bool = False, group: int = BLOCK):
         assert capacity % BLOCK == 0 and head_dim == 128
-        assert group in (32, 64, BLOCK) and not (k_per_token and group != BLOCK)
+        assert group in (32, 64, BLOCK)
         self.B, self.H, self.D, self.bits, self.capacity = batch, n_kv_heads, head_dim, bits, capacity
         self.k_per_token = k_per_token          # KT: K statistics per token instead of per channel
         self.group = group
@@ -187,7 +197,8 @@ class IntCache:
             self.k_params = np.zeros((batch, n_kv_heads, nbc, head_dim), np.uint32)
             self.v_params = np.zeros((batch, n_kv_heads, nbc, BLOCK), np.uint32)
         else:
-            self.k_params = np.zeros((batch, n_kv_heads, nbc, BLOCK // group, head_dim), np.uint32)
+            kshape = (BLOCK, head_dim // group) if k_per_token else (BLOCK // group, head_dim)
+            self.k_params = np.zeros((batch, n_kv_heads, nbc) + kshape, np.uint32)
             self.v_params = np.zeros((batch, n_kv_heads, nbc, BLOCK, head_dim // group), np.uint32)
         self.k_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.v_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
@@ -199,7 +210,8 @@ class IntCache:
         for b in range(self.B):
             for h in range(self.H):
                 if self.group != BLOCK:
-                    kc, ks, kz = quantize_k_block_grouped(kblk[b, h], self.bits, self.group)
+                    quant_kg = quantize_k_block_per_token_grouped if self.k_per_token else quantize_k_block_grouped
+                    kc, ks, kz = quant_kg(kblk[b, h], self.bits, self.group)
                     vc, vs, vz = quantize_v_block_grouped(vblk[b, h], self.bits, self.group)
                 else:
                     quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
@@ -259,9 +271,10 @@ class IntCache:
             vc = unpack_words(self.v_codes[b, h, n], self.bits).astype(np.float64).T    # [c][t] -> [t][c]
             ks, kz = unpack_half2(self.k_params[b, h, n])
             vs, vz = unpack_half2(self.v_params[b, h, n])
-            if self.group != BLOCK:      # ks, kz [128/group, D]; vs, vz [128, D/group]
+            if self.group != BLOCK:      # ks, kz [128/group, D] (k_per_token: [128, D/group]); vs, vz [128, D/group]
                 ks, kz, vs, vz = (x.astype(np.float64) for x in (ks, kz, vs, vz))
-                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * np.repeat(ks, self.group, axis=0) + np.repeat(kz, self.group, axis=0)
+                kax = 1 if self.k_per_token else 0
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * np.repeat(ks, self.group, axis=kax) + np.repeat(kz, self.group, axis=kax)
                 Vh[n * BLOCK:(n + 1) * BLOCK] = vc * np.repeat(vs, self.group, axis=1) + np.repeat(vz, self.group, axis=1)
                 continue
             if self.k_per_token:
@@ -288,13 +301,14 @@ class PagedIntCache:
       block_table int32 [B, max_pages]                 seq_lens int32 [B]
 
     Paging is a pure relocation: every block holds exactly the bytes IntCache would hold
-    (with group = 64 or 32: k_params uint32 [P, H, 128/group, D], v_params uint32 [P, H, 128, D/group]).
+    (with group = 64 or 32: k_params uint32 [P, H, 128/group, D], v_params uint32 [P, H, 128, D/group];
+    k_per_token with a group: k_params uint32 [P, H, 128, D/group]).
     """
 
     def __init__(self, batch: int, n_kv_heads: int, bits: int, num_pages: int, max_pages: int,
                  block_table: np.ndarray, head_dim: int = 128, k_per_token: bool = False, group: int = BLOCK):
         assert head_dim == 128 and block_table.shape == (batch, max_pages)
-        assert group in (32, 64, BLOCK) and not (k_per_token and group != BLOCK)
+        assert group in (32, 64, BLOCK)
         self.B, self.H, self.D, self.bits = batch, n_kv_heads, head_dim, bits
         self.k_per_token = k_per_token
         self.group = group
@@ -305,7 +319,8 @@ class PagedIntCache:
             self.k_params = np.zeros((num_pages, n_kv_heads, head_dim), np.uint32)
             self.v_params = np.zeros((num_pages, n_kv_heads, BLOCK), np.uint32)
         else:
-            self.k_params = np.zeros((num_pages, n_kv_heads, BLOCK // group, head_dim), np.uint32)
+            kshape = (BLOCK, head_dim // group) if k_per_token else (BLOCK // group, head_dim)
+            self.k_params = np.zeros((num_pages, n_kv_heads) + kshape, np.uint32)
             self.v_params = np.zeros((num_pages, n_kv_heads, BLOCK, head_dim // group), np.uint32)
         self.k_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.v_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
@@ -325,7 +340,8 @@ class PagedIntCache:
         quant_k = quantize_k_block_per_token if self.k_per_token else quantize_k_block
         for h in range(self.H):
             if self.group != BLOCK:
-                kc, ks, kz = quantize_k_block_grouped(kblk[h], self.bits, self.group)
+                quant_kg = quantize_k_block_per_token_grouped if self.k_per_token else quantize_k_block_grouped
+                kc, ks, kz = quant_kg(kblk[h], self.bits, self.group)
                 vc, vs, vz = quantize_v_block_grouped(vblk[h], self.bits, self.group)
             else:
                 kc, ks, kz = quant_k(kblk[h], self.bits)
@@ -373,9 +389,10 @@ class PagedIntCache:
             vc = unpack_words(self.v_codes[p, h], self.bits).astype(np.float64).T
             ks, kz = unpack_half2(self.k_params[p, h])
             vs, vz = unpack_half2(self.v_params[p, h])
-            if self.group != BLOCK:      # ks, kz [128/group, D]; vs, vz [128, D/group]
+            if self.group != BLOCK:      # ks, kz [128/group, D] (k_per_token: [128, D/group]); vs, vz [128, D/group]
                 ks, kz, vs, vz = (x.astype(np.float64) for x in (ks, kz, vs, vz))
-                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * np.repeat(ks, self.group, axis=0) + np.repeat(kz, self.group, axis=0)
+                kax = 1 if self.k_per_token else 0
+                Kh[n * BLOCK:(n + 1) * BLOCK] = kc * np.repeat(ks, self.group, axis=kax) + np.repeat(kz, self.group, axis=kax)
                 Vh[n * BLOCK:(n + 1) * BLOCK] = vc * np.repeat(vs, self.group, axis=1) + np.repeat(vz, self.group, axis=1)
                 continue
             if self.k_per_token:

@@ -135,3 +135,99 @@ def test_cache_layout_state_machine_and_attention(bits, group):
     for name in ("k_codes", "v_codes", "k_params", "v_params"):
         assert np.array_equal(getattr(pre, name), getattr(gc, name)), name
     assert np.array_equal(pre.k_res[:, :, :16], gc.k_res[:, :, :16])
+
+
+# ---- per-token K with channel groups (the KT setting with a group: parameters of shape (T_n, d/group))
+
+@pytest.mark.parametrize("bits", [4, 2])
+@pytest.mark.parametrize("group", [32, 64])
+def test_per_token_k_groups_brute_force(bits, group):
+    """Every element against min / max / scale taken by hand over its own (token, channel group), and the
+    transposition symmetry: per-token groups of K are channel-wise groups of K^T."""
+    K, _ = _blocks(13)
+    kc, ks, kz = O.quantize_k_block_per_token_grouped(K, bits, group)
+    assert kc.shape == (128, 128) and ks.shape == kz.shape == (128, 128 // group)
+    qmax = 2 ** bits - 1
+    rng = np.random.default_rng(5)
+    for t, c in zip(rng.integers(0, 128, 300), rng.integers(0, 128, 300)):
+        g = c // group
+        vals = [float(K[t, g * group + i]) for i in range(group)]
+        mn, mx = min(vals), max(vals)
+        s = np.float16(np.float32(np.float32(mx) - np.float32(mn)) / np.float32(qmax))
+        assert _bits_equal(ks[t, g], s) and float(kz[t, g]) == mn
+        code = 0 if s == 0 else int(np.clip(np.rint((np.float32(K[t, c]) - np.float32(mn)) / np.float32(s)), 0, qmax))
+        assert kc[t, c] == code
+    ct, st, zt = O.quantize_k_block_grouped(np.ascontiguousarray(K.T), bits, group)
+    assert np.array_equal(ct.T, kc) and _bits_equal(st.T, ks) and _bits_equal(zt.T, kz)
+    # group 128 is the KT quantizer
+    c0, s0, z0 = O.quantize_k_block_per_token(K, bits)
+    c1, s1, z1 = O.quantize_k_block_per_token_grouped(K, bits, 128)
+    assert np.array_equal(c0, c1) and _bits_equal(s0, s1[:, 0]) and _bits_equal(z0, z1[:, 0])
+
+
+def test_per_token_k_groups_worked_example():
+    K = np.zeros((128, 128), np.float16)
+    K[5, 64:96] = np.tile(np.arange(16, dtype=np.float16) * np.float16(0.5) - np.float16(1.0), 2)   # scale 0.5, zero -1
+    K[5, 96:128] = np.float16(-2.25)                                                                  # constant group
+    codes, scale, zero = O.quantize_k_block_per_token_grouped(K, 4, 32)
+    assert scale[5, 2] == np.float16(0.5) and zero[5, 2] == -1 and np.array_equal(codes[5, 64:96], np.tile(np.arange(16), 2))
+    assert scale[5, 3] == 0 and zero[5, 3] == np.float16(-2.25) and not codes[5, 96:].any()
+    assert scale[5, 0] == 0 and zero[5, 0] == 0
+
+
+@pytest.mark.parametrize("bits,group", [(4, 32), (2, 64)])
+def test_per_token_k_groups_cache_and_attention(bits, group):
+    w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=4, n_kv_heads=2, context=300, seed=22)
+    K, V = W.make_kv(w)
+    gc = O.IntCache(2, 2, bits, 512, k_per_token=True, group=group); gc.quant_pack_kv(K, V)
+    kt = O.IntCache(2, 2, bits, 512, k_per_token=True); kt.quant_pack_kv(K, V)
+    cw = O.IntCache(2, 2, bits, 512, group=group); cw.quant_pack_kv(K, V)
+    assert gc.k_params.shape == gc.v_params.shape == (2, 2, 4, 128, 128 // group)
+    # V is what the channel-wise grouped cache holds; K differs from both relatives only in its statistics axis
+    assert np.array_equal(gc.v_codes, cw.v_codes) and np.array_equal(gc.v_params, cw.v_params)
+    assert gc.k_codes.shape == kt.k_codes.shape and np.array_equal(gc.k_res, kt.k_res)
+    kc, ks, kz = O.quantize_k_block_per_token_grouped(K[1, 1, 128:256], bits, group)
+    assert np.array_equal(O.unpack_words(gc.k_codes[1, 1, 1], bits), kc)
+    assert np.array_equal(gc.k_params[1, 1, 1], O.pack_half2(ks, kz))
+    Kh, Vh = gc.dequant(1, 1)
+    assert np.array_equal(Kh[128:256], kc * np.repeat(ks.astype(np.float64), group, axis=1) + np.repeat(kz.astype(np.float64), group, axis=1))
+    assert np.array_equal(Vh, cw.dequant(1, 1)[1])
+    # attention over it = brute-force softmax over the dequantized rows
+    q = W.make_q(w)
+    out = O.decode_attn(gc, q, 0.09)
+    for hq in (2, 3):
+        s = 0.09 * np.array([sum(float(Kh[t, c]) * float(q[1, hq, c]) for c in range(128)) for t in range(300)])
+        p = np.exp(s - s.max())
+        ref = (p[:, None] * Vh).sum(axis=0) / p.sum()
+        assert np.abs(out[1, hq] - ref).max() < 1e-12
+    # smaller K groups track K more closely than one group per token
+    exact = np.stack([O.attention_weights(q[1, h].astype(np.float64), K[1, 0].astype(np.float64), 0.09) for h in range(2)])
+    w_g = np.stack([O.attention_weights(q[1, h].astype(np.float64), gc.dequant(1, 0)[0], 0.09) for h in range(2)])
+    w_t = np.stack([O.attention_weights(q[1, h].astype(np.float64), kt.dequant(1, 0)[0], 0.09) for h in range(2)])
+    assert np.abs(w_g - exact).sum() < np.abs(w_t - exact).sum()
+    # appends flush with the same rule; a flushed block equals the prefilled one
+    pre = O.IntCache(2, 2, bits, 512, k_per_token=True, group=group)
+    news = [W.make_new_kv(w, i) for i in range(100)]
+    for kn, vn in news:
+        gc.append_kv(kn, vn)
+    K2 = np.concatenate([K, np.stack([kn for kn, _ in news], axis=2)], axis=2)
+    V2 = np.concatenate([V, np.stack([vn for _, vn in news], axis=2)], axis=2)
+    pre.quant_pack_kv(K2, V2)
+    for name in ("k_codes", "v_codes", "k_params", "v_params"):
+        assert np.array_equal(getattr(pre, name), getattr(gc, name)), name
+
+
+def test_per_token_k_groups_paged_is_a_relocation():
+    w = W.scaled(W.CONFIGS["cfg1"], batch=2, n_q_heads=4, n_kv_heads=2, context=300, seed=23)
+    K, V = W.make_kv(w)
+    table = np.array([[5, 2, 7, -1], [0, 6, 1, -1]], np.int32)
+    pc = O.PagedIntCache(2, 2, 4, 8, 4, table, k_per_token=True, group=32)
+    cc = O.IntCache(2, 2, 4, 512, k_per_token=True, group=32)
+    cc.quant_pack_kv(K, V)
+    for b in range(2):
+        pc.quant_pack_kv(b, K[b], V[b])
+    assert pc.k_params.shape == (8, 2, 128, 4)
+    for b in range(2):
+        for n in range(2):
+            assert np.array_equal(pc.k_codes[table[b, n]], cc.k_codes[b, :, n]) and np.array_equal(pc.k_params[table[b, n]], cc.k_params[b, :, n])
+    assert np.array_equal(O.decode_attn(pc, W.make_q(w), 0.09), O.decode_attn(cc, W.make_q(w), 0.09))
