@@ -28,7 +28,8 @@ HBM_PEAK_GBPS = 8000.0
 N_LAYERS = 32
 # packed K + packed V + their parameters, per token and KV head
 PER_TOKEN_BYTES = {"int4": 136, "int2": 72, "mxfp4": 136, "int4_kt": 136, "int2_kt": 72,
-                   "int4_g64": 144, "int4_g32": 160, "int2_g64": 80, "int2_g32": 96}
+                   "int4_g64": 144, "int4_g32": 160, "int2_g64": 80, "int2_g32": 96,
+                   "int4_kt_g64": 144, "int4_kt_g32": 160, "int2_kt_g64": 80, "int2_kt_g32": 96}
 VARIANTS = {
     "": "the configuration as listed",
     "paged": "the same tokens in a paged cache (128-token pages scattered over a pool, lengths on the device): "
@@ -38,6 +39,8 @@ VARIANTS = {
     "gq16": "16 query heads per KV head (128/8 heads)",
     "g64": "quantization groups of 64 instead of 128 (formats int4_g64 / int2_g64)",
     "g32": "quantization groups of 32 (formats int4_g32 / int2_g32)",
+    "kt_g64": "K per token with quantization groups of 64 channels (formats int4_kt_g64 / int2_kt_g64)",
+    "kt_g32": "K per token with quantization groups of 32 channels (formats int4_kt_g32 / int2_kt_g32)",
 }
 
 
@@ -76,7 +79,7 @@ def _oracle_worker(job):
         if w.fmt == "mxfp4":
             oc = O.MxCache(1, 1, cap)
         else:
-            oc = O.IntCache(1, 1, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token=w.fmt.endswith("_kt"),
+            oc = O.IntCache(1, 1, 4 if w.fmt.startswith("int4") else 2, cap, k_per_token="_kt" in w.fmt,
                             group=64 if w.fmt.endswith("_g64") else 32 if w.fmt.endswith("_g32") else 128)
         oc.quant_pack_kv(K1, V1)          # untimed: prefill
         b, h = divmod(unit, w.n_kv_heads)
@@ -240,7 +243,7 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
     from paper_2503_18773_amd import binding as B
     from paper_2503_18773_amd import workloads as W
     w = W.CONFIGS[workload]
-    if args.variant in ("kt", "g64", "g32"):
+    if args.variant in ("kt", "g64", "g32", "kt_g64", "kt_g32"):
         w = W.scaled(w, fmt=w.fmt + "_" + args.variant)
     elif args.variant in ("gq8", "gq16"):
         w = W.scaled(w, n_q_heads=int(args.variant[2:]) * w.n_kv_heads)

@@ -17,8 +17,9 @@
  *    "Batches" setting, Sec. V-A: same length, padded); bd_paged_cache (further down) keeps
  *    per-sequence lengths on the device (the "Page" setting).
  *  - head_dim is 128.  The residual block N_r (Eq. 1) is 128 tokens for every integer format; the
- *    quantization group is 128 as well, except for the _G64 / _G32 formats (64 / 32); the MX group
- *    is 32 for BD_FMT_MXFP4, which keeps no residual.
+ *    quantization group is 128 as well, except for the _G64 / _G32 formats (64 / 32, with K
+ *    channel-wise or, _KT_G64 / _KT_G32, per token); the MX group is 32 for BD_FMT_MXFP4, which
+ *    keeps no residual.
  *  - Arguments are validated before anything is launched: a validation error (any status but
  *    BD_ERR_HIP) means nothing was enqueued and no state changed.  BD_ERR_HIP is a failed launch
  *    in the middle of a call: kernels enqueued before it stay enqueued, and the in-out lengths
@@ -83,7 +84,15 @@ typedef enum {
   BD_FMT_INT4_G64 = 5,
   BD_FMT_INT4_G32 = 6,
   BD_FMT_INT2_G64 = 7,
-  BD_FMT_INT2_G32 = 8
+  BD_FMT_INT2_G32 = 8,
+  /* K per token with a quantization group as well (the KT setting with a group; Sec. IV-C(1): tensor-wise
+   * parameters of shape (T_n, d/group)): K statistics over 64 or 32 channels per token, exactly like V's.
+   * Codes as in BD_FMT_INT4 / INT2; k_params and v_params both uint32 [B][H][capacity][D/group]
+   * (paged: [P][H][128][D/group]). */
+  BD_FMT_INT4_KT_G64 = 9,
+  BD_FMT_INT4_KT_G32 = 10,
+  BD_FMT_INT2_KT_G64 = 11,
+  BD_FMT_INT2_KT_G32 = 12
 } bd_format;
 
 /* Element type of the attention output rows `out` (Fig. 2 caption: Out = softmax(Q D(K')^T) D(V')). */

@@ -10,9 +10,12 @@ import os
 
 BD_FMT_INT4, BD_FMT_INT2, BD_FMT_MXFP4, BD_FMT_INT4_KT, BD_FMT_INT2_KT = 0, 1, 2, 3, 4
 BD_FMT_INT4_G64, BD_FMT_INT4_G32, BD_FMT_INT2_G64, BD_FMT_INT2_G32 = 5, 6, 7, 8
+BD_FMT_INT4_KT_G64, BD_FMT_INT4_KT_G32, BD_FMT_INT2_KT_G64, BD_FMT_INT2_KT_G32 = 9, 10, 11, 12
 FORMATS = {"int4": BD_FMT_INT4, "int2": BD_FMT_INT2, "mxfp4": BD_FMT_MXFP4, "int4_kt": BD_FMT_INT4_KT,
            "int2_kt": BD_FMT_INT2_KT, "int4_g64": BD_FMT_INT4_G64, "int4_g32": BD_FMT_INT4_G32,
-           "int2_g64": BD_FMT_INT2_G64, "int2_g32": BD_FMT_INT2_G32}
+           "int2_g64": BD_FMT_INT2_G64, "int2_g32": BD_FMT_INT2_G32,
+           "int4_kt_g64": BD_FMT_INT4_KT_G64, "int4_kt_g32": BD_FMT_INT4_KT_G32,
+           "int2_kt_g64": BD_FMT_INT2_KT_G64, "int2_kt_g32": BD_FMT_INT2_KT_G32}
 BLOCK = 128
 BD_OUT_HALF, BD_OUT_F32 = 0, 1
 BD_STATIC_SCRATCH_BYTES = 4 << 20   # include/bitdecode.h

@@ -128,9 +128,10 @@ int32_t bd_choose_splits(const bd_cache* c, int32_t packed_len) {
   // (2-bit codes: the kernel is bound by arithmetic and the second split pays earlier -- 40.7 against 44.6 us
   // at 32 sequences x 8K tokens)
   if (units >= 256 && (long)nb * units <= (fmt_is_int(c->format) && fmt_bits(c->format) == 2 ? 12288 : 16384)) return 1;
-  // (one kernel instance runs one workgroup per compute unit: 4-bit codes in groups of 32 with more than
-  // 4 query heads per KV head)
-  const long target = c->format == BD_FMT_INT4_G32 && c->n_q_heads / c->n_kv_heads > 4 ? 256 : 512;
+  // (some kernel instances run one workgroup per compute unit: groups of 32 with more than 4 query heads
+  // per KV head, for 4-bit codes and for per-token K)
+  const bool one_wg = fmt_group(c->format) == 32 && (fmt_bits(c->format) == 4 || fmt_kt(c->format)) && c->n_q_heads / c->n_kv_heads > 4;
+  const long target = one_wg ? 256 : 512;
   int want = (int)((target + units - 1) / units);
   if (want < 1) want = 1;
   // (no rebalancing: quanta are dealt to the splits round robin, so a count that does not divide them

@@ -28,14 +28,17 @@ hipError_t launch_quant_blocks(const void* k, const void* v, long src_unit_strid
                                int nblocks, int units, const bd_cache* c, int dst_blk0,
                                hipStream_t st);
 
-static inline bool fmt_is_int(int f) { return f != BD_FMT_MXFP4 && f >= BD_FMT_INT4 && f <= BD_FMT_INT2_G32; }
+static inline bool fmt_is_int(int f) { return f != BD_FMT_MXFP4 && f >= BD_FMT_INT4 && f <= BD_FMT_INT2_KT_G32; }
 static inline int fmt_bits(int f) {
-  return (f == BD_FMT_INT2 || f == BD_FMT_INT2_KT || f == BD_FMT_INT2_G64 || f == BD_FMT_INT2_G32) ? 2 : 4;
+  return (f == BD_FMT_INT2 || f == BD_FMT_INT2_KT || f == BD_FMT_INT2_G64 || f == BD_FMT_INT2_G32 ||
+          f == BD_FMT_INT2_KT_G64 || f == BD_FMT_INT2_KT_G32) ? 2 : 4;
 }
-static inline bool fmt_kt(int f) { return f == BD_FMT_INT4_KT || f == BD_FMT_INT2_KT; }
+static inline bool fmt_kt(int f) { return f == BD_FMT_INT4_KT || f == BD_FMT_INT2_KT || (f >= BD_FMT_INT4_KT_G64 && f <= BD_FMT_INT2_KT_G32); }
 // quantization group: tokens per K group and channels per V group
 static inline int fmt_group(int f) {
-  return (f == BD_FMT_INT4_G64 || f == BD_FMT_INT2_G64) ? 64 : (f == BD_FMT_INT4_G32 || f == BD_FMT_INT2_G32) ? 32 : 128;
+  return (f == BD_FMT_INT4_G64 || f == BD_FMT_INT2_G64 || f == BD_FMT_INT4_KT_G64 || f == BD_FMT_INT2_KT_G64)   ? 64
+         : (f == BD_FMT_INT4_G32 || f == BD_FMT_INT2_G32 || f == BD_FMT_INT4_KT_G32 || f == BD_FMT_INT2_KT_G32) ? 32
+                                                                                                                : 128;
 }
 hipError_t launch_copy_rows(const void* ksrc, const void* vsrc, long src_unit_stride, int src_tok0,
                             void* kdst, void* vdst, long dst_unit_stride, int dst_tok0, int ntok,

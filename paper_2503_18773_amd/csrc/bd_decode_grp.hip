@@ -60,8 +60,9 @@ struct GrpArgs {
   int step;   // paged: 1 when this launch is the attention of a fused step
 };
 
-template <int GQP, int NV>
+template <int GQP, int NV, bool KT>
 struct GrpWaveLds {
+  __attribute__((aligned(16))) uint16_t zeros[8];   // per-token K: what a lane outside a chain's channel group feeds the matrix unit
   // (rows of qhi, qlo and pbuf padded by 16 bytes: lanes of different heads read the same offset of
   // their rows, and rows a multiple of 256 bytes apart would all fall on the same LDS banks)
   uint16_t qhi[GQP][kD + 8];   // Q' per head, high fp16 piece, in B-operand slot order
@@ -71,7 +72,11 @@ struct GrpWaveLds {
   uint16_t pbuf[GQP][kBlock + 8];  // P' of the channel group in work, in B-operand slot order
   float zq[GQP];               // per head: sum_c Q_c z_c of the token group in work
   float ksb[GQP];              // per head: what turns the first product into scores (undoes the range normalisation of Q')
-  uint32_t kpar[NV][kD];       // K parameters (half2) of the block, per token group and channel
+  uint32_t kpar[KT ? 1 : NV][kD];   // K parameters (half2) of the block, per token group and channel
+  // per-token K: (scale * 2^24, zero) per (channel group, token) of the block, and per head the sums of the
+  // (normalised, scaled) query over each channel group
+  float2 ktpar[KT ? NV : 1][kParSlots];
+  float qsum[GQP][NV];
 };
 template <int GQP, int NV>
 struct GrpMergeLds {
@@ -81,22 +86,33 @@ struct GrpMergeLds {
 
 constexpr size_t gmax(size_t x, size_t y) { return x > y ? x : y; }
 
-// Every instance fits 256 registers (two waves per SIMD) but one: 4-bit codes in groups of 32 with
-// more than 4 heads per workgroup, which would spill and runs one wave per SIMD instead.
-constexpr int grp_waves_per_simd(int bits, int group, int gqp) { return bits == 4 && group == 32 && gqp == 8 ? 1 : 2; }
+// Every instance fits 256 registers (two waves per SIMD) but those for groups of 32 with more than 4 heads
+// per workgroup and 4-bit codes or per-token K, which would spill and run one wave per SIMD instead.
+constexpr int grp_waves_per_simd(int bits, int group, int gqp, bool kt) {
+  return (bits == 4 || kt) && group == 32 && gqp == 8 ? 1 : 2;
+}
 
 // G: quantization group (64 or 32).  GQP: heads per workgroup, padded to 4 or 8 (larger query groups
 // take ceil(g_q / 8) workgroups per split and KV head; 16 heads' LDS scratch would not fit); MFMA
 // column c carries head c % GQP (the copies compute the same numbers).
 // PAGED: blocks are found through the block table and every sequence has its own length.
-template <int BITS, int G, int GQP, bool PAGED>
-__global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_grp_kernel(GrpArgs a) {
+// KT: K is quantized per token and channel group like V (parameters [token][D/G]):
+//   S[t, h] = sum_g s_(t,g) * (sum_{c in g} code_tc Q_c) + sum_g z_(t,g) * (sum_{c in g} Q_c).
+//   A lane group holds 32 consecutive channels of a token and the matrix instruction sums over the lane
+//   groups, so the channel groups are kept apart in the COLUMNS instead: Q' = Q (normalised, fp16 high + low
+//   pair, prepared once per kernel) enters 2 * NG "virtual columns" per head -- (piece, channel group), zero
+//   in the lane groups outside that channel group -- which the COPIES copies of the head's column carry in
+//   2 * NG / COPIES chains of MFMAs; each partial product is scaled with the (token, channel group)
+//   parameters in fp32 and the copies are added with DPP row rotations, after which every copy holds S^T as
+//   in the channel-wise case.
+template <int BITS, int G, int GQP, bool PAGED, bool KT>
+__global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP, KT)) void decode_grp_kernel(GrpArgs a) {
   // With one wave per SIMD nothing but the wave's own arithmetic hides its memory latency, so it
   // requests a block's values before its keys are consumed and the next block's keys right after
   // ("deep").  With two waves the other one covers and the short queue of the group-128 kernel is
   // better (measured, groups of 64: 13.2 against 13.7 us at 32K, 30.9 against 33.2 us at 128K),
   // except for 2-bit codes, whose blocks are half the bytes (42.9 against 45.3 us at 8 x 32K).
-  constexpr bool kDeep = BITS == 2 || grp_waves_per_simd(BITS, G, GQP) == 1;
+  constexpr bool kDeep = BITS == 2 || grp_waves_per_simd(BITS, G, GQP, KT) == 1;
   using F = Fmt<BITS>;
   constexpr int WORDS = F::WORDS;
   constexpr int KROW = kD * BITS / 32;       // K words per token
@@ -107,7 +123,9 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
   constexpr int COPIES = 16 / GQP;           // MFMA columns per head
   static_assert(COPIES >= 2 && COPIES % 2 == 0, "the high / low pieces of Q' need an even number of copies");
   constexpr int OWN = 4 / COPIES;            // 32-token chunks whose softmax a lane runs
-  using WL = GrpWaveLds<GQP, NV>;
+  using WL = GrpWaveLds<GQP, NV, KT>;
+  constexpr int CH = KT ? 2 * NG / COPIES : 0;   // per-token K: MFMA chains per S^T tile
+  static_assert(!KT || (2 * NG) % COPIES == 0, "virtual columns per head must fill the copies");
   using ML = GrpMergeLds<GQP, NV>;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem_raw[gmax(sizeof(ML), kWaves * sizeof(WL))];
@@ -180,7 +198,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
       *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
     }
     workgroup_global_sync();
-    quant_block<BITS, false, G>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
+    quant_block<BITS, KT, G>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
                                 const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
                                 (size_t)flush_page * a.n_kv_heads + hkv);
     workgroup_global_sync();
@@ -261,12 +279,29 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
   u4_t kp0, kp1;              // K parameters (half2) of this lane's two channel runs, token group g % NG
   uint32_t vp[2 * NV];        // V parameters (half2) of tokens 2*lane, 2*lane+1, per channel group
 
+  uint32_t ktp[KT ? 2 * NV : 1];   // per-token K: K parameters (half2) of tokens 2*lane, 2*lane+1, per channel group
   auto issue_params = [&](size_t bi) {
-    // lane group g fetches token group g % NG (its 16 lanes cover the 128 channels); the token
-    // groups meet in LDS, which keeps 8 registers in flight instead of 8 per token group
-    const uint32_t* pp = a.k_params + (bi * NG + (g % NG)) * kD;
-    kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
-    kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
+    if constexpr (KT) {
+      const uint32_t* kpp = a.k_params + (bi * kBlock + 2 * lane) * NV;
+      if constexpr (NV == 4) {
+        const u4_t x = *reinterpret_cast<const u4_t*>(kpp), y = *reinterpret_cast<const u4_t*>(kpp + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          ktp[i] = x[i];
+          ktp[4 + i] = y[i];
+        }
+      } else {
+        const u4_t x = *reinterpret_cast<const u4_t*>(kpp);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ktp[i] = x[i];
+      }
+    } else {
+      // lane group g fetches token group g % NG (its 16 lanes cover the 128 channels); the token
+      // groups meet in LDS, which keeps 8 registers in flight instead of 8 per token group
+      const uint32_t* pp = a.k_params + (bi * NG + (g % NG)) * kD;
+      kp0 = *reinterpret_cast<const u4_t*>(pp + run0);
+      kp1 = *reinterpret_cast<const u4_t*>(pp + run1);
+    }
     const uint32_t* vpp = a.v_params + (bi * kBlock + 2 * lane) * NV;
     if constexpr (NV == 4) {
       const u4_t x = *reinterpret_cast<const u4_t*>(vpp), y = *reinterpret_cast<const u4_t*>(vpp + 4);
@@ -343,6 +378,65 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     }
   };
 
+  // Per-token K: Q' = Q * position factor (no K scale in it), once per kernel, and the sums of Q over each
+  // channel group for the zero terms.
+  float zq_k[KT ? CH : 1];      // chain k of this lane's copy: sum of Q over its channel group if it carries the high piece, else 0
+  float qinv = 1.0f;            // undoes the query's normalisation
+  constexpr bool kKeepB = CH == 1;     // the chains' B operands stay in registers when there is one chain, else they are read per chunk
+  h8_t bqk[1][4];
+  auto chain_operand = [&](int k, int j) {
+    const int v = k * COPIES + cp;                       // virtual column: piece v & 1, channel group v >> 1
+    const bool live = (g >> (G == 64 ? 1 : 0)) == (v >> 1);
+    const uint16_t* row = (v & 1) ? &wl.qlo[head][8 * (4 * g + j)] : &wl.qhi[head][8 * (4 * g + j)];
+    return *reinterpret_cast<const h8_t*>(live ? row : wl.zeros);
+  };
+  if constexpr (KT) {
+    if (lane < 8) wl.zeros[lane] = 0;
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int ph = 4 * p + (lane >> 4);
+      const f4_t qa = *reinterpret_cast<const f4_t*>(&q_s[ph][run0]);
+      const f4_t qb = *reinterpret_cast<const f4_t*>(&q_s[ph][run1]);
+      uint16_t qh[8], ql[8];
+      float part[2] = {0.0f, 0.0f};
+#pragma unroll
+      for (int run = 0; run < 2; ++run)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float qc = run ? qb[i] : qa[i];
+          const float t = qc * F::un(i);
+          const uint16_t hi = f2h(t);
+          qh[2 * i + run] = hi;
+          ql[2 * i + run] = f2h(t - h2f(hi));
+          part[run] += qc;
+        }
+      u4_t phi, plo;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        phi[v] = (uint32_t)qh[2 * v] | ((uint32_t)qh[2 * v + 1] << 16);
+        plo[v] = (uint32_t)ql[2 * v] | ((uint32_t)ql[2 * v + 1] << 16);
+      }
+      *reinterpret_cast<u4_t*>(&wl.qhi[ph][8 * prep_sg]) = phi;
+      *reinterpret_cast<u4_t*>(&wl.qlo[ph][8 * prep_sg]) = plo;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const float x = row_sum16((run0 / G == v ? part[0] : 0.0f) + (run1 / G == v ? part[1] : 0.0f));
+        if (prep_sg == 0) wl.qsum[ph][v] = x;
+      }
+    }
+    wave_sync();
+    qinv = qinv_s[head];
+#pragma unroll
+    for (int k = 0; k < CH; ++k) {
+      const int v = k * COPIES + cp;
+      zq_k[k] = (v & 1) ? 0.0f : wl.qsum[head][v >> 1];
+    }
+    if constexpr (kKeepB) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bqk[0][j] = chain_operand(0, j);
+    }
+  }
+
   // Paged: table entry of block n (-1 past the end of the row), and the first block at or after
   // n, in this wave's stride, whose entry names a page of the pool; entries that do not are
   // skipped and reported in *status.
@@ -373,7 +467,15 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
     if (PAGED) nblk = first_valid(nblk, nblk < blk1 ? table_entry(nblk) : -1, nbi);
     const bool has_next = nblk < blk1;
     if constexpr (kDeep) issue_values(bi);
-    if (g < NG) {   // K parameters of the block: every token group from the lane group that fetched it
+    if constexpr (KT) {   // K parameters of the block's tokens, per channel group
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const uint32_t pr = ktp[u * NV + v];
+          wl.ktpar[v][par_slot(2 * lane + u)] = make_float2(h2f((uint16_t)(pr & 0xFFFFu)) * kTwo24, h2f((uint16_t)(pr >> 16)));
+        }
+    } else if (g < NG) {   // K parameters of the block: every token group from the lane group that fetched it
       *reinterpret_cast<u4_t*>(&wl.kpar[g][run0]) = kp0;
       *reinterpret_cast<u4_t*>(&wl.kpar[g][run1]) = kp1;
     }
@@ -401,6 +503,52 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       __builtin_amdgcn_sched_barrier(0);
+      if constexpr (KT) {
+        if (c == 0) wave_sync();   // the block's K parameters are staged
+        h8_t bload[kKeepB ? 1 : CH][4];
+        if constexpr (!kKeepB) {
+#pragma unroll
+          for (int k = 0; k < CH; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bload[k][j] = chain_operand(k, j);
+        }
+        auto bop = [&](int k, int j) -> h8_t {
+          if constexpr (!kKeepB) return bload[k][j];
+          else return bqk[k][j];
+        };
+        const bool mine = c % COPIES == cp;
+#pragma unroll
+        for (int run = 0; run < 2; ++run) {
+          const int T = 2 * c + run;
+          h8_t ak[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) ak[j] = F::dequant(kraw[T].w, j);
+          float val[4] = {0.f, 0.f, 0.f, 0.f};
+          const int slot = par_slot(F::run_base(4 * c + g, run));
+#pragma unroll
+          for (int k = 0; k < CH; ++k) {
+            f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak[j], bop(k, j), acc, 0, 0, 0);
+            const float2* par = &wl.ktpar[(k * COPIES + cp) >> 1][slot];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float2 sz = par[r];
+              val[r] = __builtin_fmaf(sz.x, acc[r], __builtin_fmaf(sz.y, zq_k[k], val[r]));
+            }
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float x = val[r];
+            if (COPIES == 4) x += dpp_f<kRowRor4>(x);
+            if (COPIES >= 2) x += dpp_f<kRowRor8>(x);
+            x *= qinv;
+            sc[c / COPIES][run][r] = mine ? x : sc[c / COPIES][run][r];
+          }
+        }
+        continue;
+      }
       if ((32 * c) % G == 0) {   // the chunk opens a token group: new Q'
         wave_sync();             // the previous Q' has been read by every lane
         prep_queries((32 * c) / G);
@@ -589,14 +737,14 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP)) void decode_
   }
 }
 
-template <int BITS, int G>
+template <int BITS, int G, bool KT = false>
 void launch_heads(const GrpArgs& a, bool paged, dim3 grid, hipStream_t st) {
   if (paged) {
-    if (a.gq <= 4) decode_grp_kernel<BITS, G, 4, true><<<grid, dim3(256), 0, st>>>(a);
-    else decode_grp_kernel<BITS, G, 8, true><<<grid, dim3(256), 0, st>>>(a);
+    if (a.gq <= 4) decode_grp_kernel<BITS, G, 4, true, KT><<<grid, dim3(256), 0, st>>>(a);
+    else decode_grp_kernel<BITS, G, 8, true, KT><<<grid, dim3(256), 0, st>>>(a);
   } else {
-    if (a.gq <= 4) decode_grp_kernel<BITS, G, 4, false><<<grid, dim3(256), 0, st>>>(a);
-    else decode_grp_kernel<BITS, G, 8, false><<<grid, dim3(256), 0, st>>>(a);
+    if (a.gq <= 4) decode_grp_kernel<BITS, G, 4, false, KT><<<grid, dim3(256), 0, st>>>(a);
+    else decode_grp_kernel<BITS, G, 8, false, KT><<<grid, dim3(256), 0, st>>>(a);
   }
 }
 
@@ -607,6 +755,10 @@ hipError_t launch_format(int format, const GrpArgs& a, bool paged, int batch, hi
     case BD_FMT_INT4_G32: launch_heads<4, 32>(a, paged, grid, st); break;
     case BD_FMT_INT2_G64: launch_heads<2, 64>(a, paged, grid, st); break;
     case BD_FMT_INT2_G32: launch_heads<2, 32>(a, paged, grid, st); break;
+    case BD_FMT_INT4_KT_G64: launch_heads<4, 64, true>(a, paged, grid, st); break;
+    case BD_FMT_INT4_KT_G32: launch_heads<4, 32, true>(a, paged, grid, st); break;
+    case BD_FMT_INT2_KT_G64: launch_heads<2, 64, true>(a, paged, grid, st); break;
+    case BD_FMT_INT2_KT_G32: launch_heads<2, 32, true>(a, paged, grid, st); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

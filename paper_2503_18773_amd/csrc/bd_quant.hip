@@ -456,6 +456,10 @@ hipError_t launch_quant_blocks(const void* k, const void* v, long src_unit_strid
     BD_QUANT_CASE(BD_FMT_INT4_G32, 4, false, 32)
     BD_QUANT_CASE(BD_FMT_INT2_G64, 2, false, 64)
     BD_QUANT_CASE(BD_FMT_INT2_G32, 2, false, 32)
+    BD_QUANT_CASE(BD_FMT_INT4_KT_G64, 4, true, 64)
+    BD_QUANT_CASE(BD_FMT_INT4_KT_G32, 4, true, 32)
+    BD_QUANT_CASE(BD_FMT_INT2_KT_G64, 2, true, 64)
+    BD_QUANT_CASE(BD_FMT_INT2_KT_G32, 2, true, 32)
     default: return hipErrorInvalidValue;
   }
 #undef BD_QUANT_CASE
@@ -520,6 +524,10 @@ hipError_t launch_paged_prefill(const bd_paged_cache* c, int seq, const void* k,
       case BD_FMT_INT4_G32: paged_quant_kernel<4, false, 32><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
       case BD_FMT_INT2_G64: paged_quant_kernel<2, false, 64><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
       case BD_FMT_INT2_G32: paged_quant_kernel<2, false, 32><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4_KT_G64: paged_quant_kernel<4, true, 64><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT4_KT_G32: paged_quant_kernel<4, true, 32><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2_KT_G64: paged_quant_kernel<2, true, 64><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
+      case BD_FMT_INT2_KT_G32: paged_quant_kernel<2, true, 32><<<grid, block, 0, st>>>(a, kk, vv, seq, L); break;
       default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
@@ -550,6 +558,10 @@ hipError_t launch_paged_append(const bd_paged_cache* c, const void* k_new, const
     case BD_FMT_INT4_G32: paged_append_kernel<4, false, 32><<<grid, block, 0, st>>>(a, kk, vv); break;
     case BD_FMT_INT2_G64: paged_append_kernel<2, false, 64><<<grid, block, 0, st>>>(a, kk, vv); break;
     case BD_FMT_INT2_G32: paged_append_kernel<2, false, 32><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4_KT_G64: paged_append_kernel<4, true, 64><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT4_KT_G32: paged_append_kernel<4, true, 32><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2_KT_G64: paged_append_kernel<2, true, 64><<<grid, block, 0, st>>>(a, kk, vv); break;
+    case BD_FMT_INT2_KT_G32: paged_append_kernel<2, true, 32><<<grid, block, 0, st>>>(a, kk, vv); break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();

@@ -206,9 +206,10 @@ __device__ __forceinline__ h2_t lanes_min(h2_t m) {
 // quant_block: the whole workgroup (256 threads) quantizes the 128 token rows at ksrc / vsrc
 // ([128][128] fp16) into packed block `dblk` of the four destination arrays.
 // KT: K statistics per token (over its 128 channels) instead of per channel (Sec. IV-C(1)).
-// G: quantization group (128, 64 or 32; not with KT): K statistics over G tokens per channel --
+// G: quantization group (128, 64 or 32): K statistics over G tokens per channel --
 //    a wave holds 32 tokens, so the cross-wave step of the ladder joins G/32 waves -- and V
 //    statistics over G channels per token; parameters [block][128/G][D] and [block][128][D/G].
+//    With KT, K's statistics run over G channels per token like V's ([block][128][D/G]).
 // A thread holds 64 values of each tensor: 8 token rows x 8 consecutive channels, i.e. one K word per
 // token and one V word per channel at 4 bits, half words at 2 bits.  Minima and maxima are taken on the fp16 pairs as loaded (packed
 // instructions), across lanes with shuffles and, for channel-wise K, across waves through LDS
@@ -221,7 +222,6 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
   constexpr int QMAX = (1 << BITS) - 1;
   constexpr int CPT = 32 / BITS;     // codes per word
   constexpr int NG = kBlock / G;     // K token groups per block == V channel groups per token
-  static_assert(!KT || G == kBlock, "per-token K has one group per token");
   __shared__ uint32_t red_lo[4][kD / 2], red_hi[4][kD / 2];   // per wave: packed fp16 minima / maxima of channel pairs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
@@ -286,8 +286,12 @@ __device__ __forceinline__ void quant_block(const uint16_t* __restrict__ ksrc, c
     };
     if constexpr (KT) {
       uint32_t lo[T], hi[T];
-      token_rows(kraw, std::integral_constant<int, NCG>{},
-                 [&](int t, uint32_t packed) { if (cg == 0) (k_params + dblk * kBlock)[(uint32_t)krow(t)] = packed; }, lo, hi);
+      constexpr int LPG = NCG / NG;   // consecutive lanes that hold one channel group of a token row
+      token_rows(kraw, std::integral_constant<int, LPG>{},
+                 [&](int t, uint32_t packed) {
+                   if (cg % LPG == 0) (k_params + dblk * (kBlock * NG))[(uint32_t)(krow(t) * NG + cg / LPG)] = packed;
+                 },
+                 lo, hi);
 #pragma unroll
       for (int t = 0; t < T; ++t) store_k_row(t, lo[t], hi[t]);
     } else {

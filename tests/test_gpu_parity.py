@@ -11,15 +11,17 @@ from tests.util import assert_attn_close, out_to_f64, to_dev
 
 pytestmark = pytest.mark.gpu
 
-BITS = {"int4": 4, "int2": 2, "int4_kt": 4, "int2_kt": 2, "int4_g64": 4, "int4_g32": 4, "int2_g64": 2, "int2_g32": 2}
-GROUP = {"int4_g64": 64, "int4_g32": 32, "int2_g64": 64, "int2_g32": 32}
+BITS = {"int4": 4, "int2": 2, "int4_kt": 4, "int2_kt": 2, "int4_g64": 4, "int4_g32": 4, "int2_g64": 2, "int2_g32": 2,
+        "int4_kt_g64": 4, "int4_kt_g32": 4, "int2_kt_g64": 2, "int2_kt_g32": 2}
+GROUP = {"int4_g64": 64, "int4_g32": 32, "int2_g64": 64, "int2_g32": 32,
+         "int4_kt_g64": 64, "int4_kt_g32": 32, "int2_kt_g64": 64, "int2_kt_g32": 32}
 GROUP_FORMATS = sorted(GROUP)
 
 
 def _int_cache_pair(w, capacity):
     """Oracle cache and GPU cache prefilled from the same K, V."""
     K, V = W.make_kv(w)
-    oc = O.IntCache(w.batch, w.n_kv_heads, BITS[w.fmt], capacity, k_per_token=w.fmt.endswith("_kt"),
+    oc = O.IntCache(w.batch, w.n_kv_heads, BITS[w.fmt], capacity, k_per_token="_kt" in w.fmt,
                     group=GROUP.get(w.fmt, 128))
     oc.quant_pack_kv(K, V)
     gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, capacity)
@@ -368,7 +370,7 @@ def test_cfg4_mxfp4_full_size_all_units():
 
 # ---------------------------------------------------------------------------- fused step
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32", "int2_g64"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32", "int2_g64", "int4_kt_g32", "int2_kt_g64"])
 def test_decode_step_equals_append_then_attention(fmt):
     """bd_decode_step is defined as bd_append_kv + bd_decode_attn: same output bits, same cache,
     same lengths, on ordinary steps, on the step that fills the residual block and after it."""
@@ -431,7 +433,7 @@ def test_decode_step_packs_the_full_block_inside_the_attention_launch(fmt, gq):
                 assert np.array_equal(a.host_buffer(i), b.host_buffer(i)), (fmt, gq, nblocks, ns, i)
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64", "int2_kt_g32"])
 @pytest.mark.parametrize("gq", [4, 20])
 def test_lazy_decode_step_attends_the_full_residual_in_fp16(fmt, gq):
     """bd_decode_step_lazy (the paper's flush order): on the step that fills the residual block the attention sees
@@ -490,7 +492,7 @@ def _paged_pair(fmt, lens, H, Hq, num_pages, max_pages, seed=31, table=None):
     rng = np.random.default_rng(seed)
     if table is None:
         table = rng.permutation(num_pages)[:B_ * max_pages].reshape(B_, max_pages).astype(np.int32)
-    oc = O.PagedIntCache(B_, H, BITS[fmt], num_pages, max_pages, table, k_per_token=fmt.endswith("_kt"),
+    oc = O.PagedIntCache(B_, H, BITS[fmt], num_pages, max_pages, table, k_per_token="_kt" in fmt,
                          group=GROUP.get(fmt, 128))
     gc = B.PagedKVCache(B_, Hq, H, fmt, num_pages, table)
     for b, L in enumerate(lens):
@@ -518,7 +520,7 @@ def _assert_paged_equal(oc, gc, what):
             assert np.array_equal(got[b, :, :r].view(np.uint16), ref[b, :, :r].view(np.uint16)), (what, name, b)
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_g32", "int2_g64", "int4_g64", "int2_g32"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_g32", "int2_g64", "int4_g64", "int2_g32", "int4_kt_g32", "int2_kt_g64", "int4_kt_g64", "int2_kt_g32"])
 def test_paged_prefill_append_and_decode_match_oracle(fmt):
     """Ragged batch on scattered pages: pool bytes bit-exact after prefill and after appends that
     carry two sequences over a flush; attention within tolerance at several split factors,
@@ -750,7 +752,7 @@ def test_paged_mx_long_batch_all_units():
     assert list(gc.seq_lens.cpu().numpy()) == [L + 1 for L in lens] and int(gc.status.item()) == 0
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32", "int2_g64"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32", "int2_g64", "int4_kt_g32", "int2_kt_g64"])
 def test_paged_fused_step_equals_append_then_attention(fmt):
     """bd_paged_decode_step against bd_paged_append_kv + bd_paged_decode_attn on a twin cache:
     outputs, pool bytes and lengths identical bit for bit over steps that cross block
@@ -908,8 +910,9 @@ def test_group_quant_adversarial_and_append_bit_exact(fmt):
     V[0, 1, 8, 0] = 65504; V[0, 1, 8, 70] = -65504
     V[0, 1, 9, 64:128] = (rng.integers(0, 3, 64) * 6e-8).astype(np.float16)
     V[0, 1, 10, 96:128] = np.array([0, 3] + [0.5, 1.5, 2.5, 1.0] * 7 + [2, 2], np.float16)
+    K[0, 1, 7:11] = V[0, 1, 7:11]               # (the same rows for per-token K groups)
     w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=2, n_kv_heads=2, context=200, fmt=fmt, seed=9)
-    oc = O.IntCache(1, 2, BITS[fmt], 384, group=GROUP[fmt]); oc.quant_pack_kv(K, V)
+    oc = O.IntCache(1, 2, BITS[fmt], 384, k_per_token="_kt" in fmt, group=GROUP[fmt]); oc.quant_pack_kv(K, V)
     gc = B.KVCache(1, 2, 2, fmt, 384); gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
     _assert_int_cache_equal(oc, gc)
     for i in range(60):
@@ -955,7 +958,7 @@ def test_group_decode_short_and_empty(fmt):
         w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=4, n_kv_heads=1, context=max(L, 1), fmt=fmt, seed=80)
         K, V = W.make_kv(w)
         K, V = np.ascontiguousarray(K[:, :, :L]), np.ascontiguousarray(V[:, :, :L])
-        oc = O.IntCache(1, 1, BITS[fmt], 256, group=GROUP[fmt]); oc.quant_pack_kv(K, V)
+        oc = O.IntCache(1, 1, BITS[fmt], 256, k_per_token="_kt" in fmt, group=GROUP[fmt]); oc.quant_pack_kv(K, V)
         gc = B.KVCache(1, 4, 1, fmt, 256); gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
         q = W.make_q(w)
         got = _decode(gc, w, q, num_splits=2)
@@ -1043,7 +1046,7 @@ def test_outputs_do_not_depend_on_the_magnitude_of_k_and_v(fmt, gq):
             # one channel group of V far smaller than the others, and for a stretch of the sequence smaller still
             V[..., 32:64] = (V[..., 32:64].astype(np.float32) * np.float32(2.0 ** -6)).astype(np.float16)
             V[:, :, :900, 32:64] = (V[:, :, :900, 32:64].astype(np.float32) * np.float32(2.0 ** -4)).astype(np.float16)
-        oc = O.IntCache(w.batch, w.n_kv_heads, BITS[fmt], 128 * 35, k_per_token=fmt.endswith("_kt"),
+        oc = O.IntCache(w.batch, w.n_kv_heads, BITS[fmt], 128 * 35, k_per_token="_kt" in fmt,
                         group=GROUP.get(fmt, 128))
         oc.quant_pack_kv(K, V)
         gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, 128 * 35)
@@ -1094,7 +1097,7 @@ def test_mx_outputs_do_not_depend_on_the_magnitude_of_k_and_v(gq):
             assert rl <= 1e-3 and ma <= 2e-3, f"mxfp4 gq={gq} K x {ks} V x {vs} splits {ns}: rel-L2 {rl:.2e}, max-abs / max |ref| {ma:.2e}"
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64", "mxfp4"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_g64", "int4_kt_g64", "mxfp4"])
 def test_peaked_and_flat_attention(fmt):
     """Queries scaled by 6 (logits of several tens: a handful of tokens take all the weight and the
     running maximum moves across blocks and splits; much larger logits only test the conditioning of
@@ -1381,7 +1384,7 @@ def test_seeded_paged_sweep():
             oc, gc, _ = _paged_mx_pair(lens, H, gq * H, num_pages, max_pages, seed=4000 + case)
         else:
             table = np.random.default_rng(5000 + case).permutation(num_pages)[:Bn * max_pages].reshape(Bn, max_pages).astype(np.int32)
-            oc = O.PagedIntCache(Bn, H, BITS[fmt], num_pages, max_pages, table, k_per_token=fmt.endswith("_kt"),
+            oc = O.PagedIntCache(Bn, H, BITS[fmt], num_pages, max_pages, table, k_per_token="_kt" in fmt,
                                  group=GROUP.get(fmt, 128))
             gc = B.PagedKVCache(Bn, gq * H, H, fmt, num_pages, table)
             for b_, L in enumerate(lens):

@@ -51,11 +51,13 @@ def test_cache_bytes_match_the_format():
     assert B.bd_cache_bytes(_desc(head_dim=64), 0) == 0
     assert B.bd_cache_bytes(c, 6) == 0
     # quantization groups of 64 / 32: the codes stay, the parameter arrays grow by 128 / group
-    for fmt, per in [(B.BD_FMT_INT4_G64, 144), (B.BD_FMT_INT4_G32, 160), (B.BD_FMT_INT2_G64, 80), (B.BD_FMT_INT2_G32, 96)]:
+    for fmt, per in [(B.BD_FMT_INT4_G64, 144), (B.BD_FMT_INT4_G32, 160), (B.BD_FMT_INT2_G64, 80), (B.BD_FMT_INT2_G32, 96),
+                     (B.BD_FMT_INT4_KT_G64, 144), (B.BD_FMT_INT4_KT_G32, 160), (B.BD_FMT_INT2_KT_G64, 80),
+                     (B.BD_FMT_INT2_KT_G32, 96)]:
         cg = _desc(format=fmt)
         assert sum(B.bd_cache_bytes(cg, i) for i in range(4)) == per * units * cap
         assert B.bd_cache_bytes(cg, 4) == units * 128 * 128 * 2
-    assert B.bd_cache_bytes(_desc(format=9), 0) == 0
+    assert B.bd_cache_bytes(_desc(format=13), 0) == 0
 
 
 @needs_lib
