@@ -111,8 +111,9 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP, KT)) void dec
   // requests a block's values before its keys are consumed and the next block's keys right after
   // ("deep").  With two waves the other one covers and the short queue of the group-128 kernel is
   // better (measured, groups of 64: 13.2 against 13.7 us at 32K, 30.9 against 33.2 us at 128K),
-  // except for 2-bit codes, whose blocks are half the bytes (42.9 against 45.3 us at 8 x 32K).
-  constexpr bool kDeep = BITS == 2 || grp_waves_per_simd(BITS, G, GQP, KT) == 1;
+  // except for 2-bit codes, whose blocks are half the bytes (42.9 against 45.3 us at 8 x 32K) -- but not for
+  // per-token K in groups of 32 at 2 bits, where the deep queue's registers would spill.
+  constexpr bool kDeep = (BITS == 2 && !(KT && G == 32)) || grp_waves_per_simd(BITS, G, GQP, KT) == 1;
   using F = Fmt<BITS>;
   constexpr int WORDS = F::WORDS;
   constexpr int KROW = kD * BITS / 32;       // K words per token
