@@ -27,7 +27,6 @@ namespace {
 
 constexpr int kWaves = 4;
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kRowShl12 = 0x10C;
 
 struct MxArgs {
   const uint8_t* k_codes;

@@ -19,7 +19,7 @@ __device__ __forceinline__ uint16_t f2h(float f) {
 }
 
 // DPP lane movement inside rows of 16 lanes.
-constexpr int kRowShl4 = 0x104, kRowShl8 = 0x108, kRowShr4 = 0x114, kRowShr8 = 0x118, kRowRor4 = 0x124, kRowRor8 = 0x128;
+constexpr int kRowShl4 = 0x104, kRowShl8 = 0x108, kRowShl12 = 0x10C, kRowShr4 = 0x114, kRowShr8 = 0x118, kRowRor4 = 0x124, kRowRor8 = 0x128;
 constexpr int kQuadSwap1 = 0xB1 /* [1,0,3,2] */, kQuadSwap2 = 0x4E /* [2,3,0,1] */;
 constexpr int kRowHalfMirror = 0x141, kRowMirror = 0x140;
 

@@ -5,6 +5,7 @@
 // subtract / divide / round-half-even in a fixed order, so contraction into FMAs is switched
 // off for this file and no fast-math substitution is allowed.
 #include "bd_common.h"
+#include "bd_device.h"
 #include "bd_quant_block.h"
 #include "bd_mx_token.h"
 
@@ -256,119 +257,120 @@ __global__ __launch_bounds__(128) void mx_quant_kernel(const uint16_t* __restric
   }
 }
 
-// Whole 128-token blocks of an MXFP4 cache (the bulk of a prefill).  256 threads; a thread takes
-// one MX group (32 channels) of a token at a time -- 64 contiguous bytes, neighbouring lanes
-// neighbouring groups, so every load and every K store is fully coalesced -- twice per tensor.
-// The group maximum is taken on the bf16 magnitudes as loaded (packed 16-bit maxima); codes
-// come from v_cvt_scalef32_pk_fp4_f32 (nearest e2m1, ties to the even code, saturating: measured
-// identical to the definition) except that it keeps the sign of values that round to zero,
-// which is cleared afterwards; groups with a very small maximum (shared exponent below -120,
-// where elements can be fp32 subnormals) take the explicit path.  V codes meet their
-// neighbouring token's (one byte = two tokens) by a DPP lane shift and reach their
-// channel-major place through an LDS tile.
-__global__ __launch_bounds__(256) void mx_quant_block_kernel(const uint16_t* __restrict__ ksrc,
-                                                              const uint16_t* __restrict__ vsrc,
-                                                              long src_unit_stride, MxDst d, int dst_blk0) {
-  constexpr int PITCH = 80;   // bytes per channel row of the tile (64 used; 16-byte aligned rows)
-  __shared__ __attribute__((aligned(16))) uint8_t tile[kD * PITCH];
-  uint8_t *k_codes = d.k_codes, *k_scales = d.k_scales, *v_codes = d.v_codes, *v_scales = d.v_scales;
-  const int unit = blockIdx.y, blk = dst_blk0 + blockIdx.x, tid = threadIdx.x, g = tid & 3;
+// Whole 128-token blocks of an MXFP4 cache (the bulk of a prefill), in the tiling of the integer block
+// quantizer: 256 threads, a thread holds 8 token rows x 8 consecutive channels of each tensor (one 16-byte
+// load per row; 16 lanes per token row, so every load of a wave covers 1 KB of contiguous source and the
+// four lanes of a DPP quad hold one MX group).  K rows are four apart inside the wave's 32 tokens, so that
+// one store of the wave covers four consecutive token rows of codes; V rows are consecutive: a channel's
+// 8 tokens are one 32-bit word of the channel-major block layout, which is the 4-bit integer layout
+// (transposed in registers, put in address order through an LDS tile, stored 16 bytes at a time).
+// The group maximum is taken on the bf16 magnitudes as loaded (packed 16-bit maxima, then the quad);
+// codes come from v_cvt_scalef32_pk_fp4_f32 (nearest e2m1, ties to the even code, saturating: measured
+// identical to the definition) except that it keeps the sign of values that round to zero, which is
+// cleared afterwards; groups with a very small maximum (shared exponent below -120, where elements can be
+// fp32 subnormals) take the explicit path.  Source rows and codes are streaming (non-temporal) accesses.
+__global__ __launch_bounds__(256, 4) void mx_quant_block_kernel(const uint16_t* __restrict__ ksrc,
+                                                                 const uint16_t* __restrict__ vsrc,
+                                                                 long src_unit_stride, MxDst d, int dst_blk0) {
+  constexpr int C = 8, T = 8, NCG = kD / C, WPC = kBlock / 8;   // 16 lanes per row; 16 words per channel
+  __shared__ uint32_t vw[kD][WPC + 1];
+  const int unit = blockIdx.y, blk = dst_blk0 + blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long bi = mx_block_index(d, unit, blk);
   if (bi < 0) return;
   const size_t src_blk = (size_t)unit * src_unit_stride + (size_t)blockIdx.x * kBlock * kD;
-#pragma unroll 1
-  for (int which = 0; which < 2; ++which) {
-    const uint16_t* src = (which == 0 ? ksrc : vsrc) + src_blk;
+  const int cg = tid % NCG, tg = tid / NCG;
+  auto krow = [&](int t) { return 32 * wave + (lane >> 4) + 4 * t; };
+  auto vrow = [&](int t) { return T * tg + t; };
+  u4_t kraw[T], vraw[T];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int tl = (tid >> 2) + 64 * i;   // token inside the block
-      const size_t tok = (size_t)bi * kBlock + tl;
-      const uint16_t* sp = src + (size_t)tl * kD + kMxGroup * g;
-      uint32_t raw[16];
+  for (int t = 0; t < T; ++t)
+    kraw[t] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(ksrc + src_blk + (size_t)krow(t) * kD + C * cg));
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const u4_t ld = *reinterpret_cast<const u4_t*>(sp + 8 * v);
-        raw[4 * v] = ld[0]; raw[4 * v + 1] = ld[1]; raw[4 * v + 2] = ld[2]; raw[4 * v + 3] = ld[3];
-      }
-      typedef unsigned short us2_t __attribute__((ext_vector_type(2)));
-      us2_t m2 = {0, 0};
+  for (int t = 0; t < T; ++t)
+    vraw[t] = __builtin_nontemporal_load(reinterpret_cast<const u4_t*>(vsrc + src_blk + (size_t)vrow(t) * kD + C * cg));
+
+  // the 8 codes of one row of this lane (channel C*cg + n at nibble n) and the group's scale byte
+  auto row_codes = [&](const u4_t& raw, uint32_t& word, uint32_t& ebyte) {
+    typedef unsigned short us2_t __attribute__((ext_vector_type(2)));
+    us2_t m2 = {0, 0};
 #pragma unroll
-      for (int w = 0; w < 16; ++w)
-        m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2_t, raw[w] & 0x7FFF7FFFu));
-      const uint32_t mag = m2[0] > m2[1] ? m2[0] : m2[1];   // bf16 bits of the largest magnitude
-      int e = 0;
-      if (mag != 0) {
-        e = (int)(mag >> 7) - 127 - 2;   // floor(log2 amax) - 2 from the exponent field
-        e = e < -127 ? -127 : e;
-      }
-      uint32_t cw[4] = {0u, 0u, 0u, 0u};   // 32 codes: channel 8w + n of the group at nibble n of cw[w]
-      if (mag != 0) {
-        if (e >= -120) {
-          const float scale = __uint_as_float((uint32_t)(e + 127) << 23);
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            uint32_t c = 0;
-#define BD_CVT_PAIR(b)                                                                                        \
-  c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, __uint_as_float(raw[4 * w + b] << 16),                      \
-                                               __uint_as_float(raw[4 * w + b] & 0xFFFF0000u), scale, b)
-            BD_CVT_PAIR(0);
-            BD_CVT_PAIR(1);
-            BD_CVT_PAIR(2);
-            BD_CVT_PAIR(3);
+    for (int w = 0; w < 4; ++w) m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(us2_t, raw[w] & 0x7FFF7FFFu));
+    uint32_t mag = m2[0] > m2[1] ? m2[0] : m2[1];   // bf16 bits of the largest magnitude of this lane's 8 values
+    mag = max(mag, dpp_u<kQuadSwap1>(mag));
+    mag = max(mag, dpp_u<kQuadSwap2>(mag));        // ... of the MX group (the quad)
+    int e = 0;
+    if (mag != 0) {
+      e = (int)(mag >> 7) - 127 - 2;   // floor(log2 amax) - 2 from the exponent field
+      e = e < -127 ? -127 : e;
+    }
+    uint32_t c = 0;
+    if (mag != 0) {
+      if (e >= -120) {
+        const float scale = __uint_as_float((uint32_t)(e + 127) << 23);
+#define BD_CVT_PAIR(b)                                                                                          \
+  c = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(c, __uint_as_float(raw[b] << 16), __uint_as_float(raw[b] & 0xFFFF0000u), \
+                                               scale, b)
+        BD_CVT_PAIR(0);
+        BD_CVT_PAIR(1);
+        BD_CVT_PAIR(2);
+        BD_CVT_PAIR(3);
 #undef BD_CVT_PAIR
-            // a value that rounds to zero is stored as +0: drop the sign of nibbles with no magnitude
-            const uint32_t m = c & 0x77777777u;
-            cw[w] = (((m + 0x77777777u) & c) & 0x88888888u) | m;
-          }
-        } else {
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-#pragma unroll
-            for (int n = 0; n < 8; ++n) {
-              const uint32_t r = raw[4 * w + (n >> 1)];
-              const float x = __uint_as_float((n & 1) ? (r & 0xFFFF0000u) : (r << 16));
-              cw[w] |= e2m1_code(x, e) << (4 * n);
-            }
-        }
-      }
-      if (which == 0) {
-        k_scales[tok * 4 + g] = (uint8_t)(e + 127);
-        u4_t out = {cw[0], cw[1], cw[2], cw[3]};
-        *reinterpret_cast<u4_t*>(k_codes + tok * (kD / 2) + g * 16) = out;
+        // a value that rounds to zero is stored as +0: drop the sign of nibbles with no magnitude
+        const uint32_t m = c & 0x77777777u;
+        c = (((m + 0x77777777u) & c) & 0x88888888u) | m;
       } else {
-        v_scales[tok * 4 + g] = (uint8_t)(e + 127);
-        // the next token's codes of the same group sit 4 lanes up
-        uint32_t pw[4];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) pw[w] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)cw[w], 0x104, 0xF, 0xF, true);
-        if (((tid >> 2) & 1) == 0) {   // even token: byte j = tl / 2 of 32 channel rows
-          const int col = ((tl >> 1) + 16 * g) & 63;   // rows of group g are rotated by 16 g bytes (bank spread)
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const uint32_t be = (cw[w] & 0x0F0F0F0Fu) | ((pw[w] & 0x0F0F0F0Fu) << 4);          // channels 0, 2, 4, 6
-            const uint32_t bo = ((cw[w] >> 4) & 0x0F0F0F0Fu) | (pw[w] & 0xF0F0F0F0u);          // channels 1, 3, 5, 7
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              const int ch = kMxGroup * g + 8 * w + 2 * k;
-              tile[ch * PITCH + col] = (uint8_t)(be >> (8 * k));
-              tile[(ch + 1) * PITCH + col] = (uint8_t)(bo >> (8 * k));
-            }
-          }
+        for (int n = 0; n < 8; ++n) {
+          const uint32_t r = raw[n >> 1];
+          const float x = __uint_as_float((n & 1) ? (r & 0xFFFF0000u) : (r << 16));
+          c |= e2m1_code(x, e) << (4 * n);
         }
       }
     }
-  }
-  __syncthreads();
-  // channel-major V codes of the block: 128 rows of 64 bytes, each thread half a row
-  {
-    const int row = tid >> 1, hf = tid & 1, gg = row >> 5;
-    uint8_t* dst = v_codes + ((size_t)bi * kD + row) * 64 + 32 * hf;
+    word = c;
+    ebyte = (uint32_t)(e + 127);
+  };
+  // the four scale bytes of a token row, gathered in the row's first lane
+  auto row_scales = [&](uint32_t ebyte) {
+    return ebyte | (dpp_u<kRowShl4>(ebyte) << 8) | (dpp_u<kRowShl8>(ebyte) << 16) | (dpp_u<kRowShl12>(ebyte) << 24);
+  };
+
+  // ---- K: token-major codes, one word per lane and row
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const int chunk = 2 * hf + c;
-      const u4_t val = *reinterpret_cast<const u4_t*>(&tile[row * PITCH + 16 * ((chunk + gg) & 3)]);
-      *reinterpret_cast<u4_t*>(dst + 16 * c) = val;
-    }
+  for (int t = 0; t < T; ++t) {
+    uint32_t word, ebyte;
+    row_codes(kraw[t], word, ebyte);
+    const size_t tok = (size_t)bi * kBlock + krow(t);
+    __builtin_nontemporal_store(word, reinterpret_cast<uint32_t*>(d.k_codes + tok * (kD / 2)) + cg);
+    const uint32_t sc4 = row_scales(ebyte);
+    if (cg == 0) *reinterpret_cast<uint32_t*>(d.k_scales + tok * 4) = sc4;
+  }
+  // ---- V: channel-major codes
+  uint32_t lo[T], hi[T];   // per token: the codes of channels 0..3 / 4..7 of this lane, one per byte
+#pragma unroll
+  for (int t = 0; t < T; ++t) {
+    uint32_t word, ebyte;
+    row_codes(vraw[t], word, ebyte);
+    const size_t tok = (size_t)bi * kBlock + vrow(t);
+    const uint32_t sc4 = row_scales(ebyte);
+    if (cg == 0) *reinterpret_cast<uint32_t*>(d.v_scales + tok * 4) = sc4;
+    const uint32_t x = word & 0x0F0F0F0Fu, y = (word >> 4) & 0x0F0F0F0Fu;   // even / odd channels, one per byte
+    lo[t] = __builtin_amdgcn_perm(y, x, 0x05010400u);   // x.b0 y.b0 x.b1 y.b1
+    hi[t] = __builtin_amdgcn_perm(y, x, 0x07030602u);   // x.b2 y.b2 x.b3 y.b3
+  }
+  uint32_t words[C];   // channel c: its 8 tokens' codes, token t at nibble t
+  transpose_code_bytes<4>(lo, words);
+  transpose_code_bytes<4>(hi, words + 4);
+#pragma unroll
+  for (int c = 0; c < C; ++c) vw[C * cg + c][tg] = words[c];
+  __syncthreads();
+  uint32_t* vdst = reinterpret_cast<uint32_t*>(d.v_codes) + (size_t)bi * (kD * WPC);
+#pragma unroll
+  for (int k = 0; k < kD * WPC / 1024; ++k) {
+    const int idx = 4 * (tid + 256 * k);
+    const uint32_t* row = &vw[idx / WPC][idx % WPC];
+    const u4_t w4 = {row[0], row[1], row[2], row[3]};
+    __builtin_nontemporal_store(w4, reinterpret_cast<u4_t*>(vdst + idx));
   }
 }
 
