@@ -222,17 +222,19 @@ def main() -> int:
         print(json.dumps({"calib_copy_bytes": 1 << 30, "launches": 5}))
         return 0
     B.lib()  # fail loudly if the HIP library is missing
-    rec = run(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    rec, cpu_job = run(args, args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
     if args.workload == "cfg1" and not args.variant and not args.no_128k:
         # the metric is quoted at 32K and at 128K: the same measurement on cfg3 (fewer steps: each moves 4x the bytes)
         torch.cuda.empty_cache()
-        r3 = run(args, "cfg3", max(args.steps // 4, 3), min(args.warmup, 2), False)
+        r3, _ = run(args, "cfg3", max(args.steps // 4, 3), min(args.warmup, 2), False)
         rec["roofline_128k"] = r3["roofline"]
         rec["stream_roof_128k"] = r3["stream_roof"]
         rec["step_128k"] = {k: r3[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "us_per_layer_call",
                                                  "pct_hbm_peak", "prefill_quant_pack_ms_per_layer")}
         rec["step_128k"]["workload"] = r3["config"]["workload"]
         rec["step_128k"]["num_splits"] = r3["config"]["num_splits"]
+    if cpu_job is not None:
+        rec["cpu_baseline"] = oracle_baseline(*cpu_job)
     print(json.dumps(rec))
     return 0
 
@@ -390,8 +392,9 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
     roofline, stream_roof = kernel_roofline(B, W, torch, w, caches, qs[-1], outs, splits, paged, sm_scale, args.variant,
                                             total_steps)
     del caches, outs, new_kv, qs
-    # ---- the oracle on the host cores, on a bounded sample of the same workload
-    cpu = oracle_baseline(w, K, V, cap, args.cpu_seconds, sm_scale) if with_cpu else None
+    # ---- the oracle on the host cores, on a bounded sample of the same workload: after every GPU measurement
+    #      of the run (ten idle seconds in between would let the GPU's clocks drop), so only its inputs are kept
+    cpu_job = (w, K, V, cap, args.cpu_seconds, sm_scale) if with_cpu else None
 
     rec = {
         "metric": "effective KV GB/s per decode step (32-layer LLaMA-8B-shape step: append + split-K attention "
@@ -411,9 +414,9 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "stream_roof": stream_roof,
-        "cpu_baseline": cpu,
+        "cpu_baseline": None,
     }
-    return rec
+    return rec, cpu_job
 
 
 if __name__ == "__main__":
