@@ -184,8 +184,8 @@ bd_status bd_decode_attn_static(const bd_cache* c, const void* q, int32_t packed
  * block the one workgroup that reads the new packed block quantizes it first (the fusion of the
  * paper's Residual Kernel, Sec. III-A(1) / Sec. IV-B, with the flush before the attention).
  * BD_FMT_MXFP4: the workgroup that reads the token's block quantizes the token into the cache before
- * it attends.  (Query groups above 16 heads, and the filling step of the _G64 / _G32 formats, run as
- * the two calls.)  All pointers as in the two calls; `out` must be non-NULL.  Every argument is validated before the
+ * it attends.  (The filling step of query groups above 16 heads -- 8 for the _G64 / _G32 formats -- runs
+ * as the two calls.)  All pointers as in the two calls; `out` must be non-NULL.  Every argument is validated before the
  * append; only BD_ERR_HIP (a failed launch) can leave the token appended without the attention
  * having been enqueued, and *packed_len / *res_len then say so. */
 bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new, const void* q,

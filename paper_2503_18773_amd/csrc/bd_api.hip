@@ -303,9 +303,9 @@ static bd_status decode_step(const bd_cache* c, const void* k_new, const void* v
   const bool fills = r == kBlock - 1;
   if (fills && pl + kBlock > c->capacity) return BD_ERR_CAPACITY;
   const bool grp = fmt_group(c->format) != kBlock;
-  if (fills && (grp || gq > 16)) {
-    // no kernel packs the block inside the attention launch for these (smaller quantization groups; several
-    // workgroups per split and KV head): the step runs as the calls it is defined by
+  if (fills && gq > (grp ? 8 : 16)) {
+    // several workgroups per split and KV head read the block the step fills, so no single one can pack it
+    // inside the attention launch: the step runs as the calls it is defined by
     if (lazy) {   // attention over the 128 fp16 rows (the token read from k_new / v_new and filed), then the flush
       s = hip_status(grp ? launch_decode_grp(c, q, pl, kBlock, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
                          : launch_decode_int(c, q, pl, kBlock, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st));
@@ -325,7 +325,8 @@ static bd_status decode_step(const bd_cache* c, const void* k_new, const void* v
   // the residual block it packs the block as well (before attending it, or, lazy, after)
   const int flush = !fills ? 0 : lazy ? 2 : 1;
   const int att_pl = flush == 1 ? pl + kBlock : pl, att_r = flush == 1 ? 0 : r + 1;
-  s = hip_status(grp ? launch_decode_grp(c, q, att_pl, att_r, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
+  s = hip_status(grp ? launch_decode_grp(c, q, att_pl, att_r, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st,
+                                         flush)
                      : launch_decode_int(c, q, att_pl, att_r, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st,
                                          flush));
   if (s != BD_OK) return s;

@@ -70,10 +70,11 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
 hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, int res_len,
                              float softmax_scale, int num_splits, float* part_o, float* part_ml,
                              const void* k_new, const void* v_new, void* out, hipStream_t st, int flush = 0);
-// formats with a quantization group of 64 or 32 (k_new / v_new as in launch_decode_int)
+// formats with a quantization group of 64 or 32 (k_new / v_new and flush as in launch_decode_int; the flush
+// forms for query groups of up to 8 heads only)
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
-                             void* out, hipStream_t st);
+                             void* out, hipStream_t st, int flush = 0);
 // (k_new / v_new as in launch_decode_paged; query groups of up to 8 heads only)
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                    float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,

@@ -103,7 +103,6 @@ struct DecodeArgs {
   //                (sequence, KV head), blockIdx.x == 0, does nothing but quantize.
   int flush_mode, flush_blk;
 };
-constexpr int kFlushNone = 0, kFlushFirst = 1, kFlushAfter = 2;
 
 // Per-wave LDS scratch.  GQP = query heads per KV head, padded to 4, 8 or 16.
 template <int GQP>

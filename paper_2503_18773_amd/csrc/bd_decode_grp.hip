@@ -58,6 +58,10 @@ struct GrpArgs {
   int32_t* status;
   int max_pages, num_pages;
   int step;   // paged: 1 when this launch is the attention of a fused step
+  // Contiguous cache, fused step whose token fills the residual block: as in the group-128 kernel
+  // (kFlushFirst: the workgroup that reads block flush_blk packs it first; kFlushAfter: the step attends the
+  // 128 fp16 rows and one extra workgroup per KV head, blockIdx.x == 0, packs them)
+  int flush_mode, flush_blk;
 };
 
 template <int GQP, int NV, bool KT>
@@ -136,7 +140,9 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP, KT)) void dec
   __shared__ __attribute__((aligned(16))) float q_s[GQP][kD];
   __shared__ float qinv_s[GQP];
 
-  const int split = blockIdx.x, b = blockIdx.z;
+  const int b = blockIdx.z;
+  const bool flush_after = !PAGED && a.flush_mode == kFlushAfter;
+  const int split = (int)blockIdx.x - (flush_after ? 1 : 0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, g = lane >> 4;
   // Every copy of a head's column receives the same S^T; copy cp keeps the chunks c with
@@ -188,6 +194,25 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP, KT)) void dec
   // blocks are dealt to the splits four at a time (one per wave), round robin: the workgroups of a
   // unit read one contiguous window of the cache at any moment
   const int blk0 = split * kWaves, blk1 = nb, bstep = kWaves * a.num_splits;
+  if (flush_after && split < 0 && head0 != 0) return;   // (one quantizing workgroup per KV head is enough)
+  if (!PAGED && a.flush_mode != kFlushNone && head0 == 0 &&
+      (flush_after ? split < 0 : split == (a.flush_blk / kWaves) % a.num_splits)) {
+    // the step's token completes the residual block: file it, then pack the 128 rows as block flush_blk
+    // (kFlushFirst: this workgroup is the block's only reader in this launch -- up to 8 heads per KV head)
+    uint16_t* kr = const_cast<uint16_t*>(a.k_res) + unit * kBlock * kD;
+    uint16_t* vr = const_cast<uint16_t*>(a.v_res) + unit * kBlock * kD;
+    if (tid < 32) {
+      const bool is_v = tid >= 16;
+      const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+      *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
+    }
+    workgroup_global_sync();
+    quant_block<BITS, KT, G>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
+                             const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
+                             unit * a.nbcap + a.flush_blk);
+    if (flush_after) return;   // (the whole workgroup: split < 0 is uniform)
+    workgroup_global_sync();
+  }
   if (PAGED && flush_page >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) {
     // the 128 residual rows become block nb - 1, which this workgroup alone reads in this launch (one
     // workgroup per split and KV head: the host takes this path for up to 8 heads per KV head)
@@ -246,7 +271,7 @@ __global__ __launch_bounds__(256, grp_waves_per_simd(BITS, G, GQP, KT)) void dec
       }
     }
   }
-  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32) {   // fused step: file the new token for later steps
+  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32 && (PAGED || a.flush_mode == kFlushNone)) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
     uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + new_slot) * kD + 8 * (tid & 15);
@@ -750,7 +775,7 @@ void launch_heads(const GrpArgs& a, bool paged, dim3 grid, hipStream_t st) {
 }
 
 hipError_t launch_format(int format, const GrpArgs& a, bool paged, int batch, hipStream_t st) {
-  dim3 grid(a.num_splits, a.n_kv_heads * ((a.gq + kGrpHeads - 1) / kGrpHeads), batch);
+  dim3 grid(a.num_splits + (a.flush_mode == kFlushAfter ? 1 : 0), a.n_kv_heads * ((a.gq + kGrpHeads - 1) / kGrpHeads), batch);
   switch (format) {
     case BD_FMT_INT4_G64: launch_heads<4, 64>(a, paged, grid, st); break;
     case BD_FMT_INT4_G32: launch_heads<4, 32>(a, paged, grid, st); break;
@@ -769,11 +794,15 @@ hipError_t launch_format(int format, const GrpArgs& a, bool paged, int batch, hi
 
 hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, int res_len, float softmax_scale,
                              int num_splits, float* part_o, float* part_ml, const void* k_new, const void* v_new,
-                             void* out, hipStream_t st) {
+                             void* out, hipStream_t st, int flush) {
   GrpArgs a;
   a.k_new = (const uint16_t*)k_new;
   a.v_new = (const uint16_t*)v_new;
-  a.new_slot = k_new ? res_len - 1 : -1;
+  // flush 1: the step's token fills the residual block, which this launch packs first (packed_len counts it,
+  // res_len is 0); flush 2: ... which this launch attends in fp16 (res_len is 128) and packs as well
+  a.flush_mode = flush == 1 ? kFlushFirst : flush == 2 ? kFlushAfter : kFlushNone;
+  a.flush_blk = flush == 1 ? packed_len / kBlock - 1 : packed_len / kBlock;
+  a.new_slot = k_new && flush != 1 ? res_len - 1 : -1;
   a.out = num_splits == 1 ? out : nullptr;
   a.out_kind = out_kind(c->format, c->out_type);
   a.k_codes = (const uint32_t*)c->k_codes;
@@ -830,6 +859,8 @@ hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float
   a.max_pages = c->max_pages_per_seq;
   a.num_pages = c->num_pages;
   a.step = step ? 1 : 0;
+  a.flush_mode = kFlushNone;
+  a.flush_blk = 0;
   return launch_format(c->format, a, true, c->batch, st);
 }
 

@@ -79,6 +79,10 @@ __device__ __forceinline__ float head_max(float x) {
   return x;
 }
 
+// Contiguous cache, fused step whose token fills the residual block (Sec. IV-B(1)): how the attention launch
+// packs the block (DecodeArgs / GrpArgs flush_mode).
+constexpr int kFlushNone = 0, kFlushFirst = 1, kFlushAfter = 2;
+
 // Element type of the output rows: the format's own half type (fp16; bf16 for MXFP4) or fp32
 // (bd_cache.out_type).
 constexpr int kOutF16 = 0, kOutBf16 = 1, kOutF32 = 2;

@@ -401,7 +401,7 @@ def test_decode_step_equals_append_then_attention(fmt):
         assert np.array_equal(a.host_buffer(i), b.host_buffer(i)), (fmt, i)
 
 
-@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int2_kt"])
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int2_kt", "int4_g32", "int2_g64", "int4_kt_g64", "int2_kt_g32"])
 @pytest.mark.parametrize("gq", [4, 8, 16, 20])
 def test_decode_step_packs_the_full_block_inside_the_attention_launch(fmt, gq):
     """The step that fills the residual block: bd_decode_step (flush first: the workgroup that reads the new
