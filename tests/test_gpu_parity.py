@@ -968,19 +968,21 @@ def test_group_decode_short_and_empty(fmt):
             assert_attn_close(got, O.decode_attn(oc, q, W.softmax_scale(w)), f"{fmt} L={L}", large_outputs=True)
 
 
-def test_group_full_size_32k_sampled_heads():
-    """cfg1's shape with 32-groups, split factor as the library picks it; two KV heads against the oracle."""
-    w = W.scaled(W.CONFIGS["cfg1"], fmt="int4_g32", context=32768 + 77)
+@pytest.mark.parametrize("fmt", ["int4_g32", "int4_kt_g32"])
+def test_group_full_size_32k_sampled_heads(fmt):
+    """cfg1's shape with 32-groups (K channel-wise and per token), split factor as the library picks it; two KV
+    heads against the oracle."""
+    w = W.scaled(W.CONFIGS["cfg1"], fmt=fmt, context=32768 + 77)
     K, V = W.make_kv(w)
     gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.fmt, 32768 + 128)
     gc.quant_pack_kv(to_dev(K, "fp16"), to_dev(V, "fp16"))
     q = W.make_q(w)
     got = _decode(gc, w, q)
     for h in (0, 5):
-        oc = O.IntCache(1, 1, 4, 32768 + 128, group=32)
+        oc = O.IntCache(1, 1, 4, 32768 + 128, k_per_token="_kt" in fmt, group=32)
         oc.quant_pack_kv(K[:, h:h + 1], V[:, h:h + 1])
         ref = O.decode_attn(oc, q[:, 4 * h:4 * h + 4], W.softmax_scale(w))
-        assert_attn_close(got[:, 4 * h:4 * h + 4], ref, f"int4_g32 32K head {h}")
+        assert_attn_close(got[:, 4 * h:4 * h + 4], ref, f"{fmt} 32K head {h}")
 
 
 @pytest.mark.parametrize("fmt", ["int4", "mxfp4"])
