@@ -164,9 +164,10 @@ def kernel_roofline(B, W, torch, w, caches, qs_last, outs, splits, paged, sm_sca
                 "timing": f"hip events around {len(caches)} back-to-back launches (one per cold layer cache), "
                           f"{reps} repetitions" + (" (paged entry point: decode + combine kernels)" if paged else "")}
     stream_roof = None
-    if not paged and not mx:
-        probe = timed(lambda li, c: B.bd_probe_stream_read(c.desc, c.packed_len))
-        code_bytes = w.batch * w.n_kv_heads * c0.packed_len * 128 * (4 if w.fmt.startswith("int4") else 2) // 8 * 2
+    if not paged:
+        ppl = c0.packed_len - c0.packed_len % 128
+        probe = timed(lambda li, c: B.bd_probe_stream_read(c.desc, ppl))
+        code_bytes = w.batch * w.n_kv_heads * ppl * 128 * (2 if w.fmt.startswith("int2") else 4) // 8 * 2
         us = float(np.mean(probe))
         stream_roof = {"avg_launch_us": round(us, 3), "min_launch_us": round(float(np.min(probe)), 3),
                        "bytes_per_launch": code_bytes, "GB/s": round(code_bytes / us / 1e3, 1),

@@ -204,7 +204,7 @@ bd_status bd_decode_step_lazy(const bd_cache* c, const void* k_new, const void* 
                               int32_t num_splits, void* workspace, void* out, void* stream);
 
 /* Measurement aid, no part of the method: one launch that reads the packed K and V codes of the first
- * packed_len tokens of every (sequence, KV head) unit of an integer-format cache, with the loads
+ * packed_len tokens (a multiple of 128) of every (sequence, KV head) unit of a cache, with the loads
  * bd_decode_attn uses, and computes nothing.  Its duration is the floor the memory system sets for a
  * decode launch over the same cache (the "KV loading dominates" end of Sec. V-C's breakdown).  `sink`
  * (device, 4 bytes, may be NULL) is written only for one value of the loaded data's checksum. */

@@ -258,7 +258,6 @@ bd_status bd_probe_stream_read(const bd_cache* c, int32_t packed_len, void* sink
   bd_status s = check_shape(c);
   if (s != BD_OK) return s;
   if ((s = check_buffers(c)) != BD_OK) return s;
-  if (!fmt_is_int(c->format)) return BD_ERR_UNSUPPORTED;
   if ((long)c->batch * c->n_kv_heads > 32767) return BD_ERR_UNSUPPORTED;   // the probe's grid: two rows per unit
   if (packed_len < 0 || packed_len % kBlock != 0 || packed_len > c->capacity) return BD_ERR_INVALID_ARG;
   if (sink && (reinterpret_cast<uintptr_t>(sink) & 3u)) return BD_ERR_ALIGNMENT;

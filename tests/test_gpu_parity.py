@@ -1418,3 +1418,24 @@ def test_seeded_paged_sweep():
             _assert_paged_mx_equal(oc, gc, what)
         else:
             _assert_paged_equal(oc, gc, what)
+
+
+@pytest.mark.parametrize("fmt", ["int4", "int2", "mxfp4", "int4_g32"])
+def test_stream_probe_reads_the_cache_and_changes_nothing(fmt):
+    """bd_probe_stream_read (measurement aid): runs over an empty, a partly filled and a full cache of every format
+    family and leaves every buffer as it was."""
+    import torch
+    w = W.scaled(W.CONFIGS["cfg4" if fmt == "mxfp4" else "cfg1"], batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 5 + 9, fmt=fmt, seed=3)
+    K, V = W.make_kv(w)
+    dt = "bf16" if fmt == "mxfp4" else "fp16"
+    gc = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, fmt, 128 * 6)
+    gc.quant_pack_kv(to_dev(K, dt), to_dev(V, dt))
+    before = [gc.host_buffer(i).copy() for i in range(4)]
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for pl in (0, 128, 128 * 5, 128 * 6):
+        B.bd_probe_stream_read(gc.desc, pl, sink)
+    torch.cuda.synchronize()
+    for i in range(4):
+        assert np.array_equal(before[i], gc.host_buffer(i))
+    with pytest.raises(B.BitDecodeError):
+        B.bd_probe_stream_read(gc.desc, 100)

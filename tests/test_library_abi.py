@@ -99,6 +99,10 @@ def test_argument_validation_happens_before_any_launch():
     assert L.bd_decode_attn_static(ctypes.byref(c), 4096, 1024, 0, 0.1, 4, None, None) == -1
     too_many = B.BD_STATIC_SCRATCH_BYTES // (c.batch * c.n_q_heads * 130 * 4) + 1
     assert L.bd_decode_attn_static(ctypes.byref(c), 4096, 1024, 0, 0.1, too_many, 4096, None) == -4
+    # the streaming-read probe: whole blocks inside the capacity, an aligned sink
+    assert L.bd_probe_stream_read(ctypes.byref(c), 1000, None, None) == -1
+    assert L.bd_probe_stream_read(ctypes.byref(c), c.capacity + 128, None, None) == -1
+    assert L.bd_probe_stream_read(ctypes.byref(c), 1024, 4098, None) == -3
     pl, rl = ctypes.c_int32(1024), ctypes.c_int32(5)
     assert L.bd_decode_step(ctypes.byref(c), 4096, 4096, 4096, ctypes.byref(pl), ctypes.byref(rl), 0.1, 4, 4096,
                             None, None) == -1                       # out is required
