@@ -326,6 +326,8 @@ class PagedIntCache:
         self.v_res = np.zeros((batch, n_kv_heads, BLOCK, head_dim), np.float16)
         self.block_table = block_table.astype(np.int32).copy()
         self.seq_lens = np.zeros(batch, np.int32)
+        # lazy flush (append_kv(flush=False)): sequences whose residual holds 128 tokens that are not packed yet
+        self.unflushed = np.zeros(batch, bool)
 
     def _page_of(self, b: int, n: int) -> int:
         if n >= self.max_pages:
@@ -363,24 +365,40 @@ class PagedIntCache:
         self.v_res[b, :, :r] = V[:, nb * BLOCK:]
         self.seq_lens[b] = L
 
-    def append_kv(self, k_new: np.ndarray, v_new: np.ndarray):
+    def append_kv(self, k_new: np.ndarray, v_new: np.ndarray, flush: bool = True):
         """One decode step of every sequence: token b goes to slot seq_lens[b] mod 128 of
         sequence b's residual; a residual that reaches 128 tokens is quantized into the
-        sequence's next page at once."""
+        sequence's next page at once.
+
+        flush=False is the order of the paper's Residual Kernel (Sec. III-A(1), Sec. IV-B(1)), as in
+        IntCache.append_kv: a sequence whose residual reaches 128 tokens keeps them in fp16 for the
+        attention of this step, and flush_if_full() after that attention packs them into the page."""
         assert k_new.shape == v_new.shape == (self.B, self.H, self.D)
+        assert not self.unflushed.any(), "a full residual must be flushed before the next append"
         for b in range(self.B):
             nb, r = divmod(int(self.seq_lens[b]), BLOCK)
             if r == BLOCK - 1:
-                self._page_of(b, nb)            # raises before anything is changed
+                self._page_of(b, nb)            # raises before anything of this sequence is changed
             self.k_res[b, :, r] = k_new[b]
             self.v_res[b, :, r] = v_new[b]
-            if r == BLOCK - 1:
-                self._store_block(b, nb, self.k_res[b], self.v_res[b])
             self.seq_lens[b] += 1
+            if r == BLOCK - 1:
+                self.unflushed[b] = True
+                if flush:
+                    self.flush_if_full()
+
+    def flush_if_full(self):
+        """Sec. IV-B(1): a residual of N_r = 128 tokens becomes the sequence's next packed block."""
+        for b in range(self.B):
+            if self.unflushed[b]:
+                self._store_block(b, int(self.seq_lens[b]) // BLOCK - 1, self.k_res[b], self.v_res[b])
+                self.unflushed[b] = False
 
     def dequant(self, b: int, h: int):
         """K_hat, V_hat [seq_lens[b], D] float64 of one (sequence, kv_head)."""
         nb, r = divmod(int(self.seq_lens[b]), BLOCK)
+        if self.unflushed[b]:                  # the newest 128 tokens are still the fp16 residual
+            nb, r = nb - 1, BLOCK
         Kh = np.empty((nb * BLOCK + r, self.D), np.float64)
         Vh = np.empty_like(Kh)
         for n in range(nb):

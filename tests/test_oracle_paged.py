@@ -144,3 +144,43 @@ def test_paged_mx_is_a_relocation_of_the_contiguous_cache():
             assert np.array_equal(p.k_scales[pg][:, :m], c.k_scales[0, :, 128 * n:128 * n + m])
             assert np.array_equal(p.v_scales[pg][:, :m], c.v_scales[0, :, 128 * n:128 * n + m])
             assert np.array_equal(p.v_codes[pg], c.v_codes[0, :, n])
+
+
+def test_lazy_flush_of_a_ragged_batch_is_the_per_sequence_lazy_flush():
+    """append_kv(flush=False) + attention + flush_if_full(): every sequence on its own behaves as the contiguous
+    cache's lazy mode (pinned in test_oracle_quant), only the sequences whose residual reached 128 tokens attend
+    fp16 rows, and the pool afterwards is the one eager steps leave."""
+    H, D = 2, 128
+    lens = [128 + 126, 90, 127, 3 * 128 + 127]
+    table = np.array([[3, 9, 0, 14], [5, 1, 13, 8], [2, 11, 6, 15], [7, 4, 12, 10]], np.int32)
+    lazy = O.PagedIntCache(4, H, 4, 16, 4, table)
+    eager = O.PagedIntCache(4, H, 4, 16, 4, table)
+    singles = []
+    for b, L in enumerate(lens):
+        w = W.scaled(W.CONFIGS["cfg1"], batch=1, n_q_heads=4, n_kv_heads=H, context=L, seed=60 + b)
+        K, V = W.make_kv(w)
+        lazy.quant_pack_kv(b, K[0], V[0])
+        eager.quant_pack_kv(b, K[0], V[0])
+        c = O.IntCache(1, H, 4, 512)
+        c.quant_pack_kv(K, V)
+        singles.append(c)
+    wq = W.scaled(W.CONFIGS["cfg1"], batch=4, n_q_heads=4, n_kv_heads=H, context=8, seed=70)
+    for step in range(3):       # sequences 2 and 3 fill at step 0, sequence 0 at step 1
+        kn, vn = W.make_new_kv(wq, step)
+        q = W.make_q(wq, step)
+        lazy.append_kv(kn, vn, flush=False)
+        assert list(lazy.unflushed) == [[False, False, True, True], [True, False, False, False], [False] * 4][step]
+        out = O.decode_attn(lazy, q, 0.09)
+        lazy.flush_if_full()
+        eager.append_kv(kn, vn)
+        out_eager = O.decode_attn(eager, q, 0.09)
+        for b in range(4):
+            singles[b].append_kv(kn[b:b + 1], vn[b:b + 1], flush=False)
+            ref = O.decode_attn(singles[b], q[b:b + 1], 0.09)
+            singles[b].flush_if_full()
+            assert np.array_equal(out[b], ref[0]), (step, b)
+            filled = (lens[b] + step) % 128 == 127
+            assert np.array_equal(out[b], out_eager[b]) != filled, (step, b)   # only a filling step differs
+        for name in ("k_codes", "v_codes", "k_params", "v_params", "seq_lens"):
+            assert np.array_equal(getattr(lazy, name), getattr(eager, name)), (step, name)
+    assert not lazy.unflushed.any()
