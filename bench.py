@@ -314,7 +314,7 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
         nbytes = 0
         for li, c in enumerate(caches):
             if paged:   # the lengths live on the device; the host knows them by counting
-                c.decode_step(kn, vn, qs[s], sm_scale, outs[li], splits)
+                c.decode_step(kn, vn, qs[s], sm_scale, outs[li], splits, lazy=args.flush == "lazy")
                 nbytes += algorithmic_bytes(w, *lengths(w.context + s + 1))
             else:
                 c.decode_step(kn, vn, qs[s], sm_scale, outs[li], num_splits=splits, lazy=args.flush == "lazy")
@@ -331,7 +331,7 @@ def run(args, workload: str, steps: int, warmup: int, with_cpu: bool) -> dict:
         g_step = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g_step):
             for li, c in enumerate(caches):
-                c.decode_step(kn_s, vn_s, q_s, sm_scale, outs[li], splits)
+                c.decode_step(kn_s, vn_s, q_s, sm_scale, outs[li], splits, lazy=args.flush == "lazy")
 
         def replay_step(s: int):
             kn_s.copy_(new_kv[s][0]); vn_s.copy_(new_kv[s][1]); q_s.copy_(qs[s])

@@ -304,6 +304,16 @@ bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const
                                const void* q, float softmax_scale, int32_t num_splits,
                                void* workspace, void* out, void* stream);
 
+/* The same step with the paper's own flush order (Sec. III-A(1), Sec. IV-B(1); see bd_decode_step_lazy): a
+ * sequence whose residual block this step's token fills is attended with its 128 residual tokens in half
+ * precision, and one extra workgroup per (sequence, KV head) of the same attention launch packs them into the
+ * sequence's next page; the other sequences of the batch behave as in bd_paged_decode_step.  Two launches for
+ * every query group size.  On return the pool, the lengths and *status are those bd_paged_decode_step leaves.
+ * BD_FMT_MXFP4 keeps no residual and behaves as in bd_paged_decode_step. */
+bd_status bd_paged_decode_step_lazy(const bd_paged_cache* c, const void* k_new, const void* v_new,
+                                    const void* q, float softmax_scale, int32_t num_splits,
+                                    void* workspace, void* out, void* stream);
+
 /* Text for a status code (static storage). */
 const char* bd_strerror(bd_status s);
 

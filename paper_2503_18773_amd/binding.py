@@ -84,6 +84,7 @@ def lib() -> ctypes.CDLL:
         L.bd_paged_append_kv.restype, L.bd_paged_append_kv.argtypes = ctypes.c_int, [PP, V, V, V]
         L.bd_paged_decode_attn.restype, L.bd_paged_decode_attn.argtypes = ctypes.c_int, [PP, V, F, I, V, V, V]
         L.bd_paged_decode_step.restype, L.bd_paged_decode_step.argtypes = ctypes.c_int, [PP, V, V, V, F, I, V, V, V]
+        L.bd_paged_decode_step_lazy.restype, L.bd_paged_decode_step_lazy.argtypes = ctypes.c_int, [PP, V, V, V, F, I, V, V, V]
         L.bd_strerror.restype, L.bd_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
         L.bd_last_hip_error.restype, L.bd_last_hip_error.argtypes = ctypes.c_int, []
         _lib = L
@@ -93,7 +94,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ["bd_cache_bytes", "bd_choose_splits", "bd_workspace_bytes", "bd_quant_pack_kv", "bd_append_kv",
            "bd_decode_attn", "bd_decode_attn_static", "bd_probe_stream_read", "bd_decode_step", "bd_decode_step_lazy", "bd_splitk_combine", "bd_strerror", "bd_last_hip_error",
            "bd_paged_cache_bytes", "bd_paged_workspace_bytes", "bd_paged_quant_pack_kv", "bd_paged_append_kv",
-           "bd_paged_decode_attn", "bd_paged_decode_step"]
+           "bd_paged_decode_attn", "bd_paged_decode_step", "bd_paged_decode_step_lazy"]
 
 
 def _ptr(t):
@@ -208,6 +209,13 @@ def bd_paged_decode_step(c: bd_paged_cache, k_new, v_new, q, softmax_scale: floa
                          stream=None):
     _check(lib().bd_paged_decode_step(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), softmax_scale, num_splits,
                                       _ptr(workspace), _ptr(out), _stream(stream)), "bd_paged_decode_step")
+
+
+def bd_paged_decode_step_lazy(c: bd_paged_cache, k_new, v_new, q, softmax_scale: float, num_splits: int, workspace, out,
+                              stream=None):
+    _check(lib().bd_paged_decode_step_lazy(ctypes.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), softmax_scale,
+                                           num_splits, _ptr(workspace), _ptr(out), _stream(stream)),
+           "bd_paged_decode_step_lazy")
 
 
 # ---- device-memory plumbing ------------------------------------------------------------------
@@ -332,9 +340,9 @@ class PagedKVCache:
         bd_paged_decode_attn(self.desc, q, softmax_scale, num_splits, self.workspace(num_splits), out, stream)
         return out
 
-    def decode_step(self, k_new, v_new, q, softmax_scale: float, out, num_splits: int, stream=None):
-        bd_paged_decode_step(self.desc, k_new, v_new, q, softmax_scale, num_splits, self.workspace(num_splits), out,
-                             stream)
+    def decode_step(self, k_new, v_new, q, softmax_scale: float, out, num_splits: int, stream=None, lazy: bool = False):
+        step = bd_paged_decode_step_lazy if lazy else bd_paged_decode_step
+        step(self.desc, k_new, v_new, q, softmax_scale, num_splits, self.workspace(num_splits), out, stream)
         return out
 
     def host_buffer(self, i: int):

@@ -447,7 +447,7 @@ bd_status bd_paged_append_kv(const bd_paged_cache* c, const void* k_new, const v
 // (main integer kernel only), is appended by the attention launch itself.
 static bd_status paged_attention(const bd_paged_cache* c, const void* q, float softmax_scale, int32_t num_splits,
                                  void* workspace, void* out, bool step, hipStream_t st,
-                                 const void* k_new = nullptr, const void* v_new = nullptr) {
+                                 const void* k_new = nullptr, const void* v_new = nullptr, bool lazy = false) {
   const bd_cache shape = shape_of(c);
   float* part_o = ws_part_o(workspace);
   float* part_ml = ws_part_ml(&shape, workspace, num_splits);
@@ -459,9 +459,9 @@ static bd_status paged_attention(const bd_paged_cache* c, const void* q, float s
                                                         direct, st)
                            : fmt_group(c->format) != kBlock
                                ? launch_decode_grp_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
-                                                         direct, st)
+                                                         direct, st, lazy)
                                : launch_decode_paged(c, q, softmax_scale, num_splits, part_o, part_ml, step, k_new, v_new,
-                                                     direct, st));
+                                                     direct, st, lazy));
   if (s != BD_OK) return s;
   if (direct) return step ? hip_status(launch_paged_bump(c, st)) : BD_OK;
   return hip_status(launch_combine(&shape, part_o, part_ml, num_splits, out, st, step ? c : nullptr));
@@ -497,6 +497,21 @@ bd_status bd_paged_decode_step(const bd_paged_cache* c, const void* k_new, const
   // kernel counts the new token in, and the merge, last in line, raises the lengths
   if ((s = hip_status(launch_paged_append(c, k_new, v_new, false, st))) != BD_OK) return s;
   return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, st);
+}
+
+bd_status bd_paged_decode_step_lazy(const bd_paged_cache* c, const void* k_new, const void* v_new, const void* q,
+                                    float softmax_scale, int32_t num_splits, void* workspace, void* out, void* stream) {
+  bd_status s = check_paged_shape(c);
+  if (s != BD_OK) return s;
+  if (c->format == BD_FMT_MXFP4)   // no residual: nothing to flush lazily
+    return bd_paged_decode_step(c, k_new, v_new, q, softmax_scale, num_splits, workspace, out, stream);
+  if ((s = check_paged_buffers(c)) != BD_OK) return s;
+  if (!k_new || !v_new || !q || !workspace || !out || num_splits < 1 || num_splits > 65533) return BD_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(workspace) || !aligned16(out))
+    return BD_ERR_ALIGNMENT;
+  // Two launches for every query group size: no workgroup has to read the block a sequence fills, so the extra
+  // workgroup per (sequence, KV head) packs it while the others attend the 128 fp16 rows.
+  return paged_attention(c, q, softmax_scale, num_splits, workspace, out, true, (hipStream_t)stream, k_new, v_new, true);
 }
 
 const char* bd_strerror(bd_status s) {

@@ -60,7 +60,7 @@ hipError_t launch_paged_bump(const bd_paged_cache* c, hipStream_t st);
 // before it; query groups of up to 16 heads only
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
-                               void* out, hipStream_t st);
+                               void* out, hipStream_t st, bool lazy = false);
 
 // k_new / v_new non-null: fused step -- residual token res_len-1 is read from k_new / v_new
 // ([B][Hkv][128]) and also stored into the residual buffers by the kernel.
@@ -78,7 +78,7 @@ hipError_t launch_decode_grp(const bd_cache* c, const void* q, int packed_len, i
 // (k_new / v_new as in launch_decode_paged; query groups of up to 8 heads only)
 hipError_t launch_decode_grp_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                    float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
-                                   void* out, hipStream_t st);
+                                   void* out, hipStream_t st, bool lazy = false);
 // k_new / v_new non-null: the launch quantizes the step's token into the cache itself (contiguous: at index
 // `length`, and attends length + 1 tokens; paged: with `step`); query groups of up to 16 heads only
 hipError_t launch_decode_mx_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,

@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
 
   const int b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bool flush_after = !PAGED && a.flush_mode == kFlushAfter;
+  const bool flush_after = a.flush_mode == kFlushAfter;
   const int split = (int)blockIdx.x - (flush_after ? 1 : 0);
   const int col = lane & 15, g = lane >> 4;            // MFMA column and contraction group
   const int head = col % GQP, cg = col / GQP;          // head carried by the column; column group
@@ -207,6 +207,11 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     len = len < 0 ? 0 : len;
     nb = len / kBlock;
     res_len = len % kBlock;
+    if (flush_after && flush_page >= 0) {   // lazy flush: this step attends the 128 residual rows in fp16
+      nb -= 1;
+      res_len = kBlock;
+      new_slot = kBlock - 1;
+    }
   }
   // Blocks are dealt to the splits four at a time (one per wave), round robin: at any moment the
   // workgroups of a (sequence, KV head) unit read one contiguous window of the cache.  (Contiguous
@@ -234,7 +239,25 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     if (flush_after) return;   // (the whole workgroup: split < 0 is uniform)
     workgroup_global_sync();
   }
-  if (PAGED && flush_page >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) {
+  if (PAGED && flush_after && split < 0) {
+    // lazy flush: the extra workgroup of a (sequence, KV head) packs the 128 rows into the page if this
+    // step's token completes them, and does nothing else
+    if (flush_page >= 0 && head0 == 0) {
+      uint16_t* kr = const_cast<uint16_t*>(a.k_res) + unit * kBlock * kD;
+      uint16_t* vr = const_cast<uint16_t*>(a.v_res) + unit * kBlock * kD;
+      if (tid < 32) {
+        const bool is_v = tid >= 16;
+        const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
+        *reinterpret_cast<u4_t*>((is_v ? vr : kr) + (kBlock - 1) * kD + 8 * (tid & 15)) = *reinterpret_cast<const u4_t*>(src);
+      }
+      workgroup_global_sync();
+      quant_block<BITS, KT, kBlock>(kr, vr, const_cast<uint32_t*>(a.k_codes), const_cast<uint32_t*>(a.v_codes),
+                                    const_cast<uint32_t*>(a.k_params), const_cast<uint32_t*>(a.v_params),
+                                    (size_t)flush_page * a.n_kv_heads + hkv);
+    }
+    return;
+  }
+  if (PAGED && !flush_after && flush_page >= 0 && split == ((nb - 1) / kWaves) % a.num_splits) {
     // This step's token completes the residual (Sec. IV-B(1)): the 128 rows become block nb - 1, which
     // this workgroup alone reads in this launch.  (One workgroup per split and KV head: the host takes
     // this path only for query groups of up to 16 heads.)
@@ -338,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void decode_int_kernel(DecodeArgs a) {
     }
     load_res_keys(wave);
   }
-  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32 && (PAGED || a.flush_mode == kFlushNone)) {   // fused step: file the new token for later steps
+  if (new_slot >= 0 && split == 0 && head0 == 0 && tid < 32 && res_len < kBlock && (PAGED || a.flush_mode == kFlushNone)) {   // fused step: file the new token for later steps
     const bool is_v = tid >= 16;
     const uint16_t* src = (is_v ? a.v_new : a.k_new) + unit * kD + 8 * (tid & 15);
     uint16_t* dst = const_cast<uint16_t*>(is_v ? a.v_res : a.k_res) + (unit * kBlock + new_slot) * kD + 8 * (tid & 15);
@@ -1005,7 +1028,7 @@ hipError_t launch_decode_int(const bd_cache* c, const void* q, int packed_len, i
 
 hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float softmax_scale, int num_splits,
                                float* part_o, float* part_ml, bool step, const void* k_new, const void* v_new,
-                               void* out, hipStream_t st) {
+                               void* out, hipStream_t st, bool lazy) {
   DecodeArgs a;
   a.step = step ? 1 : 0;
   a.out = num_splits == 1 ? out : nullptr;
@@ -1020,7 +1043,9 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.k_new = (const uint16_t*)k_new;   // non-null: the step's token, which this launch appends itself
   a.v_new = (const uint16_t*)v_new;
   a.new_slot = -1;
-  a.flush_mode = kFlushNone;
+  // lazy: a sequence whose residual this step's token fills is attended with its 128 fp16 rows, and one extra
+  // workgroup per (sequence, KV head), blockIdx.x == 0, packs them into the sequence's next page
+  a.flush_mode = lazy ? kFlushAfter : kFlushNone;
   a.flush_blk = 0;
   a.part_o = part_o;
   a.part_ml = part_ml;
@@ -1035,7 +1060,7 @@ hipError_t launch_decode_paged(const bd_paged_cache* c, const void* q, float sof
   a.status = c->status;
   a.max_pages = c->max_pages_per_seq;
   a.num_pages = c->num_pages;
-  dim3 grid(num_splits, c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
+  dim3 grid(num_splits + (lazy ? 1 : 0), c->n_kv_heads * ((a.gq + 15) / 16), c->batch), block(256);
   launch_instance(c->format, a.gq, false, true, a, grid, block, st);
   return hipGetLastError();
 }

@@ -1439,3 +1439,57 @@ def test_stream_probe_reads_the_cache_and_changes_nothing(fmt):
         assert np.array_equal(before[i], gc.host_buffer(i))
     with pytest.raises(B.BitDecodeError):
         B.bd_probe_stream_read(gc.desc, 100)
+
+
+@pytest.mark.parametrize("fmt", ["int4", "int2", "int4_kt", "int4_g32", "int2_kt_g64"])
+@pytest.mark.parametrize("gq", [4, 20])
+def test_paged_lazy_step_attends_full_residuals_in_fp16(fmt, gq):
+    """bd_paged_decode_step_lazy on a ragged batch: a sequence whose residual the step's token fills is attended
+    with its 128 fp16 rows (the oracle's lazy mode), the others as in the eager step; after every step the pool,
+    the residual rows in use and the lengths are the eager step's, bit for bit; steps on which no sequence fills
+    give the eager step's outputs bit for bit; a sequence without a page for the block it fills drops its token."""
+    import torch
+    H, Hq = 2, 2 * gq
+    lens = [127, 128 * 2 + 126, 40, 128 * 5 + 127, 128 + 127]
+    table = np.random.default_rng(12).permutation(60)[:5 * 9].reshape(5, 9).astype(np.int32)
+    oc, lz, _ = _paged_pair(fmt, lens, H, Hq, num_pages=60, max_pages=9, table=table)
+    _, eg, _ = _paged_pair(fmt, lens, H, Hq, num_pages=60, max_pages=9, table=table)
+    bad = table.copy(); bad[4, 1] = 99           # sequence 4 fills its residual at step 0 and has no page for the block
+    for gc in (lz, eg):
+        gc.block_table.copy_(torch.from_numpy(bad))
+    w = W.scaled(W.CONFIGS["cfg1"], batch=5, n_q_heads=Hq, n_kv_heads=H, context=128, seed=64)
+    out_l = torch.empty((5, Hq, 128), dtype=torch.float16, device="cuda:0")
+    out_e = torch.empty_like(out_l)
+    good = [(s_, h) for s_ in range(4) for h in range(H)]
+    for step in range(3):        # step 0: sequences 0 and 3 fill (4 drops its token); step 1: sequence 1; step 2: none
+        kn, vn, q = W.make_new_kv(w, step), None, W.make_q(w, step)
+        kn, vn = kn
+        ns = (3, 1, 4)[step]
+        lz.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out_l, ns, lazy=True)
+        eg.decode_step(to_dev(kn, "fp16"), to_dev(vn, "fp16"), to_dev(q, "fp16"), W.softmax_scale(w), out_e, ns)
+        torch.cuda.synchronize()
+        # the oracle, lazily (sequence 4 is left out: its table row is broken)
+        kn4, vn4 = kn.copy(), vn.copy()
+        oc_lens = oc.seq_lens.copy()
+        oc.block_table[4, 1] = table[4, 1]       # (the oracle raises on a bad entry; keep its sequence 4 out of the comparison)
+        oc.append_kv(kn4, vn4, flush=False)
+        ref = O.decode_attn(oc, q, W.softmax_scale(w), units=good)
+        oc.flush_if_full()
+        got = out_to_f64(out_l)
+        assert_attn_close(got[:4], ref[:4], f"{fmt} gq={gq} lazy paged step {step}", large_outputs=True)
+        fills = [(int(oc_lens[b]) % 128) == 127 for b in range(5)]
+        for b in range(5):
+            same = torch.equal(out_l[b].view(torch.int16), out_e[b].view(torch.int16))
+            if not fills[b] or b == 4:
+                assert same, (step, b)           # (sequence 4's token is dropped by both: it attends what it had)
+        assert torch.equal(lz.seq_lens, eg.seq_lens) and int(lz.status.item()) == int(eg.status.item()) == 2
+        for i in range(4):
+            assert torch.equal(lz.buffers[i], eg.buffers[i]), (step, i)
+        lens_now = lz.seq_lens.cpu().numpy()
+        for i in (4, 5):
+            ra = lz.host_buffer(i).view(np.float16).reshape(5, H, 128, 128)
+            rb = eg.host_buffer(i).view(np.float16).reshape(5, H, 128, 128)
+            for b in range(5):
+                r = int(lens_now[b]) % 128
+                assert np.array_equal(ra[b, :, :r].view(np.uint16), rb[b, :, :r].view(np.uint16)), (step, i, b)
+    assert list(lz.seq_lens.cpu().numpy()) == [130, 128 * 2 + 129, 43, 128 * 5 + 130, 128 + 127]
