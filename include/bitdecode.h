@@ -193,7 +193,7 @@ bd_status bd_decode_step(const bd_cache* c, const void* k_new, const void* v_new
                          int32_t num_splits, void* workspace, void* out, void* stream);
 
 /* The same step with the paper's own flush order (Sec. III-A(1), Sec. IV-B(1): the Residual Kernel
- * attends the half-precision residual block and "optionally quantizes it" when it has reached N_r
+ * attends the half-precision residual block and quantizes it, in the same kernel, only once it holds N_r
  * tokens): identical to bd_decode_step on every step but the one that fills the residual block.  On
  * that step the attention reads the block's 128 tokens in fp16 -- no quantization error on them yet --
  * and the same launch packs them (one extra workgroup per KV head); on return the lengths and the
@@ -206,7 +206,7 @@ bd_status bd_decode_step_lazy(const bd_cache* c, const void* k_new, const void* 
 /* Measurement aid, no part of the method: one launch that reads the packed K and V codes of the first
  * packed_len tokens (a multiple of 128) of every (sequence, KV head) unit of a cache, with the loads
  * bd_decode_attn uses, and computes nothing.  Its duration is the floor the memory system sets for a
- * decode launch over the same cache (the "KV loading dominates" end of Sec. V-C's breakdown).  `sink`
+ * decode launch over the same cache (where the breakdown of Sec. V-C ends up once loading the cache is all that is left).  `sink`
  * (device, 4 bytes, may be NULL) is written only for one value of the loaded data's checksum. */
 bd_status bd_probe_stream_read(const bd_cache* c, int32_t packed_len, void* sink, void* stream);
 

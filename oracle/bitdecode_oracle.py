@@ -239,7 +239,7 @@ class IntCache:
         tokens is quantized into the next packed block at once.
 
         flush=False is the order of the paper's Residual Kernel (Sec. III-A(1), Sec. IV-B(1): it attends
-        the half-precision residual and only then "optionally quantizes it (when res_len = N_r)"):
+        the half-precision residual first and quantizes it afterwards, once it holds N_r tokens):
         the token is appended, a full residual (res_len == 128) stays in fp16 for the attention of this
         step, and flush_if_full() after that attention packs it."""
         assert k_new.shape == v_new.shape == (self.B, self.H, self.D)

@@ -302,21 +302,10 @@ static bd_status decode_step(const bd_cache* c, const void* k_new, const void* v
   const bool fills = r == kBlock - 1;
   if (fills && pl + kBlock > c->capacity) return BD_ERR_CAPACITY;
   const bool grp = fmt_group(c->format) != kBlock;
-  if (fills && gq > (grp ? 8 : 16)) {
+  if (fills && !lazy && gq > (grp ? 8 : 16)) {
     // several workgroups per split and KV head read the block the step fills, so no single one can pack it
-    // inside the attention launch: the step runs as the calls it is defined by
-    if (lazy) {   // attention over the 128 fp16 rows (the token read from k_new / v_new and filed), then the flush
-      s = hip_status(grp ? launch_decode_grp(c, q, pl, kBlock, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st)
-                         : launch_decode_int(c, q, pl, kBlock, softmax_scale, num_splits, part_o, part_ml, k_new, v_new, out, st));
-      if (s != BD_OK) return s;
-      if (num_splits > 1 && (s = hip_status(launch_combine(c, part_o, part_ml, num_splits, out, st))) != BD_OK) return s;
-      if ((s = hip_status(launch_quant_blocks(c->k_res, c->v_res, (long)kBlock * kD, 0, 1, c->batch * c->n_kv_heads, c,
-                                              pl / kBlock, st))) != BD_OK)
-        return s;
-      *packed_len = pl + kBlock;
-      *res_len = 0;
-      return BD_OK;
-    }
+    // inside the attention launch before it is read: the step runs as the calls it is defined by.  (The lazy
+    // order has no such reader: its extra workgroup packs the block for any group size.)
     if ((s = bd_append_kv(c, k_new, v_new, packed_len, res_len, stream)) != BD_OK) return s;
     return bd_decode_attn(c, q, *packed_len, *res_len, softmax_scale, num_splits, workspace, out, stream);
   }
