@@ -115,6 +115,7 @@ for cfg, fmt in [("cfg1", "int4"), ("cfg3", "int4"), ("cfg2", "int2"), ("cfg4", 
 for cfg, fmt, var in [("cfg1", "int4", "paged"), ("cfg3", "int4", "paged"), ("cfg4", "mxfp4", "paged"),
                       ("cfg1", "int4_kt", "kt"), ("cfg1", "int4", "gq8"), ("cfg1", "int4", "gq16"),
                       ("cfg1", "int4_g32", "g32"), ("cfg1", "int4_g64", "g64"), ("cfg3", "int4_g32", "g32"),
+                      ("cfg1", "int4_kt_g32", "kt_g32"), ("cfg3", "int4_kt_g32", "kt_g32"),
                       ("cfg4", "mxfp4", "gq8"), ("cfg2", "int2", "paged")]:
     base = f"{RAW}/prof_{cfg}_{var}"
     if not os.path.isdir(base): continue
